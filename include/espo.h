@@ -1,0 +1,169 @@
+/*
+ * espo.h -- C ABI of the ESPO per-generation-step hot path for AMD MI355X (gfx950).
+ *
+ * ESPO (Early-Stopping Proximal Policy Optimization) changes how rollouts are
+ * collected: at every decode step it derives a regret signal from the policy
+ * logits, smooths it per trajectory, and ends the trajectory as an absorbing
+ * failure once the smoothed regret exceeds a value-dependent threshold
+ * (Section 4, Algorithm 1).  GAE is then run on the truncated trajectories with
+ * the failure reward placed at the stop step (Section 4.4, Eq. failure_reward,
+ * Eq. gae).
+ *
+ * Two operations are exported:
+ *   espo_step        one decode step for a batch of trajectories (Algorithm 1 body)
+ *   espo_advantages  TD errors + GAE over the truncated trajectories (Section 3, 4.4)
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory owned by the caller; the library
+ *     never allocates, frees or keeps them.  "host" pointers are ordinary host
+ *     memory read during the call only.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  Calls never synchronise; outputs are valid once the
+ *     stream has reached the point of the call.
+ *   - Return value: ESPO_OK (0) or a negative espo_status.  On any error nothing
+ *     has been enqueued.
+ *   - No global mutable state: calls from several host threads on different
+ *     streams are safe as long as they do not share output or workspace buffers.
+ */
+#ifndef ESPO_H_
+#define ESPO_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  ESPO_OK = 0,
+  ESPO_EINVAL = -1,     /* null pointer, negative size, bad temperature / parameter */
+  ESPO_EALIGN = -2,     /* logits base or row pitch not 16-byte aligned              */
+  ESPO_EWORKSPACE = -3, /* workspace missing or smaller than required                */
+  ESPO_EHIP = -4,       /* the HIP runtime refused the launch                        */
+  ESPO_ERANGE = -5      /* a size exceeds what the kernels index (see each call)     */
+} espo_status;
+
+typedef enum { ESPO_F32 = 0, ESPO_BF16 = 1 } espo_dtype;
+
+/*
+ * Parameters that stay frozen for a whole rollout batch (Section 4.2: the batch
+ * statistics are only updated at the batch boundary; Algorithm 1 "Require").
+ */
+typedef struct {
+  float mu_g;           /* EMA batch mean of the regret, Eq. normalized_gap           */
+  float var_g;          /* EMA batch variance of the regret (sigma_g^2)               */
+  float delta;          /* numerical stabiliser under the square root, > 0            */
+  float clip_c;         /* clipping bound c >= 0 of the normalised regret             */
+  float alpha_s;        /* smoothing factor of Eq. smoothed_score, in [0,1]           */
+  float beta;           /* threshold multiplier of Eq. stop_rule, >= 0                */
+  float eps;            /* floor on the value in Eq. stop_rule                        */
+  int32_t stop_enabled; /* "warmup complete" gate of Algorithm 1; 0 = never stop      */
+  int32_t eos_id;       /* token id that ends a trajectory naturally; -1 = none       */
+} espo_params;
+
+/*
+ * espo_step -- one decode step of Algorithm 1 for B trajectories.
+ *
+ * For every row b with alive[b] != 0, in one pass over logits[b, 0:V]:
+ *   1. pi = softmax(x / temperature) (the distribution actually sampled);
+ *      row maximum m and S = sum_v exp((x_v - m)/temperature).
+ *   2. token a = argmax_v (x_v/temperature + G_v), G_v = -ln(-ln u_v)  (Gumbel-max
+ *      draw from pi).  u_v = (2 r_v + 1) / 2^24 with r_v the top 23 bits of word
+ *      (v & 3) of Philox4x32-10( counter = (v >> 2, step, b, 0x4553504F),
+ *      key = (seed & 0xffffffff, seed >> 32) ).  Equal scores: lowest v wins.
+ *      Scores of contenders are formed in double precision.
+ *   3. regret g = max_a log pi(a) - log pi(a_t) = (m - x_a)/temperature
+ *      (Eq. step_gap), evaluated in fp32 as (m - x_a) * (1.0f/temperature).
+ *   4. g~ = clip((g - mu_g) * (1.0f/sqrtf(var_g + delta)), -c, c)   (Eq. normalized_gap)
+ *   5. z[b] <- fmaf(alpha_s, z[b], (1.0f - alpha_s) * g~)            (Eq. smoothed_score;
+ *      the state before the first step is 0 and step 0 already updates it, as
+ *      Algorithm 1 does).
+ *   6. stop = stop_enabled && z[b] > beta * fmaxf(values[b], eps)   (Eq. stop_rule,
+ *      strict).  If stop: alive[b] = 0 and stop_step[b] = step (the trajectory
+ *      keeps the token of this step and has length step + 1; Eq. failure_reward).
+ *      If eos_id >= 0 and a == eos_id the row ends naturally instead: alive[b] = 0
+ *      and stop_step[b] is left alone.
+ *   Outputs: tokens[b] = a, regret[b] = g, logprob[b] = -g - ln S.
+ * Steps 3-6 are single correctly rounded fp32 operations in exactly the order
+ * written, so a host re-computation reproduces z, the mask and the stop step bit
+ * for bit.
+ * For rows with alive[b] == 0 the logits are not read; tokens[b] = -1,
+ * regret[b] = 0, logprob[b] = 0, and z, alive, stop_step are left untouched.
+ *
+ * Arguments
+ *   logits      device, [B, row_stride] elements of `dt` (row-major, row b starts
+ *               at element b*row_stride); only the first V of each row are read.
+ *               Base address and row pitch in bytes must be multiples of 16.
+ *               -inf entries are allowed (masked vocabulary); NaN and +inf are not
+ *               supported (results for that row are unspecified, no fault).
+ *   dt          ESPO_F32 or ESPO_BF16.
+ *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V < 2^31 - 8.
+ *   row_stride  elements between rows, >= V.
+ *   temperature > 0 and finite.
+ *   seed, step  key and counter word of the random stream; step >= 0.
+ *   values      device, [B] fp32 critic values V_phi(s_t) of this step.
+ *   params      host, read during the call.
+ *   z           device, [B] fp32 in/out.
+ *   alive       device, [B] uint8 in/out (1 = live).
+ *   stop_step   device, [B] int32 in/out (caller initialises to -1).
+ *   tokens      device, [B] int32 out.
+ *   regret      device, [B] fp32 out.
+ *   logprob     device, [B] fp32 out, may be NULL.
+ *   workspace   device, at least espo_step_workspace_bytes(B, V, dt) bytes,
+ *               256-byte aligned.  It must be zero-filled once before its first
+ *               use; every call leaves it zero-filled again, so it can be reused
+ *               by the next call on the same stream without clearing.  Calls that
+ *               may overlap in time need separate workspaces.
+ *   stream      hipStream_t as void*.
+ */
+int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,
+              float temperature, uint64_t seed, int32_t step,
+              const float* values, const espo_params* params,
+              float* z, uint8_t* alive, int32_t* stop_step,
+              int32_t* tokens, float* regret, float* logprob,
+              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace espo_step needs for this shape (0 on invalid arguments). */
+size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt);
+
+/*
+ * espo_advantages -- TD errors and GAE on truncated trajectories
+ * (Section 3: delta_t and Eq. gae; Section 4.4: Eq. failure_reward, no bootstrap
+ * beyond the absorbing state).
+ *
+ * For row b let L = min(max(lengths[b], 0), T).  With
+ *   r_t = rewards[b,t] for t < L-1,
+ *   r_{L-1} = stopped[b] ? r_fail : rewards[b,L-1]     (the failure reward replaces
+ *                                                       whatever was stored there),
+ *   V_L = 0                                             (no bootstrap past the end),
+ *   td[b,t]  = r_t + gamma * values[b,t+1] - values[b,t]            for t < L,
+ *   adv[b,t] = sum_{l=0}^{L-1-t} (gamma*lambda)^l td[b,t+l]          for t < L,
+ * and td[b,t] = adv[b,t] = 0 for L <= t < T.  rewards and values are never read at
+ * t >= L.
+ *
+ * Arguments
+ *   rewards, values  device, [B, T] fp32 row-major, 16-byte aligned base; T*4 need
+ *                    not be a multiple of 16.
+ *   lengths          device, [B] int32 (clamped to [0, T] on the device).
+ *   stopped          device, [B] uint8, non-zero = ended by the stop rule.
+ *   B, T             B >= 0, T >= 0 (either 0 is a no-op); T < 2^31.
+ *   r_fail, gamma, lambda   scalars; gamma, lambda finite.
+ *   td, adv          device, [B, T] fp32 out, 16-byte aligned base.
+ *   stream           hipStream_t as void*.
+ */
+int espo_advantages(const float* rewards, const float* values,
+                    const int32_t* lengths, const uint8_t* stopped,
+                    int64_t B, int64_t T, float r_fail, float gamma, float lambda,
+                    float* td, float* adv, void* stream);
+
+/* Static, human-readable text for a status code (never NULL). */
+const char* espo_strerror(int code);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int espo_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ESPO_H_ */

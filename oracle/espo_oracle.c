@@ -1,0 +1,322 @@
+/*
+ * espo_oracle.c -- plain CPU oracle for the ESPO per-step hot path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct statement of
+ * what the GPU kernels must compute.  It is used by the test-suite, by the smoke
+ * check and by the "cpu_baseline" leg of the benchmark, and by nothing else; the
+ * GPU library neither links nor imports it, and it shares no source, header, table
+ * or helper with the GPU code.
+ *
+ * What follows the paper, and where:
+ *   oracle_step        Algorithm 1 (body of the while loop), Eq. step_gap,
+ *                      Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule,
+ *                      Eq. failure_reward.  The paper only says "sample a_t from pi";
+ *                      the draw is realised as Gumbel-max over a Philox4x32-10 stream
+ *                      (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3",
+ *                      SC'11), which is the stream definition the GPU path shares.
+ *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
+ *                      Section 4.4 (failure reward at the stop step, no bootstrap).
+ *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
+ *
+ * Pins (tests marked "not gpu"): hand values of the regret on 3-token rows, closed
+ * forms of the smoothed state, stop rule never/always firing, softmax frequencies of
+ * the sampler on tiny vocabularies, moments of the Gumbel variates, GAE against the
+ * explicit double sum and against telescoping identities.
+ * Parity unpinned by the paper: the identity of the sampled token on a large
+ * vocabulary (the paper fixes no random stream); it is pinned by the distribution
+ * tests and the structural Philox tests only.
+ *
+ * Precision: scores, the softmax sum and the advantages are in double.  The scalar
+ * chain g -> g~ -> z -> test is in fp32, one rounding per operation in the order
+ * written below, because the stop decision is an integer decided by floating point
+ * and must be taken in the precision the kernel uses.  Build with -ffp-contract=off.
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+  float mu_g, var_g, delta, clip_c, alpha_s, beta, eps;
+  int32_t stop_enabled;
+  int32_t eos_id;
+} oracle_params;
+
+/* ------------------------------------------------------------------ Philox4x32-10 */
+/* Salmon et al. 2011: four 32-bit counter words, two key words, ten rounds.  One
+ * round multiplies words 0 and 2 by fixed odd constants, keeps the low halves and
+ * folds the high halves into the other two words together with the round key; the
+ * key advances by a Weyl sequence between rounds. */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+  uint32_t k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+    uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+    uint32_t n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    uint32_t n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+#define ORACLE_STREAM_TAG 0x4553504Fu
+
+/* The 32-bit word that belongs to vocabulary index v of row `row` at `step`. */
+uint32_t oracle_stream_word(uint64_t seed, int64_t row, int32_t step, int64_t v) {
+  uint32_t ctr[4] = {(uint32_t)(v >> 2), (uint32_t)step, (uint32_t)row, ORACLE_STREAM_TAG};
+  uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  oracle_philox4x32_10(ctr, key, out);
+  return out[v & 3];
+}
+
+/* u in (0,1): the top 23 bits r of the word give u = (2r+1)/2^24. */
+double oracle_uniform(uint32_t word) {
+  uint32_t r = word >> 9;
+  return (double)(2u * r + 1u) / 16777216.0;
+}
+
+/* Standard Gumbel variate G = -ln(-ln u). */
+double oracle_gumbel(uint32_t word) { return -log(-log(oracle_uniform(word))); }
+
+static inline float load_logit(const void* base, int dtype, int64_t idx) {
+  if (dtype == 0) return ((const float*)base)[idx];
+  uint32_t bits = (uint32_t)((const uint16_t*)base)[idx] << 16; /* bf16 -> fp32, exact */
+  float f;
+  memcpy(&f, &bits, 4);
+  return f;
+}
+
+int oracle_num_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void oracle_set_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+/*
+ * One decode step for B rows.  Arrays are host memory with the same meaning and
+ * layout as the GPU entry point's.  Extra, optional (NULL-able) arguments:
+ *   forced_tokens[b] >= 0  use that token instead of the draw (near-tie protocol);
+ *   best_score / second_score / second_token  the two largest perturbed scores of
+ *                          the draw and the index of the runner-up;
+ *   sum_exp                S = sum_v exp(y_v - y_max);
+ *   row_max                the row maximum m.
+ * Returns 0, or -1 on invalid arguments.
+ */
+int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row_stride,
+                float temperature, uint64_t seed, int32_t step,
+                const float* values, const oracle_params* p,
+                float* z, uint8_t* alive, int32_t* stop_step,
+                int32_t* tokens, float* regret, float* logprob,
+                const int32_t* forced_tokens,
+                double* best_score, double* second_score, int32_t* second_token,
+                double* sum_exp, float* row_max) {
+  if (!logits || !values || !p || !z || !alive || !stop_step || !tokens || !regret) return -1;
+  if (B < 0 || V < 1 || row_stride < V || !(temperature > 0.0f) || !isfinite(temperature)) return -1;
+  if (dtype != 0 && dtype != 1) return -1;
+
+  const float inv_tau = 1.0f / temperature;              /* one fp32 division        */
+  const float rsd = 1.0f / sqrtf(p->var_g + p->delta);   /* 1/sqrt(sigma_g^2+delta)  */
+  const float oma = 1.0f - p->alpha_s;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t b = 0; b < B; ++b) {
+    if (!alive[b]) {                                     /* done rows are not decoded */
+      tokens[b] = -1;
+      regret[b] = 0.0f;
+      if (logprob) logprob[b] = 0.0f;
+      if (best_score) best_score[b] = 0.0;
+      if (second_score) second_score[b] = 0.0;
+      if (second_token) second_token[b] = -1;
+      if (sum_exp) sum_exp[b] = 0.0;
+      if (row_max) row_max[b] = 0.0f;
+      continue;
+    }
+    const int64_t base = b * row_stride;
+
+    /* row maximum (exact) */
+    float m = -INFINITY;
+    for (int64_t v = 0; v < V; ++v) {
+      float x = load_logit(logits, dtype, base + v);
+      if (x > m) m = x;
+    }
+    const double y_max = (double)m * (double)inv_tau;
+
+    /* softmax normaliser and Gumbel-max draw, in index order */
+    double S = 0.0;
+    double s1 = -INFINITY, s2 = -INFINITY;
+    int64_t a1 = -1, a2 = -1;
+    for (int64_t v = 0; v < V; ++v) {
+      float x = load_logit(logits, dtype, base + v);
+      double y = (double)x * (double)inv_tau;            /* tempered logit           */
+      S += exp(y - y_max);
+      double s = y + oracle_gumbel(oracle_stream_word(seed, b, step, v));
+      if (s > s1) {                                      /* strict: lowest index wins */
+        s2 = s1; a2 = a1;
+        s1 = s; a1 = v;
+      } else if (s > s2) {
+        s2 = s; a2 = v;
+      }
+    }
+    int64_t a = a1;
+    if (forced_tokens && forced_tokens[b] >= 0) a = forced_tokens[b];
+    if (a < 0) a = 0;                                    /* row of -inf only: unspecified */
+    const float x_a = load_logit(logits, dtype, base + a);
+
+    /* scalar chain, fp32, one rounding per operation */
+    const float d = m - x_a;
+    const float g = d * inv_tau;                         /* Eq. step_gap              */
+    const float n = (g - p->mu_g) * rsd;
+    const float gt = fminf(fmaxf(n, -p->clip_c), p->clip_c);   /* Eq. normalized_gap  */
+    const float t = oma * gt;
+    const float zn = fmaf(p->alpha_s, z[b], t);          /* Eq. smoothed_score        */
+    const float thr = p->beta * fmaxf(values[b], p->eps);
+    const int stop = p->stop_enabled && (zn > thr);      /* Eq. stop_rule, strict     */
+
+    tokens[b] = (int32_t)a;
+    regret[b] = g;
+    z[b] = zn;
+    if (logprob) logprob[b] = (float)(-(double)g - log(S));
+    if (p->eos_id >= 0 && a == (int64_t)p->eos_id) {
+      alive[b] = 0;                                      /* natural end, not a failure */
+    } else if (stop) {
+      alive[b] = 0;                                      /* absorbing failure          */
+      stop_step[b] = step;
+    }
+    if (best_score) best_score[b] = s1;
+    if (second_score) second_score[b] = s2;
+    if (second_token) second_token[b] = (int32_t)a2;
+    if (sum_exp) sum_exp[b] = S;
+    if (row_max) row_max[b] = m;
+  }
+  return 0;
+}
+
+/*
+ * The scalar chain alone: given the regret g of a live row, advance (z, alive,
+ * stop_step) exactly as oracle_step does.  Lets a test replay the state of every
+ * row of a large batch from a recorded regret/token stream.
+ */
+int oracle_state_update(int64_t B, const float* g, const int32_t* tokens, const float* values,
+                        const oracle_params* p, int32_t step,
+                        float* z, uint8_t* alive, int32_t* stop_step) {
+  if (!g || !tokens || !values || !p || !z || !alive || !stop_step || B < 0) return -1;
+  const float rsd = 1.0f / sqrtf(p->var_g + p->delta);
+  const float oma = 1.0f - p->alpha_s;
+  for (int64_t b = 0; b < B; ++b) {
+    if (!alive[b]) continue;
+    const float n = (g[b] - p->mu_g) * rsd;
+    const float gt = fminf(fmaxf(n, -p->clip_c), p->clip_c);
+    const float t = oma * gt;
+    const float zn = fmaf(p->alpha_s, z[b], t);
+    const float thr = p->beta * fmaxf(values[b], p->eps);
+    const int stop = p->stop_enabled && (zn > thr);
+    z[b] = zn;
+    if (p->eos_id >= 0 && tokens[b] == p->eos_id) {
+      alive[b] = 0;
+    } else if (stop) {
+      alive[b] = 0;
+      stop_step[b] = step;
+    }
+  }
+  return 0;
+}
+
+/*
+ * TD errors and GAE on truncated trajectories, by the backward recursion
+ * A_t = delta_t + gamma*lambda*A_{t+1} that Eq. gae unrolls to.  Outputs in double.
+ * `scale` (optional) receives sum_l (gamma*lambda)^l |delta_{t+l}|, the magnitude
+ * against which a reassociated fp32 sum is to be judged.
+ */
+int oracle_advantages(const float* rewards, const float* values,
+                      const int32_t* lengths, const uint8_t* stopped,
+                      int64_t B, int64_t T, float r_fail, float gamma, float lambda,
+                      double* td, double* adv, double* scale) {
+  if (B < 0 || T < 0) return -1;
+  if (B == 0 || T == 0) return 0;
+  if (!rewards || !values || !lengths || !stopped || !td || !adv) return -1;
+  const double gam = (double)gamma;
+  const double c = (double)gamma * (double)lambda;
+
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    const float* r = rewards + b * T;
+    const float* val = values + b * T;
+    double* d = td + b * T;
+    double* A = adv + b * T;
+    double* sc = scale ? scale + b * T : NULL;
+    for (int64_t t = L; t < T; ++t) {
+      d[t] = 0.0;
+      A[t] = 0.0;
+      if (sc) sc[t] = 0.0;
+    }
+    double a_next = 0.0;      /* advantage beyond the last token is zero            */
+    double s_next = 0.0;
+    for (int64_t t = L - 1; t >= 0; --t) {
+      double r_t = (double)r[t];
+      if (t == L - 1 && stopped[b]) r_t = (double)r_fail;       /* Eq. failure_reward */
+      const double v_next = (t + 1 < L) ? (double)val[t + 1] : 0.0;  /* no bootstrap  */
+      const double delta = r_t + gam * v_next - (double)val[t];
+      a_next = delta + c * a_next;
+      s_next = fabs(delta) + fabs(c) * s_next;
+      d[t] = delta;
+      A[t] = a_next;
+      if (sc) sc[t] = s_next;
+    }
+  }
+  return 0;
+}
+
+/*
+ * Eq. gae as printed: A_t = sum_{l=0}^{L-t-1} (gamma*lambda)^l delta_{t+l}, every
+ * power and every delta formed from scratch.  O(L^2); for small T only.
+ */
+int oracle_gae_bruteforce(const float* rewards, const float* values,
+                          const int32_t* lengths, const uint8_t* stopped,
+                          int64_t B, int64_t T, float r_fail, float gamma, float lambda,
+                          double* adv) {
+  if (B < 0 || T < 0) return -1;
+  if (B == 0 || T == 0) return 0;
+  if (!rewards || !values || !lengths || !stopped || !adv) return -1;
+  const double c = (double)gamma * (double)lambda;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    for (int64_t t = 0; t < T; ++t) {
+      double acc = 0.0;
+      for (int64_t l = 0; t + l < L; ++l) {
+        const int64_t u = t + l;
+        double r_u = (double)rewards[b * T + u];
+        if (u == L - 1 && stopped[b]) r_u = (double)r_fail;
+        const double v_u = (double)values[b * T + u];
+        const double v_un = (u + 1 < L) ? (double)values[b * T + u + 1] : 0.0;
+        const double delta = r_u + (double)gamma * v_un - v_u;
+        acc += pow(c, (double)l) * delta;
+      }
+      adv[b * T + t] = (t < L) ? acc : 0.0;
+    }
+  }
+  return 0;
+}

@@ -1,0 +1,15 @@
+"""ESPO per-generation-step hot path for AMD MI355X (gfx950): Python binding of the C ABI.
+
+`espo_step` and `espo_advantages` are thin argument-marshalling wrappers around the
+shared library built from `csrc/`; nothing is computed in Python and there is no CPU
+fallback.  Importing the package does not load the library; the first call does.
+"""
+__all__ = ["espo_step", "espo_advantages", "espo_step_workspace_bytes", "EspoParams", "EspoError",
+           "load_library", "library_path"]
+
+
+def __getattr__(name):
+    if name in __all__:
+        from . import binding
+        return getattr(binding, name)
+    raise AttributeError(name)
