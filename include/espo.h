@@ -68,11 +68,21 @@ typedef struct {
  * For every row b with alive[b] != 0, in one pass over logits[b, 0:V]:
  *   1. pi = softmax(x / temperature) (the distribution actually sampled);
  *      row maximum m and S = sum_v exp((x_v - m)/temperature).
- *   2. token a = argmax_v (x_v/temperature + G_v), G_v = -ln(-ln u_v)  (Gumbel-max
- *      draw from pi).  u_v = (2 r_v + 1) / 2^24 with r_v the top 23 bits of word
- *      (v & 3) of Philox4x32-10( counter = (v >> 2, step, b, 0x4553504F),
- *      key = (seed & 0xffffffff, seed >> 32) ).  Equal scores: lowest v wins.
- *      Scores of contenders are formed in double precision.
+ *   2. token a = argmax_v (x_v/temperature + G_v) with iid standard Gumbel G_v
+ *      (Gumbel-max draw from pi; the paper only asks for a_t ~ pi).  Equal scores:
+ *      lowest v wins.  Scores of contenders are formed in double precision.
+ *      The variates come from Philox4x32-10 keyed by the seed and are generated
+ *      top-down in blocks of 512 consecutive vocabulary indices, which has the same
+ *      joint law as drawing each G_v on its own but lets a block be ruled out from
+ *      one random number.  With u(w) = (2 (w >> 9) + 1) / 2^24 and
+ *      key = (seed & 0xffffffff, seed >> 32):
+ *        block q = v / 512 holds n_q = min(512, V - 512 q) indices;
+ *        (w0, w1) = words 0, 1 of Philox(counter = (q, step, b, 0x4553504F), key);
+ *        M_q   = ln n_q - ln(-ln u(w0))       the largest variate of the block,
+ *        pos_q = (w1 * n_q) >> 32             the index (within the block) that gets it;
+ *        w_v   = word (v & 3) of Philox(counter = (v >> 2, step, b, 0x6573706F), key);
+ *        G_v   = M_q                           if v = 512 q + pos_q,
+ *              = -ln(exp(-M_q) - ln u(w_v))    otherwise.
  *   3. regret g = max_a log pi(a) - log pi(a_t) = (m - x_a)/temperature
  *      (Eq. step_gap), evaluated in fp32 as (m - x_a) * (1.0f/temperature).
  *   4. g~ = clip((g - mu_g) * (1.0f/sqrtf(var_g + delta)), -c, c)   (Eq. normalized_gap)

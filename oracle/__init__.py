@@ -9,6 +9,8 @@ from .espo_oracle import (  # noqa: F401
     gae_bruteforce,
     advantages,
     gumbel,
+    gumbel_at,
+    block_draw,
     num_threads,
     philox4x32_10,
     set_threads,

@@ -11,9 +11,10 @@
  *   oracle_step        Algorithm 1 (body of the while loop), Eq. step_gap,
  *                      Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule,
  *                      Eq. failure_reward.  The paper only says "sample a_t from pi";
- *                      the draw is realised as Gumbel-max over a Philox4x32-10 stream
- *                      (Salmon et al., "Parallel random numbers: as easy as 1, 2, 3",
- *                      SC'11), which is the stream definition the GPU path shares.
+ *                      the draw is realised as Gumbel-max, a = argmax_v (y_v + G_v) with
+ *                      iid standard Gumbel G_v, over a Philox4x32-10 stream (Salmon et
+ *                      al., "Parallel random numbers: as easy as 1, 2, 3", SC'11); the
+ *                      stream definition below is the one the GPU path implements too.
  *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
  *                      Section 4.4 (failure reward at the stop step, no bootstrap).
  *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
@@ -67,16 +68,24 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
   out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
-#define ORACLE_STREAM_TAG 0x4553504Fu
-
-/* The 32-bit word that belongs to vocabulary index v of row `row` at `step`. */
-uint32_t oracle_stream_word(uint64_t seed, int64_t row, int32_t step, int64_t v) {
-  uint32_t ctr[4] = {(uint32_t)(v >> 2), (uint32_t)step, (uint32_t)row, ORACLE_STREAM_TAG};
-  uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
-  uint32_t out[4];
-  oracle_philox4x32_10(ctr, key, out);
-  return out[v & 3];
-}
+/*
+ * Random stream of the draw.  The Gumbel variates G_v (v = 0..V-1) of one row and step
+ * are iid standard Gumbel, generated top-down in blocks of 512 consecutive vocabulary
+ * indices (the joint law of n iid Gumbels factorises into: their maximum M, which is
+ * Gumbel shifted by ln n; the position of the maximum, uniform; and the others, iid
+ * Gumbel truncated to (-inf, M) -- Maddison, Tarlow & Minka, "A* sampling", 2014):
+ *   block q = v / 512 holds indices [512 q, min(512 q + 512, V)), n_q of them;
+ *   (w0, w1) = words 0, 1 of Philox(counter = (q, step, row, TAG_BLOCK), key = seed);
+ *   M_q   = ln n_q - ln(-ln u(w0))          maximum of the block's variates
+ *   pos_q = (w1 * n_q) >> 32                 which index of the block attains it
+ *   w_v   = word (v & 3) of Philox(counter = (v >> 2, step, row, TAG_ELEM), key = seed)
+ *   G_v   = M_q                               if v = 512 q + pos_q
+ *         = -ln(exp(-M_q) - ln u(w_v))        otherwise (inverse cdf of the truncation)
+ * with u(w) = (2 (w >> 9) + 1) / 2^24 in (0, 1).
+ */
+#define ORACLE_TAG_BLOCK 0x4553504Fu
+#define ORACLE_TAG_ELEM 0x6573706Fu
+#define ORACLE_BLOCK 512
 
 /* u in (0,1): the top 23 bits r of the word give u = (2r+1)/2^24. */
 double oracle_uniform(uint32_t word) {
@@ -86,6 +95,45 @@ double oracle_uniform(uint32_t word) {
 
 /* Standard Gumbel variate G = -ln(-ln u). */
 double oracle_gumbel(uint32_t word) { return -log(-log(oracle_uniform(word))); }
+
+/* The 32-bit word that belongs to vocabulary index v of row `row` at `step`. */
+uint32_t oracle_stream_word(uint64_t seed, int64_t row, int32_t step, int64_t v) {
+  uint32_t ctr[4] = {(uint32_t)(v >> 2), (uint32_t)step, (uint32_t)row, ORACLE_TAG_ELEM};
+  uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  oracle_philox4x32_10(ctr, key, out);
+  return out[v & 3];
+}
+
+/* Maximum M_q of block q (which holds n indices) and the offset pos_q that attains it. */
+void oracle_block_draw(uint64_t seed, int64_t row, int32_t step, int64_t q, int64_t n,
+                       double* M, int64_t* pos) {
+  uint32_t ctr[4] = {(uint32_t)q, (uint32_t)step, (uint32_t)row, ORACLE_TAG_BLOCK};
+  uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+  uint32_t out[4];
+  oracle_philox4x32_10(ctr, key, out);
+  *M = log((double)n) + oracle_gumbel(out[0]);
+  *pos = (int64_t)(((uint64_t)out[1] * (uint64_t)n) >> 32);
+}
+
+/* G_v for an index v of the block that starts at `first` and drew (M, pos). */
+static double gumbel_in_block(uint64_t seed, int64_t row, int32_t step, int64_t v,
+                              int64_t first, double M, int64_t pos) {
+  if (v == first + pos) return M;
+  const double u = oracle_uniform(oracle_stream_word(seed, row, step, v));
+  return -log(exp(-M) - log(u));
+}
+
+/* The Gumbel variate of vocabulary index v in a row of V entries. */
+double oracle_gumbel_at(uint64_t seed, int64_t row, int32_t step, int64_t v, int64_t V) {
+  const int64_t q = v / ORACLE_BLOCK;
+  const int64_t first = q * ORACLE_BLOCK;
+  const int64_t n = (V - first < ORACLE_BLOCK) ? V - first : ORACLE_BLOCK;
+  double M;
+  int64_t pos;
+  oracle_block_draw(seed, row, step, q, n, &M, &pos);
+  return gumbel_in_block(seed, row, step, v, first, M, pos);
+}
 
 static inline float load_logit(const void* base, int dtype, int64_t idx) {
   if (dtype == 0) return ((const float*)base)[idx];
@@ -164,11 +212,18 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
     double S = 0.0;
     double s1 = -INFINITY, s2 = -INFINITY;
     int64_t a1 = -1, a2 = -1;
+    double M_q = 0.0;
+    int64_t pos_q = 0, first_q = 0;
     for (int64_t v = 0; v < V; ++v) {
+      if (v % ORACLE_BLOCK == 0) {                       /* a new block: draw its maximum */
+        first_q = v;
+        const int64_t n_q = (V - v < ORACLE_BLOCK) ? V - v : ORACLE_BLOCK;
+        oracle_block_draw(seed, b, step, v / ORACLE_BLOCK, n_q, &M_q, &pos_q);
+      }
       float x = load_logit(logits, dtype, base + v);
       double y = (double)x * (double)inv_tau;            /* tempered logit           */
       S += exp(y - y_max);
-      double s = y + oracle_gumbel(oracle_stream_word(seed, b, step, v));
+      double s = y + gumbel_in_block(seed, b, step, v, first_q, M_q, pos_q);
       if (s > s1) {                                      /* strict: lowest index wins */
         s2 = s1; a2 = a1;
         s1 = s; a1 = v;

@@ -78,6 +78,10 @@ def _load():
         lib.oracle_uniform.argtypes = [C.c_uint32]
         lib.oracle_gumbel.restype = C.c_double
         lib.oracle_gumbel.argtypes = [C.c_uint32]
+        lib.oracle_gumbel_at.restype = C.c_double
+        lib.oracle_gumbel_at.argtypes = [u64, i64, i32, i64, i64]
+        lib.oracle_block_draw.restype = None
+        lib.oracle_block_draw.argtypes = [u64, i64, i32, i64, i64, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
         lib.oracle_num_threads.restype = C.c_int
         lib.oracle_set_threads.argtypes = [C.c_int]
         _lib = lib
@@ -123,6 +127,19 @@ def uniform(word: int) -> float:
 
 def gumbel(word: int) -> float:
     return float(_load().oracle_gumbel(word))
+
+
+def gumbel_at(seed: int, row: int, step_: int, v: int, V: int) -> float:
+    """Gumbel variate G_v of vocabulary index v in a row of V entries."""
+    return float(_load().oracle_gumbel_at(seed, row, step_, v, V))
+
+
+def block_draw(seed: int, row: int, step_: int, q: int, n: int):
+    """(M_q, pos_q): maximum of block q's variates and the offset that attains it."""
+    M = C.c_double()
+    pos = C.c_int64()
+    _load().oracle_block_draw(seed, row, step_, q, n, C.byref(M), C.byref(pos))
+    return float(M.value), int(pos.value)
 
 
 def step(logits: np.ndarray, temperature: float, seed: int, step_: int, values: np.ndarray,

@@ -214,8 +214,8 @@ def test_ties_break_to_lowest_index_and_runner_up(oracle):
     assert set(out["second_token"].tolist()) <= {3, 7}
     # recompute the two scores from the stream definition: y + G
     for b in range(64):
-        s3 = 5.0 + oracle.gumbel(oracle.stream_word(99, b, 0, 3))
-        s7 = 5.0 + oracle.gumbel(oracle.stream_word(99, b, 0, 7))
+        s3 = 5.0 + oracle.gumbel_at(99, b, 0, 3, 12)
+        s7 = 5.0 + oracle.gumbel_at(99, b, 0, 7, 12)
         assert out["tokens"][b] == (3 if s3 >= s7 else 7)
         assert out["best_score"][b] == max(s3, s7) and out["second_score"][b] == min(s3, s7)
 
@@ -278,11 +278,11 @@ def test_philox_avalanche_and_bijection(oracle):
 
 
 def test_stream_word_layout(oracle):
-    """word(v) is lane v & 3 of the block whose counter is (v >> 2, step, row, tag)."""
+    """word(v) is lane v & 3 of the Philox block whose counter is (v >> 2, step, row, tag)."""
     seed = (0xABCDEF01 << 32) | 0x12345678
     for v in (0, 1, 2, 3, 4, 5, 152063, 2 ** 31 - 9):
         for row, step in ((0, 0), (5, 17), (511, 1023)):
-            blk = _philox_py([v >> 2, step, row, 0x4553504F], [0x12345678, 0xABCDEF01])
+            blk = _philox_py([v >> 2, step, row, 0x6573706F], [0x12345678, 0xABCDEF01])
             assert oracle.stream_word(seed, row, step, v) == blk[v & 3]
 
 
@@ -314,6 +314,89 @@ def test_stream_moments(oracle):
     assert abs(G.var() - math.pi ** 2 / 6) < 0.03
     lag = np.corrcoef(u[:-1], u[1:])[0, 1]
     assert abs(lag) < 5 / math.sqrt(n)
+
+
+def test_block_draw_layout_and_law(oracle):
+    """M_q = ln n - ln(-ln u(w0)), pos_q = (w1 n) >> 32 from the block's own Philox call."""
+    seed = (0x0BADF00D << 32) | 0x00C0FFEE
+    for q, n, row, step in ((0, 512, 0, 0), (296, 512, 511, 1023), (3, 76, 7, 5), (1, 1, 2, 2)):
+        blk = _philox_py([q, step, row, 0x4553504F], [0x00C0FFEE, 0x0BADF00D])
+        u = (2 * (blk[0] >> 9) + 1) / 2.0 ** 24
+        M, pos = oracle.block_draw(seed, row, step, q, n)
+        assert abs(M - (math.log(n) - math.log(-math.log(u)))) < 1e-12
+        assert pos == (blk[1] * n) >> 32 and 0 <= pos < n
+    # M - ln n is standard Gumbel, pos is uniform, and the two are independent
+    n = 512
+    draws = [oracle.block_draw(77, r, s, q, n) for r in range(20) for s in range(20) for q in range(50)]
+    M = np.array([d[0] for d in draws]) - math.log(n)
+    pos = np.array([d[1] for d in draws])
+    assert stats.kstest(M, lambda g: np.exp(-np.exp(-g))).pvalue > 1e-4
+    assert stats.chisquare(np.bincount(pos // 32, minlength=16)).pvalue > 1e-4
+    assert abs(np.corrcoef(M, pos)[0, 1]) < 5 / math.sqrt(len(M))
+
+
+def test_blockwise_variates_are_iid_standard_gumbel(oracle):
+    """The top-down construction (block maximum, its position, truncated rest) must have
+    the joint law of iid standard Gumbels: checked on the marginal cdf, on the block
+    maximum, on the second largest value and on independence across neighbours."""
+    V = 1100                                                      # blocks of 512, 512 and 76
+    rows = 160
+    G = np.array([[oracle.gumbel_at(5, r, 3, v, V) for v in range(V)] for r in range(rows)])
+    cdf = lambda g: np.exp(-np.exp(-g))
+    assert stats.kstest(G.ravel(), cdf).pvalue > 1e-4             # marginal law
+    assert abs(G.mean() - 0.5772156649015329) < 5 * math.sqrt((math.pi ** 2 / 6) / G.size)
+    assert abs(G.var() - math.pi ** 2 / 6) < 0.03
+    for lo, hi in ((0, 512), (512, 1024), (1024, 1100)):
+        blk = G[:, lo:hi]
+        n = hi - lo
+        for r in range(rows):
+            M, pos = oracle.block_draw(5, r, 3, lo // 512, n)
+            assert blk[r].argmax() == pos and blk[r, pos] == M    # the drawn maximum is the maximum
+            assert (np.delete(blk[r], pos) < M).all()
+        # maximum of n iid Gumbels ~ Gumbel(ln n); second largest has cdf F^n + n F^(n-1) (1 - F)
+        assert stats.kstest(blk.max(1) - math.log(n), cdf).pvalue > 1e-4
+        second = np.sort(blk, 1)[:, -2] if n > 1 else None
+        F2 = lambda g: cdf(g) ** n + n * cdf(g) ** (n - 1) * (1 - cdf(g))
+        assert stats.kstest(second, F2).pvalue > 1e-4
+    # the argmax over the whole row is uniform over indices (no block is favoured)
+    big = np.array([[oracle.gumbel_at(6, r, 0, v, V) for v in range(V)] for r in range(600)])
+    which = np.digitize(big.argmax(1), [512, 1024])
+    exp = 600 * np.array([512, 512, 76]) / V
+    assert stats.chisquare(np.bincount(which, minlength=3), exp).pvalue > 1e-4
+    assert abs(np.corrcoef(G[:, :-1].ravel(), G[:, 1:].ravel())[0, 1]) < 5 / math.sqrt(G.size)
+
+
+def test_sampler_frequencies_across_blocks(oracle):
+    """Softmax frequencies on a vocabulary that spans three blocks (one ragged): heavy tokens
+    in each block plus a flat background, so block maxima, positions and truncated variates
+    all take part in the argmax."""
+    V, tau = 1100, 0.9
+    x = np.full(V, -2.0, np.float32)
+    heavy = {5: 3.0, 300: 2.0, 511: 2.5, 512: 1.5, 900: 3.5, 1023: 1.0, 1024: 2.0, 1099: 3.0}
+    for k, val in heavy.items():
+        x[k] = val
+    B, steps = 1024, 40
+    logits = np.tile(x, (B, 1))
+    p = _params(oracle, stop_enabled=0)
+    vals = np.zeros(B, np.float32)
+    keys = sorted(heavy)
+    counts = np.zeros(len(keys) + 3, np.int64)
+    for t in range(steps):
+        z, alive, ss = _state(B)
+        tok = oracle.step(logits, tau, 4321, t, vals, p, z, alive, ss)["tokens"]
+        for i, k in enumerate(keys):
+            counts[i] += (tok == k).sum()
+        bg = ~np.isin(tok, keys)
+        counts[len(keys):] += np.bincount(np.digitize(tok[bg], [512, 1024]), minlength=3)
+    probs = special.softmax(x.astype(np.float64) * np.float64(np.float32(1.0) / np.float32(tau)))
+    bgmask = np.ones(V, bool)
+    bgmask[keys] = False
+    blk = np.digitize(np.arange(V), [512, 1024])
+    exp = np.array([probs[k] for k in keys] + [probs[bgmask & (blk == j)].sum() for j in range(3)])
+    n = B * steps
+    assert counts.sum() == n and abs(exp.sum() - 1) < 1e-12
+    chi2 = ((counts - n * exp) ** 2 / (n * exp)).sum()
+    assert chi2 < stats.chi2.ppf(1 - 1e-4, df=len(exp) - 1), (chi2, counts / n, exp)
 
 
 # ------------------------------------------------------------------ normalise, smooth (Eq. normalized_gap, smoothed_score)
