@@ -298,8 +298,10 @@ int oracle_state_update(int64_t B, const float* g, const int32_t* tokens, const 
 /*
  * TD errors and GAE on truncated trajectories, by the backward recursion
  * A_t = delta_t + gamma*lambda*A_{t+1} that Eq. gae unrolls to.  Outputs in double.
- * `scale` (optional) receives sum_l (gamma*lambda)^l |delta_{t+l}|, the magnitude
- * against which a reassociated fp32 sum is to be judged.
+ * `scale` (optional) receives sum_l |gamma*lambda|^l (|r| + |gamma V'| + |V|)_{t+l}, the
+ * magnitude of the terms that enter the sum: an fp32 evaluation rounds each delta to a
+ * relative 2^-24 of its largest term (not of delta itself, which may cancel) and each
+ * partial sum likewise, so errors are judged against this magnitude.
  */
 int oracle_advantages(const float* rewards, const float* values,
                       const int32_t* lengths, const uint8_t* stopped,
@@ -334,7 +336,7 @@ int oracle_advantages(const float* rewards, const float* values,
       const double v_next = (t + 1 < L) ? (double)val[t + 1] : 0.0;  /* no bootstrap  */
       const double delta = r_t + gam * v_next - (double)val[t];
       a_next = delta + c * a_next;
-      s_next = fabs(delta) + fabs(c) * s_next;
+      s_next = (fabs(r_t) + fabs(gam * v_next) + fabs((double)val[t])) + fabs(c) * s_next;
       d[t] = delta;
       A[t] = a_next;
       if (sc) sc[t] = s_next;

@@ -1,0 +1,145 @@
+"""ctypes binding of libespo.so: same names as the C ABI, argument marshalling only.
+
+Tensors are torch tensors on the GPU (used for their device pointers and the current
+HIP stream); every step of the path runs in the library's kernels.  There is no CPU
+fallback: if the shared library is missing the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libespo.so")
+_lib = None
+
+ESPO_F32, ESPO_BF16 = 0, 1
+
+
+class EspoError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"espo error {code}: {text}")
+        self.code = code
+
+
+class _Params(C.Structure):
+    _fields_ = [("mu_g", C.c_float), ("var_g", C.c_float), ("delta", C.c_float),
+                ("clip_c", C.c_float), ("alpha_s", C.c_float), ("beta", C.c_float),
+                ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32)]
+
+
+@dataclass
+class EspoParams:
+    """Mirror of `espo_params` (include/espo.h)."""
+    mu_g: float = 0.0
+    var_g: float = 1.0
+    delta: float = 1e-8
+    clip_c: float = 10.0
+    alpha_s: float = 0.9
+    beta: float = 7.0
+    eps: float = 0.2
+    stop_enabled: int = 1
+    eos_id: int = -1
+
+    def _c(self) -> _Params:
+        return _Params(self.mu_g, self.var_g, self.delta, self.clip_c, self.alpha_s, self.beta,
+                       self.eps, int(self.stop_enabled), int(self.eos_id))
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libespo.so (built in-tree by `build.py`); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2605_29860_amd.build` "
+                "(there is no fallback path)")
+        lib = C.CDLL(_LIB_PATH)
+        vp, i64, i32, u64, f32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float, C.c_size_t
+        lib.espo_step.restype = C.c_int
+        lib.espo_step.argtypes = [vp, C.c_int, i64, i64, i64, f32, u64, i32, vp, C.POINTER(_Params),
+                                  vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.espo_step_workspace_bytes.restype = sz
+        lib.espo_step_workspace_bytes.argtypes = [i64, i64, C.c_int]
+        lib.espo_advantages.restype = C.c_int
+        lib.espo_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
+        lib.espo_strerror.restype = C.c_char_p
+        lib.espo_strerror.argtypes = [C.c_int]
+        lib.espo_version.restype = C.c_int
+        _lib = lib
+    return _lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise EspoError(rc, load_library().espo_strerror(rc).decode())
+
+
+def _dev(t: torch.Tensor, dtype, name: str):
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name}: need a contiguous GPU tensor of {dtype}")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+def espo_step_workspace_bytes(B: int, V: int, dtype: torch.dtype) -> int:
+    dt = ESPO_BF16 if dtype == torch.bfloat16 else ESPO_F32
+    return int(load_library().espo_step_workspace_bytes(B, V, dt))
+
+
+def espo_step(logits: torch.Tensor, temperature: float, seed: int, step: int, values: torch.Tensor,
+              params: EspoParams, z: torch.Tensor, alive: torch.Tensor, stop_step: torch.Tensor,
+              tokens: torch.Tensor, regret: torch.Tensor, logprob: torch.Tensor | None = None,
+              V: int | None = None, workspace: torch.Tensor | None = None, stream=None) -> None:
+    """One decode step; see `espo_step` in include/espo.h.  `logits` is [B, row_stride]."""
+    lib = load_library()
+    if logits.dtype == torch.bfloat16:
+        dt = ESPO_BF16
+    elif logits.dtype == torch.float32:
+        dt = ESPO_F32
+    else:
+        raise TypeError("logits must be bfloat16 or float32")
+    if logits.dim() != 2 or logits.stride(1) != 1 or not logits.is_cuda:
+        raise TypeError("logits: need a 2-D GPU tensor with unit stride along the vocabulary")
+    B, width = logits.shape
+    row_stride = logits.stride(0) if B > 1 else width
+    V = width if V is None else int(V)
+    ws_ptr, ws_bytes = None, 0
+    if workspace is not None:
+        ws_ptr, ws_bytes = C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+    p = params._c()
+    rc = lib.espo_step(C.c_void_p(logits.data_ptr()), dt, B, V, row_stride, float(temperature), int(seed),
+                       int(step), _dev(values, torch.float32, "values"), C.byref(p),
+                       _dev(z, torch.float32, "z"), _dev(alive, torch.uint8, "alive"),
+                       _dev(stop_step, torch.int32, "stop_step"), _dev(tokens, torch.int32, "tokens"),
+                       _dev(regret, torch.float32, "regret"), _dev(logprob, torch.float32, "logprob"),
+                       ws_ptr, ws_bytes, _stream(stream))
+    _check(rc)
+
+
+def espo_advantages(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.Tensor,
+                    stopped: torch.Tensor, r_fail: float, gamma: float, lam: float,
+                    td: torch.Tensor, adv: torch.Tensor, stream=None) -> None:
+    """TD errors and GAE on truncated trajectories; see `espo_advantages` in include/espo.h."""
+    lib = load_library()
+    if rewards.dim() != 2:
+        raise TypeError("rewards: need [B, T]")
+    B, T = rewards.shape
+    rc = lib.espo_advantages(_dev(rewards, torch.float32, "rewards"), _dev(values, torch.float32, "values"),
+                             _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
+                             B, T, float(r_fail), float(gamma), float(lam),
+                             _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"), _stream(stream))
+    _check(rc)

@@ -1,0 +1,73 @@
+// C ABI of the library: argument validation and dispatch.  Every entry point is declared
+// and documented in include/espo.h.
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "../../include/espo.h"
+#include "espo_host.h"
+
+namespace {
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+int espo_version(void) { return 100; }
+
+const char* espo_strerror(int code) {
+  switch (code) {
+    case ESPO_OK: return "success";
+    case ESPO_EINVAL: return "invalid argument (null pointer, negative size, or parameter out of range)";
+    case ESPO_EALIGN: return "logits/rewards/values base address or row pitch is not 16-byte aligned";
+    case ESPO_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case ESPO_EHIP: return "the HIP runtime rejected the kernel launch";
+    case ESPO_ERANGE: return "size exceeds what the kernels index";
+    default: return "unknown espo status";
+  }
+}
+
+size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt) {
+  (void)B; (void)V; (void)dt;
+  return 0;  // a row is handled by a single workgroup: no inter-workgroup scratch
+}
+
+int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,
+              float temperature, uint64_t seed, int32_t step, const float* values,
+              const espo_params* params, float* z, uint8_t* alive, int32_t* stop_step,
+              int32_t* tokens, float* regret, float* logprob, void* workspace, size_t workspace_bytes,
+              void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (dt != ESPO_F32 && dt != ESPO_BF16) return ESPO_EINVAL;
+  if (B < 0 || V < 1 || row_stride < V || step < 0) return ESPO_EINVAL;
+  if (!params) return ESPO_EINVAL;
+  if (!(temperature > 0.0f) || !isfinite(temperature)) return ESPO_EINVAL;
+  if (!(params->alpha_s >= 0.0f && params->alpha_s <= 1.0f)) return ESPO_EINVAL;
+  if (!(params->var_g + params->delta > 0.0f) || !isfinite(params->var_g + params->delta)) return ESPO_EINVAL;
+  if (!(params->clip_c >= 0.0f) || !(params->beta >= 0.0f) || isnan(params->eps) || isnan(params->mu_g)) return ESPO_EINVAL;
+  if (B == 0) return ESPO_OK;
+  if (!logits || !values || !z || !alive || !stop_step || !tokens || !regret) return ESPO_EINVAL;
+  if (V > espo::kMaxVocab || B > 0x7fffffff) return ESPO_ERANGE;
+  const size_t esize = dt == ESPO_BF16 ? 2 : 4;
+  if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
+  return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params, z,
+                           alive, stop_step, tokens, regret, logprob, (hipStream_t)stream);
+}
+
+int espo_advantages(const float* rewards, const float* values, const int32_t* lengths,
+                    const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma, float lambda,
+                    float* td, float* adv, void* stream) {
+  if (B < 0 || T < 0) return ESPO_EINVAL;
+  if (!isfinite(gamma) || !isfinite(lambda) || isnan(r_fail)) return ESPO_EINVAL;
+  if (B == 0 || T == 0) return ESPO_OK;
+  if (!rewards || !values || !lengths || !stopped || !td || !adv) return ESPO_EINVAL;
+  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv)) return ESPO_EALIGN;
+  return espo::launch_advantages(rewards, values, lengths, stopped, B, T, r_fail, gamma, lambda, td, adv,
+                                 (hipStream_t)stream);
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,23 @@
+// Host-side declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/espo.h"
+
+namespace espo {
+
+constexpr size_t kMaxStepLds = 64 * 1024;          // dynamic LDS a step workgroup may ask for
+constexpr int64_t kMaxVocab = (int64_t)512 * 8000;  // 8 bytes of LDS per 512-index block
+
+int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
+                uint64_t seed, int32_t step, const float* values, const espo_params& p, float* z,
+                uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
+                hipStream_t stream);
+
+int launch_advantages(const float* rewards, const float* values, const int32_t* lengths,
+                      const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
+                      float lambda, float* td, float* adv, hipStream_t stream);
+
+}  // namespace espo

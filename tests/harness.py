@@ -1,0 +1,139 @@
+"""Shared helpers of the GPU parity tests: run the HIP path and the CPU oracle on the same
+bits and compare them to the stated bar.
+
+Bar (from the build's target): stop steps, masks, the smoothed state and the regret are
+bit-exact; tokens are bit-exact except where the oracle's two largest perturbed scores
+lie within 1e-6 relative, in which case the runner-up is accepted and forced into the
+oracle so that the rest of the trajectory stays comparable; log-probabilities agree
+within rtol * max(|ref|, 1) with rtol 1e-5 for fp32 logits and 2e-3 for bf16 logits.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2605_29860_amd as espo
+from paper_2605_29860_amd.workloads import to_host_bits
+
+RTOL_F32 = 1e-5
+RTOL_BF16 = 2e-3
+NEAR_TIE = 1e-6
+
+
+def params_pair(**kw):
+    """The same frozen parameters for the GPU binding and for the oracle."""
+    return espo.EspoParams(**kw), oracle.OracleParams(**kw)
+
+
+class GpuState:
+    """Per-row state and per-step outputs as GPU tensors."""
+
+    def __init__(self, B, device="cuda", z=None, alive=None, stop_step=None):
+        self.z = torch.zeros(B, dtype=torch.float32, device=device) if z is None else z.to(device).clone()
+        self.alive = torch.ones(B, dtype=torch.uint8, device=device) if alive is None else alive.to(device).clone()
+        self.stop_step = (torch.full((B,), -1, dtype=torch.int32, device=device)
+                          if stop_step is None else stop_step.to(device).clone())
+        self.tokens = torch.full((B,), -7, dtype=torch.int32, device=device)
+        self.regret = torch.full((B,), -7.0, dtype=torch.float32, device=device)
+        self.logprob = torch.full((B,), -7.0, dtype=torch.float32, device=device)
+
+    def host(self):
+        return {k: getattr(self, k).cpu().numpy() for k in ("z", "alive", "stop_step", "tokens", "regret", "logprob")}
+
+
+def gpu_step(logits, tau, seed, step, values, gparams, st: GpuState, V=None):
+    espo.espo_step(logits, tau, seed, step, values, gparams, st.z, st.alive, st.stop_step,
+                   st.tokens, st.regret, st.logprob, V=V)
+
+
+def compare_step(logits, tau, seed, step, values, gparams, oparams, st: GpuState, V=None, rows=None,
+                 stats=None):
+    """Runs one step on both sides from the GPU's current state and compares all outputs.
+
+    `rows` restricts the oracle to a subset of rows (the GPU always runs the whole batch).
+    Returns the GPU's host-side outputs of the step.
+    """
+    B = logits.shape[0]
+    rows = np.arange(B) if rows is None else np.asarray(rows)
+    ridx = torch.as_tensor(rows, device=logits.device, dtype=torch.long)
+    before = {"z": st.z[ridx].cpu().numpy(), "alive": st.alive[ridx].cpu().numpy(),
+              "stop_step": st.stop_step[ridx].cpu().numpy()}
+    vals_h = values[ridx].cpu().numpy()
+    bits = np.ascontiguousarray(to_host_bits(logits[ridx]))
+    gpu_step(logits, tau, seed, step, values, gparams, st, V=V)
+    torch.cuda.synchronize()
+    got = st.host()
+
+    # the oracle keys its stream by the row id in the full batch: give it a batch in which
+    # the subset sits at its real positions (other rows dead)
+    nfull = int(rows.max()) + 1 if len(rows) else 0
+    full_bits = np.zeros((nfull, bits.shape[1]), bits.dtype)
+    full_bits[rows] = bits
+    z = np.zeros(nfull, np.float32); z[rows] = before["z"]
+    alive = np.zeros(nfull, np.uint8); alive[rows] = before["alive"]
+    ss = np.full(nfull, -1, np.int32); ss[rows] = before["stop_step"]
+    vals = np.zeros(nfull, np.float32); vals[rows] = vals_h
+    z0, alive0, ss0 = z.copy(), alive.copy(), ss.copy()
+    ref = oracle.step(full_bits, tau, seed, step, vals, oparams, z, alive, ss, V=V)
+
+    tok_g = got["tokens"][rows]
+    tok_o = ref["tokens"][rows]
+    mism = rows[tok_g != tok_o]
+    if len(mism):
+        forced = np.full(nfull, -1, np.int32)
+        for b in mism:
+            s1, s2 = ref["best_score"][b], ref["second_score"][b]
+            ok = got["tokens"][b] == ref["second_token"][b] and (s1 - s2) <= NEAR_TIE * abs(s1)
+            assert ok, (f"step {step} row {b}: token {got['tokens'][b]} != oracle {ref['tokens'][b]} "
+                        f"(runner-up {ref['second_token'][b]}, scores {s1!r} {s2!r})")
+            forced[b] = got["tokens"][b]
+        if stats is not None:
+            stats["near_ties"] = stats.get("near_ties", 0) + len(mism)
+        z, alive, ss = z0, alive0, ss0
+        ref = oracle.step(full_bits, tau, seed, step, vals, oparams, z, alive, ss, V=V, forced_tokens=forced)
+
+    where = f"step {step}"
+    np.testing.assert_array_equal(got["tokens"][rows], ref["tokens"][rows], err_msg=where)
+    np.testing.assert_array_equal(got["regret"][rows].view(np.uint32), ref["regret"][rows].view(np.uint32), err_msg=where)
+    np.testing.assert_array_equal(got["z"][rows].view(np.uint32), z[rows].view(np.uint32), err_msg=where)
+    np.testing.assert_array_equal(got["alive"][rows], alive[rows], err_msg=where)
+    np.testing.assert_array_equal(got["stop_step"][rows], ss[rows], err_msg=where)
+    rtol = RTOL_BF16 if logits.dtype == torch.bfloat16 else RTOL_F32
+    lp_g, lp_o = got["logprob"][rows].astype(np.float64), ref["logprob"][rows].astype(np.float64)
+    err = np.abs(lp_g - lp_o)
+    assert (err <= rtol * np.maximum(np.abs(lp_o), 1.0)).all(), (where, err.max(), lp_g[err.argmax()], lp_o[err.argmax()])
+    if stats is not None:
+        stats["max_logprob_err"] = max(stats.get("max_logprob_err", 0.0), float(err.max()) if len(err) else 0.0)
+        stats["rows_checked"] = stats.get("rows_checked", 0) + int(before["alive"].sum())
+    return got
+
+
+def check_advantages(rewards, values, lengths, stopped, r_fail, gamma, lam, rtol=RTOL_F32):
+    """GPU TD errors / GAE against the double-precision oracle on the same inputs.
+
+    Tolerance: |err| <= rtol * max(|ref|, scale) with scale = sum_l c^l (|r| + |gamma V'| + |V|),
+    the magnitude of the terms that fp32 rounding and reassociation act on (delta itself
+    may cancel to almost nothing); padding must be exactly zero.
+    """
+    B, T = rewards.shape
+    td = torch.full((B, T), 7.0, dtype=torch.float32, device=rewards.device)
+    adv = torch.full((B, T), 7.0, dtype=torch.float32, device=rewards.device)
+    espo.espo_advantages(rewards, values, lengths, stopped, r_fail, gamma, lam, td, adv)
+    torch.cuda.synchronize()
+    r_h, v_h = rewards.cpu().numpy(), values.cpu().numpy()
+    L_h, s_h = lengths.cpu().numpy(), stopped.cpu().numpy()
+    td_o, adv_o, scale = oracle.advantages(r_h, v_h, L_h, s_h, r_fail, gamma, lam)
+    td_g, adv_g = td.cpu().numpy().astype(np.float64), adv.cpu().numpy().astype(np.float64)
+    pad = np.arange(T)[None, :] >= np.clip(L_h, 0, T)[:, None]
+    assert (td_g[pad] == 0).all() and (adv_g[pad] == 0).all(), "padding must be exactly zero"
+    assert np.isfinite(td_g).all() and np.isfinite(adv_g).all()
+    # delta_t is three fp32 operations on exact inputs
+    e_td = np.abs(td_g - td_o)
+    mag = np.abs(r_h.astype(np.float64)) + np.abs(v_h.astype(np.float64)) * 2 + 1
+    mag[pad] = 1
+    assert (e_td <= 4e-7 * mag).all(), e_td.max()
+    e_adv = np.abs(adv_g - adv_o)
+    tol = rtol * np.maximum(np.abs(adv_o), scale)
+    assert (e_adv <= tol).all(), (e_adv.max(), np.unravel_index((e_adv - tol).argmax(), e_adv.shape))
+    return float((e_adv / np.maximum(scale, 1e-30))[~pad].max()) if (~pad).any() else 0.0

@@ -1,0 +1,86 @@
+"""Parity of the HIP espo_advantages with the CPU oracle, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2605_29860_amd as espo  # noqa: E402
+from paper_2605_29860_amd import workloads as W  # noqa: E402
+import harness as H  # noqa: E402
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _batch(B, T, seed, lengths=None, stop_p=0.4, poison=True):
+    g = torch.Generator().manual_seed(seed)
+    rewards = torch.randn(B, T, generator=g)
+    values = torch.rand(B, T, generator=g) * 2 - 1
+    L = torch.randint(0, T + 1, (B,), generator=g) if lengths is None else torch.as_tensor(lengths)
+    stopped = (torch.rand(B, generator=g) < stop_p).to(torch.uint8)
+    if poison:
+        pad = torch.arange(T)[None, :] >= L.clamp(0, T)[:, None]
+        rewards[pad] = float("nan")
+        values[pad] = float("nan")
+    return rewards.cuda(), values.cuda(), L.to(torch.int32).cuda(), stopped.cuda()
+
+
+@pytest.mark.parametrize("T", [1, 3, 4, 7, 8, 9, 64, 511, 512, 2047, 2048, 2049, 4100, 6151])
+def test_shapes_and_ragged_lengths(T):
+    _say(f"[case] advantages T={T}")
+    B = 9
+    L = [0, T, 1, max(T - 1, 0), T // 2, min(T, 2048), min(T, 2049), min(T, 513), T]
+    for gamma, lam in ((1.0, 0.95), (0.99, 0.9), (1.0, 1.0), (0.9, 0.0)):
+        r, v, Lt, s = _batch(B, T, seed=T, lengths=L)
+        H.check_advantages(r, v, Lt, s, -1.0, gamma, lam)
+
+
+def test_out_of_range_lengths_and_empty():
+    _say("[case] advantages clamping / empty")
+    B, T = 4, 100
+    r, v, _, s = _batch(B, T, seed=1, lengths=[T, T, T, T], poison=False)
+    L = torch.tensor([-3, T + 50, 0, 17], dtype=torch.int32).cuda()
+    H.check_advantages(r, v, L, s, -1.0, 1.0, 0.95)
+    e = torch.zeros(0, 5, device="cuda")
+    espo.espo_advantages(e, e, torch.zeros(0, dtype=torch.int32, device="cuda"),
+                         torch.zeros(0, dtype=torch.uint8, device="cuda"), -1.0, 1.0, 0.95, e.clone(), e.clone())
+    with pytest.raises(espo.EspoError):
+        espo.espo_advantages(r, v, L, s, -1.0, float("nan"), 0.95, torch.empty_like(r), torch.empty_like(r))
+
+
+def test_closed_forms_on_device():
+    _say("[case] advantages closed forms")
+    # zero values, stopped: A_t = r_fail c^(L-1-t); gamma = lambda = 1: A_t = return-to-go - V_t
+    B, T = 3, 5000
+    z = torch.zeros(B, T, device="cuda")
+    L = torch.tensor([5000, 3000, 1], dtype=torch.int32, device="cuda")
+    st = torch.ones(B, dtype=torch.uint8, device="cuda")
+    td, adv = torch.empty_like(z), torch.empty_like(z)
+    espo.espo_advantages(z, z, L, st, -1.0, 1.0, 0.95, td, adv)
+    a = adv.cpu().numpy().astype(np.float64)
+    c = float(np.float32(0.95))
+    for b, n in enumerate([5000, 3000, 1]):
+        ref = -1.0 * c ** (n - 1 - np.arange(n))
+        np.testing.assert_allclose(a[b, :n], ref, rtol=2e-5, atol=1e-30)
+        assert (a[b, n:] == 0).all()
+    r, v, Lr, s = _batch(6, 3000, seed=5)
+    H.check_advantages(r, v, Lr, s, -2.0, 1.0, 1.0)
+
+
+def test_config5_full_size():
+    _say("[case] config 5 (B=1024, T=16384)")
+    r, v, L, s = W.advantage_batch(device="cuda", poison=True, seed=5)
+    assert r.shape == (1024, 16384)
+    worst = H.check_advantages(r, v, L, s, -1.0, 1.0, 0.95)
+    frac = float(s.float().mean())
+    _say(f"  config 5: valid tokens {int(L.sum())}, stopped fraction {frac:.2f}, worst scaled error {worst:.2e}")
+    assert 0.2 < frac < 0.4
+    # a second call on the same inputs gives the same bits
+    td1, adv1 = torch.empty_like(r), torch.empty_like(r)
+    td2, adv2 = torch.empty_like(r), torch.empty_like(r)
+    espo.espo_advantages(r, v, L, s, -1.0, 1.0, 0.95, td1, adv1)
+    espo.espo_advantages(r, v, L, s, -1.0, 1.0, 0.95, td2, adv2)
+    torch.cuda.synchronize()
+    assert torch.equal(td1, td2) and torch.equal(adv1, adv2)

@@ -1,0 +1,289 @@
+"""Parity of the HIP espo_step with the CPU oracle, through the C ABI (needs an MI355X)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+import paper_2605_29860_amd as espo  # noqa: E402
+from paper_2605_29860_amd import workloads as W  # noqa: E402
+import harness as H  # noqa: E402
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _rand_logits(B, V, stride, dtype, seed, sigma=3.0):
+    g = torch.Generator().manual_seed(seed)
+    x = torch.randn(B, stride, generator=g) * sigma
+    return x.to(dtype).cuda()
+
+
+# --------------------------------------------------------------------------- small shapes, edge cases
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("V", [1, 3, 8, 37, 511, 512, 513, 1100, 8192, 8200, 16391, 40000])
+def test_shapes_and_ragged_tails(V, dtype):
+    _say(f"[case] shapes V={V} dtype={dtype}")
+    B = 5
+    stride = ((V + 7) // 8) * 8 + 8                         # padded rows: pitch is a multiple of 16 bytes
+    logits = _rand_logits(B, V, stride, dtype, seed=V)
+    logits[:, V:] = 1e4                                      # beyond V must never be looked at
+    gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=1.0)
+    st = H.GpuState(B, z=torch.tensor([0.0, 0.5, -0.3, 2.0, 0.1]), alive=torch.tensor([1, 1, 0, 1, 1], dtype=torch.uint8))
+    vals = torch.tensor([0.5, -1.0, 0.3, 0.0, 1.0], device="cuda")
+    for step in range(3):
+        got = H.compare_step(logits, 0.8, 17, step, vals, gp, op, st, V=V)
+        assert got["tokens"][2] == -1 and got["regret"][2] == 0 and got["logprob"][2] == 0
+        assert ((got["tokens"] < V) & (got["tokens"] >= -1)).all()
+
+
+def test_masked_vocabulary_and_ties():
+    _say("[case] masked vocabulary, exact ties")
+    B, V = 8, 3000
+    x = torch.randn(B, V, generator=torch.Generator().manual_seed(1)) * 2
+    x[:, ::2] = float("-inf")
+    x[:, 1001] = 6.0
+    x[:, 2001] = 6.0                                         # two exactly equal modes in different blocks
+    for dtype in (torch.float32, torch.bfloat16):
+        logits = x.to(dtype).cuda()
+        gp, op = H.params_pair()
+        st = H.GpuState(B)
+        vals = torch.zeros(B, device="cuda")
+        for step in range(4):
+            got = H.compare_step(logits, 1.0, 5, step, vals, gp, op, st)
+            live = got["tokens"] >= 0
+            assert (got["tokens"][live] % 2 == 1).all()
+
+
+def test_flat_rows_visit_many_blocks():
+    _say("[case] flat rows")
+    # uniform logits: no block stands out, so the bound-based pruning has the least to work with
+    B, V = 4, 20000
+    for dtype in (torch.float32, torch.bfloat16):
+        logits = torch.full((B, V), 0.75, dtype=dtype).cuda()
+        gp, op = H.params_pair(stop_enabled=0)
+        st = H.GpuState(B)
+        vals = torch.zeros(B, device="cuda")
+        for step in range(6):
+            got = H.compare_step(logits, 1.0, 99, step, vals, gp, op, st)
+            assert (got["regret"] == 0).all()
+            np.testing.assert_allclose(got["logprob"], -np.log(V), rtol=1e-5)
+
+
+def test_extreme_temperatures_and_large_logits():
+    _say("[case] temperatures")
+    B, V = 6, 5000
+    logits = _rand_logits(B, V, V, torch.float32, seed=3, sigma=30.0)
+    for tau in (0.05, 0.6, 1.0, 4.0):
+        gp, op = H.params_pair(stop_enabled=0)
+        st = H.GpuState(B)
+        H.compare_step(logits, tau, 11, 0, torch.zeros(B, device="cuda"), gp, op, st)
+
+
+def test_eos_and_warmup_gate():
+    _say("[case] eos / warmup")
+    B, V = 4, 600
+    x = torch.full((B, V), -30.0)
+    x[:, 77] = 10.0
+    logits = x.cuda()
+    vals = torch.zeros(B, device="cuda")
+    gp, op = H.params_pair(eos_id=77)
+    st = H.GpuState(B, z=torch.full((B,), 9.0))
+    got = H.compare_step(logits, 1.0, 0, 3, vals, gp, op, st)
+    assert (got["alive"] == 0).all() and (got["stop_step"] == -1).all()
+    gp, op = H.params_pair(stop_enabled=0)
+    st = H.GpuState(B, z=torch.full((B,), 9.0))
+    got = H.compare_step(logits, 1.0, 0, 3, vals, gp, op, st)
+    assert (got["alive"] == 1).all()
+    gp, op = H.params_pair()
+    st = H.GpuState(B, z=torch.full((B,), 9.0))
+    got = H.compare_step(logits, 1.0, 0, 3, vals, gp, op, st)
+    assert (got["alive"] == 0).all() and (got["stop_step"] == 3).all()
+
+
+def test_empty_batch_and_argument_errors():
+    _say("[case] errors")
+    gp, _ = H.params_pair()
+    B, V = 2, 64
+    logits = torch.zeros(B, V, dtype=torch.bfloat16, device="cuda")
+    st = H.GpuState(B)
+    vals = torch.zeros(B, device="cuda")
+    espo.espo_step(logits[:0], 1.0, 0, 0, vals[:0], gp, st.z[:0], st.alive[:0], st.stop_step[:0],
+                   st.tokens[:0], st.regret[:0], st.logprob[:0])
+    for tau in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(espo.EspoError) as e:
+            H.gpu_step(logits, tau, 0, 0, vals, gp, st)
+        assert e.value.code == -1
+    with pytest.raises(espo.EspoError) as e:                 # V beyond the row pitch
+        H.gpu_step(logits, 1.0, 0, 0, vals, gp, st, V=V + 1)
+    assert e.value.code == -1
+    odd = torch.zeros(B, 72, dtype=torch.bfloat16, device="cuda")[:, 4:68]   # base not 16-byte aligned
+    with pytest.raises(espo.EspoError) as e:
+        H.gpu_step(odd, 1.0, 0, 0, vals, gp, st)
+    assert e.value.code == -2
+    bad, _ = H.params_pair(alpha_s=1.5)
+    with pytest.raises(espo.EspoError):
+        H.gpu_step(logits, 1.0, 0, 0, vals, bad, st)
+    torch.cuda.synchronize()
+    assert (st.tokens.cpu().numpy() == -7).all()              # nothing was launched
+
+
+# --------------------------------------------------------------------------- config 1: small reference rollout
+def test_config1_small_reference_rollout():
+    _say("[case] config 1 rollout")
+    cfg = W.SmallReference()
+    gp, op = H.params_pair(**cfg.params.as_dict())
+    vals_all = cfg.values("cuda")
+    st = H.GpuState(cfg.B)
+    stats = {}
+    tokens = np.zeros((cfg.B, cfg.T), np.int32)
+    for t in range(cfg.T):
+        got = H.compare_step(cfg.logits(t, "cuda"), cfg.temperature, cfg.seed, t,
+                             vals_all[:, t].contiguous(), gp, op, st, stats=stats)
+        tokens[:, t] = got["tokens"]
+    end = st.host()
+    assert end["alive"].tolist() == [1, 1, 0, 0]              # rows 0-1 survive, rows 2-3 must stop
+    assert (end["stop_step"][:2] == -1).all() and (end["stop_step"][2:] > 0).all()
+    for b in (2, 3):
+        assert (tokens[b, end["stop_step"][b] + 1:] == -1).all()
+    # advantages on the resulting truncated trajectories
+    lengths = np.where(end["stop_step"] >= 0, end["stop_step"] + 1, cfg.T).astype(np.int32)
+    stopped = (end["stop_step"] >= 0).astype(np.uint8)
+    rewards = torch.zeros(cfg.B, cfg.T)
+    for b in range(cfg.B):
+        if not stopped[b]:
+            rewards[b, lengths[b] - 1] = 1.0
+    H.check_advantages(rewards.cuda(), vals_all, torch.as_tensor(lengths).cuda(),
+                       torch.as_tensor(stopped).cuda(), cfg.r_fail, cfg.gamma, cfg.lam)
+    _say(f"  config 1: stop steps {end['stop_step'].tolist()} stats {stats}")
+
+
+# --------------------------------------------------------------------------- config 2: one fused step, Qwen vocabulary
+def test_config2_single_fused_step():
+    _say("[case] config 2")
+    B, V = 64, W.QWEN_VOCAB
+    gen = W.ZipfLogits(V=V, seed=2, device="cuda")
+    logits = gen.rows(B, step=0)
+    z, alive, ss = W.seeded_state(B, seed=2, device="cuda")
+    vals = W.step_values(B, 2, 0, -0.2, 1.0, device="cuda")
+    gp, op = H.params_pair(**W.RolloutParams().as_dict())
+    st = H.GpuState(B, z=z, alive=alive, stop_step=ss)
+    stats = {}
+    got = H.compare_step(logits, 0.6, 2, 0, vals, gp, op, st, stats=stats)
+    assert (got["tokens"][7::8] == -1).all() and (got["tokens"][got["alive"] == 1] >= 0).all()
+    assert (got["z"][7::8] == z.cpu().numpy()[7::8]).all()   # dead rows untouched
+    _say(f"  config 2: mean regret {got['regret'][got['tokens'] >= 0].mean():.3f} stats {stats}")
+
+
+# --------------------------------------------------------------------------- configs 3, 4: rollout loops at full batch size
+def _rollout(B, steps, plant_fraction, onset_lo, onset_hi, seed, oracle_rows, oracle_steps, val_lo, val_hi):
+    V = W.QWEN_VOCAB
+    gen = W.ZipfLogits(V=V, seed=seed, device="cuda")
+    plant = W.RegretPlant.make(B, V, plant_fraction, onset_lo, onset_hi, seed)
+    gp, op = H.params_pair(**W.RolloutParams().as_dict())
+    st = H.GpuState(B)
+    # host replay of the scalar chain for every row, from the GPU's own regret stream
+    import oracle
+    z_r, alive_r, ss_r = np.zeros(B, np.float32), np.ones(B, np.uint8), np.full(B, -1, np.int32)
+    buf = torch.empty(B, V, dtype=torch.bfloat16, device="cuda")
+    stats = {}
+    live_curve = []
+    for t in range(steps):
+        x = gen.rows(B, step=t, out=None)
+        x = plant.apply(x.float(), t).to(torch.bfloat16)
+        buf.copy_(x)
+        vals = W.step_values(B, seed, t, val_lo, val_hi, device="cuda")
+        alive_before = st.alive.cpu().numpy().copy()
+        if t in oracle_steps:
+            got = H.compare_step(buf, 0.6, seed, t, vals, gp, op, st, rows=oracle_rows, stats=stats)
+        else:
+            H.gpu_step(buf, 0.6, seed, t, vals, gp, st)
+            torch.cuda.synchronize()
+            got = st.host()
+        # invariants on all rows
+        dead = alive_before == 0
+        assert (got["tokens"][dead] == -1).all() and (got["regret"][dead] == 0).all()
+        live = ~dead
+        assert ((got["tokens"][live] >= 0) & (got["tokens"][live] < V)).all()
+        assert (got["regret"][live] >= 0).all()
+        assert (got["alive"] <= alive_before).all()          # never revived
+        oracle.state_update(got["regret"], got["tokens"], vals.cpu().numpy(), op, t, z_r, alive_r, ss_r)
+        np.testing.assert_array_equal(got["z"].view(np.uint32), z_r.view(np.uint32), err_msg=f"step {t}")
+        np.testing.assert_array_equal(got["alive"], alive_r, err_msg=f"step {t}")
+        np.testing.assert_array_equal(got["stop_step"], ss_r, err_msg=f"step {t}")
+        live_curve.append(int(alive_r.sum()))
+        if t % 64 == 0:
+            _say(f"  step {t}: live {live_curve[-1]}/{B}")
+    return plant, st.host(), live_curve, stats
+
+
+def test_config3_sustained_rollout():
+    _say("[case] config 3 (B=512, 1024 steps)")
+    B, steps, seed = 512, 1024, 3
+    plant_preview = W.RegretPlant.make(B, W.QWEN_VOCAB, 0.25, 8, 1000, seed)
+    planted = plant_preview.rows[:8].tolist()
+    others = [r for r in range(0, B, 61) if r not in planted][:8]
+    rows = sorted(planted + others)
+    osteps = set(range(0, steps, 40)) | {1, 2, steps - 1} | {int(o) for o in plant_preview.onset[:8]} \
+        | {int(o) + 3 for o in plant_preview.onset[:8] if o + 3 < steps}
+    plant, end, curve, stats = _rollout(B, steps, 0.25, 8, 1000, seed, rows, osteps, 0.2, 1.0)
+    stopped_planted = (end["stop_step"][plant.rows] >= 0).mean()
+    _say(f"  config 3: live at end {curve[-1]}, planted rows stopped {stopped_planted:.2f}, stats {stats}")
+    assert stopped_planted > 0.9
+    assert 0.6 * B < curve[-1] < 0.8 * B                      # about a quarter of the batch stops
+    on = end["stop_step"][plant.rows]
+    assert (on[on >= 0] >= plant.onset[on >= 0]).all()        # never before the drift starts
+
+
+def test_config4_heavy_termination():
+    _say("[case] config 4 (B=1024, 256 steps)")
+    B, steps, seed = 1024, 256, 4
+    plant_preview = W.RegretPlant.make(B, W.QWEN_VOCAB, 0.6, 12, 190, seed)
+    planted = plant_preview.rows[:8].tolist()
+    others = [r for r in range(0, B, 127) if r not in planted][:8]
+    rows = sorted(planted + others)
+    osteps = set(range(0, steps, 16)) | {steps - 1} | {int(o) + 2 for o in plant_preview.onset[:8]}
+    plant, end, curve, stats = _rollout(B, steps, 0.6, 12, 190, seed, rows, osteps, 0.2, 1.0)
+    ss = end["stop_step"][plant.rows]
+    _say(f"  config 4: live at end {curve[-1]}, planted stop steps in [{ss[ss >= 0].min()}, {ss.max()}], stats {stats}")
+    assert (ss >= 0).mean() > 0.95
+    assert ((ss[ss >= 0] >= 12) & (ss[ss >= 0] <= 230)).all()
+    assert 0.3 * B < curve[-1] < 0.5 * B
+
+
+# --------------------------------------------------------------------------- replay / resume / batch independence
+def test_determinism_resume_and_batch_independence():
+    _say("[case] determinism")
+    B, V, steps = 24, 9000, 12
+    gen = W.ZipfLogits(V=V, seed=9, device="cuda")
+    gp, _ = H.params_pair(mu_g=1.0, var_g=2.0, beta=2.0)
+
+    def run(rows, start, stop, st):
+        outs = []
+        for t in range(start, stop):
+            x = gen.rows(B, step=t)[rows].contiguous()
+            vals = W.step_values(B, 9, t, 0.0, 1.0, device="cuda")[rows].contiguous()
+            H.gpu_step(x, 0.6, 9, t, vals, gp, st)
+            torch.cuda.synchronize()
+            outs.append(st.host())
+        return outs
+
+    allrows = torch.arange(B, device="cuda")
+    a = run(allrows, 0, steps, H.GpuState(B))
+    b = run(allrows, 0, steps, H.GpuState(B))
+    for x, y in zip(a, b):
+        for k in x:
+            np.testing.assert_array_equal(x[k].view(np.uint8), y[k].view(np.uint8))
+    # resume: copy the state out after 5 steps, continue in a fresh state object
+    st = H.GpuState(B)
+    run(allrows, 0, 5, st)
+    st2 = H.GpuState(B, z=st.z.cpu(), alive=st.alive.cpu(), stop_step=st.stop_step.cpu())
+    c = run(allrows, 5, steps, st2)
+    for k in c[-1]:
+        np.testing.assert_array_equal(c[-1][k].view(np.uint8), a[-1][k].view(np.uint8))
+    # a row's stream is keyed by its index in the batch: the first rows of a larger batch
+    # behave exactly like a smaller batch made of them
+    d = run(allrows[:7], 0, steps, H.GpuState(7))
+    for k in d[-1]:
+        np.testing.assert_array_equal(d[-1][k].view(np.uint8), a[-1][k][:7].view(np.uint8))

@@ -1,0 +1,63 @@
+"""The C-ABI library loads and exports every symbol that include/espo.h declares.
+
+Runs without a GPU: nothing is launched, only argument checking is exercised.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2605_29860_amd import binding
+    if not os.path.exists(binding.library_path()):
+        from paper_2605_29860_amd import build
+        build.build_library()
+    return binding.load_library()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "espo.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(espo_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared_functions()
+    assert {"espo_step", "espo_advantages", "espo_step_workspace_bytes", "espo_strerror", "espo_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings_and_version(lib):
+    assert lib.espo_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5, -99):
+        s = lib.espo_strerror(code)
+        assert s and len(s) > 3
+        seen.add(s)
+    assert len(seen) == 7
+
+
+def test_argument_checks_need_no_gpu(lib):
+    from paper_2605_29860_amd.binding import _Params
+    p = _Params(0, 1, 1e-8, 10, 0.9, 7, 0.2, 1, -1)
+    fake = ctypes.c_void_p(0x1000)
+    def step(B=1, V=8, stride=8, tau=1.0, logits=fake, params=ctypes.byref(p), dt=1, stepno=0):
+        return lib.espo_step(logits, dt, B, V, stride, tau, 0, stepno, fake, params, fake, fake, fake, fake, fake,
+                             None, None, 0, None)
+    assert step(B=0) == 0                                   # empty batch is a no-op
+    assert step(tau=0.0) == -1 and step(tau=float("nan")) == -1
+    assert step(V=0) == -1 and step(stride=4) == -1 and step(B=-1) == -1 and step(stepno=-1) == -1
+    assert step(dt=7) == -1 and step(params=None) == -1 and step(logits=None) == -1
+    assert step(logits=ctypes.c_void_p(0x1008)) == -2       # misaligned base
+    assert step(V=3, stride=3) == -2                        # row pitch of 6 bytes
+    assert step(V=5_000_000, stride=5_000_000) == -5        # beyond the supported vocabulary
+    adv = lambda B=1, T=8, g=1.0: lib.espo_advantages(fake, fake, fake, fake, B, T, -1.0, g, 0.95, fake, fake, None)
+    assert adv(B=0) == 0 and adv(T=0) == 0
+    assert adv(B=-1) == -1 and adv(g=float("inf")) == -1
+    assert lib.espo_step_workspace_bytes(512, 152064, 1) == 0
