@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the ESPO per-step hot path on one MI355X.
+
+A "step" is one `espo_step` call over a batch of 512 trajectories with Qwen-vocabulary
+bf16 logits (the sustained-rollout workload: state carried from step to step, about a
+quarter of the rows driven over the stop threshold at seeded steps, dead rows skipped).
+Every step reads its own logit buffer, all of them generated on the device before the
+timed region (288 GB of HBM hold hundreds of 156 MB steps), so no step can be served
+from a cache.  The companion `espo_advantages` pass is timed on the B=1024, T=16384 batch
+and reported in the same JSON line, as is the CPU oracle on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+STEP_SCALAR_BYTES = 34         # per live row: value, z in/out, alive in/out, stop step, token, regret, logprob
+B_STEP, V_STEP = 512, 152064
+B_ADV, T_ADV = 1024, 16384
+
+
+def _traffic_from_profiles(kernel: str):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary was committed."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{kernel}.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--adv-reps", type=int, default=60)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU; rows shard over GPUs without any exchange, "
+              "so a multi-GPU figure would be N independent copies of this run. Use --gpus 1.", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2605_29860_amd as espo
+    from paper_2605_29860_amd import workloads as W
+
+    if not os.path.exists(espo.library_path()):
+        from paper_2605_29860_amd import build
+        build.build_library()
+    espo.load_library()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    K, Wm = args.steps, args.warmup
+    total = K + Wm
+    seed, tau = 3, 0.6
+
+    # ------------------------------------------------------------------ inputs, resident in HBM (untimed)
+    gen = W.ZipfLogits(V=V_STEP, seed=seed, device=dev)
+    plant = W.RegretPlant.make(B_STEP, V_STEP, 0.25, Wm, max(Wm, total - 24), seed)
+    logits = torch.empty(total, B_STEP, V_STEP, dtype=torch.bfloat16, device=dev)
+    values = torch.empty(total, B_STEP, dtype=torch.float32, device=dev)
+    for s in range(total):
+        gen.rows(B_STEP, step=s, out=logits[s])
+        plant.apply(logits[s], s)
+        values[s] = W.step_values(B_STEP, seed, s, 0.2, 1.0, device=dev)
+    params = espo.EspoParams(**W.RolloutParams().as_dict())
+    tokens = torch.empty(B_STEP, dtype=torch.int32, device=dev)
+    regret = torch.empty(B_STEP, dtype=torch.float32, device=dev)
+    logprob = torch.empty(B_STEP, dtype=torch.float32, device=dev)
+
+    def run(first, last, z, alive, ss, events=None):
+        for s in range(first, last):
+            if events is not None:
+                events[s - first][0].record()
+            espo.espo_step(logits[s], tau, seed, s, values[s], params, z, alive, ss, tokens, regret, logprob)
+            if events is not None:
+                events[s - first][1].record()
+
+    def fresh_state():
+        z, alive, ss = W.initial_state(B_STEP, device=dev)
+        run(0, Wm, z, alive, ss)                 # warmup steps are the first steps of the trajectory
+        torch.cuda.synchronize()
+        return z, alive, ss
+
+    # ------------------------------------------------------------------ timed region: exactly K steps
+    z, alive, ss = fresh_state()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(Wm, total, z, alive, ss)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ss_h = ss.cpu().numpy()
+    steps_idx = np.arange(Wm, total)
+    live = ((ss_h[None, :] < 0) | (ss_h[None, :] >= steps_idx[:, None])).sum(1)   # rows decoded at each timed step
+    live_rows = int(live.sum())
+
+    # same K steps again with an event pair around every launch: duration of the kernel itself
+    z2, alive2, ss2 = fresh_state()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    run(Wm, total, z2, alive2, ss2, events=ev)
+    torch.cuda.synchronize()
+    assert torch.equal(ss2, ss) and torch.equal(z2, z), "replay of the timed steps is not deterministic"
+    kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+    step_bytes = live * (V_STEP * 2 + STEP_SCALAR_BYTES) + (B_STEP - live) * 1
+    step_gbs = float(step_bytes.sum() / (kern_ms.sum() * 1e-3) / 1e9)
+
+    # ------------------------------------------------------------------ advantages (B=1024, T=16384), rotated buffers
+    nbuf = 3
+    adv_in = [W.advantage_batch(B=B_ADV, T=T_ADV, seed=50 + i, device=dev) for i in range(nbuf)]
+    adv_out = [(torch.empty(B_ADV, T_ADV, device=dev), torch.empty(B_ADV, T_ADV, device=dev)) for _ in range(nbuf)]
+    def adv_call(i):
+        r, v, L, s = adv_in[i % nbuf]
+        td, ad = adv_out[i % nbuf]
+        espo.espo_advantages(r, v, L, s, -1.0, 1.0, 0.95, td, ad)
+    for i in range(nbuf):
+        adv_call(i)
+    torch.cuda.synchronize()
+    aev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.adv_reps)]
+    ta = time.perf_counter()
+    for i in range(args.adv_reps):
+        aev[i][0].record()
+        adv_call(i)
+        aev[i][1].record()
+    torch.cuda.synchronize()
+    adv_wall = time.perf_counter() - ta
+    adv_ms = np.array([a.elapsed_time(b) for a, b in aev])
+    valid = np.array([int(adv_in[i % nbuf][2].sum()) for i in range(args.adv_reps)])
+    adv_bytes = valid * 16 + (B_ADV * T_ADV - valid) * 8 + B_ADV * 5
+    adv_gbs = float(adv_bytes.sum() / (adv_ms.sum() * 1e-3) / 1e9)
+
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample (context only)
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build_oracle()
+        op = oracle.OracleParams(**W.RolloutParams().as_dict())
+        bits = W.to_host_bits(logits[0])
+        zc, ac, sc = (np.zeros(B_STEP, np.float32), np.ones(B_STEP, np.uint8), np.full(B_STEP, -1, np.int32))
+        vals0 = values[0].cpu().numpy()
+        tc = time.perf_counter()
+        oracle.step(bits, tau, seed, 0, vals0, op, zc, ac, sc)
+        cpu_s = time.perf_counter() - tc
+        r, v, L, s = [x.cpu().numpy() for x in adv_in[0]]
+        tc = time.perf_counter()
+        oracle.advantages(r, v, L, s, -1.0, 1.0, 0.95, want_scale=False)
+        cpu_adv_s = time.perf_counter() - tc
+        cpu = {"value": B_STEP / cpu_s, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"one full step of the workload (512 rows x 152064 bf16 logits, step 0), {cpu_s:.2f} s",
+               "advantages_tokens_per_s": float(L.clip(0, T_ADV).sum() / cpu_adv_s)}
+
+    out = {
+        "metric": "logit rows/sec & HBM GB/s (fused step, V=152064 bf16); advantages tokens/sec",
+        "value": live_rows / wall, "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 logits, fp32 arithmetic (fp64 for the scores of contenders)", "data": "synthetic",
+        "config": {"workload": "sustained rollout step loop: B=512, V=152064 bf16, state carried, "
+                               "~25% of rows planted to stop, one resident logit buffer per step",
+                   "B": B_STEP, "V": V_STEP, "temperature": tau, "live_rows_mean": float(live.mean()),
+                   "live_rows_last": int(live[-1])},
+        "step_hbm_gbs_wall": float(step_bytes.sum() / wall / 1e9),
+        "roofline": {"kernel": "espo_step_kernel<bf16>", "bound": "hbm", "achieved": step_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS,
+                     "avg_launch_us": float(kern_ms.mean() * 1e3),
+                     "algorithmic_bytes_per_launch": float(step_bytes.mean()),
+                     "traffic": _traffic_from_profiles("espo_step")},
+        "advantages": {"workload": "B=1024, T=16384 fp32, lengths U[512,16384], 30% stopped, 3 rotated buffer sets",
+                       "tokens_per_s": float(valid.sum() / adv_wall), "ms_per_call": adv_wall / args.adv_reps * 1e3,
+                       "roofline": {"kernel": "espo_advantages_kernel", "bound": "hbm", "achieved": adv_gbs,
+                                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": adv_gbs / HBM_PEAK_GBS,
+                                    "avg_launch_us": float(adv_ms.mean() * 1e3),
+                                    "algorithmic_bytes_per_launch": float(adv_bytes.mean()),
+                                    "traffic": _traffic_from_profiles("espo_advantages")}},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -159,44 +159,43 @@ __device__ __forceinline__ double gumbel_at(const StepArgs& a, int row, int64_t 
 
 // Exact evaluation of block q by one wave.  Only indices with y_v + M_q >= bound can beat
 // a score `bound` that some index is already known to attain (G_v <= M_q), so the rest are
-// skipped.  `best` is this lane's running best; `bound` is raised as scores are found.
+// skipped.  `best` is this lane's running best; the lane's bound rises as scores are found.
+// Pass 0 scores each lane's largest logit (64 exact scores at once give a tight bound for
+// the block), passes 1..7 take the lane's other indices in order.  One evaluation site and
+// no unrolling: this code runs a few times per row and should stay small.
 template <int DT>
-__device__ void visit_block(const StepArgs& a, const void* rowp, int row, int q, double bound, Best& best) {
+__device__ __forceinline__ void visit_block(const StepArgs& a, const void* rowp, int row, int q, double bound, Best& best) {
   const int lane = threadIdx.x & (kWave - 1);
   const BlockDraw d = block_draw(a, row, q);
   const int64_t v0 = (int64_t)q * kDrawBlock + lane * 8;
   const double itau = (double)a.inv_tau;
-  // the lane's largest logit first: 64 exact scores in one go give a tight bound
+  float x[8];
+  unpack<DT>(load_raw<DT>(rowp, v0, a.V), x);
   float xt = kNegInf;
-  int jt = -1;
-  for (int j = 0; j < 8; ++j) {
-    const int64_t v = v0 + j;
-    if (v < a.V) {
-      const float x = load_one<DT>(rowp, v);
-      if (x > xt) { xt = x; jt = j; }
-    }
-  }
-  double mine = -__builtin_huge_val();
-  if (jt >= 0) {
-    const double y = (double)xt * itau;
-    if (y + d.M >= bound) {
-      const double s = y + gumbel_at(a, row, v0 + jt, d);
-      mine = s;
-      if (better(s, (int32_t)(v0 + jt), best)) best = Best{s, (int32_t)(v0 + jt), xt};
-    }
-  }
+  int jt = 0;
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) mine = fmax(mine, __shfl_xor(mine, off));
-  bound = fmax(bound, mine);
   for (int j = 0; j < 8; ++j) {
+    if (v0 + j >= a.V) x[j] = kNegInf;
+    if (x[j] > xt) { xt = x[j]; jt = j; }
+  }
+#pragma unroll 1
+  for (int pass = 0; pass < 8; ++pass) {
+    const int j = pass == 0 ? jt : (pass <= jt ? pass - 1 : pass);
+    float xj = x[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) xj = (j == k) ? x[k] : xj;
     const int64_t v = v0 + j;
-    if (j == jt || v >= a.V) continue;
-    const float x = load_one<DT>(rowp, v);
-    const double y = (double)x * itau;
-    if (y + d.M >= bound) {
+    const double y = (double)xj * itau;
+    if (v < a.V && y + d.M >= bound) {
       const double s = y + gumbel_at(a, row, v, d);
-      if (better(s, (int32_t)v, best)) best = Best{s, (int32_t)v, x};
+      if (better(s, (int32_t)v, best)) best = Best{s, (int32_t)v, xj};
       bound = fmax(bound, s);
+    }
+    if (pass == 0) {  // share the best of the 64 lane maxima before looking at the rest
+      double top = bound;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
+      bound = top;
     }
   }
 }
@@ -349,38 +348,42 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
   }
   const int qstar = qx;
 
+  // Round 0: wave 0 evaluates the block with the largest bound; its best score rules out
+  // every block whose bound is lower.  Round 1: the survivors, dealt round-robin to the waves.
   Best best{-__builtin_huge_val(), -1, 0.0f};
-  if (wave == 0) {
-    visit_block<DT>(a, rowp, row, qstar, -__builtin_huge_val(), best);
-    best = wave_best(best);
-    if (lane == 0) {
-      float lf = (float)best.s;  // round the bound down so that it never overshoots
-      if ((double)lf > best.s) lf = __builtin_bit_cast(float, __builtin_bit_cast(int32_t, lf) + (lf > 0.0f ? -1 : 1));
-      if (lf == 0.0f && best.s < 0.0) lf = -1e-37f;
-      s_bound[0] = best.v >= 0 ? lf : kNegInf;
+  double bound = -__builtin_huge_val();
+#pragma unroll 1
+  for (int round = 0; round < 2; ++round) {
+    const int count = round == 0 ? 1 : *s_nsurv;
+    const int stride = round == 0 ? 1 : kStepWaves;
+#pragma unroll 1
+    for (int k = (round == 0 && wave != 0) ? 1 : (round == 0 ? 0 : wave); k < count; k += stride) {
+      visit_block<DT>(a, rowp, row, round == 0 ? qstar : s_surv[k], bound, best);
+      double top = best.s;
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
+      bound = fmax(bound, top);
+    }
+    if (round == 0) {
+      if (tid == 0) {
+        float lf = (float)bound;  // round the shared bound down so that it never overshoots
+        if ((double)lf > bound) lf = __builtin_bit_cast(float, __builtin_bit_cast(int32_t, lf) + (lf > 0.0f ? -1 : 1));
+        if (lf == 0.0f && bound < 0.0) lf = -1e-37f;
+        s_bound[0] = lf;
+      }
+      __syncthreads();
+      const float bound_f = s_bound[0];
+      for (int q = tid; q < nblocks; q += kStepThreads)
+        if (q != qstar && s_ub[q] >= bound_f) s_surv[atomicAdd(s_nsurv, 1)] = q;
+      __syncthreads();
+      bound = fmax(bound, (double)bound_f);
     }
   }
-  __syncthreads();
-  const float bound_f = s_bound[0];
-  for (int q = tid; q < nblocks; q += kStepThreads)
-    if (q != qstar && s_ub[q] >= bound_f) s_surv[atomicAdd(s_nsurv, 1)] = q;
-  __syncthreads();
-  const int nsurv = *s_nsurv;
-  {
-    double bound = (double)bound_f;
-    for (int k = wave; k < nsurv; k += kStepWaves) {
-      visit_block<DT>(a, rowp, row, s_surv[k], bound, best);
-      double mine = best.s;
-#pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) mine = fmax(mine, __shfl_xor(mine, off));
-      bound = fmax(bound, mine);
-    }
-    if (nsurv > wave || wave == 0) best = wave_best(best);
-    if (lane == 0) {
-      s_best_s[wave] = best.s;
-      s_best_v[wave] = best.v;
-      s_best_x[wave] = best.x;
-    }
+  best = wave_best(best);
+  if (lane == 0) {
+    s_best_s[wave] = best.s;
+    s_best_v[wave] = best.v;
+    s_best_x[wave] = best.x;
   }
   __syncthreads();
 
