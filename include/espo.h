@@ -72,16 +72,16 @@ typedef struct {
  *      (Gumbel-max draw from pi; the paper only asks for a_t ~ pi).  Equal scores:
  *      lowest v wins.  Scores of contenders are formed in double precision.
  *      The variates come from Philox4x32-10 keyed by the seed and are generated
- *      top-down in blocks of 512 consecutive vocabulary indices, which has the same
+ *      top-down in blocks of 64 consecutive vocabulary indices, which has the same
  *      joint law as drawing each G_v on its own but lets a block be ruled out from
  *      one random number.  With u(w) = (2 (w >> 9) + 1) / 2^24 and
  *      key = (seed & 0xffffffff, seed >> 32):
- *        block q = v / 512 holds n_q = min(512, V - 512 q) indices;
+ *        block q = v / 64 holds n_q = min(64, V - 64 q) indices;
  *        (w0, w1) = words 0, 1 of Philox(counter = (q, step, b, 0x4553504F), key);
  *        M_q   = ln n_q - ln(-ln u(w0))       the largest variate of the block,
  *        pos_q = (w1 * n_q) >> 32             the index (within the block) that gets it;
  *        w_v   = word (v & 3) of Philox(counter = (v >> 2, step, b, 0x6573706F), key);
- *        G_v   = M_q                           if v = 512 q + pos_q,
+ *        G_v   = M_q                           if v = 64 q + pos_q,
  *              = -ln(exp(-M_q) - ln u(w_v))    otherwise.
  *   3. regret g = max_a log pi(a) - log pi(a_t) = (m - x_a)/temperature
  *      (Eq. step_gap), evaluated in fp32 as (m - x_a) * (1.0f/temperature).
@@ -108,7 +108,8 @@ typedef struct {
  *               -inf entries are allowed (masked vocabulary); NaN and +inf are not
  *               supported (results for that row are unspecified, no fault).
  *   dt          ESPO_F32 or ESPO_BF16.
- *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V < 2^31 - 8.
+ *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 512000
+ *               (ESPO_ERANGE beyond: the per-block bounds of a row live in LDS).
  *   row_stride  elements between rows, >= V.
  *   temperature > 0 and finite.
  *   seed, step  key and counter word of the random stream; step >= 0.

@@ -70,22 +70,22 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
 
 /*
  * Random stream of the draw.  The Gumbel variates G_v (v = 0..V-1) of one row and step
- * are iid standard Gumbel, generated top-down in blocks of 512 consecutive vocabulary
+ * are iid standard Gumbel, generated top-down in blocks of 64 consecutive vocabulary
  * indices (the joint law of n iid Gumbels factorises into: their maximum M, which is
  * Gumbel shifted by ln n; the position of the maximum, uniform; and the others, iid
  * Gumbel truncated to (-inf, M) -- Maddison, Tarlow & Minka, "A* sampling", 2014):
- *   block q = v / 512 holds indices [512 q, min(512 q + 512, V)), n_q of them;
+ *   block q = v / 64 holds indices [64 q, min(64 q + 64, V)), n_q of them;
  *   (w0, w1) = words 0, 1 of Philox(counter = (q, step, row, TAG_BLOCK), key = seed);
  *   M_q   = ln n_q - ln(-ln u(w0))          maximum of the block's variates
  *   pos_q = (w1 * n_q) >> 32                 which index of the block attains it
  *   w_v   = word (v & 3) of Philox(counter = (v >> 2, step, row, TAG_ELEM), key = seed)
- *   G_v   = M_q                               if v = 512 q + pos_q
+ *   G_v   = M_q                               if v = 64 q + pos_q
  *         = -ln(exp(-M_q) - ln u(w_v))        otherwise (inverse cdf of the truncation)
  * with u(w) = (2 (w >> 9) + 1) / 2^24 in (0, 1).
  */
 #define ORACLE_TAG_BLOCK 0x4553504Fu
 #define ORACLE_TAG_ELEM 0x6573706Fu
-#define ORACLE_BLOCK 512
+#define ORACLE_BLOCK 64
 
 /* u in (0,1): the top 23 bits r of the word give u = (2r+1)/2^24. */
 double oracle_uniform(uint32_t word) {

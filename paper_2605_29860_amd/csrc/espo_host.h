@@ -9,7 +9,7 @@
 namespace espo {
 
 constexpr size_t kMaxStepLds = 64 * 1024;          // dynamic LDS a step workgroup may ask for
-constexpr int64_t kMaxVocab = (int64_t)512 * 8000;  // 8 bytes of LDS per 512-index block
+constexpr int64_t kMaxVocab = (int64_t)512 * 1000;  // 64 bytes of LDS per 512-index tile
 
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float* z,

@@ -1,17 +1,18 @@
 // espo_step: one decode step of ESPO rollout collection (Algorithm 1 body) on gfx950.
 //
-// One workgroup of 16 wavefronts owns one row.  The row is streamed exactly once
-// through 16-byte nontemporal loads; a wave iteration covers one block of 512
-// consecutive vocabulary indices (8 per lane), which is also the block of the random
-// stream, so everything a block contributes is wave-uniform:
-//   phase 1 (streaming, HBM bound): per block the maximum logit, the running softmax
-//     sum against a lazily advanced reference, and an fp32 upper bound
-//     ub_q >= max_v (y_v + G_v) built from the block's largest Gumbel variate M_q;
-//   phase 2 (a handful of blocks): the block with the largest bound is evaluated
-//     exactly in double, its best score L rules out every block with ub_q < L, the
-//     few survivors are evaluated the same way, and one lane runs the scalar chain
-//     regret -> normalise/clip -> smoothed state -> stop test (Eq. step_gap,
-//     Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule).
+// One workgroup of 16 wavefronts owns one row.  The row is streamed exactly once through
+// 16-byte nontemporal loads; a wave iteration covers a tile of 512 consecutive vocabulary
+// indices, 8 per lane, so that each aligned group of 8 lanes holds exactly one 64-index
+// block of the random stream.
+//   phase 1 (streaming, HBM bound): per lane the running maximum and the softmax sum
+//     against a lazily advanced per-lane reference; per block the maximum logit (three
+//     DPP steps) and an fp32 upper bound ub_q >= max_v (y_v + G_v) built from the block's
+//     largest Gumbel variate M_q, kept in LDS.
+//   phase 2 (a handful of blocks): the blocks with the largest bounds are evaluated
+//     exactly in double, their best score L rules out every block with ub_q < L, the few
+//     survivors are evaluated the same way, and one lane runs the scalar chain regret ->
+//     normalise/clip -> smoothed state -> stop test (Eq. step_gap, Eq. normalized_gap,
+//     Eq. smoothed_score, Eq. stop_rule).
 // Pruning only ever discards indices that provably cannot attain the maximum, so the
 // token equals the exhaustive argmax with lowest-index tie-break.
 #include <hip/hip_runtime.h>
@@ -27,13 +28,15 @@ namespace {
 
 constexpr int kStepThreads = 1024;
 constexpr int kStepWaves = kStepThreads / kWave;
-constexpr int kRing = 4;            // 16-byte loads kept in flight per lane
-constexpr float kRescaleAt = 64.0f; // advance the softmax reference when a block tops it by 2^64
+constexpr int kTile = 512;                        // indices per wave iteration
+constexpr int kGroups = kTile / kDrawBlock;       // draw blocks per tile = lane groups per wave
+constexpr int kRing = 4;                          // 16-byte loads kept in flight per lane
+constexpr float kRescaleAt = 64.0f;               // advance a lane's softmax reference when topped by 2^64
 
 struct StepArgs {
   const void* logits;
   int64_t V, row_stride;
-  int nblocks;
+  int ntiles, nblocks;
   float inv_tau, k2;   // 1/temperature (fp32 division) and inv_tau * log2(e)
   uint32_t key0, key1;
   int32_t step;
@@ -157,17 +160,19 @@ __device__ __forceinline__ double gumbel_at(const StepArgs& a, int row, int64_t 
   return -log(d.emM - log(uniform_f64(w)));
 }
 
-// Exact evaluation of block q by one wave.  Only indices with y_v + M_q >= bound can beat
-// a score `bound` that some index is already known to attain (G_v <= M_q), so the rest are
-// skipped.  `best` is this lane's running best; the lane's bound rises as scores are found.
-// Pass 0 scores each lane's largest logit (64 exact scores at once give a tight bound for
-// the block), passes 1..7 take the lane's other indices in order.  One evaluation site and
-// no unrolling: this code runs a few times per row and should stay small.
+// Exact evaluation of up to 8 blocks by one wave: lane group g (8 lanes x 8 indices) takes
+// block q (q < 0: the group idles).  Only indices with y_v + M_q >= bound can beat a score
+// `bound` that some index is already known to attain (G_v <= M_q), so the rest are skipped.
+// `best` is the lane's running best; the lane's bound rises as scores are found.  Pass 0
+// scores each lane's largest logit and shares the best of the group's 8 scores, passes 1..7
+// take the lane's other indices in order.  One evaluation site and no unrolling: this code
+// runs a few times per row and should stay small.
 template <int DT>
-__device__ __forceinline__ void visit_block(const StepArgs& a, const void* rowp, int row, int q, double bound, Best& best) {
+__device__ __forceinline__ void visit_blocks(const StepArgs& a, const void* rowp, int row, int q, double bound, Best& best) {
   const int lane = threadIdx.x & (kWave - 1);
-  const BlockDraw d = block_draw(a, row, q);
-  const int64_t v0 = (int64_t)q * kDrawBlock + lane * 8;
+  const bool active = q >= 0;
+  const BlockDraw d = block_draw(a, row, active ? q : 0);
+  const int64_t v0 = active ? (int64_t)q * kDrawBlock + (lane & 7) * 8 : a.V;
   const double itau = (double)a.inv_tau;
   float x[8];
   unpack<DT>(load_raw<DT>(rowp, v0, a.V), x);
@@ -186,15 +191,15 @@ __device__ __forceinline__ void visit_block(const StepArgs& a, const void* rowp,
     for (int k = 1; k < 8; ++k) xj = (j == k) ? x[k] : xj;
     const int64_t v = v0 + j;
     const double y = (double)xj * itau;
-    if (v < a.V && y + d.M >= bound) {
+    if (xj > kNegInf && y + d.M >= bound) {   // masked (-inf) entries never win
       const double s = y + gumbel_at(a, row, v, d);
       if (better(s, (int32_t)v, best)) best = Best{s, (int32_t)v, xj};
       bound = fmax(bound, s);
     }
-    if (pass == 0) {  // share the best of the 64 lane maxima before looking at the rest
+    if (pass == 0) {  // share the best of the group's 8 lane maxima before looking at the rest
       double top = bound;
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
+      for (int off = 4; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
       bound = top;
     }
   }
@@ -236,74 +241,79 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
   }
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int nblocks = a.nblocks;
+  const int grp = lane >> 3;
+  const int ntiles = a.ntiles;
+  const int nslots = ntiles * kGroups;  // block slots incl. the non-existent ones of the last tile
 
-  // LDS: ub[nblocks] | surv[nblocks] | per-wave partials | scalars
+  // LDS: ub[nslots] | surv[nslots] | per-wave partials | scalars
   float* s_ub = (float*)smem_raw;
-  int* s_surv = (int*)(s_ub + nblocks);
-  double* s_best_s = (double*)(smem_raw + (((size_t)nblocks * 8 + 15) & ~(size_t)15));
+  int* s_surv = (int*)(s_ub + nslots);
+  double* s_best_s = (double*)(smem_raw + (((size_t)nslots * 8 + 15) & ~(size_t)15));
   int* s_best_v = (int*)(s_best_s + kStepWaves);
   float* s_best_x = (float*)(s_best_v + kStepWaves);
   float* s_m = s_best_x + kStepWaves;
-  float* s_ref = s_m + kStepWaves;
-  float* s_sum = s_ref + kStepWaves;
-  float* s_bound = s_sum + kStepWaves;  // [0] = score bound after the first visit
+  float* s_sum = s_m + kStepWaves;
+  float* s_top_ub = s_sum + kStepWaves;            // [16 waves][8 groups]: largest bound seen
+  int* s_top_q = (int*)(s_top_ub + kStepWaves * kGroups);
+  float* s_bound = (float*)(s_top_q + kStepWaves * kGroups);
   int* s_nsurv = (int*)(s_bound + 1);
 
   const void* rowp = DT == ESPO_BF16 ? (const void*)((const uint16_t*)a.logits + (int64_t)row * a.row_stride)
                                      : (const void*)((const float*)a.logits + (int64_t)row * a.row_stride);
 
   // ------------------------------------------------------------ phase 1: stream the row
-  const int nit = (nblocks + kStepWaves - 1) / kStepWaves;  // wave iteration `it` handles block it*16 + wave
+  const int nit = (ntiles + kStepWaves - 1) / kStepWaves;  // wave iteration `it` handles tile it*16 + wave
   Raw<DT> ring[kRing];
 #pragma unroll
   for (int d = 0; d < kRing; ++d) {
-    const int q = d * kStepWaves + wave;
-    ring[d] = load_raw<DT>(rowp, (d < nit && q < nblocks) ? (int64_t)q * kDrawBlock + lane * 8 : a.V, a.V);
+    const int t = d * kStepWaves + wave;
+    ring[d] = load_raw<DT>(rowp, (d < nit && t < ntiles) ? (int64_t)t * kTile + lane * 8 : a.V, a.V);
+  }
+  // While the first loads are in flight: M_q bounds of all blocks, one Philox call each.
+  for (int b = tid; b < nslots; b += kStepThreads) {
+    float mub = kNegInf;
+    if (b < a.nblocks) {
+      const int64_t n = a.V - (int64_t)b * kDrawBlock < kDrawBlock ? a.V - (int64_t)b * kDrawBlock : kDrawBlock;
+      const Philox4 p = philox4x32_10((uint32_t)b, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
+      mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[0]);
+    }
+    s_ub[b] = mub;
   }
   if (tid == 0) *s_nsurv = 0;
+  __syncthreads();
 
-  // Softmax sum against a lazily advanced, wave-uniform reference: the lane accumulates
+  // Softmax sum against a lazily advanced per-lane reference: the lane accumulates
   // sum_v 2^(x_v k2 + nrk) with nrk = -(reference logit) * k2; the final combine multiplies
   // by 2^-(m k2 + nrk), so the rounding of nrk itself cancels.
   float nrk = 1e30f;
-  float sum = 0.0f;            // lane's share of sum_v 2^(x_v k2 + nrk)
-  float m_w = kNegInf;         // wave's running maximum logit
-  float gub = 0.0f;            // lane i: Gumbel bound of the block of iteration (chunk + i)
+  float sum = 0.0f;
+  float m_l = kNegInf;       // lane's running maximum logit
+  float top_ub = kNegInf;    // largest block bound this lane group has produced, and its block
+  int top_q = -1;
 
   for (int it0 = 0; it0 < nit; it0 += kRing) {
 #pragma unroll
     for (int d = 0; d < kRing; ++d) {
       const int it = it0 + d;
       if (it >= nit) break;
-      if ((it & (kWave - 1)) == 0) {  // bounds for the next 64 iterations, one block per lane
-        const int ql = (it + lane) * kStepWaves + wave;
-        if (ql < nblocks) {
-          const Philox4 p = philox4x32_10((uint32_t)ql, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
-          gub = gumbel_upper_f32(p.w[0]);
-        }
-      }
-      const int q = it * kStepWaves + wave;
+      const int t = it * kStepWaves + wave;
       float x[8];
       unpack<DT>(ring[d], x);
       {  // refill this ring slot
-        const int qn = q + kRing * kStepWaves;
-        ring[d] = load_raw<DT>(rowp, (it + kRing < nit && qn < nblocks) ? (int64_t)qn * kDrawBlock + lane * 8 : a.V, a.V);
+        const int tn = t + kRing * kStepWaves;
+        ring[d] = load_raw<DT>(rowp, (it + kRing < nit && tn < ntiles) ? (int64_t)tn * kTile + lane * 8 : a.V, a.V);
       }
-      if (q >= nblocks) continue;  // wave-uniform
-      const int64_t first = (int64_t)q * kDrawBlock;
-      const int64_t nq = (a.V - first < kDrawBlock) ? a.V - first : kDrawBlock;
-      if (nq < kDrawBlock) {  // ragged last block: indices at or beyond V do not exist
+      if (t >= ntiles) continue;  // wave-uniform
+      const int64_t e0 = (int64_t)t * kTile + lane * 8;
+      if ((int64_t)(t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          if (lane * 8 + j >= nq) x[j] = kNegInf;
+          if (e0 + j >= a.V) x[j] = kNegInf;
       }
-      const float gm = fmaxf(fmaxf(__builtin_fmaxf(x[0], x[1]), fmaxf(x[2], x[3])),
-                             fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      const float bm = wave_max(gm);  // block maximum, wave-uniform
-      m_w = fmaxf(m_w, bm);
-      if (fmaf(bm, a.k2, nrk) > kRescaleAt) {  // wave-uniform: move the reference up to bm
-        const float nrk_new = -bm * a.k2;
+      const float gm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+      m_l = fmaxf(m_l, gm);
+      if (fmaf(gm, a.k2, nrk) > kRescaleAt) {  // rare: move this lane's reference up to gm
+        const float nrk_new = -gm * a.k2;
         sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
         nrk = nrk_new;
       }
@@ -314,70 +324,81 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
         acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
       }
       sum += acc0 + acc1;
-      // upper bound of every perturbed score in the block: y_max + M_q, rounded up
-      const float g_q = uniform_f32(gub, it & (kWave - 1));
-      const float lnn = __builtin_amdgcn_logf((float)nq) * kLn2 + 2e-6f;
+      // upper bound of every perturbed score in the lane group's block: y_max + M_q, rounded up
+      const float bm = group8_max(gm);
+      const int q = t * kGroups + grp;
+      const float mub = s_ub[q];
       const float ym = bm * a.inv_tau;
-      const float ub = ym + (lnn + g_q) + (1e-5f + 4e-7f * (fabsf(ym) + fabsf(g_q) + lnn));
-      if (lane == 0) s_ub[q] = ub;
+      const float ub = ym + mub + (1e-5f + 4e-7f * (fminf(fabsf(ym), 1e30f) + fabsf(mub)));
+      s_ub[q] = ub;  // the 8 lanes of the group store the same value
+      if (ub > top_ub) { top_ub = ub; top_q = q; }
     }
   }
   {
-    const float tot = wave_sum(sum);
-    if (lane == 0) {
-      s_m[wave] = m_w;
-      s_ref[wave] = nrk;
-      s_sum[wave] = tot;
+    const float m_w = wave_max(m_l);
+    if (lane == 0) s_m[wave] = m_w;
+    if ((lane & 7) == 0) {
+      s_top_ub[wave * kGroups + grp] = top_ub;
+      s_top_q[wave * kGroups + grp] = top_q;
     }
   }
   __syncthreads();
+  float m = s_m[0];  // row maximum
+#pragma unroll
+  for (int w = 1; w < kStepWaves; ++w) m = fmaxf(m, s_m[w]);
+  {
+    const float part = sum > 0.0f ? sum * __builtin_amdgcn_exp2f(-fmaf(m, a.k2, nrk)) : 0.0f;
+    const float tot = wave_sum(part);
+    if (lane == 0) s_sum[wave] = tot;
+  }
 
   // ------------------------------------------------------------ phase 2: exact argmax
-  // block with the largest bound (lowest index among equals); every wave finds it alone
-  float ubx = kNegInf;
-  int qx = 0x7fffffff;
-  for (int q = lane; q < nblocks; q += kWave) {
-    const float u = s_ub[q];
-    if (u > ubx) { ubx = u; qx = q; }
-  }
-#pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) {
-    const float ou = __shfl_xor(ubx, off);
-    const int oq = __shfl_xor(qx, off);
-    if (ou > ubx || (ou == ubx && oq < qx)) { ubx = ou; qx = oq; }
-  }
-  const int qstar = qx;
-
-  // Round 0: wave 0 evaluates the block with the largest bound; its best score rules out
-  // every block whose bound is lower.  Round 1: the survivors, dealt round-robin to the waves.
+  // Round 0: wave 0 evaluates eight strong blocks at once (lane group g takes the best block
+  // that any wave's group g has seen; the block with the largest bound overall is among
+  // them).  Their best score rules out every block whose bound is lower.  Round 1: the
+  // survivors, eight per wave visit.
   Best best{-__builtin_huge_val(), -1, 0.0f};
   double bound = -__builtin_huge_val();
-#pragma unroll 1
-  for (int round = 0; round < 2; ++round) {
-    const int count = round == 0 ? 1 : *s_nsurv;
-    const int stride = round == 0 ? 1 : kStepWaves;
-#pragma unroll 1
-    for (int k = (round == 0 && wave != 0) ? 1 : (round == 0 ? 0 : wave); k < count; k += stride) {
-      visit_block<DT>(a, rowp, row, round == 0 ? qstar : s_surv[k], bound, best);
-      double top = best.s;
+  if (wave == 0) {
+    const int j = lane & 7;
+    float u0 = s_top_ub[j * kGroups + grp], u1 = s_top_ub[(j + 8) * kGroups + grp];
+    int q0 = s_top_q[j * kGroups + grp], q1 = s_top_q[(j + 8) * kGroups + grp];
+    if (u1 > u0 || (u1 == u0 && (uint32_t)q1 < (uint32_t)q0)) { u0 = u1; q0 = q1; }
 #pragma unroll
-      for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
-      bound = fmax(bound, top);
+    for (int off = 4; off >= 1; off >>= 1) {
+      const float ou = __shfl_xor(u0, off);
+      const int oq = __shfl_xor(q0, off);
+      if (ou > u0 || (ou == u0 && (uint32_t)oq < (uint32_t)q0)) { u0 = ou; q0 = oq; }
     }
-    if (round == 0) {
-      if (tid == 0) {
-        float lf = (float)bound;  // round the shared bound down so that it never overshoots
-        if ((double)lf > bound) lf = __builtin_bit_cast(float, __builtin_bit_cast(int32_t, lf) + (lf > 0.0f ? -1 : 1));
-        if (lf == 0.0f && bound < 0.0) lf = -1e-37f;
-        s_bound[0] = lf;
-      }
-      __syncthreads();
-      const float bound_f = s_bound[0];
-      for (int q = tid; q < nblocks; q += kStepThreads)
-        if (q != qstar && s_ub[q] >= bound_f) s_surv[atomicAdd(s_nsurv, 1)] = q;
-      __syncthreads();
-      bound = fmax(bound, (double)bound_f);
+    visit_blocks<DT>(a, rowp, row, q0, bound, best);
+    double top = best.s;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
+    bound = top;
+    if (q0 >= 0 && j == 0) s_ub[q0] = kNegInf;  // visited: keep it off the survivor list
+    if (lane == 0) {
+      float lf = (float)bound;  // round the shared bound down so that it never overshoots
+      if ((double)lf > bound) lf = __builtin_bit_cast(float, __builtin_bit_cast(int32_t, lf) + (lf > 0.0f ? -1 : 1));
+      if (lf == 0.0f && bound < 0.0) lf = -1e-37f;
+      s_bound[0] = lf;
     }
+  }
+  __syncthreads();
+  const float bound_f = s_bound[0];
+  for (int q = tid; q < nslots; q += kStepThreads) {
+    const float u = s_ub[q];
+    if (u > kNegInf && u >= bound_f) s_surv[atomicAdd(s_nsurv, 1)] = q;
+  }
+  __syncthreads();
+  const int nsurv = *s_nsurv;
+  bound = fmax(bound, (double)bound_f);
+#pragma unroll 1
+  for (int k0 = wave * kGroups; k0 < nsurv; k0 += kStepWaves * kGroups) {
+    visit_blocks<DT>(a, rowp, row, (k0 + grp < nsurv) ? s_surv[k0 + grp] : -1, bound, best);
+    double top = best.s;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
+    bound = fmax(bound, top);
   }
   best = wave_best(best);
   if (lane == 0) {
@@ -390,35 +411,31 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
   // ------------------------------------------------------------ finalize: one lane
   if (tid == 0) {
     Best win{s_best_s[0], s_best_v[0], s_best_x[0]};
-    float m = s_m[0];
-    for (int w = 1; w < kStepWaves; ++w) {
+    for (int w = 1; w < kStepWaves; ++w)
       if (s_best_v[w] >= 0 && better(s_best_s[w], s_best_v[w], win)) win = Best{s_best_s[w], s_best_v[w], s_best_x[w]};
-      m = fmaxf(m, s_m[w]);
-    }
     float S = 0.0f;  // sum_v exp((x_v - m)/tau), waves combined in a fixed order
-    for (int w = 0; w < kStepWaves; ++w)
-      if (s_sum[w] > 0.0f) S += s_sum[w] * __builtin_amdgcn_exp2f(-fmaf(m, a.k2, s_ref[w]));
+    for (int w = 0; w < kStepWaves; ++w) S += s_sum[w];
     int32_t tok = win.v;
     float x_a = win.x;
     if (tok < 0) { tok = 0; x_a = load_one<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
 
     const ChainOut c = scalar_chain(a, m, x_a, a.z[row], a.values[row]);
-    const float g = c.g, zn = c.z;
-    const bool stop = c.stop;
     a.tokens[row] = tok;
-    a.regret[row] = g;
-    a.z[row] = zn;
-    if (a.logprob) a.logprob[row] = -g - logf(S);
+    a.regret[row] = c.g;
+    a.z[row] = c.z;
+    if (a.logprob) a.logprob[row] = -c.g - logf(S);
     if (a.eos_id >= 0 && tok == a.eos_id) {
       a.alive[row] = 0;  // natural end
-    } else if (stop) {
+    } else if (c.stop) {
       a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
       a.stop_step[row] = a.step;
     }
   }
 }
 
-size_t step_lds_bytes(int nblocks) { return (((size_t)nblocks * 8 + 15) & ~(size_t)15) + kStepWaves * 32 + 16; }
+size_t step_lds_bytes(int ntiles) {
+  return (((size_t)ntiles * kGroups * 8 + 15) & ~(size_t)15) + kStepWaves * (8 + 4 + 4 + 4 + 4) + kStepWaves * kGroups * 8 + 16;
+}
 
 }  // namespace
 
@@ -430,6 +447,7 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.logits = logits;
   a.V = V;
   a.row_stride = row_stride;
+  a.ntiles = (int)((V + kTile - 1) / kTile);
   a.nblocks = (int)((V + kDrawBlock - 1) / kDrawBlock);
   a.inv_tau = 1.0f / temperature;
   a.k2 = a.inv_tau * kLog2e;
@@ -452,7 +470,7 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.tokens = tokens;
   a.regret = regret;
   a.logprob = logprob;
-  const size_t lds = step_lds_bytes(a.nblocks);
+  const size_t lds = step_lds_bytes(a.ntiles);
   if (lds > kMaxStepLds) return ESPO_ERANGE;
   const dim3 grid((unsigned)B), block(kStepThreads);
   if (dt == ESPO_BF16)
