@@ -108,8 +108,9 @@ typedef struct {
  *               -inf entries are allowed (masked vocabulary); NaN and +inf are not
  *               supported (results for that row are unspecified, no fault).
  *   dt          ESPO_F32 or ESPO_BF16.
- *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 512000
- *               (ESPO_ERANGE beyond: the per-block bounds of a row live in LDS).
+ *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 320000 for bf16
+ *               and 1 <= V <= 240000 for fp32 logits (ESPO_ERANGE beyond: the per-block
+ *               bounds of a row live in LDS).
  *   row_stride  elements between rows, >= V.
  *   temperature > 0 and finite.
  *   seed, step  key and counter word of the random stream; step >= 0.
@@ -167,6 +168,16 @@ int espo_advantages(const float* rewards, const float* values,
                     const int32_t* lengths, const uint8_t* stopped,
                     int64_t B, int64_t T, float r_fail, float gamma, float lambda,
                     float* td, float* adv, void* stream);
+
+/*
+ * Diagnostics for the callers that test the library (not part of the method): espo_step
+ * scores contenders in fp32 first and repeats the search in double only when the two best
+ * scores overlap within the fp32 error margin.  `scale` >= 1 multiplies that margin for all
+ * later espo_step calls of the process (1 = default; a huge value sends every row through
+ * the double-precision search).  The sampled token does not depend on it.
+ * Returns ESPO_EINVAL for scale < 1 or NaN.
+ */
+int espo_debug_set_score_margin_scale(float scale);
 
 /* Static, human-readable text for a status code (never NULL). */
 const char* espo_strerror(int code);

@@ -73,6 +73,8 @@ def load_library():
         lib.espo_strerror.restype = C.c_char_p
         lib.espo_strerror.argtypes = [C.c_int]
         lib.espo_version.restype = C.c_int
+        lib.espo_debug_set_score_margin_scale.restype = C.c_int
+        lib.espo_debug_set_score_margin_scale.argtypes = [f32]
         _lib = lib
     return _lib
 
@@ -93,6 +95,11 @@ def _dev(t: torch.Tensor, dtype, name: str):
 def _stream(stream):
     s = torch.cuda.current_stream() if stream is None else stream
     return C.c_void_p(s.cuda_stream)
+
+
+def espo_debug_set_score_margin_scale(scale: float) -> None:
+    """Diagnostics: widen the fp32 score margin of espo_step (see include/espo.h)."""
+    _check(load_library().espo_debug_set_score_margin_scale(float(scale)))
 
 
 def espo_step_workspace_bytes(B: int, V: int, dtype: torch.dtype) -> int:

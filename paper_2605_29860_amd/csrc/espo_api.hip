@@ -6,16 +6,26 @@
 #include "../../include/espo.h"
 #include "espo_host.h"
 
+#include <atomic>
+
 namespace {
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+std::atomic<float> g_margin_scale{1.0f};
 
 }  // namespace
 
 #pragma GCC visibility push(default)
 extern "C" {
 
-int espo_version(void) { return 100; }
+int espo_version(void) { return 200; }
+
+int espo_debug_set_score_margin_scale(float scale) {
+  if (!(scale >= 1.0f)) return ESPO_EINVAL;  // below 1 the fast path would no longer be exact
+  g_margin_scale.store(scale);
+  return ESPO_OK;
+}
 
 const char* espo_strerror(int code) {
   switch (code) {
@@ -49,11 +59,11 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
   if (!(params->clip_c >= 0.0f) || !(params->beta >= 0.0f) || isnan(params->eps) || isnan(params->mu_g)) return ESPO_EINVAL;
   if (B == 0) return ESPO_OK;
   if (!logits || !values || !z || !alive || !stop_step || !tokens || !regret) return ESPO_EINVAL;
-  if (V > espo::kMaxVocab || B > 0x7fffffff) return ESPO_ERANGE;
+  if (V > espo::kMaxVocab || B > 0x7fffffff || espo::step_shared_bytes(dt, V) > espo::kMaxStepLds) return ESPO_ERANGE;
   const size_t esize = dt == ESPO_BF16 ? 2 : 4;
   if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
-  return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params, z,
-                           alive, stop_step, tokens, regret, logprob, (hipStream_t)stream);
+  return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params,
+                           g_margin_scale.load(), z, alive, stop_step, tokens, regret, logprob, (hipStream_t)stream);
 }
 
 int espo_advantages(const float* rewards, const float* values, const int32_t* lengths,

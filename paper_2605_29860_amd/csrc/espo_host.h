@@ -9,11 +9,14 @@
 namespace espo {
 
 constexpr size_t kMaxStepLds = 64 * 1024;          // dynamic LDS a step workgroup may ask for
-constexpr int64_t kMaxVocab = (int64_t)512 * 1000;  // 64 bytes of LDS per 512-index tile
+constexpr int64_t kMaxVocab = 320000;               // 64 bytes of LDS per 512-index tile plus 17-33 KB fixed
+
+// Bytes of dynamic LDS a step workgroup needs for this dtype and vocabulary.
+size_t step_shared_bytes(int dt, int64_t V);
 
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
-                uint64_t seed, int32_t step, const float* values, const espo_params& p, float* z,
-                uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
+                uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
+                float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
                 hipStream_t stream);
 
 int launch_advantages(const float* rewards, const float* values, const int32_t* lengths,

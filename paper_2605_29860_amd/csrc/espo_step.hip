@@ -7,14 +7,17 @@
 //   phase 1 (streaming, HBM bound): per lane the running maximum and the softmax sum
 //     against a lazily advanced per-lane reference; per block the maximum logit (three
 //     DPP steps) and an fp32 upper bound ub_q >= max_v (y_v + G_v) built from the block's
-//     largest Gumbel variate M_q, kept in LDS.
-//   phase 2 (a handful of blocks): the blocks with the largest bounds are evaluated
-//     exactly in double, their best score L rules out every block with ub_q < L, the few
-//     survivors are evaluated the same way, and one lane runs the scalar chain regret ->
-//     normalise/clip -> smoothed state -> stop test (Eq. step_gap, Eq. normalized_gap,
-//     Eq. smoothed_score, Eq. stop_rule).
+//     largest Gumbel variate M_q, kept in LDS.  Each lane group also keeps the raw data of
+//     the block with the largest bound it has seen, so that phase 2 seldom re-reads memory.
+//   phase 2 (a handful of blocks, lanes = the 64 indices of a block): the block with the
+//     largest bound is scored, the best score rules out every block with a lower bound,
+//     the few survivors are scored by the waves in parallel.  Scores are first formed in
+//     fp32 with a proven error margin; if the best two cannot be told apart within that
+//     margin the same procedure is repeated in double, which decides exactly.
+//   One lane then runs the scalar chain regret -> normalise/clip -> smoothed state -> stop
+//   test (Eq. step_gap, Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule).
 // Pruning only ever discards indices that provably cannot attain the maximum, so the
-// token equals the exhaustive argmax with lowest-index tie-break.
+// token equals the exhaustive double-precision argmax with lowest-index tie-break.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -30,14 +33,16 @@ constexpr int kStepThreads = 1024;
 constexpr int kStepWaves = kStepThreads / kWave;
 constexpr int kTile = 512;                        // indices per wave iteration
 constexpr int kGroups = kTile / kDrawBlock;       // draw blocks per tile = lane groups per wave
+constexpr int kSlots = kStepWaves * kGroups;      // lane groups per workgroup
 constexpr int kRing = 4;                          // 16-byte loads kept in flight per lane
 constexpr float kRescaleAt = 64.0f;               // advance a lane's softmax reference when topped by 2^64
 
 struct StepArgs {
   const void* logits;
-  int64_t V, row_stride;
-  int ntiles, nblocks;
+  int64_t row_stride;
+  int32_t V, ntiles, nblocks;
   float inv_tau, k2;   // 1/temperature (fp32 division) and inv_tau * log2(e)
+  float margin_scale;  // scales the fp32 score margin (1 in production)
   uint32_t key0, key1;
   int32_t step;
   const float* values;
@@ -61,31 +66,21 @@ struct Raw {
   uint32_t w[kWords];
 };
 
-constexpr uint32_t kBf16NegInfPair = 0xFF80FF80u;
-constexpr uint32_t kF32NegInf = 0xFF800000u;
-
-// Lane's 8 consecutive elements starting at e0 (a multiple of 8) of a row; elements of a
-// 16-byte group that starts at or beyond V read as -inf.
 template <int DT>
-__device__ __forceinline__ Raw<DT> load_raw(const void* row, int64_t e0, int64_t V) {
+constexpr int elem_bytes() { return DT == ESPO_BF16 ? 2 : 4; }
+
+// The lane's 8 consecutive elements starting at element e0 (a multiple of 8, e0 < V).
+template <int DT>
+__device__ __forceinline__ Raw<DT> load_raw(const void* row, uint32_t e0, uint32_t V) {
   Raw<DT> r;
-  if constexpr (DT == ESPO_BF16) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r.w[i] = kBf16NegInfPair;
-    if (e0 < V) {
-      const u32x4 t = __builtin_nontemporal_load((const u32x4*)((const uint16_t*)row + e0));
-      r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) r.w[i] = kF32NegInf;
-    if (e0 < V) {
-      const u32x4 t = __builtin_nontemporal_load((const u32x4*)((const float*)row + e0));
-      r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
-    }
+  const char* p = (const char*)row + (size_t)(e0 * (uint32_t)elem_bytes<DT>());
+  const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
+  r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
+  if constexpr (DT == ESPO_F32) {  // the row pitch is a multiple of 4 floats only: guard the second half
+    r.w[4] = r.w[5] = r.w[6] = r.w[7] = 0xFF800000u;
     if (e0 + 4 < V) {
-      const u32x4 t = __builtin_nontemporal_load((const u32x4*)((const float*)row + e0 + 4));
-      r.w[4] = t.x; r.w[5] = t.y; r.w[6] = t.z; r.w[7] = t.w;
+      const u32x4 u = __builtin_nontemporal_load((const u32x4*)(p + 16));
+      r.w[4] = u.x; r.w[5] = u.y; r.w[6] = u.z; r.w[7] = u.w;
     }
   }
   return r;
@@ -106,101 +101,114 @@ __device__ __forceinline__ void unpack(const Raw<DT>& r, float x[8]) {
 }
 
 template <int DT>
-__device__ __forceinline__ float load_one(const void* row, int64_t v) {
+__device__ __forceinline__ float elem_at(const void* base, int64_t idx) {
   if constexpr (DT == ESPO_BF16)
-    return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)row)[v] << 16);
+    return __builtin_bit_cast(float, (uint32_t)((const uint16_t*)base)[idx] << 16);
   else
-    return ((const float*)row)[v];
+    return ((const float*)base)[idx];
 }
 
-// ---------------------------------------------------------------- exact evaluation
-struct Best {
-  double s;   // perturbed score y + G
-  int32_t v;  // vocabulary index, -1 = none yet
-  float x;    // its logit
+// ---------------------------------------------------------------- scores
+// A candidate for the argmax: score s = y + G known to within +-e, its index and logit.
+template <typename F>
+struct Cand {
+  F s;
+  float e;
+  int32_t v;
+  float x;
 };
 
-__device__ __forceinline__ bool better(double s, int32_t v, const Best& b) {
-  return s > b.s || (s == b.s && (uint32_t)v < (uint32_t)b.v);
-}
+// Running state of the search: the best candidate and `hi2`, the largest upper end s + e
+// among all other scored indices.  The winner is certain iff best.s - best.e > hi2.
+template <typename F>
+struct Search {
+  Cand<F> best;
+  F hi2;
+  __device__ __forceinline__ void init() {
+    best = Cand<F>{(F)-__builtin_huge_val(), 0.0f, -1, 0.0f};
+    hi2 = (F)-__builtin_huge_val();
+  }
+  __device__ __forceinline__ void offer(const Cand<F>& c) {
+    if (c.v < 0 || c.v == best.v) return;  // nothing, or the element that already leads
+    if (c.s > best.s || (c.s == best.s && (uint32_t)c.v < (uint32_t)best.v)) {
+      if (best.v >= 0) hi2 = hi2 > best.s + (F)best.e ? hi2 : best.s + (F)best.e;
+      best = c;
+    } else {
+      hi2 = hi2 > c.s + (F)c.e ? hi2 : c.s + (F)c.e;
+    }
+  }
+  __device__ __forceinline__ void merge(const Search& o) {
+    hi2 = hi2 > o.hi2 ? hi2 : o.hi2;
+    offer(o.best);
+  }
+  __device__ __forceinline__ F lower() const { return best.v >= 0 ? best.s - (F)best.e : (F)-__builtin_huge_val(); }
+};
 
-__device__ __forceinline__ Best wave_best(Best b) {
+template <typename F>
+__device__ __forceinline__ Search<F> wave_merge(Search<F> s) {
 #pragma unroll
   for (int off = 32; off >= 1; off >>= 1) {
-    Best o;
-    o.s = __shfl_xor(b.s, off);
-    o.v = __shfl_xor(b.v, off);
-    o.x = __shfl_xor(b.x, off);
-    if (better(o.s, o.v, b)) b = o;
+    Search<F> o;
+    o.best.s = __shfl_xor(s.best.s, off);
+    o.best.e = __shfl_xor(s.best.e, off);
+    o.best.v = __shfl_xor(s.best.v, off);
+    o.best.x = __shfl_xor(s.best.x, off);
+    o.hi2 = __shfl_xor(s.hi2, off);
+    s.merge(o);
   }
-  return b;
+  return s;
 }
 
-struct BlockDraw {
-  double M, emM;  // largest Gumbel variate of the block and exp(-M)
-  int64_t vpos;   // vocabulary index that receives it
-};
+// -ln u(word) in the working precision.  fp32: |ln u| >= ln 2 for u < 1/2, and log1p keeps
+// full relative accuracy for u >= 1/2 (1 - u is exact in fp32).
+template <typename F>
+__device__ __forceinline__ F neg_log_uniform(uint32_t word);
+template <>
+__device__ __forceinline__ double neg_log_uniform<double>(uint32_t word) { return -log(uniform_f64(word)); }
+template <>
+__device__ __forceinline__ float neg_log_uniform<float>(uint32_t word) {
+  const uint32_t r = word >> 9;
+  if (r < (1u << 22)) return -logf((float)(2u * r + 1u) * (1.0f / 16777216.0f));
+  return -log1pf(-((float)(16777215u - 2u * r) * (1.0f / 16777216.0f)));
+}
+__device__ __forceinline__ float flog(float x) { return logf(x); }
+__device__ __forceinline__ double flog(double x) { return log(x); }
+__device__ __forceinline__ float fexp(float x) { return expf(x); }
+__device__ __forceinline__ double fexp(double x) { return exp(x); }
 
-__device__ __forceinline__ BlockDraw block_draw(const StepArgs& a, int row, int q) {
-  const int64_t first = (int64_t)q * kDrawBlock;
-  const int64_t n = (a.V - first < kDrawBlock) ? a.V - first : kDrawBlock;
-  const Philox4 p = philox4x32_10((uint32_t)q, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
-  BlockDraw d;
-  d.M = log((double)n) - log(-log(uniform_f64(p.w[0])));
-  d.emM = exp(-d.M);
-  d.vpos = first + (int64_t)(((uint64_t)p.w[1] * (uint64_t)n) >> 32);
-  return d;
+// Error margin of an fp32 score y + G.  The library functions used (logf, log1pf, expf)
+// are accurate to 3 ulp; propagated through M_q = ln n - ln(-ln u), exp(-M_q) and
+// G = -ln(exp(-M_q) - ln u) this gives |G32 - G| < 1e-5 for |G| <= 24, and the product and
+// sum forming y + G add 2^-23 (|y| + |G|).  The margin below is four times that.
+__device__ __forceinline__ float score_margin(const StepArgs& a, float y) {
+  return a.margin_scale * (4e-5f + 2.5e-7f * fabsf(y));
 }
 
-// G_v of the stream definition, in double.
-__device__ __forceinline__ double gumbel_at(const StepArgs& a, int row, int64_t v, const BlockDraw& d) {
-  if (v == d.vpos) return d.M;
-  const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
-  const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
-  return -log(d.emM - log(uniform_f64(w)));
-}
-
-// Exact evaluation of up to 8 blocks by one wave: lane group g (8 lanes x 8 indices) takes
-// block q (q < 0: the group idles).  Only indices with y_v + M_q >= bound can beat a score
-// `bound` that some index is already known to attain (G_v <= M_q), so the rest are skipped.
-// `best` is the lane's running best; the lane's bound rises as scores are found.  Pass 0
-// scores each lane's largest logit and shares the best of the group's 8 scores, passes 1..7
-// take the lane's other indices in order.  One evaluation site and no unrolling: this code
-// runs a few times per row and should stay small.
-template <int DT>
-__device__ __forceinline__ void visit_blocks(const StepArgs& a, const void* rowp, int row, int q, double bound, Best& best) {
+// Scores the 64 indices of block q, one per lane.  `data` points at the block's 64 elements
+// (LDS copy or the row itself).  Only indices whose upper bound y + M_q (+ margins) reaches
+// `bound` can beat a score that is already known to be attained, the rest are skipped.
+template <int DT, typename F>
+__device__ __forceinline__ void visit_block(const StepArgs& a, int row, int q, const void* data, F bound, Search<F>& st) {
   const int lane = threadIdx.x & (kWave - 1);
-  const bool active = q >= 0;
-  const BlockDraw d = block_draw(a, row, active ? q : 0);
-  const int64_t v0 = active ? (int64_t)q * kDrawBlock + (lane & 7) * 8 : a.V;
-  const double itau = (double)a.inv_tau;
-  float x[8];
-  unpack<DT>(load_raw<DT>(rowp, v0, a.V), x);
-  float xt = kNegInf;
-  int jt = 0;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    if (v0 + j >= a.V) x[j] = kNegInf;
-    if (x[j] > xt) { xt = x[j]; jt = j; }
-  }
-#pragma unroll 1
-  for (int pass = 0; pass < 8; ++pass) {
-    const int j = pass == 0 ? jt : (pass <= jt ? pass - 1 : pass);
-    float xj = x[0];
-#pragma unroll
-    for (int k = 1; k < 8; ++k) xj = (j == k) ? x[k] : xj;
-    const int64_t v = v0 + j;
-    const double y = (double)xj * itau;
-    if (xj > kNegInf && y + d.M >= bound) {   // masked (-inf) entries never win
-      const double s = y + gumbel_at(a, row, v, d);
-      if (better(s, (int32_t)v, best)) best = Best{s, (int32_t)v, xj};
-      bound = fmax(bound, s);
-    }
-    if (pass == 0) {  // share the best of the group's 8 lane maxima before looking at the rest
-      double top = bound;
-#pragma unroll
-      for (int off = 4; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
-      bound = top;
+  const int32_t first = q * kDrawBlock;
+  const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
+  const Philox4 pb = philox4x32_10((uint32_t)q, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
+  const F M = flog((F)n) - flog(neg_log_uniform<F>(pb.w[0]));       // largest variate of the block
+  const F emM = fexp(-M);
+  const int32_t vpos = first + (int32_t)(((uint64_t)pb.w[1] * (uint64_t)n) >> 32);  // index that receives it
+  if (lane < n) {
+    const int32_t v = first + lane;
+    const float x = elem_at<DT>(data, lane);
+    const F y = (F)x * (F)a.inv_tau;
+    const float e = sizeof(F) == 4 ? score_margin(a, (float)y) : 0.0f;
+    if (x > kNegInf && (y + M) + (F)(2.0f * e) >= bound) {   // masked (-inf) entries never win
+      F G = M;
+      if (v != vpos) {
+        const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
+        const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
+        G = -flog(emM + neg_log_uniform<F>(w));
+      }
+      st.offer(Cand<F>{y + G, e, v, x});
     }
   }
 }
@@ -225,9 +233,146 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, flo
   return ChainOut{g, zn, a.stop_enabled && (zn > thr)};             // Eq. stop_rule (strict)
 }
 
+// ---------------------------------------------------------------- shared memory
+struct StepShared {
+  float* ub;        // [nslots] bound per block slot (tile * 8 + group)
+  int* surv;        // [nslots] survivor list
+  void* top_raw;    // [kSlots][64 elements] data of each lane group's best block
+  int* top_q;       // [kSlots] which block each lane group kept
+  float* m;         // [kStepWaves] wave maxima
+  float* sum;       // [kStepWaves] wave softmax sums (relative to the row maximum)
+  double* res_s;    // [kStepWaves] per-wave search results
+  double* res_hi2;
+  float* res_e;
+  int* res_v;
+  float* res_x;
+  float* lo;        // [kStepWaves] score each wave knows to be attained
+  int* visq;        // [kStepWaves] block each wave scored before the first barrier, or -1
+  int* nsurv;       // [1]
+  int* mshared;     // [1] largest wave maximum published so far (order-preserving int key)
+};
+
+template <int DT>
+__device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
+  StepShared s;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { void* p = base + off; off += (bytes + 15) & ~(size_t)15; return p; };
+  s.res_s = (double*)take(kStepWaves * 8);
+  s.res_hi2 = (double*)take(kStepWaves * 8);
+  s.top_raw = take((size_t)kSlots * kDrawBlock * elem_bytes<DT>());
+  s.top_q = (int*)take(kSlots * 4);
+  s.m = (float*)take(kStepWaves * 4);
+  s.sum = (float*)take(kStepWaves * 4);
+  s.res_e = (float*)take(kStepWaves * 4);
+  s.res_v = (int*)take(kStepWaves * 4);
+  s.res_x = (float*)take(kStepWaves * 4);
+  s.lo = (float*)take(kStepWaves * 4);
+  s.visq = (int*)take(kStepWaves * 4);
+  s.nsurv = (int*)take(16);
+  s.mshared = s.nsurv + 1;
+  s.ub = (float*)take((size_t)nslots * 4);
+  s.surv = (int*)take((size_t)nslots * 4);
+  return s;
+}
+
+size_t step_lds_bytes(int dt, int ntiles) {
+  const size_t esz = dt == ESPO_BF16 ? 2 : 4;
+  const size_t nslots = (size_t)ntiles * kGroups;
+  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 7 * kStepWaves * 4 + 16 +
+         2 * ((nslots * 4 + 15) & ~(size_t)15);
+}
+
+// Slot (wave, group) that streamed block q in phase 1.
+__device__ __forceinline__ int slot_of(int q) { return ((q >> 3) & (kStepWaves - 1)) * kGroups + (q & (kGroups - 1)); }
+
+// ---------------------------------------------------------------- phase 2
+__device__ __forceinline__ int float_key(float f) {  // order-preserving map to signed int
+  const int b = __builtin_bit_cast(int, f);
+  return b >= 0 ? b : b ^ 0x7fffffff;
+}
+
+template <typename F>
+__device__ __forceinline__ float round_down_f32(F v) {
+  float f = (float)v;
+  if ((F)f > v) f = __builtin_bit_cast(float, __builtin_bit_cast(int32_t, f) + (f > 0.0f ? -1 : 1));
+  if (f == 0.0f && v < (F)0) f = -1e-37f;
+  return f;
+}
+
+// Finds the argmax over the row in precision F.  `bound0` is a score that is known to be
+// attained or exceeded (prunes from the start); `q_own` is the block this wave scores
+// first, without waiting for the others (or -1).  Every block whose bound reaches the best
+// score found that way is then scored, one block per wave visit.  `between` runs right
+// after the first barrier.  Returns the winner, the same in every thread; all threads of
+// the workgroup must call it.
+template <int DT, typename F, typename Between>
+__device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepShared& sh, const void* rowp, int row,
+                                                 int nslots, int q_own, F bound0, Between between) {
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  auto data_of = [&](int q) -> const void* {  // LDS copy if a lane group kept this block, else the row
+    const int slot = slot_of(q);
+    if (sh.top_q[slot] == q) return (const char*)sh.top_raw + (size_t)slot * kDrawBlock * elem_bytes<DT>();
+    return (const char*)rowp + (size_t)q * kDrawBlock * elem_bytes<DT>();
+  };
+  Search<F> st;
+  st.init();
+  F bound = bound0;
+  if (q_own >= 0) {
+    visit_block<DT, F>(a, row, q_own, data_of(q_own), bound, st);
+    st = wave_merge(st);
+    const F lo = st.lower();
+    bound = bound > lo ? bound : lo;
+  }
+  if (lane == 0) {
+    sh.lo[wave] = round_down_f32(bound);  // rounded down: a shared bound must never overshoot
+    sh.visq[wave] = q_own;
+  }
+  if (tid == 0) *sh.nsurv = 0;
+  __syncthreads();
+  between();
+  float bound_f = sh.lo[0];
+#pragma unroll
+  for (int w = 1; w < kStepWaves; ++w) bound_f = fmaxf(bound_f, sh.lo[w]);
+  for (int q = tid; q < nslots; q += kStepThreads) {
+    const float u = sh.ub[q];
+    if (u > kNegInf && u >= bound_f && sh.visq[(q >> 3) & (kStepWaves - 1)] != q) sh.surv[atomicAdd(sh.nsurv, 1)] = q;
+  }
+  __syncthreads();
+  const int nsurv = *sh.nsurv;
+  bound = bound > (F)bound_f ? bound : (F)bound_f;
+#pragma unroll 1
+  for (int k = wave; k < nsurv; k += kStepWaves) {
+    const int q = sh.surv[k];
+    visit_block<DT, F>(a, row, q, data_of(q), bound, st);
+    st = wave_merge(st);
+    const F lo = st.lower();
+    bound = bound > lo ? bound : lo;
+  }
+  if (lane == 0) {
+    sh.res_s[wave] = (double)st.best.s;
+    sh.res_hi2[wave] = (double)st.hi2;
+    sh.res_e[wave] = st.best.e;
+    sh.res_v[wave] = st.best.v;
+    sh.res_x[wave] = st.best.x;
+  }
+  __syncthreads();
+  Search<F> all;
+  all.init();
+#pragma unroll 1
+  for (int w = 0; w < kStepWaves; ++w) {  // fixed order: deterministic
+    Search<F> o;
+    o.best = Cand<F>{(F)sh.res_s[w], sh.res_e[w], sh.res_v[w], sh.res_x[w]};
+    o.hi2 = (F)sh.res_hi2[w];
+    all.merge(o);
+  }
+  return all;
+}
+
 // ---------------------------------------------------------------- the kernel
 template <int DT>
-__global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
+__global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
@@ -244,42 +389,33 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
   const int grp = lane >> 3;
   const int ntiles = a.ntiles;
   const int nslots = ntiles * kGroups;  // block slots incl. the non-existent ones of the last tile
-
-  // LDS: ub[nslots] | surv[nslots] | per-wave partials | scalars
-  float* s_ub = (float*)smem_raw;
-  int* s_surv = (int*)(s_ub + nslots);
-  double* s_best_s = (double*)(smem_raw + (((size_t)nslots * 8 + 15) & ~(size_t)15));
-  int* s_best_v = (int*)(s_best_s + kStepWaves);
-  float* s_best_x = (float*)(s_best_v + kStepWaves);
-  float* s_m = s_best_x + kStepWaves;
-  float* s_sum = s_m + kStepWaves;
-  float* s_top_ub = s_sum + kStepWaves;            // [16 waves][8 groups]: largest bound seen
-  int* s_top_q = (int*)(s_top_ub + kStepWaves * kGroups);
-  float* s_bound = (float*)(s_top_q + kStepWaves * kGroups);
-  int* s_nsurv = (int*)(s_bound + 1);
-
-  const void* rowp = DT == ESPO_BF16 ? (const void*)((const uint16_t*)a.logits + (int64_t)row * a.row_stride)
-                                     : (const void*)((const float*)a.logits + (int64_t)row * a.row_stride);
+  const StepShared sh = carve<DT>(smem_raw, nslots);
+  const void* rowp = (const char*)a.logits + (size_t)row * (size_t)a.row_stride * elem_bytes<DT>();
 
   // ------------------------------------------------------------ phase 1: stream the row
-  const int nit = (ntiles + kStepWaves - 1) / kStepWaves;  // wave iteration `it` handles tile it*16 + wave
+  // Wave iteration i handles tile i*16 + wave.  Lanes whose 16-byte group starts at or beyond
+  // V (last tile only) read the last valid group instead and are masked below.
+  const int my_tiles = wave < ntiles ? (ntiles - wave + kStepWaves - 1) / kStepWaves : 0;
+  const uint32_t last_group = (uint32_t)(a.V - 1) & ~7u;
+  const uint32_t lane_off = (uint32_t)lane * 8u;
   Raw<DT> ring[kRing];
 #pragma unroll
-  for (int d = 0; d < kRing; ++d) {
-    const int t = d * kStepWaves + wave;
-    ring[d] = load_raw<DT>(rowp, (d < nit && t < ntiles) ? (int64_t)t * kTile + lane * 8 : a.V, a.V);
-  }
+  for (int d = 0; d < kRing; ++d)
+    if (d < my_tiles) {
+      const uint32_t e0 = (uint32_t)(d * kStepWaves + wave) * kTile + lane_off;
+      ring[d] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
+    }
   // While the first loads are in flight: M_q bounds of all blocks, one Philox call each.
   for (int b = tid; b < nslots; b += kStepThreads) {
     float mub = kNegInf;
     if (b < a.nblocks) {
-      const int64_t n = a.V - (int64_t)b * kDrawBlock < kDrawBlock ? a.V - (int64_t)b * kDrawBlock : kDrawBlock;
+      const int32_t n = a.V - b * kDrawBlock < kDrawBlock ? a.V - b * kDrawBlock : kDrawBlock;
       const Philox4 p = philox4x32_10((uint32_t)b, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
       mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[0]);
     }
-    s_ub[b] = mub;
+    sh.ub[b] = mub;
   }
-  if (tid == 0) *s_nsurv = 0;
+  if (tid == 0) *sh.mshared = float_key(kNegInf);
   __syncthreads();
 
   // Softmax sum against a lazily advanced per-lane reference: the lane accumulates
@@ -287,138 +423,108 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
   // by 2^-(m k2 + nrk), so the rounding of nrk itself cancels.
   float nrk = 1e30f;
   float sum = 0.0f;
-  float m_l = kNegInf;       // lane's running maximum logit
-  float top_ub = kNegInf;    // largest block bound this lane group has produced, and its block
+  float top_bm = kNegInf;    // largest block maximum this lane group has seen, and its block
   int top_q = -1;
+  char* const my_raw = (char*)sh.top_raw + ((size_t)(wave * kGroups + grp) * kDrawBlock + (lane & 7) * 8) * elem_bytes<DT>();
 
-  for (int it0 = 0; it0 < nit; it0 += kRing) {
+#pragma unroll 1
+  for (int i0 = 0; i0 < my_tiles; i0 += kRing) {
 #pragma unroll
     for (int d = 0; d < kRing; ++d) {
-      const int it = it0 + d;
-      if (it >= nit) break;
-      const int t = it * kStepWaves + wave;
-      float x[8];
-      unpack<DT>(ring[d], x);
-      {  // refill this ring slot
-        const int tn = t + kRing * kStepWaves;
-        ring[d] = load_raw<DT>(rowp, (it + kRing < nit && tn < ntiles) ? (int64_t)tn * kTile + lane * 8 : a.V, a.V);
-      }
-      if (t >= ntiles) continue;  // wave-uniform
-      const int64_t e0 = (int64_t)t * kTile + lane * 8;
-      if ((int64_t)(t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
+      const int i = i0 + d;
+      if (i < my_tiles) {  // wave-uniform
+        const int t = i * kStepWaves + wave;
+        const Raw<DT> cur = ring[d];
+        if (i + kRing < my_tiles) {  // refill this ring slot
+          const uint32_t en = (uint32_t)(t + kRing * kStepWaves) * kTile + lane_off;
+          ring[d] = load_raw<DT>(rowp, en < last_group ? en : last_group, (uint32_t)a.V);
+        }
+        float x[8];
+        unpack<DT>(cur, x);
+        if ((t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
+          const int32_t e0 = t * kTile + (int32_t)lane_off;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          if (e0 + j >= a.V) x[j] = kNegInf;
-      }
-      const float gm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-      m_l = fmaxf(m_l, gm);
-      if (fmaf(gm, a.k2, nrk) > kRescaleAt) {  // rare: move this lane's reference up to gm
-        const float nrk_new = -gm * a.k2;
-        sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
-        nrk = nrk_new;
-      }
-      float acc0 = 0.0f, acc1 = 0.0f;
+          for (int j = 0; j < 8; ++j)
+            if (e0 + j >= a.V) x[j] = kNegInf;
+        }
+        const float gm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        if (fmaf(gm, a.k2, nrk) > kRescaleAt) {  // rare: move this lane's reference up to gm
+          const float nrk_new = -gm * a.k2;
+          sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
+          nrk = nrk_new;
+        }
+        float acc0 = 0.0f, acc1 = 0.0f;
 #pragma unroll
-      for (int j = 0; j < 8; j += 2) {
-        acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
-        acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
+        for (int j = 0; j < 8; j += 2) {
+          acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
+          acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
+        }
+        sum += acc0 + acc1;
+        // upper bound of every perturbed score in the lane group's block: y_max + M_q, rounded up
+        const float bm = group8_max(gm);
+        const int q = t * kGroups + grp;
+        const float mub = sh.ub[q];
+        const float ym = bm * a.inv_tau;
+        const float ub = ym + mub + (1e-5f + 4e-7f * (fminf(fabsf(ym), 1e30f) + fabsf(mub)));
+        sh.ub[q] = ub;  // the 8 lanes of the group store the same value
+        if (bm > top_bm) {  // keep the data of the block that holds the group's largest logit
+          top_bm = bm;
+          top_q = q;
+          *(u32x4*)my_raw = u32x4{cur.w[0], cur.w[1], cur.w[2], cur.w[3]};
+          if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{cur.w[4], cur.w[5], cur.w[6], cur.w[7]};
+        }
       }
-      sum += acc0 + acc1;
-      // upper bound of every perturbed score in the lane group's block: y_max + M_q, rounded up
-      const float bm = group8_max(gm);
-      const int q = t * kGroups + grp;
-      const float mub = s_ub[q];
-      const float ym = bm * a.inv_tau;
-      const float ub = ym + mub + (1e-5f + 4e-7f * (fminf(fabsf(ym), 1e30f) + fabsf(mub)));
-      s_ub[q] = ub;  // the 8 lanes of the group store the same value
-      if (ub > top_ub) { top_ub = ub; top_q = q; }
     }
   }
-  {
-    const float m_w = wave_max(m_l);
-    if (lane == 0) s_m[wave] = m_w;
-    if ((lane & 7) == 0) {
-      s_top_ub[wave * kGroups + grp] = top_ub;
-      s_top_q[wave * kGroups + grp] = top_q;
-    }
-  }
-  __syncthreads();
-  float m = s_m[0];  // row maximum
+  // The wave's largest logit and the block that holds it (lowest block among equals).
+  float bmw = top_bm;
+  int qw = top_q;
 #pragma unroll
-  for (int w = 1; w < kStepWaves; ++w) m = fmaxf(m, s_m[w]);
+  for (int off = 32; off >= 8; off >>= 1) {
+    const float ob = __shfl_xor(bmw, off);
+    const int oq = __shfl_xor(qw, off);
+    if (ob > bmw || (ob == bmw && (uint32_t)oq < (uint32_t)qw)) { bmw = ob; qw = oq; }
+  }
+  if (lane == 0) sh.m[wave] = bmw;
+  if ((lane & 7) == 0) sh.top_q[wave * kGroups + grp] = top_q;
+  // Waves whose maximum is close to the largest one published so far score their block right
+  // away; this only decides how much work is spent, never the result.
+  int q_own = -1;
   {
+    int seen = float_key(bmw);
+    if (lane == 0) seen = max(atomicMax(sh.mshared, seen), seen);
+    seen = __builtin_amdgcn_readfirstlane(seen);
+    const float seen_f = __builtin_bit_cast(float, seen >= 0 ? seen : seen ^ 0x7fffffff);
+    if (qw >= 0 && (bmw - seen_f) * a.inv_tau >= -2.0f) q_own = qw;
+  }
+  __builtin_amdgcn_s_waitcnt(0);  // the lane groups' saved blocks must be in LDS before this wave reads them
+
+  // ------------------------------------------------------------ phase 2: argmax of y + G
+  float m = kNegInf;
+  auto softmax_sum = [&]() {  // after the first barrier: row maximum, then the wave's share of the sum
+    m = sh.m[0];
+#pragma unroll
+    for (int w = 1; w < kStepWaves; ++w) m = fmaxf(m, sh.m[w]);
     const float part = sum > 0.0f ? sum * __builtin_amdgcn_exp2f(-fmaf(m, a.k2, nrk)) : 0.0f;
     const float tot = wave_sum(part);
-    if (lane == 0) s_sum[wave] = tot;
+    if (lane == 0) sh.sum[wave] = tot;
+  };
+  const Search<float> fast = find_argmax<DT, float>(a, sh, rowp, row, nslots, q_own, kNegInf, softmax_sum);
+  int32_t tok = fast.best.v;
+  float x_a = fast.best.x;
+  if (fast.best.v >= 0 && !(fast.best.s - fast.best.e > fast.hi2)) {
+    // the two best fp32 scores overlap within their margins: decide in double (rare)
+    __syncthreads();  // everyone has read the fp32 results
+    const Search<double> exact = find_argmax<DT, double>(a, sh, rowp, row, nslots, q_own, (double)fast.lower(), [] {});
+    tok = exact.best.v;
+    x_a = exact.best.x;
   }
-
-  // ------------------------------------------------------------ phase 2: exact argmax
-  // Round 0: wave 0 evaluates eight strong blocks at once (lane group g takes the best block
-  // that any wave's group g has seen; the block with the largest bound overall is among
-  // them).  Their best score rules out every block whose bound is lower.  Round 1: the
-  // survivors, eight per wave visit.
-  Best best{-__builtin_huge_val(), -1, 0.0f};
-  double bound = -__builtin_huge_val();
-  if (wave == 0) {
-    const int j = lane & 7;
-    float u0 = s_top_ub[j * kGroups + grp], u1 = s_top_ub[(j + 8) * kGroups + grp];
-    int q0 = s_top_q[j * kGroups + grp], q1 = s_top_q[(j + 8) * kGroups + grp];
-    if (u1 > u0 || (u1 == u0 && (uint32_t)q1 < (uint32_t)q0)) { u0 = u1; q0 = q1; }
-#pragma unroll
-    for (int off = 4; off >= 1; off >>= 1) {
-      const float ou = __shfl_xor(u0, off);
-      const int oq = __shfl_xor(q0, off);
-      if (ou > u0 || (ou == u0 && (uint32_t)oq < (uint32_t)q0)) { u0 = ou; q0 = oq; }
-    }
-    visit_blocks<DT>(a, rowp, row, q0, bound, best);
-    double top = best.s;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
-    bound = top;
-    if (q0 >= 0 && j == 0) s_ub[q0] = kNegInf;  // visited: keep it off the survivor list
-    if (lane == 0) {
-      float lf = (float)bound;  // round the shared bound down so that it never overshoots
-      if ((double)lf > bound) lf = __builtin_bit_cast(float, __builtin_bit_cast(int32_t, lf) + (lf > 0.0f ? -1 : 1));
-      if (lf == 0.0f && bound < 0.0) lf = -1e-37f;
-      s_bound[0] = lf;
-    }
-  }
-  __syncthreads();
-  const float bound_f = s_bound[0];
-  for (int q = tid; q < nslots; q += kStepThreads) {
-    const float u = s_ub[q];
-    if (u > kNegInf && u >= bound_f) s_surv[atomicAdd(s_nsurv, 1)] = q;
-  }
-  __syncthreads();
-  const int nsurv = *s_nsurv;
-  bound = fmax(bound, (double)bound_f);
-#pragma unroll 1
-  for (int k0 = wave * kGroups; k0 < nsurv; k0 += kStepWaves * kGroups) {
-    visit_blocks<DT>(a, rowp, row, (k0 + grp < nsurv) ? s_surv[k0 + grp] : -1, bound, best);
-    double top = best.s;
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) top = fmax(top, __shfl_xor(top, off));
-    bound = fmax(bound, top);
-  }
-  best = wave_best(best);
-  if (lane == 0) {
-    s_best_s[wave] = best.s;
-    s_best_v[wave] = best.v;
-    s_best_x[wave] = best.x;
-  }
-  __syncthreads();
 
   // ------------------------------------------------------------ finalize: one lane
   if (tid == 0) {
-    Best win{s_best_s[0], s_best_v[0], s_best_x[0]};
-    for (int w = 1; w < kStepWaves; ++w)
-      if (s_best_v[w] >= 0 && better(s_best_s[w], s_best_v[w], win)) win = Best{s_best_s[w], s_best_v[w], s_best_x[w]};
     float S = 0.0f;  // sum_v exp((x_v - m)/tau), waves combined in a fixed order
-    for (int w = 0; w < kStepWaves; ++w) S += s_sum[w];
-    int32_t tok = win.v;
-    float x_a = win.x;
-    if (tok < 0) { tok = 0; x_a = load_one<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
-
+    for (int w = 0; w < kStepWaves; ++w) S += sh.sum[w];
+    if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
     const ChainOut c = scalar_chain(a, m, x_a, a.z[row], a.values[row]);
     a.tokens[row] = tok;
     a.regret[row] = c.g;
@@ -433,24 +539,23 @@ __global__ __launch_bounds__(kStepThreads) void espo_step_kernel(StepArgs a) {
   }
 }
 
-size_t step_lds_bytes(int ntiles) {
-  return (((size_t)ntiles * kGroups * 8 + 15) & ~(size_t)15) + kStepWaves * (8 + 4 + 4 + 4 + 4) + kStepWaves * kGroups * 8 + 16;
-}
-
 }  // namespace
 
+size_t step_shared_bytes(int dt, int64_t V) { return step_lds_bytes(dt, (int)((V + kTile - 1) / kTile)); }
+
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
-                uint64_t seed, int32_t step, const float* values, const espo_params& p, float* z,
-                uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
+                uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
+                float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
                 hipStream_t stream) {
   StepArgs a;
   a.logits = logits;
-  a.V = V;
+  a.V = (int32_t)V;
   a.row_stride = row_stride;
   a.ntiles = (int)((V + kTile - 1) / kTile);
   a.nblocks = (int)((V + kDrawBlock - 1) / kDrawBlock);
   a.inv_tau = 1.0f / temperature;
   a.k2 = a.inv_tau * kLog2e;
+  a.margin_scale = margin_scale;
   a.key0 = (uint32_t)(seed & 0xffffffffu);
   a.key1 = (uint32_t)(seed >> 32);
   a.step = step;
@@ -470,7 +575,7 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.tokens = tokens;
   a.regret = regret;
   a.logprob = logprob;
-  const size_t lds = step_lds_bytes(a.ntiles);
+  const size_t lds = step_lds_bytes(dt, a.ntiles);
   if (lds > kMaxStepLds) return ESPO_ERANGE;
   const dim3 grid((unsigned)B), block(kStepThreads);
   if (dt == ESPO_BF16)
