@@ -77,9 +77,12 @@ typedef struct {
  *      one random number.  With u(w) = (2 (w >> 9) + 1) / 2^24 and
  *      key = (seed & 0xffffffff, seed >> 32):
  *        block q = v / 64 holds n_q = min(64, V - 64 q) indices;
- *        (w0, w1) = words 0, 1 of Philox(counter = (q, step, b, 0x4553504F), key);
- *        M_q   = ln n_q - ln(-ln u(w0))       the largest variate of the block,
- *        pos_q = (w1 * n_q) >> 32             the index (within the block) that gets it;
+ *        w     = word (q & 3) of Philox(counter = (q >> 2, step, b, 0x4553504F), key);
+ *        M_q   = ln n_q - ln(-ln u(w))        the largest variate of the block,
+ *        pos_q = (w >> 3) & 63                the index (within the block) that gets it
+ *                (bits that u(w) does not use); a ragged last block (n_q < 64) takes
+ *                pos_q = (w' * n_q) >> 32 with w' = word 0 of
+ *                Philox(counter = (q, step, b, 0x52414747), key) instead;
  *        w_v   = word (v & 3) of Philox(counter = (v >> 2, step, b, 0x6573706F), key);
  *        G_v   = M_q                           if v = 64 q + pos_q,
  *              = -ln(exp(-M_q) - ln u(w_v))    otherwise.

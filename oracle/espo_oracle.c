@@ -75,9 +75,11 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
  * Gumbel shifted by ln n; the position of the maximum, uniform; and the others, iid
  * Gumbel truncated to (-inf, M) -- Maddison, Tarlow & Minka, "A* sampling", 2014):
  *   block q = v / 64 holds indices [64 q, min(64 q + 64, V)), n_q of them;
- *   (w0, w1) = words 0, 1 of Philox(counter = (q, step, row, TAG_BLOCK), key = seed);
- *   M_q   = ln n_q - ln(-ln u(w0))          maximum of the block's variates
- *   pos_q = (w1 * n_q) >> 32                 which index of the block attains it
+ *   w     = word (q & 3) of Philox(counter = (q >> 2, step, row, TAG_BLOCK), key = seed);
+ *   M_q   = ln n_q - ln(-ln u(w))            maximum of the block's variates
+ *   pos_q = (w >> 3) & 63                     which index of the block attains it (n_q = 64;
+ *           the ragged last block takes (w' * n_q) >> 32 with w' = word 0 of
+ *           Philox(counter = (q, step, row, TAG_RAGGED), key = seed) instead)
  *   w_v   = word (v & 3) of Philox(counter = (v >> 2, step, row, TAG_ELEM), key = seed)
  *   G_v   = M_q                               if v = 64 q + pos_q
  *         = -ln(exp(-M_q) - ln u(w_v))        otherwise (inverse cdf of the truncation)
@@ -85,6 +87,7 @@ void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t
  */
 #define ORACLE_TAG_BLOCK 0x4553504Fu
 #define ORACLE_TAG_ELEM 0x6573706Fu
+#define ORACLE_TAG_RAGGED 0x52414747u
 #define ORACLE_BLOCK 64
 
 /* u in (0,1): the top 23 bits r of the word give u = (2r+1)/2^24. */
@@ -108,12 +111,19 @@ uint32_t oracle_stream_word(uint64_t seed, int64_t row, int32_t step, int64_t v)
 /* Maximum M_q of block q (which holds n indices) and the offset pos_q that attains it. */
 void oracle_block_draw(uint64_t seed, int64_t row, int32_t step, int64_t q, int64_t n,
                        double* M, int64_t* pos) {
-  uint32_t ctr[4] = {(uint32_t)q, (uint32_t)step, (uint32_t)row, ORACLE_TAG_BLOCK};
+  uint32_t ctr[4] = {(uint32_t)(q >> 2), (uint32_t)step, (uint32_t)row, ORACLE_TAG_BLOCK};
   uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
   uint32_t out[4];
   oracle_philox4x32_10(ctr, key, out);
-  *M = log((double)n) + oracle_gumbel(out[0]);
-  *pos = (int64_t)(((uint64_t)out[1] * (uint64_t)n) >> 32);
+  const uint32_t w = out[q & 3];
+  *M = log((double)n) + oracle_gumbel(w);               /* top 23 bits of w */
+  if (n == ORACLE_BLOCK) {
+    *pos = (int64_t)((w >> 3) & 63u);                    /* six of the bits u(w) does not use */
+  } else {                                               /* the ragged last block: own draw */
+    uint32_t ctr2[4] = {(uint32_t)q, (uint32_t)step, (uint32_t)row, ORACLE_TAG_RAGGED};
+    oracle_philox4x32_10(ctr2, key, out);
+    *pos = (int64_t)(((uint64_t)out[0] * (uint64_t)n) >> 32);
+  }
 }
 
 /* G_v for an index v of the block that starts at `first` and drew (M, pos). */

@@ -51,10 +51,14 @@ __device__ __forceinline__ float wave_sum(float v) {
 // Maximum over each aligned group of 8 lanes, returned to all 8 (xor-butterfly: swap within
 // pairs, swap pairs within quads, mirror the two quads of the group).
 constexpr int kDppQuadXor1 = 0xB1, kDppQuadXor2 = 0x4E, kDppHalfMirror = 0x141;
+template <int Ctrl>
+__device__ __forceinline__ float dpp_all_lanes(float v) {  // every lane has a source: no fill value needed
+  return __builtin_bit_cast(float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), Ctrl, 0xf, 0xf, true));
+}
 __device__ __forceinline__ float group8_max(float v) {
-  v = fmaxf(v, dpp_f32<kDppQuadXor1, 0xf>(v, v));
-  v = fmaxf(v, dpp_f32<kDppQuadXor2, 0xf>(v, v));
-  v = fmaxf(v, dpp_f32<kDppHalfMirror, 0xf>(v, v));
+  v = fmaxf(v, dpp_all_lanes<kDppQuadXor1>(v));
+  v = fmaxf(v, dpp_all_lanes<kDppQuadXor2>(v));
+  v = fmaxf(v, dpp_all_lanes<kDppHalfMirror>(v));
   return v;
 }
 
@@ -86,6 +90,7 @@ __device__ __forceinline__ Philox4 philox4x32_10(uint32_t c0, uint32_t c1, uint3
 
 constexpr uint32_t kTagBlock = 0x4553504Fu;  // counter word 3 of the per-block draw
 constexpr uint32_t kTagElem = 0x6573706Fu;   // counter word 3 of the per-index draw
+constexpr uint32_t kTagRagged = 0x52414747u; // counter word 3 of the position draw of a ragged last block
 constexpr int kDrawBlock = 64;               // vocabulary indices per block of the draw
 
 // u = (2r+1)/2^24 with r the top 23 bits of the word: never 0 or 1, exact in fp32.

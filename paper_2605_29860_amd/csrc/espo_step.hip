@@ -192,10 +192,15 @@ __device__ __forceinline__ void visit_block(const StepArgs& a, int row, int q, c
   const int lane = threadIdx.x & (kWave - 1);
   const int32_t first = q * kDrawBlock;
   const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
-  const Philox4 pb = philox4x32_10((uint32_t)q, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
-  const F M = flog((F)n) - flog(neg_log_uniform<F>(pb.w[0]));       // largest variate of the block
+  const Philox4 pb = philox4x32_10((uint32_t)(q >> 2), (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
+  const uint32_t wb = (q & 3) == 0 ? pb.w[0] : (q & 3) == 1 ? pb.w[1] : (q & 3) == 2 ? pb.w[2] : pb.w[3];
+  const F M = flog((F)n) - flog(neg_log_uniform<F>(wb));            // largest variate of the block
   const F emM = fexp(-M);
-  const int32_t vpos = first + (int32_t)(((uint64_t)pb.w[1] * (uint64_t)n) >> 32);  // index that receives it
+  int32_t vpos = first + (int32_t)((wb >> 3) & 63u);               // index that receives it
+  if (n < kDrawBlock) {                                            // ragged last block: own position draw
+    const Philox4 pr = philox4x32_10((uint32_t)q, (uint32_t)a.step, (uint32_t)row, kTagRagged, a.key0, a.key1);
+    vpos = first + (int32_t)(((uint64_t)pr.w[0] * (uint64_t)n) >> 32);
+  }
   if (lane < n) {
     const int32_t v = first + lane;
     const float x = elem_at<DT>(data, lane);
@@ -405,15 +410,20 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       const uint32_t e0 = (uint32_t)(d * kStepWaves + wave) * kTile + lane_off;
       ring[d] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
     }
-  // While the first loads are in flight: M_q bounds of all blocks, one Philox call each.
-  for (int b = tid; b < nslots; b += kStepThreads) {
-    float mub = kNegInf;
-    if (b < a.nblocks) {
-      const int32_t n = a.V - b * kDrawBlock < kDrawBlock ? a.V - b * kDrawBlock : kDrawBlock;
-      const Philox4 p = philox4x32_10((uint32_t)b, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
-      mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[0]);
+  // While the first loads are in flight: M_q bounds of all blocks, four per Philox call.
+  for (int c = tid; c * 4 < nslots; c += kStepThreads) {
+    const Philox4 p = philox4x32_10((uint32_t)c, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int b = c * 4 + j;
+      float mub = kNegInf;
+      if (b < a.nblocks) {
+        const int32_t n = a.V - b * kDrawBlock < kDrawBlock ? a.V - b * kDrawBlock : kDrawBlock;
+        mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[j]);
+        mub += 1e-5f + 4e-7f * fabsf(mub);  // room for the rounding of y_max + M_q below
+      }
+      if (b < nslots) sh.ub[b] = mub;
     }
-    sh.ub[b] = mub;
   }
   if (tid == 0) *sh.mshared = float_key(kNegInf);
   __syncthreads();
@@ -434,13 +444,8 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       const int i = i0 + d;
       if (i < my_tiles) {  // wave-uniform
         const int t = i * kStepWaves + wave;
-        const Raw<DT> cur = ring[d];
-        if (i + kRing < my_tiles) {  // refill this ring slot
-          const uint32_t en = (uint32_t)(t + kRing * kStepWaves) * kTile + lane_off;
-          ring[d] = load_raw<DT>(rowp, en < last_group ? en : last_group, (uint32_t)a.V);
-        }
         float x[8];
-        unpack<DT>(cur, x);
+        unpack<DT>(ring[d], x);
         if ((t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
           const int32_t e0 = t * kTile + (int32_t)lane_off;
 #pragma unroll
@@ -448,10 +453,13 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
             if (e0 + j >= a.V) x[j] = kNegInf;
         }
         const float gm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        if (fmaf(gm, a.k2, nrk) > kRescaleAt) {  // rare: move this lane's reference up to gm
-          const float nrk_new = -gm * a.k2;
-          sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
-          nrk = nrk_new;
+        if (__builtin_amdgcn_ballot_w64(fmaf(gm, a.k2, nrk) > kRescaleAt) != 0) {  // rare after the first tile
+          asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
+          if (fmaf(gm, a.k2, nrk) > kRescaleAt) {  // move this lane's reference up to gm
+            const float nrk_new = -gm * a.k2;
+            sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
+            nrk = nrk_new;
+          }
         }
         float acc0 = 0.0f, acc1 = 0.0f;
 #pragma unroll
@@ -463,15 +471,18 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         // upper bound of every perturbed score in the lane group's block: y_max + M_q, rounded up
         const float bm = group8_max(gm);
         const int q = t * kGroups + grp;
-        const float mub = sh.ub[q];
-        const float ym = bm * a.inv_tau;
-        const float ub = ym + mub + (1e-5f + 4e-7f * (fminf(fabsf(ym), 1e30f) + fabsf(mub)));
+        float ub = fmaf(fmaxf(bm, -1e30f), a.inv_tau, sh.ub[q]);
+        ub = fmaf(fabsf(ub), 4e-7f, ub);
         sh.ub[q] = ub;  // the 8 lanes of the group store the same value
         if (bm > top_bm) {  // keep the data of the block that holds the group's largest logit
           top_bm = bm;
           top_q = q;
-          *(u32x4*)my_raw = u32x4{cur.w[0], cur.w[1], cur.w[2], cur.w[3]};
-          if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{cur.w[4], cur.w[5], cur.w[6], cur.w[7]};
+          *(u32x4*)my_raw = u32x4{ring[d].w[0], ring[d].w[1], ring[d].w[2], ring[d].w[3]};
+          if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{ring[d].w[4], ring[d].w[5], ring[d].w[6], ring[d].w[7]};
+        }
+        if (i + kRing < my_tiles) {  // refill this ring slot
+          const uint32_t en = (uint32_t)(t + kRing * kStepWaves) * kTile + lane_off;
+          ring[d] = load_raw<DT>(rowp, en < last_group ? en : last_group, (uint32_t)a.V);
         }
       }
     }

@@ -317,14 +317,18 @@ def test_stream_moments(oracle):
 
 
 def test_block_draw_layout_and_law(oracle):
-    """M_q = ln n - ln(-ln u(w0)), pos_q = (w1 n) >> 32 from the block's own Philox call."""
+    """M_q and pos_q come from one word of a Philox call shared by four blocks (own call if ragged)."""
     seed = (0x0BADF00D << 32) | 0x00C0FFEE
-    for q, n, row, step in ((0, 64, 0, 0), (2375, 64, 511, 1023), (3, 12, 7, 5), (1, 1, 2, 2)):
-        blk = _philox_py([q, step, row, 0x4553504F], [0x00C0FFEE, 0x0BADF00D])
-        u = (2 * (blk[0] >> 9) + 1) / 2.0 ** 24
+    for q, n, row, step in ((0, 64, 0, 0), (2375, 64, 511, 1023), (6, 64, 1, 1), (3, 12, 7, 5), (1, 1, 2, 2)):
+        w = _philox_py([q >> 2, step, row, 0x4553504F], [0x00C0FFEE, 0x0BADF00D])[q & 3]
+        u = (2 * (w >> 9) + 1) / 2.0 ** 24
         M, pos = oracle.block_draw(seed, row, step, q, n)
         assert abs(M - (math.log(n) - math.log(-math.log(u)))) < 1e-12
-        assert pos == (blk[1] * n) >> 32 and 0 <= pos < n
+        if n == 64:
+            assert pos == (w >> 3) & 63
+        else:
+            w2 = _philox_py([q, step, row, 0x52414747], [0x00C0FFEE, 0x0BADF00D])[0]
+            assert pos == (w2 * n) >> 32 and 0 <= pos < n
     # M - ln n is standard Gumbel, pos is uniform, and the two are independent
     n = 64
     draws = [oracle.block_draw(77, r, s, q, n) for r in range(20) for s in range(20) for q in range(50)]
