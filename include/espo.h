@@ -111,9 +111,8 @@ typedef struct {
  *               -inf entries are allowed (masked vocabulary); NaN and +inf are not
  *               supported (results for that row are unspecified, no fault).
  *   dt          ESPO_F32 or ESPO_BF16.
- *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 320000 for bf16
- *               and 1 <= V <= 240000 for fp32 logits (ESPO_ERANGE beyond: the per-block
- *               bounds of a row live in LDS).
+ *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 400000
+ *               (ESPO_ERANGE beyond: the per-block bounds of a row live in LDS).
  *   row_stride  elements between rows, >= V.
  *   temperature > 0 and finite.
  *   seed, step  key and counter word of the random stream; step >= 0.

@@ -8,8 +8,8 @@
 
 namespace espo {
 
-constexpr size_t kMaxStepLds = 64 * 1024;          // dynamic LDS a step workgroup may ask for
-constexpr int64_t kMaxVocab = 320000;               // 64 bytes of LDS per 512-index tile plus 17-33 KB fixed
+constexpr size_t kMaxStepLds = 128 * 1024;         // dynamic LDS a step workgroup may ask for (160 KB per CU)
+constexpr int64_t kMaxVocab = 400000;               // 96 bytes of LDS per 512-index tile plus 26-42 KB fixed
 
 // Bytes of dynamic LDS a step workgroup needs for this dtype and vocabulary.
 size_t step_shared_bytes(int dt, int64_t V);

@@ -35,6 +35,7 @@ constexpr int kTile = 512;                        // indices per wave iteration
 constexpr int kGroups = kTile / kDrawBlock;       // draw blocks per tile = lane groups per wave
 constexpr int kSlots = kStepWaves * kGroups;      // lane groups per workgroup
 constexpr int kRing = 4;                          // 16-byte loads kept in flight per lane
+constexpr int kMaxCand = 2048;                    // indices the second round can score in one sweep
 constexpr float kRescaleAt = 64.0f;               // advance a lane's softmax reference when topped by 2^64
 
 struct StepArgs {
@@ -184,38 +185,57 @@ __device__ __forceinline__ float score_margin(const StepArgs& a, float y) {
   return a.margin_scale * (4e-5f + 2.5e-7f * fabsf(y));
 }
 
-// Scores the 64 indices of block q, one per lane.  `data` points at the block's 64 elements
-// (LDS copy or the row itself).  Only indices whose upper bound y + M_q (+ margins) reaches
-// `bound` can beat a score that is already known to be attained, the rest are skipped.
-template <int DT, typename F>
-__device__ __forceinline__ void visit_block(const StepArgs& a, int row, int q, const void* data, F bound, Search<F>& st) {
-  const int lane = threadIdx.x & (kWave - 1);
+// The block-level part of the draw for block q: its largest variate M_q, exp(-M_q), and the
+// index that receives M_q.
+template <typename F>
+struct BlockDraw {
+  F M, emM;
+  int32_t vpos;
+};
+
+template <typename F>
+__device__ __forceinline__ BlockDraw<F> block_draw(const StepArgs& a, int row, int q) {
   const int32_t first = q * kDrawBlock;
   const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
   const Philox4 pb = philox4x32_10((uint32_t)(q >> 2), (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
   const uint32_t wb = (q & 3) == 0 ? pb.w[0] : (q & 3) == 1 ? pb.w[1] : (q & 3) == 2 ? pb.w[2] : pb.w[3];
-  const F M = flog((F)n) - flog(neg_log_uniform<F>(wb));            // largest variate of the block
-  const F emM = fexp(-M);
-  int32_t vpos = first + (int32_t)((wb >> 3) & 63u);               // index that receives it
-  if (n < kDrawBlock) {                                            // ragged last block: own position draw
+  BlockDraw<F> d;
+  d.M = flog((F)n) - flog(neg_log_uniform<F>(wb));
+  d.emM = fexp(-d.M);
+  d.vpos = first + (int32_t)((wb >> 3) & 63u);
+  if (n < kDrawBlock) {  // ragged last block: own position draw
     const Philox4 pr = philox4x32_10((uint32_t)q, (uint32_t)a.step, (uint32_t)row, kTagRagged, a.key0, a.key1);
-    vpos = first + (int32_t)(((uint64_t)pr.w[0] * (uint64_t)n) >> 32);
+    d.vpos = first + (int32_t)(((uint64_t)pr.w[0] * (uint64_t)n) >> 32);
   }
-  if (lane < n) {
-    const int32_t v = first + lane;
-    const float x = elem_at<DT>(data, lane);
-    const F y = (F)x * (F)a.inv_tau;
-    const float e = sizeof(F) == 4 ? score_margin(a, (float)y) : 0.0f;
-    if (x > kNegInf && (y + M) + (F)(2.0f * e) >= bound) {   // masked (-inf) entries never win
-      F G = M;
-      if (v != vpos) {
-        const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
-        const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
-        G = -flog(emM + neg_log_uniform<F>(w));
-      }
-      st.offer(Cand<F>{y + G, e, v, x});
+  return d;
+}
+
+// Scores index v (logit x) of a block with draw d and offers it to the search, unless its
+// upper bound y + M_q (+ margins) cannot reach `bound`, a score already known to be attained.
+template <typename F>
+__device__ __forceinline__ void score_index(const StepArgs& a, int row, int32_t v, float x, const BlockDraw<F>& d,
+                                            F bound, Search<F>& st) {
+  const F y = (F)x * (F)a.inv_tau;
+  const float e = sizeof(F) == 4 ? score_margin(a, (float)y) : 0.0f;
+  if (x > kNegInf && (y + d.M) + (F)(2.0f * e) >= bound) {   // masked (-inf) entries never win
+    F G = d.M;
+    if (v != d.vpos) {
+      const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
+      const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
+      G = -flog(d.emM + neg_log_uniform<F>(w));
     }
+    st.offer(Cand<F>{y + G, e, v, x});
   }
+}
+
+// Scores the 64 indices of block q, one per lane.  `data` points at the block's 64 elements
+// (LDS copy or the row itself).
+template <int DT, typename F>
+__device__ __forceinline__ void visit_block(const StepArgs& a, int row, int q, const void* data, F bound, Search<F>& st) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const BlockDraw<F> d = block_draw<F>(a, row, q);
+  const int32_t v = q * kDrawBlock + lane;
+  if (v < a.V) score_index<F>(a, row, v, elem_at<DT>(data, lane), d, bound, st);
 }
 
 // The scalar chain regret -> normalised, clipped regret -> smoothed state -> stop test.
@@ -240,7 +260,9 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, flo
 
 // ---------------------------------------------------------------- shared memory
 struct StepShared {
-  float* ub;        // [nslots] bound per block slot (tile * 8 + group)
+  float* mub;       // [nslots] upper bound of M_q per block slot (tile * 8 + group)
+  float* ub;        // [nslots] upper bound of the block's best score
+  int* cand;        // [kMaxCand] indices that pass the cheap test in the second round
   int* surv;        // [nslots] survivor list
   void* top_raw;    // [kSlots][64 elements] data of each lane group's best block
   int* top_q;       // [kSlots] which block each lane group kept
@@ -254,6 +276,7 @@ struct StepShared {
   float* lo;        // [kStepWaves] score each wave knows to be attained
   int* visq;        // [kStepWaves] block each wave scored before the first barrier, or -1
   int* nsurv;       // [1]
+  int* ncand;       // [1]
   int* mshared;     // [1] largest wave maximum published so far (order-preserving int key)
 };
 
@@ -275,6 +298,9 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.visq = (int*)take(kStepWaves * 4);
   s.nsurv = (int*)take(16);
   s.mshared = s.nsurv + 1;
+  s.ncand = s.nsurv + 2;
+  s.cand = (int*)take(kMaxCand * 4);
+  s.mub = (float*)take((size_t)nslots * 4);
   s.ub = (float*)take((size_t)nslots * 4);
   s.surv = (int*)take((size_t)nslots * 4);
   return s;
@@ -283,8 +309,8 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
 size_t step_lds_bytes(int dt, int ntiles) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
-  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 7 * kStepWaves * 4 + 16 +
-         2 * ((nslots * 4 + 15) & ~(size_t)15);
+  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 7 * kStepWaves * 4 + 16 + kMaxCand * 4 +
+         3 * ((nslots * 4 + 15) & ~(size_t)15);
 }
 
 // Slot (wave, group) that streamed block q in phase 1.
@@ -334,27 +360,49 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
     sh.lo[wave] = round_down_f32(bound);  // rounded down: a shared bound must never overshoot
     sh.visq[wave] = q_own;
   }
-  if (tid == 0) *sh.nsurv = 0;
+  if (tid == 0) { *sh.nsurv = 0; *sh.ncand = 0; }
   __syncthreads();
   between();
   float bound_f = sh.lo[0];
 #pragma unroll
   for (int w = 1; w < kStepWaves; ++w) bound_f = fmaxf(bound_f, sh.lo[w]);
+  // blocks whose bound reaches the best score found so far
   for (int q = tid; q < nslots; q += kStepThreads) {
     const float u = sh.ub[q];
-    if (u > kNegInf && u >= bound_f && sh.visq[(q >> 3) & (kStepWaves - 1)] != q) sh.surv[atomicAdd(sh.nsurv, 1)] = q;
+    if (u > -1e30f && u >= bound_f && sh.visq[(q >> 3) & (kStepWaves - 1)] != q) sh.surv[atomicAdd(sh.nsurv, 1)] = q;
   }
   __syncthreads();
   const int nsurv = *sh.nsurv;
   bound = bound > (F)bound_f ? bound : (F)bound_f;
-#pragma unroll 1
-  for (int k = wave; k < nsurv; k += kStepWaves) {
-    const int q = sh.surv[k];
-    visit_block<DT, F>(a, row, q, data_of(q), bound, st);
-    st = wave_merge(st);
-    const F lo = st.lower();
-    bound = bound > lo ? bound : lo;
+  // their indices, one per thread: keep those whose own bound y_v + M_q still reaches it
+  for (int item = tid; item < nsurv * kDrawBlock; item += kStepThreads) {
+    const int q = sh.surv[item >> 6];
+    const int32_t v = q * kDrawBlock + (item & (kDrawBlock - 1));
+    if (v < a.V) {
+      const float x = elem_at<DT>(rowp, v);
+      float t = fmaf(x, a.inv_tau, sh.mub[q]);
+      t = fmaf(fabsf(t), 4e-7f, t);
+      if (x > kNegInf && t >= bound_f) {
+        const int k = atomicAdd(sh.ncand, 1);
+        if (k < kMaxCand) sh.cand[k] = v;
+      }
+    }
   }
+  __syncthreads();
+  const int ncand = *sh.ncand;
+  if (ncand <= kMaxCand) {  // the usual case: score them all at once, one index per thread
+    for (int k = tid; k < ncand; k += kStepThreads) {
+      const int32_t v = sh.cand[k];
+      score_index<F>(a, row, v, elem_at<DT>(rowp, v), block_draw<F>(a, row, v >> 6), bound, st);
+    }
+  } else {  // very flat rows: whole blocks, one per wave visit
+#pragma unroll 1
+    for (int k = wave; k < nsurv; k += kStepWaves) {
+      const int q = sh.surv[k];
+      visit_block<DT, F>(a, row, q, data_of(q), bound, st);
+    }
+  }
+  st = wave_merge(st);
   if (lane == 0) {
     sh.res_s[wave] = (double)st.best.s;
     sh.res_hi2[wave] = (double)st.hi2;
@@ -422,7 +470,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[j]);
         mub += 1e-5f + 4e-7f * fabsf(mub);  // room for the rounding of y_max + M_q below
       }
-      if (b < nslots) sh.ub[b] = mub;
+      if (b < nslots) sh.mub[b] = mub;
     }
   }
   if (tid == 0) *sh.mshared = float_key(kNegInf);
@@ -471,7 +519,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         // upper bound of every perturbed score in the lane group's block: y_max + M_q, rounded up
         const float bm = group8_max(gm);
         const int q = t * kGroups + grp;
-        float ub = fmaf(fmaxf(bm, -1e30f), a.inv_tau, sh.ub[q]);
+        float ub = fmaf(fmaxf(bm, -1e30f), a.inv_tau, sh.mub[q]);
         ub = fmaf(fabsf(ub), 4e-7f, ub);
         sh.ub[q] = ub;  // the 8 lanes of the group store the same value
         if (bm > top_bm) {  // keep the data of the block that holds the group's largest logit
@@ -589,6 +637,10 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   const size_t lds = step_lds_bytes(dt, a.ntiles);
   if (lds > kMaxStepLds) return ESPO_ERANGE;
   const dim3 grid((unsigned)B), block(kStepThreads);
+  if (lds > 64 * 1024) {  // beyond the default limit the kernel has to be told (very large vocabularies)
+    const void* fn = dt == ESPO_BF16 ? (const void*)espo_step_kernel<ESPO_BF16> : (const void*)espo_step_kernel<ESPO_F32>;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStepLds) != hipSuccess) return ESPO_EHIP;
+  }
   if (dt == ESPO_BF16)
     hipLaunchKernelGGL(espo_step_kernel<ESPO_BF16>, grid, block, lds, stream, a);
   else
