@@ -35,7 +35,6 @@ constexpr int kTile = 512;                        // indices per wave iteration
 constexpr int kGroups = kTile / kDrawBlock;       // draw blocks per tile = lane groups per wave
 constexpr int kSlots = kStepWaves * kGroups;      // lane groups per workgroup
 constexpr int kRing = 4;                          // 16-byte loads kept in flight per lane
-constexpr int kMaxCand = 2048;                    // indices the second round can score in one sweep
 constexpr float kRescaleAt = 64.0f;               // advance a lane's softmax reference when topped by 2^64
 
 struct StepArgs {
@@ -168,19 +167,20 @@ template <>
 __device__ __forceinline__ double neg_log_uniform<double>(uint32_t word) { return -log(uniform_f64(word)); }
 template <>
 __device__ __forceinline__ float neg_log_uniform<float>(uint32_t word) {
-  const uint32_t r = word >> 9;
-  if (r < (1u << 22)) return -logf((float)(2u * r + 1u) * (1.0f / 16777216.0f));
-  return -log1pf(-((float)(16777215u - 2u * r) * (1.0f / 16777216.0f)));
+  return -__builtin_amdgcn_logf((float)(2u * (word >> 9) + 1u) * (1.0f / 16777216.0f)) * kLn2;
 }
-__device__ __forceinline__ float flog(float x) { return logf(x); }
+// fp32 ln and exp from the hardware log2 / exp2.  Measured over all inputs that occur here
+// (every positive float in [2^-26, 64) for ln, every u(w); [-40, 8] for exp): relative error
+// below 1.7e-7 for ln, also next to 1, and below 2e-6 for exp; a GPU test re-measures this.
+__device__ __forceinline__ float flog(float x) { return __builtin_amdgcn_logf(x) * kLn2; }
 __device__ __forceinline__ double flog(double x) { return log(x); }
-__device__ __forceinline__ float fexp(float x) { return expf(x); }
+__device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
 __device__ __forceinline__ double fexp(double x) { return exp(x); }
 
-// Error margin of an fp32 score y + G.  The library functions used (logf, log1pf, expf)
-// are accurate to 3 ulp; propagated through M_q = ln n - ln(-ln u), exp(-M_q) and
-// G = -ln(exp(-M_q) - ln u) this gives |G32 - G| < 1e-5 for |G| <= 24, and the product and
-// sum forming y + G add 2^-23 (|y| + |G|).  The margin below is four times that.
+// Error margin of an fp32 score y + G.  With ln accurate to 1.7e-7 and exp to 2e-6 (relative):
+// -ln u carries 1.7e-7, M_q = ln n - ln(-ln u) at most 5e-6 for |M_q| <= 25, exp(-M_q) 7e-6
+// relative, G = -ln(exp(-M_q) - ln u) at most 1.1e-5, and the product and sum forming y + G
+// add 2^-23 (|y| + |G|).  The margin below is more than three times that.
 __device__ __forceinline__ float score_margin(const StepArgs& a, float y) {
   return a.margin_scale * (4e-5f + 2.5e-7f * fabsf(y));
 }
@@ -262,7 +262,6 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, flo
 struct StepShared {
   float* mub;       // [nslots] upper bound of M_q per block slot (tile * 8 + group)
   float* ub;        // [nslots] upper bound of the block's best score
-  int* cand;        // [kMaxCand] indices that pass the cheap test in the second round
   int* surv;        // [nslots] survivor list
   void* top_raw;    // [kSlots][64 elements] data of each lane group's best block
   int* top_q;       // [kSlots] which block each lane group kept
@@ -276,7 +275,6 @@ struct StepShared {
   float* lo;        // [kStepWaves] score each wave knows to be attained
   int* visq;        // [kStepWaves] block each wave scored before the first barrier, or -1
   int* nsurv;       // [1]
-  int* ncand;       // [1]
   int* mshared;     // [1] largest wave maximum published so far (order-preserving int key)
 };
 
@@ -298,8 +296,6 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.visq = (int*)take(kStepWaves * 4);
   s.nsurv = (int*)take(16);
   s.mshared = s.nsurv + 1;
-  s.ncand = s.nsurv + 2;
-  s.cand = (int*)take(kMaxCand * 4);
   s.mub = (float*)take((size_t)nslots * 4);
   s.ub = (float*)take((size_t)nslots * 4);
   s.surv = (int*)take((size_t)nslots * 4);
@@ -309,7 +305,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
 size_t step_lds_bytes(int dt, int ntiles) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
-  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 7 * kStepWaves * 4 + 16 + kMaxCand * 4 +
+  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 7 * kStepWaves * 4 + 16 +
          3 * ((nslots * 4 + 15) & ~(size_t)15);
 }
 
@@ -350,57 +346,40 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
   Search<F> st;
   st.init();
   F bound = bound0;
-  if (q_own >= 0) {
-    visit_block<DT, F>(a, row, q_own, data_of(q_own), bound, st);
-    st = wave_merge(st);
-    const F lo = st.lower();
-    bound = bound > lo ? bound : lo;
-  }
-  if (lane == 0) {
-    sh.lo[wave] = round_down_f32(bound);  // rounded down: a shared bound must never overshoot
-    sh.visq[wave] = q_own;
-  }
-  if (tid == 0) { *sh.nsurv = 0; *sh.ncand = 0; }
-  __syncthreads();
-  between();
-  float bound_f = sh.lo[0];
-#pragma unroll
-  for (int w = 1; w < kStepWaves; ++w) bound_f = fmaxf(bound_f, sh.lo[w]);
-  // blocks whose bound reaches the best score found so far
-  for (int q = tid; q < nslots; q += kStepThreads) {
-    const float u = sh.ub[q];
-    if (u > -1e30f && u >= bound_f && sh.visq[(q >> 3) & (kStepWaves - 1)] != q) sh.surv[atomicAdd(sh.nsurv, 1)] = q;
-  }
-  __syncthreads();
-  const int nsurv = *sh.nsurv;
-  bound = bound > (F)bound_f ? bound : (F)bound_f;
-  // their indices, one per thread: keep those whose own bound y_v + M_q still reaches it
-  for (int item = tid; item < nsurv * kDrawBlock; item += kStepThreads) {
-    const int q = sh.surv[item >> 6];
-    const int32_t v = q * kDrawBlock + (item & (kDrawBlock - 1));
-    if (v < a.V) {
-      const float x = elem_at<DT>(rowp, v);
-      float t = fmaf(x, a.inv_tau, sh.mub[q]);
-      t = fmaf(fabsf(t), 4e-7f, t);
-      if (x > kNegInf && t >= bound_f) {
-        const int k = atomicAdd(sh.ncand, 1);
-        if (k < kMaxCand) sh.cand[k] = v;
-      }
-    }
-  }
-  __syncthreads();
-  const int ncand = *sh.ncand;
-  if (ncand <= kMaxCand) {  // the usual case: score them all at once, one index per thread
-    for (int k = tid; k < ncand; k += kStepThreads) {
-      const int32_t v = sh.cand[k];
-      score_index<F>(a, row, v, elem_at<DT>(rowp, v), block_draw<F>(a, row, v >> 6), bound, st);
-    }
-  } else {  // very flat rows: whole blocks, one per wave visit
+  int q = q_own, k = wave, nsurv = 0;
+  bool first = true;
 #pragma unroll 1
-    for (int k = wave; k < nsurv; k += kStepWaves) {
-      const int q = sh.surv[k];
+  while (true) {  // one visit site for the wave's own block and for the survivors
+    if (q >= 0) {
       visit_block<DT, F>(a, row, q, data_of(q), bound, st);
+      const float lo = wave_max(round_down_f32(st.lower()));  // best score this wave has seen, rounded down
+      bound = bound > (F)lo ? bound : (F)lo;
     }
+    if (first) {
+      first = false;
+      if (lane == 0) {
+        sh.lo[wave] = round_down_f32(bound);  // rounded down: a shared bound must never overshoot
+        sh.visq[wave] = q_own;
+      }
+      if (tid == 0) *sh.nsurv = 0;
+      __syncthreads();
+      between();
+      float bound_f = sh.lo[0];
+#pragma unroll
+      for (int w = 1; w < kStepWaves; ++w) bound_f = fmaxf(bound_f, sh.lo[w]);
+      // blocks whose bound reaches the best score found so far
+      for (int b = tid; b < nslots; b += kStepThreads) {
+        const float u = sh.ub[b];
+        if (u > -1e30f && u >= bound_f && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv[atomicAdd(sh.nsurv, 1)] = b;
+      }
+      __syncthreads();
+      nsurv = *sh.nsurv;
+      bound = bound > (F)bound_f ? bound : (F)bound_f;
+    } else {
+      k += kStepWaves;
+    }
+    if (k >= nsurv) break;
+    q = sh.surv[k];
   }
   st = wave_merge(st);
   if (lane == 0) {
