@@ -47,6 +47,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--adv-reps", type=int, default=60)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; rows shard over GPUs without any exchange, "
@@ -98,17 +99,21 @@ def main() -> int:
 
     # ------------------------------------------------------------------ timed region: exactly K steps
     z, alive, ss = fresh_state()
+    region = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    region[0].record()                           # on the stream the kernels are launched on (torch's current one)
     run(Wm, total, z, alive, ss)
+    region[1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    region_ms = region[0].elapsed_time(region[1])
     ss_h = ss.cpu().numpy()
     steps_idx = np.arange(Wm, total)
     live = ((ss_h[None, :] < 0) | (ss_h[None, :] >= steps_idx[:, None])).sum(1)   # rows decoded at each timed step
     live_rows = int(live.sum())
 
-    # same K steps again with an event pair around every launch: duration of the kernel itself
+    # same K steps again with an event pair around every launch (each pair adds a few microseconds of its own)
     z2, alive2, ss2 = fresh_state()
     ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
     run(Wm, total, z2, alive2, ss2, events=ev)
@@ -116,7 +121,7 @@ def main() -> int:
     assert torch.equal(ss2, ss) and torch.equal(z2, z), "replay of the timed steps is not deterministic"
     kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
     step_bytes = live * (V_STEP * 2 + STEP_SCALAR_BYTES) + (B_STEP - live) * 1
-    step_gbs = float(step_bytes.sum() / (kern_ms.sum() * 1e-3) / 1e9)
+    step_gbs = float(step_bytes.sum() / (region_ms * 1e-3) / 1e9)   # events around the K back-to-back launches
 
     # ------------------------------------------------------------------ advantages (B=1024, T=16384), rotated buffers
     nbuf = 3
@@ -130,17 +135,24 @@ def main() -> int:
         adv_call(i)
     torch.cuda.synchronize()
     aev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.adv_reps)]
+    aregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
     ta = time.perf_counter()
+    aregion[0].record()
     for i in range(args.adv_reps):
+        adv_call(i)
+    aregion[1].record()
+    torch.cuda.synchronize()
+    adv_wall = time.perf_counter() - ta
+    adv_region_ms = aregion[0].elapsed_time(aregion[1])
+    for i in range(args.adv_reps):               # again, one event pair per launch
         aev[i][0].record()
         adv_call(i)
         aev[i][1].record()
     torch.cuda.synchronize()
-    adv_wall = time.perf_counter() - ta
     adv_ms = np.array([a.elapsed_time(b) for a, b in aev])
     valid = np.array([int(adv_in[i % nbuf][2].sum()) for i in range(args.adv_reps)])
     adv_bytes = valid * 16 + (B_ADV * T_ADV - valid) * 8 + B_ADV * 5
-    adv_gbs = float(adv_bytes.sum() / (adv_ms.sum() * 1e-3) / 1e9)
+    adv_gbs = float(adv_bytes.sum() / (adv_region_ms * 1e-3) / 1e9)
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample (context only)
     cpu = None
@@ -148,40 +160,47 @@ def main() -> int:
         import oracle
         oracle.build_oracle()
         op = oracle.OracleParams(**W.RolloutParams().as_dict())
-        bits = W.to_host_bits(logits[0])
         zc, ac, sc = (np.zeros(B_STEP, np.float32), np.ones(B_STEP, np.uint8), np.full(B_STEP, -1, np.int32))
-        vals0 = values[0].cpu().numpy()
-        tc = time.perf_counter()
-        oracle.step(bits, tau, seed, 0, vals0, op, zc, ac, sc)
-        cpu_s = time.perf_counter() - tc
+        cpu_s, cpu_rows, cpu_steps = 0.0, 0, 0
+        while cpu_s < args.cpu_seconds and cpu_steps < total:      # the first steps of the same trajectory
+            bits = W.to_host_bits(logits[cpu_steps])               # copy to the host: untimed
+            vals_h = values[cpu_steps].cpu().numpy()
+            cpu_rows += int(ac.sum())
+            tc = time.perf_counter()
+            oracle.step(bits, tau, seed, cpu_steps, vals_h, op, zc, ac, sc)
+            cpu_s += time.perf_counter() - tc
+            cpu_steps += 1
         r, v, L, s = [x.cpu().numpy() for x in adv_in[0]]
         tc = time.perf_counter()
         oracle.advantages(r, v, L, s, -1.0, 1.0, 0.95, want_scale=False)
         cpu_adv_s = time.perf_counter() - tc
-        cpu = {"value": B_STEP / cpu_s, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"one full step of the workload (512 rows x 152064 bf16 logits, step 0), {cpu_s:.2f} s",
+        cpu = {"value": cpu_rows / cpu_s, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": f"the first {cpu_steps} steps of the same workload ({cpu_rows} live rows x 152064 bf16 "
+                         f"logits), {cpu_s:.1f} s of oracle time",
                "advantages_tokens_per_s": float(L.clip(0, T_ADV).sum() / cpu_adv_s)}
 
     out = {
         "metric": "logit rows/sec & HBM GB/s (fused step, V=152064 bf16); advantages tokens/sec",
         "value": live_rows / wall, "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 logits, fp32 arithmetic (fp64 for the scores of contenders)", "data": "synthetic",
+        "dtype": "f32", "data": "synthetic",
         "config": {"workload": "sustained rollout step loop: B=512, V=152064 bf16, state carried, "
                                "~25% of rows planted to stop, one resident logit buffer per step",
-                   "B": B_STEP, "V": V_STEP, "temperature": tau, "live_rows_mean": float(live.mean()),
+                   "B": B_STEP, "V": V_STEP, "logits_dtype": "bf16", "temperature": tau, "live_rows_mean": float(live.mean()),
                    "live_rows_last": int(live[-1])},
         "step_hbm_gbs_wall": float(step_bytes.sum() / wall / 1e9),
         "roofline": {"kernel": "espo_step_kernel<bf16>", "bound": "hbm", "achieved": step_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS,
-                     "avg_launch_us": float(kern_ms.mean() * 1e3),
+                     "avg_launch_us": region_ms / K * 1e3,
+                     "avg_launch_us_event_pair_each": float(kern_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(step_bytes.mean()),
                      "traffic": _traffic_from_profiles("espo_step")},
         "advantages": {"workload": "B=1024, T=16384 fp32, lengths U[512,16384], 30% stopped, 3 rotated buffer sets",
                        "tokens_per_s": float(valid.sum() / adv_wall), "ms_per_call": adv_wall / args.adv_reps * 1e3,
                        "roofline": {"kernel": "espo_advantages_kernel", "bound": "hbm", "achieved": adv_gbs,
                                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": adv_gbs / HBM_PEAK_GBS,
-                                    "avg_launch_us": float(adv_ms.mean() * 1e3),
+                                    "avg_launch_us": adv_region_ms / args.adv_reps * 1e3,
+                                    "avg_launch_us_event_pair_each": float(adv_ms.mean() * 1e3),
                                     "algorithmic_bytes_per_launch": float(adv_bytes.mean()),
                                     "traffic": _traffic_from_profiles("espo_advantages")}},
         "cpu_baseline": cpu,

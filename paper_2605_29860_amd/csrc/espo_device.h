@@ -37,6 +37,21 @@ __device__ __forceinline__ float wave_max(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
+// Minimum of unsigned values over the 64 lanes, wave-uniform.
+template <int Ctrl, int RowMask>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t identity, uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)identity, (int)v, Ctrl, RowMask, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t v) {
+  v = min(v, dpp_u32<kDppRowShr1, 0xf>(0xffffffffu, v));
+  v = min(v, dpp_u32<kDppRowShr2, 0xf>(0xffffffffu, v));
+  v = min(v, dpp_u32<kDppRowShr4, 0xf>(0xffffffffu, v));
+  v = min(v, dpp_u32<kDppRowShr8, 0xf>(0xffffffffu, v));
+  v = min(v, dpp_u32<kDppBcast15, 0xa>(0xffffffffu, v));
+  v = min(v, dpp_u32<kDppBcast31, 0xc>(0xffffffffu, v));
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 // Sum over the 64 lanes in a fixed order (deterministic), wave-uniform result.
 __device__ __forceinline__ float wave_sum(float v) {
   v += dpp_f32<kDppRowShr1, 0xf>(0.0f, v);

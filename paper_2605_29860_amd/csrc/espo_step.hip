@@ -9,11 +9,11 @@
 //     DPP steps) and an fp32 upper bound ub_q >= max_v (y_v + G_v) built from the block's
 //     largest Gumbel variate M_q, kept in LDS.  Each lane group also keeps the raw data of
 //     the block with the largest bound it has seen, so that phase 2 seldom re-reads memory.
-//   phase 2 (a handful of blocks, lanes = the 64 indices of a block): the block with the
-//     largest bound is scored, the best score rules out every block with a lower bound,
-//     the few survivors are scored by the waves in parallel.  Scores are first formed in
-//     fp32 with a proven error margin; if the best two cannot be told apart within that
-//     margin the same procedure is repeated in double, which decides exactly.
+//   phase 2 (a handful of blocks, lanes = the 64 indices of a block): every wave scores the
+//     block with the largest bound it has streamed, the best score found rules out every
+//     block with a lower bound, the few survivors are scored by the waves in parallel.
+//     Scores are first formed in fp32 with a proven error margin; if the best two cannot be
+//     told apart within that margin the search is repeated in double, which decides exactly.
 //   One lane then runs the scalar chain regret -> normalise/clip -> smoothed state -> stop
 //   test (Eq. step_gap, Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule).
 // Pruning only ever discards indices that provably cannot attain the maximum, so the
@@ -178,9 +178,10 @@ __device__ __forceinline__ float fexp(float x) { return __builtin_amdgcn_exp2f(x
 __device__ __forceinline__ double fexp(double x) { return exp(x); }
 
 // Error margin of an fp32 score y + G.  With ln accurate to 1.7e-7 and exp to 2e-6 (relative):
-// -ln u carries 1.7e-7, M_q = ln n - ln(-ln u) at most 5e-6 for |M_q| <= 25, exp(-M_q) 7e-6
-// relative, G = -ln(exp(-M_q) - ln u) at most 1.1e-5, and the product and sum forming y + G
-// add 2^-23 (|y| + |G|).  The margin below is more than three times that.
+// -ln u carries 1.7e-7, M_q = ln n - ln(-ln u) at most 5e-6 for |M_q| <= 25, exp(-M_q) at most
+// 7e-6 relative (4e-7 where it is formed as (-ln u)/n), G = -ln(exp(-M_q) - ln u) at most
+// 1.1e-5, and the product and sum forming y + G add 2^-23 (|y| + |G|).  The margin below is
+// more than three times that.
 __device__ __forceinline__ float score_margin(const StepArgs& a, float y) {
   return a.margin_scale * (4e-5f + 2.5e-7f * fabsf(y));
 }
@@ -260,9 +261,10 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, flo
 
 // ---------------------------------------------------------------- shared memory
 struct StepShared {
-  float* mub;       // [nslots] upper bound of M_q per block slot (tile * 8 + group)
+  float* mub;       // [nslots] upper bound of M_q per block slot (tile * 8 + group); phase 1 only
+  int* surv;        // [nslots] survivor list of phase 2 (same memory as mub)
+  uint32_t* wq;     // [nslots] the block's word of the random stream
   float* ub;        // [nslots] upper bound of the block's best score
-  int* surv;        // [nslots] survivor list
   void* top_raw;    // [kSlots][64 elements] data of each lane group's best block
   int* top_q;       // [kSlots] which block each lane group kept
   float* m;         // [kStepWaves] wave maxima
@@ -274,8 +276,9 @@ struct StepShared {
   float* res_x;
   float* lo;        // [kStepWaves] score each wave knows to be attained
   int* visq;        // [kStepWaves] block each wave scored before the first barrier, or -1
+  float* fres;      // [5][kStepWaves] per-wave results of the fp32 search: s, e, x, hi2, v
   int* nsurv;       // [1]
-  int* mshared;     // [1] largest wave maximum published so far (order-preserving int key)
+  int* bkey;        // [1] best attained score published during long survivor lists (order-preserving key)
 };
 
 template <int DT>
@@ -294,18 +297,20 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.res_x = (float*)take(kStepWaves * 4);
   s.lo = (float*)take(kStepWaves * 4);
   s.visq = (int*)take(kStepWaves * 4);
+  s.fres = (float*)take(5 * kStepWaves * 4);
   s.nsurv = (int*)take(16);
-  s.mshared = s.nsurv + 1;
+  s.bkey = s.nsurv + 1;
   s.mub = (float*)take((size_t)nslots * 4);
+  s.surv = (int*)s.mub;
   s.ub = (float*)take((size_t)nslots * 4);
-  s.surv = (int*)take((size_t)nslots * 4);
+  s.wq = (uint32_t*)take((size_t)nslots * 4);
   return s;
 }
 
 size_t step_lds_bytes(int dt, int ntiles) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
-  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 7 * kStepWaves * 4 + 16 +
+  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 12 * kStepWaves * 4 + 16 +
          3 * ((nslots * 4 + 15) & ~(size_t)15);
 }
 
@@ -402,6 +407,145 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
   return all;
 }
 
+// ---------------------------------------------------------------- phase 2 in fp32
+// State of the fp32 search, per lane while blocks are visited and wave-uniform once reduced:
+// the best index scored (score s known to within +-e, logit x) and hi2, the largest upper
+// end s + e among all other scored indices.  The winner is certain iff s - e > hi2.
+struct Best {
+  float s, e, x, hi2;
+  int32_t v;
+};
+
+__device__ __forceinline__ Best no_best() { return Best{kNegInf, 0.0f, 0.0f, kNegInf, -1}; }
+
+// Scores the 64 indices of block q in fp32, one per lane.  Every block is visited at most
+// once in this search, so a lane never meets the same index twice.
+template <int DT>
+__device__ __forceinline__ void fast_visit(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int q,
+                                           Best& st) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int32_t first = q * kDrawBlock;
+  const int32_t v = first + lane;
+  const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
+  // the index's own word depends on nothing else here: its ten rounds overlap the loads
+  const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
+  const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
+  const int slot = slot_of(q);
+  const void* data = sh.top_q[slot] == q ? (const void*)((const char*)sh.top_raw + (size_t)slot * kDrawBlock * elem_bytes<DT>())
+                                         : (const void*)((const char*)rowp + (size_t)first * elem_bytes<DT>());
+  const float x = elem_at<DT>(data, lane < n ? lane : n - 1);
+  const uint32_t wb = sh.wq[q];
+  const float nlb = neg_log_uniform<float>(wb);
+  const float M = flog((float)n) - flog(nlb);                 // M_q = ln n - ln(-ln u)
+  const float emM = nlb * __builtin_amdgcn_rcpf((float)n);    // exp(-M_q) = (-ln u) / n
+  int32_t vpos = first + (int32_t)((wb >> 3) & 63u);
+  if (n < kDrawBlock) {  // ragged last block: own position draw
+    const Philox4 pr = philox4x32_10((uint32_t)q, (uint32_t)a.step, (uint32_t)row, kTagRagged, a.key0, a.key1);
+    vpos = first + (int32_t)(((uint64_t)pr.w[0] * (uint64_t)n) >> 32);
+  }
+  const float G = v == vpos ? M : -flog(emM + neg_log_uniform<float>(w));
+  const float y = x * a.inv_tau;
+  const float sc = y + G;
+  const float e = score_margin(a, y);
+  if (lane < n && x > kNegInf) {  // masked (-inf) entries never win
+    if (sc > st.s) {
+      st.hi2 = fmaxf(st.hi2, st.s + st.e);
+      st.s = sc; st.e = e; st.x = x; st.v = v;
+    } else {
+      st.hi2 = fmaxf(st.hi2, sc + e);
+    }
+  }
+}
+
+// Combines the lanes' states into the wave's: highest score, lowest index among equals.
+__device__ __forceinline__ Best wave_best(const Best& st) {
+  const float smax = wave_max(st.s);
+  const bool cand = st.v >= 0 && st.s == smax;
+  const uint32_t vmin = wave_min_u32(cand ? (uint32_t)st.v : 0xffffffffu);
+  if (vmin == 0xffffffffu) return no_best();
+  const bool win = cand && (uint32_t)st.v == vmin;
+  const int src = (int)__builtin_ctzll(__builtin_amdgcn_ballot_w64(win));
+  Best r;
+  r.s = smax;
+  r.v = (int32_t)vmin;
+  r.e = uniform_f32(st.e, src);
+  r.x = uniform_f32(st.x, src);
+  r.hi2 = wave_max(win ? st.hi2 : fmaxf(st.hi2, st.s + st.e));
+  return r;
+}
+
+__device__ __forceinline__ float key_float(int k) { return __builtin_bit_cast(float, k >= 0 ? k : k ^ 0x7fffffff); }
+
+// The fp32 search over the row.  Every wave first scores `q_own`, the block with the largest
+// bound it has streamed; the best lower end s - e found that way is a score known to be
+// attained, and every other block whose bound reaches it is then scored, one block per wave
+// visit.  `between` runs right after the first barrier.  Returns the wave-uniform result,
+// the same in every wave; all threads of the workgroup must call it.
+template <int DT, typename Between>
+__device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int nslots,
+                                            int q_own, Between between) {
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  Best st = no_best();
+  int q = q_own, k = wave, nsurv = 0;
+  bool first = true;
+#pragma unroll 1
+  while (true) {  // one visit site for the wave's own block and for the survivors
+    if (q >= 0) fast_visit<DT>(a, sh, rowp, row, q, st);
+    if (first) {
+      first = false;
+      const float lo = wave_max(st.s - st.e);
+      if (lane == 0) {
+        sh.lo[wave] = lo;
+        sh.visq[wave] = q_own;
+      }
+      if (tid == 0) *sh.nsurv = 0;
+      __syncthreads();
+      between();
+      const float bound = wave_max(lane < kStepWaves ? sh.lo[lane] : kNegInf);
+      for (int b = tid; b < nslots; b += kStepThreads) {  // blocks whose bound reaches the best score found so far
+        const float u = sh.ub[b];
+        if (u > -1e30f && u >= bound && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv[atomicAdd(sh.nsurv, 1)] = b;
+      }
+      if (tid == 0) *sh.bkey = float_key(bound);
+      __syncthreads();
+      nsurv = *sh.nsurv;
+    } else {
+      if (nsurv > kStepWaves) {  // long list: publish what this wave has attained, later visits may then be skipped
+        const float lo = wave_max(st.s - st.e);
+        if (lane == 0) atomicMax(sh.bkey, float_key(lo));
+      }
+      k += kStepWaves;
+    }
+    q = -1;
+    while (k < nsurv) {  // this wave's next survivor that can still matter
+      const int c = sh.surv[k];
+      if (nsurv <= kStepWaves || sh.ub[c] >= key_float(*sh.bkey)) { q = c; break; }
+      k += kStepWaves;
+    }
+    if (q < 0) break;
+  }
+  const Best mine = wave_best(st);
+  if (lane == 0) {
+    sh.fres[0 * kStepWaves + wave] = mine.s;
+    sh.fres[1 * kStepWaves + wave] = mine.e;
+    sh.fres[2 * kStepWaves + wave] = mine.x;
+    sh.fres[3 * kStepWaves + wave] = mine.hi2;
+    sh.fres[4 * kStepWaves + wave] = __builtin_bit_cast(float, mine.v);
+  }
+  __syncthreads();
+  Best t = no_best();
+  if (lane < kStepWaves) {
+    t.s = sh.fres[0 * kStepWaves + lane];
+    t.e = sh.fres[1 * kStepWaves + lane];
+    t.x = sh.fres[2 * kStepWaves + lane];
+    t.hi2 = sh.fres[3 * kStepWaves + lane];
+    t.v = __builtin_bit_cast(int32_t, sh.fres[4 * kStepWaves + lane]);
+  }
+  return wave_best(t);
+}
+
 // ---------------------------------------------------------------- the kernel
 template <int DT>
 __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) {
@@ -449,10 +593,12 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[j]);
         mub += 1e-5f + 4e-7f * fabsf(mub);  // room for the rounding of y_max + M_q below
       }
-      if (b < nslots) sh.mub[b] = mub;
+      if (b < nslots) {
+        sh.mub[b] = mub;
+        sh.wq[b] = p.w[j];
+      }
     }
   }
-  if (tid == 0) *sh.mshared = float_key(kNegInf);
   __syncthreads();
 
   // Softmax sum against a lazily advanced per-lane reference: the lane accumulates
@@ -460,7 +606,8 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   // by 2^-(m k2 + nrk), so the rounding of nrk itself cancels.
   float nrk = 1e30f;
   float sum = 0.0f;
-  float top_bm = kNegInf;    // largest block maximum this lane group has seen, and its block
+  float mx = kNegInf;        // largest logit this lane group has seen
+  float top_ub = kNegInf;    // largest block bound this lane group has seen, and its block
   int top_q = -1;
   char* const my_raw = (char*)sh.top_raw + ((size_t)(wave * kGroups + grp) * kDrawBlock + (lane & 7) * 8) * elem_bytes<DT>();
 
@@ -501,8 +648,9 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         float ub = fmaf(fmaxf(bm, -1e30f), a.inv_tau, sh.mub[q]);
         ub = fmaf(fabsf(ub), 4e-7f, ub);
         sh.ub[q] = ub;  // the 8 lanes of the group store the same value
-        if (bm > top_bm) {  // keep the data of the block that holds the group's largest logit
-          top_bm = bm;
+        mx = fmaxf(mx, bm);
+        if (ub > top_ub) {  // keep the data of the block with the group's largest bound
+          top_ub = ub;
           top_q = q;
           *(u32x4*)my_raw = u32x4{ring[d].w[0], ring[d].w[1], ring[d].w[2], ring[d].w[3]};
           if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{ring[d].w[4], ring[d].w[5], ring[d].w[6], ring[d].w[7]};
@@ -514,65 +662,54 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       }
     }
   }
-  // The wave's largest logit and the block that holds it (lowest block among equals).
-  float bmw = top_bm;
-  int qw = top_q;
-#pragma unroll
-  for (int off = 32; off >= 8; off >>= 1) {
-    const float ob = __shfl_xor(bmw, off);
-    const int oq = __shfl_xor(qw, off);
-    if (ob > bmw || (ob == bmw && (uint32_t)oq < (uint32_t)qw)) { bmw = ob; qw = oq; }
-  }
-  if (lane == 0) sh.m[wave] = bmw;
+  // The wave's largest logit, and the block with its largest bound (lowest block among equals).
+  const float mw = wave_max(mx);
+  const float ubw = wave_max(top_ub);
+  const int q_own = (int)wave_min_u32(top_q >= 0 && top_ub == ubw ? (uint32_t)top_q : 0xffffffffu);  // -1 if none
+  if (lane == 0) sh.m[wave] = mw;
   if ((lane & 7) == 0) sh.top_q[wave * kGroups + grp] = top_q;
-  // Waves whose maximum is close to the largest one published so far score their block right
-  // away; this only decides how much work is spent, never the result.
-  int q_own = -1;
-  {
-    int seen = float_key(bmw);
-    if (lane == 0) seen = max(atomicMax(sh.mshared, seen), seen);
-    seen = __builtin_amdgcn_readfirstlane(seen);
-    const float seen_f = __builtin_bit_cast(float, seen >= 0 ? seen : seen ^ 0x7fffffff);
-    if (qw >= 0 && (bmw - seen_f) * a.inv_tau >= -2.0f) q_own = qw;
+  float z_prev = 0.0f, value = 0.0f;  // wanted at the very end: fetched now, off the critical path
+  if (tid == 0) {
+    z_prev = a.z[row];
+    value = a.values[row];
   }
-  __builtin_amdgcn_s_waitcnt(0);  // the lane groups' saved blocks must be in LDS before this wave reads them
 
   // ------------------------------------------------------------ phase 2: argmax of y + G
   float m = kNegInf;
   auto softmax_sum = [&]() {  // after the first barrier: row maximum, then the wave's share of the sum
-    m = sh.m[0];
-#pragma unroll
-    for (int w = 1; w < kStepWaves; ++w) m = fmaxf(m, sh.m[w]);
+    m = wave_max(lane < kStepWaves ? sh.m[lane] : kNegInf);
     const float part = sum > 0.0f ? sum * __builtin_amdgcn_exp2f(-fmaf(m, a.k2, nrk)) : 0.0f;
     const float tot = wave_sum(part);
     if (lane == 0) sh.sum[wave] = tot;
   };
-  const Search<float> fast = find_argmax<DT, float>(a, sh, rowp, row, nslots, q_own, kNegInf, softmax_sum);
-  int32_t tok = fast.best.v;
-  float x_a = fast.best.x;
-  if (fast.best.v >= 0 && !(fast.best.s - fast.best.e > fast.hi2)) {
+  const Best fast = fast_argmax<DT>(a, sh, rowp, row, nslots, q_own, softmax_sum);
+  int32_t tok = fast.v;
+  float x_a = fast.x;
+  if (fast.v >= 0 && !(fast.s - fast.e > fast.hi2)) {
     // the two best fp32 scores overlap within their margins: decide in double (rare)
     __syncthreads();  // everyone has read the fp32 results
-    const Search<double> exact = find_argmax<DT, double>(a, sh, rowp, row, nslots, q_own, (double)fast.lower(), [] {});
+    const Search<double> exact =
+        find_argmax<DT, double>(a, sh, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
     tok = exact.best.v;
     x_a = exact.best.x;
   }
 
   // ------------------------------------------------------------ finalize: one lane
-  if (tid == 0) {
-    float S = 0.0f;  // sum_v exp((x_v - m)/tau), waves combined in a fixed order
-    for (int w = 0; w < kStepWaves; ++w) S += sh.sum[w];
-    if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
-    const ChainOut c = scalar_chain(a, m, x_a, a.z[row], a.values[row]);
-    a.tokens[row] = tok;
-    a.regret[row] = c.g;
-    a.z[row] = c.z;
-    if (a.logprob) a.logprob[row] = -c.g - logf(S);
-    if (a.eos_id >= 0 && tok == a.eos_id) {
-      a.alive[row] = 0;  // natural end
-    } else if (c.stop) {
-      a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
-      a.stop_step[row] = a.step;
+  if (wave == 0) {
+    const float S = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // sum_v exp((x_v - m)/tau), fixed order
+    if (lane == 0) {
+      if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
+      const ChainOut c = scalar_chain(a, m, x_a, z_prev, value);
+      a.tokens[row] = tok;
+      a.regret[row] = c.g;
+      a.z[row] = c.z;
+      if (a.logprob) a.logprob[row] = -c.g - flog(S);
+      if (a.eos_id >= 0 && tok == a.eos_id) {
+        a.alive[row] = 0;  // natural end
+      } else if (c.stop) {
+        a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
+        a.stop_step[row] = a.step;
+      }
     }
   }
 }
