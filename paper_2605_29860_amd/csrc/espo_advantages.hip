@@ -2,14 +2,16 @@
 // Eq. gae; Section 4.4: failure reward at the stop step, no bootstrap past the end).
 //
 // A_t = delta_t + c A_{t+1} (c = gamma*lambda) is a first-order linear recurrence that
-// runs backwards over each row's valid prefix [0, L).  One workgroup owns one row and
-// walks it in tiles of 2048 tokens from the tile that holds L-1 down to tile 0; tiles at
-// or beyond L are only zero-filled.  Inside a tile every lane holds 8 consecutive tokens
-// (two 16-byte loads per input array), runs the recurrence serially over them, the 64
-// lane results are combined by a suffix scan with the weights c^8, c^16, ... inside the
-// wave, the four wave results through LDS, and one scalar carries A at the tile boundary
-// into the next (earlier) tile.  The next tile's loads are issued before the scan so that
-// HBM latency overlaps the arithmetic.
+// runs backwards over each row's valid prefix [0, L).  One workgroup of 16 wavefronts owns
+// one row and walks it in tiles of 4096 tokens from the tile that holds L-1 down to tile 0;
+// tiles at or beyond L are only zero-filled.  Inside a tile every lane holds 4 consecutive
+// tokens (one 16-byte load per input array, one 16-byte store per output array), and the
+// lanes are laid out backwards: thread 0 holds the tile's last four tokens.  That turns the
+// suffix sums of the recurrence into prefix sums over the lanes, which the DPP row shifts
+// and row broadcasts of gfx9 compute in six steps without touching LDS; the sixteen wave
+// totals are combined the same way after one trip through LDS, and a single scalar carries A
+// across the tile boundary.  Only that scalar depends on the previous tile, so the next
+// tile's loads are issued before the current one is reduced.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -21,10 +23,11 @@
 namespace espo {
 namespace {
 
-constexpr int kAdvThreads = 256;
+constexpr int kAdvThreads = 1024;
 constexpr int kAdvWaves = kAdvThreads / kWave;
-constexpr int kPerLane = 8;
-constexpr int kTile = kAdvThreads * kPerLane;  // 2048 tokens
+constexpr int kPerLane = 4;
+constexpr int kAdvTile = kAdvThreads * kPerLane;  // 4096 tokens
+constexpr int kDppWaveShr1 = 0x138;               // lane i takes lane i-1 across the whole wave
 
 struct AdvArgs {
   const float* rewards;
@@ -33,69 +36,75 @@ struct AdvArgs {
   const uint8_t* stopped;
   int64_t T;
   float r_fail, gamma, c;
-  float cj[kPerLane + 1];  // c^0 .. c^8
-  float cscan[6];          // c^(8*2^k), k = 0..5: weights of the in-wave suffix scan
-  float cwave;             // c^512: weight between consecutive waves
+  float cj[kPerLane + 1];  // c^0 .. c^4
+  float clane[6];          // c^(4*2^k), k = 0..5: a distance of 2^k lanes
+  float cwave[5];          // c^(256*2^k), k = 0..4: a distance of 2^k waves; cwave[4] spans a tile
   float* td;
   float* adv;
 };
 
 struct TileIn {
   float r[kPerLane], v[kPerLane];
+  float halo;  // value of the token after the wave's span (lane 0 only)
 };
 
-// Loads the lane's 8 tokens starting at t0; tokens at or beyond L are never read.
+// c^(unit * e) for 0 <= e < 2^Bits from the table of c^(unit * 2^k).
+template <int Bits>
+__device__ __forceinline__ float pow_from_table(const float* tab, int e) {
+  float w = 1.0f;
+#pragma unroll
+  for (int k = 0; k < Bits; ++k)
+    if (e & (1 << k)) w *= tab[k];
+  return w;
+}
+
+// Loads the lane's 4 tokens starting at t0 and, in lane 0, the value at t0 + 4; tokens at or
+// beyond L are never read.
 template <bool VEC>
-__device__ __forceinline__ TileIn load_tile(const float* __restrict__ rrow, const float* __restrict__ vrow,
-                                            int64_t t0, int64_t L) {
+__device__ __forceinline__ TileIn load_tile(const float* __restrict__ rrow, const float* __restrict__ vrow, int64_t t0,
+                                            int64_t L, bool want_halo) {
   TileIn in;
 #pragma unroll
   for (int j = 0; j < kPerLane; ++j) { in.r[j] = 0.0f; in.v[j] = 0.0f; }
-  if constexpr (VEC) {
+  in.halo = 0.0f;
+  if (VEC && t0 + kPerLane <= L) {
+    const f32x4 a = __builtin_nontemporal_load((const f32x4*)(rrow + t0));
+    const f32x4 b = __builtin_nontemporal_load((const f32x4*)(vrow + t0));
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int64_t t = t0 + 4 * h;
-      if (t + 4 <= L) {
-        const f32x4 a = __builtin_nontemporal_load((const f32x4*)(rrow + t));
-        const f32x4 b = __builtin_nontemporal_load((const f32x4*)(vrow + t));
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { in.r[4 * h + j] = a[j]; in.v[4 * h + j] = b[j]; }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-          if (t + j < L) { in.r[4 * h + j] = rrow[t + j]; in.v[4 * h + j] = vrow[t + j]; }
-      }
-    }
+    for (int j = 0; j < kPerLane; ++j) { in.r[j] = a[j]; in.v[j] = b[j]; }
   } else {
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j)
       if (t0 + j < L) { in.r[j] = rrow[t0 + j]; in.v[j] = vrow[t0 + j]; }
   }
+  if (want_halo && t0 + kPerLane < L) in.halo = vrow[t0 + kPerLane];
   return in;
 }
 
 template <bool VEC>
-__device__ __forceinline__ void store8(float* __restrict__ row, int64_t t0, int64_t T, const float x[kPerLane]) {
-  if constexpr (VEC) {
-    if (t0 + kPerLane <= T) {
-      __builtin_nontemporal_store(f32x4{x[0], x[1], x[2], x[3]}, (f32x4*)(row + t0));
-      __builtin_nontemporal_store(f32x4{x[4], x[5], x[6], x[7]}, (f32x4*)(row + t0 + 4));
-      return;
-    }
+__device__ __forceinline__ void store4(float* __restrict__ row, int64_t t0, int64_t T, const float x[kPerLane]) {
+  if (VEC) {
+    if (t0 < T) __builtin_nontemporal_store(f32x4{x[0], x[1], x[2], x[3]}, (f32x4*)(row + t0));  // T % 4 == 0 here
+    return;
   }
 #pragma unroll
   for (int j = 0; j < kPerLane; ++j)
     if (t0 + j < T) row[t0 + j] = x[j];
 }
 
+// One step of a weighted inclusive prefix sum over lanes: s += w * (s of the lane the DPP control names).
+template <int Ctrl, int RowMask>
+__device__ __forceinline__ float scan_step(float s, float w) {
+  return fmaf(w, dpp_f32<Ctrl, RowMask>(0.0f, s), s);
+}
+
 template <bool VEC>
-__global__ __launch_bounds__(kAdvThreads) void espo_advantages_kernel(AdvArgs a) {
-  __shared__ float s_wave[kAdvWaves];   // per-wave scan result at its first token
-  __shared__ float s_vfirst[kAdvWaves + 1];  // first value of each wave's span (for the V_{t+1} of the lane before)
+__global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs a) {
+  __shared__ float s_tot[2][kAdvWaves];  // wave totals, double-buffered by tile parity
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int64_t T = a.T;
   int64_t L = a.lengths[row];
   L = L < 0 ? 0 : (L > T ? T : L);
@@ -105,93 +114,93 @@ __global__ __launch_bounds__(kAdvThreads) void espo_advantages_kernel(AdvArgs a)
   float* drow = a.td + (int64_t)row * T;
   float* arow = a.adv + (int64_t)row * T;
 
-  const int64_t ntiles = (T + kTile - 1) / kTile;
-  const int64_t nvalid = (L + kTile - 1) / kTile;  // tiles that hold at least one valid token
+  const int64_t ntiles = (T + kAdvTile - 1) / kAdvTile;
+  const int64_t nvalid = (L + kAdvTile - 1) / kAdvTile;  // tiles that hold at least one valid token
+  const int64_t lane_off = (int64_t)(kAdvThreads - 1 - tid) * kPerLane;  // backwards: thread 0 holds the last tokens
 
   // tiles wholly beyond the trajectory: outputs are exactly zero
-  const float zero[kPerLane] = {0, 0, 0, 0, 0, 0, 0, 0};
+  const float zero[kPerLane] = {0, 0, 0, 0};
   for (int64_t k = ntiles - 1; k >= nvalid; --k) {
-    const int64_t t0 = k * kTile + (int64_t)tid * kPerLane;
-    store8<VEC>(drow, t0, T, zero);
-    store8<VEC>(arow, t0, T, zero);
+    store4<VEC>(drow, k * kAdvTile + lane_off, T, zero);
+    store4<VEC>(arow, k * kAdvTile + lane_off, T, zero);
   }
   if (nvalid == 0) return;
 
+  // per-lane weights of the cross-row scan steps and of the carry into this lane and this wave
+  const float w_b15 = pow_from_table<5>(a.clane, (lane & 15) + 1);  // from lane 15 of the row before
+  const float w_b31 = pow_from_table<6>(a.clane, (lane & 31) + 1);  // from lane 31
+  const float w_lane = pow_from_table<6>(a.clane, lane);            // c^(4 lane): the wave's carry-in seen from this lane
+  const float w_wave = pow_from_table<4>(a.cwave, wave);            // c^(256 wave): the tile's carry-in seen from this wave
+
   float carry = 0.0f;  // A at the first token of the tile processed before (the later one)
-  TileIn cur = load_tile<VEC>(rrow, vrow, (nvalid - 1) * kTile + (int64_t)tid * kPerLane, L);
+  TileIn cur = load_tile<VEC>(rrow, vrow, (nvalid - 1) * kAdvTile + lane_off, L, lane == 0);
   for (int64_t k = nvalid - 1; k >= 0; --k) {
-    const int64_t t0 = k * kTile + (int64_t)tid * kPerLane;
+    const int64_t t0 = k * kAdvTile + lane_off;
     TileIn nxt;
-    if (k > 0) nxt = load_tile<VEC>(rrow, vrow, t0 - kTile, L);  // prefetch the earlier tile
+    if (k > 0) nxt = load_tile<VEC>(rrow, vrow, t0 - kAdvTile, L, lane == 0);  // the earlier tile, in flight during the scan
 
-    // V_{t+1} of the lane's last token: first value of the next lane / wave / tile
-    if (lane == 0) s_vfirst[wave] = cur.v[0];
-    float vnext = __shfl_down(cur.v[0], 1);
-    __syncthreads();
-    if (lane == kWave - 1) {
-      if (wave + 1 < kAdvWaves) vnext = s_vfirst[wave + 1];
-      else vnext = (t0 + kPerLane < L) ? vrow[t0 + kPerLane] : 0.0f;
-    }
+    // V_{t+1} of the lane's last token: first value of the lane that holds the following tokens
+    float vnext = dpp_f32<kDppWaveShr1, 0xf>(0.0f, cur.v[0]);
+    if (lane == 0) vnext = cur.halo;
 
-    // delta_t and the serial recurrence over the lane's 8 tokens (later tokens first)
+    // delta_t and the recurrence over the lane's 4 tokens, later tokens first
+    const int64_t rem = L - t0;  // valid tokens from t0 on (may be <= 0 or large)
     float d[kPerLane], loc[kPerLane];
     float acc = 0.0f;
+    if (__builtin_amdgcn_ballot_w64(rem <= kPerLane) == 0) {  // whole wave strictly inside the trajectory
 #pragma unroll
-    for (int j = kPerLane - 1; j >= 0; --j) {
-      const int64_t t = t0 + j;
-      float vn = (j == kPerLane - 1) ? vnext : cur.v[j + 1];
-      if (t + 1 >= L) vn = 0.0f;                           // no bootstrap beyond the last token
-      float r = cur.r[j];
-      if (stopped && t == L - 1) r = a.r_fail;              // Eq. failure_reward
-      float dj = (r + a.gamma * vn) - cur.v[j];
-      if (t >= L) dj = 0.0f;
-      d[j] = dj;
-      acc = dj + a.c * acc;
-      loc[j] = acc;
+      for (int j = kPerLane - 1; j >= 0; --j) {
+        const float vn = (j == kPerLane - 1) ? vnext : cur.v[j + 1];
+        d[j] = (cur.r[j] + a.gamma * vn) - cur.v[j];
+        acc = d[j] + a.c * acc;
+        loc[j] = acc;
+      }
+    } else {
+#pragma unroll
+      for (int j = kPerLane - 1; j >= 0; --j) {
+        float vn = (j == kPerLane - 1) ? vnext : cur.v[j + 1];
+        if (j + 1 >= rem) vn = 0.0f;                        // no bootstrap beyond the last token
+        float r = cur.r[j];
+        if (stopped && j + 1 == rem) r = a.r_fail;          // Eq. failure_reward
+        float dj = (r + a.gamma * vn) - cur.v[j];
+        if (j >= rem) dj = 0.0f;
+        d[j] = dj;
+        acc = dj + a.c * acc;
+        loc[j] = acc;
+      }
     }
 
-    // suffix scan over the lanes of the wave: s_i = sum_{i' >= i} c^(8 (i'-i)) loc_i'[0]
+    // inclusive prefix over the lanes: s_i = sum_{i' <= i} c^(4 (i - i')) acc_i'
     float s = acc;
-#pragma unroll
-    for (int kk = 0; kk < 6; ++kk) {
-      const int dist = 1 << kk;
-      const float o = __shfl_down(s, dist);
-      if (lane + dist < kWave) s = fmaf(a.cscan[kk], o, s);
-    }
-    if (lane == 0) s_wave[wave] = s;
+    s = scan_step<kDppRowShr1, 0xf>(s, a.clane[0]);
+    s = scan_step<kDppRowShr2, 0xf>(s, a.clane[1]);
+    s = scan_step<kDppRowShr4, 0xf>(s, a.clane[2]);
+    s = scan_step<kDppRowShr8, 0xf>(s, a.clane[3]);
+    s = scan_step<kDppBcast15, 0xa>(s, w_b15);
+    s = scan_step<kDppBcast31, 0xc>(s, w_b31);
+    const int par = (int)(k & 1);
+    if (lane == kWave - 1) s_tot[par][wave] = s;
     __syncthreads();
-    // value of A at the first token after this wave's span, then after this lane's span
-    float after_wave = carry;
-    for (int w = kAdvWaves - 1; w > wave; --w) after_wave = fmaf(a.cwave, after_wave, s_wave[w]);
-    const float tile_first = [&] {  // A at the tile's first token = new carry
-      float x = carry;
-      for (int w = kAdvWaves - 1; w >= 0; --w) x = fmaf(a.cwave, x, s_wave[w]);
-      return x;
-    }();
-    // A at the next lane's first token: its in-wave suffix plus the decayed tail
-    float s_next = __shfl_down(s, 1);
-    // c^(8 (63 - lane)) * after_wave, built from the scan weights (binary expansion)
-    float tail_w = after_wave;
-    {
-      const int e = kWave - 1 - lane;
-#pragma unroll
-      for (int kk = 0; kk < 6; ++kk)
-        if (e & (1 << kk)) tail_w *= a.cscan[kk];
-    }
-    const float a_next = (lane == kWave - 1) ? after_wave : (s_next + tail_w);
+    // the same scan over the sixteen wave totals, one per lane of the first row
+    float p = lane < kAdvWaves ? s_tot[par][lane] : 0.0f;
+    p = scan_step<kDppRowShr1, 0xf>(p, a.cwave[0]);
+    p = scan_step<kDppRowShr2, 0xf>(p, a.cwave[1]);
+    p = scan_step<kDppRowShr4, 0xf>(p, a.cwave[2]);
+    p = scan_step<kDppRowShr8, 0xf>(p, a.cwave[3]);
+    // A at the first token after this wave's span
+    const float before = wave > 0 ? uniform_f32(p, wave - 1) : 0.0f;
+    const float wave_in = fmaf(w_wave, carry, before);
+    carry = fmaf(a.cwave[4], carry, uniform_f32(p, kAdvWaves - 1));  // A at the tile's first token
+    // A at the first token after this lane's span
+    const float s_prev = dpp_f32<kDppWaveShr1, 0xf>(0.0f, s);
+    const float a_next = fmaf(w_lane, wave_in, s_prev);
 
     float outA[kPerLane];
 #pragma unroll
-    for (int j = 0; j < kPerLane; ++j) {
-      const int64_t t = t0 + j;
-      outA[j] = (t < L) ? fmaf(a.cj[kPerLane - j], a_next, loc[j]) : 0.0f;
-    }
-    store8<VEC>(drow, t0, T, d);
-    store8<VEC>(arow, t0, T, outA);
-
-    carry = tile_first;
+    for (int j = 0; j < kPerLane; ++j) outA[j] = (j < rem) ? fmaf(a.cj[kPerLane - j], a_next, loc[j]) : 0.0f;
+    store4<VEC>(drow, t0, T, d);
+    store4<VEC>(arow, t0, T, outA);
     if (k > 0) cur = nxt;
-    __syncthreads();  // s_wave / s_vfirst are rewritten by the next tile
   }
 }
 
@@ -211,8 +220,8 @@ int launch_advantages(const float* rewards, const float* values, const int32_t* 
   const double c = (double)gamma * (double)lambda;
   a.c = (float)c;
   for (int j = 0; j <= kPerLane; ++j) a.cj[j] = (float)pow(c, (double)j);
-  for (int k = 0; k < 6; ++k) a.cscan[k] = (float)pow(c, (double)(kPerLane << k));
-  a.cwave = (float)pow(c, (double)(kPerLane * kWave));
+  for (int k = 0; k < 6; ++k) a.clane[k] = (float)pow(c, (double)(kPerLane << k));
+  for (int k = 0; k < 5; ++k) a.cwave[k] = (float)pow(c, (double)((kPerLane * kWave) << k));
   a.td = td;
   a.adv = adv;
   const bool vec = (T % 4 == 0);
