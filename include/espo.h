@@ -124,11 +124,10 @@ typedef struct {
  *   tokens      device, [B] int32 out.
  *   regret      device, [B] fp32 out.
  *   logprob     device, [B] fp32 out, may be NULL.
- *   workspace   device, at least espo_step_workspace_bytes(B, V, dt) bytes,
- *               256-byte aligned.  It must be zero-filled once before its first
- *               use; every call leaves it zero-filled again, so it can be reused
- *               by the next call on the same stream without clearing.  Calls that
- *               may overlap in time need separate workspaces.
+ *   workspace   device scratch of at least espo_step_workspace_bytes(B, V, dt) bytes.
+ *               A row is handled by one workgroup, so that size is 0 in this version
+ *               and NULL / 0 may be passed; the argument is kept so that the ABI need
+ *               not change if a later version spreads a row over several workgroups.
  *   stream      hipStream_t as void*.
  */
 int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,
@@ -138,7 +137,7 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
               int32_t* tokens, float* regret, float* logprob,
               void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace espo_step needs for this shape (0 on invalid arguments). */
+/* Bytes of workspace espo_step needs for this shape (0 in this version). */
 size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt);
 
 /*
@@ -180,6 +179,18 @@ int espo_advantages(const float* rewards, const float* values,
  * Returns ESPO_EINVAL for scale < 1 or NaN.
  */
 int espo_debug_set_score_margin_scale(float scale);
+
+/*
+ * Diagnostics: measures on the device the accuracy of the hardware logarithm and exponential
+ * that the fp32 scores of espo_step are built from, against the double-precision functions.
+ * `out` is device memory, 3 floats that the caller has set to zero; once the stream has
+ * reached the call they hold the largest relative error of
+ *   out[0]  ln u over every value u(w) = (2r+1)/2^24, r = 0 .. 2^23-1, the stream can produce,
+ *   out[1]  ln x over 2^23 positive floats spread over [2^-26, 64),
+ *   out[2]  exp x over 2^23 points of [-40, 8].
+ * The margin of the fp32 scores assumes at most 1.7e-7, 1.7e-7 and 2e-6.
+ */
+int espo_debug_math_errors(float* out, void* stream);
 
 /* Static, human-readable text for a status code (never NULL). */
 const char* espo_strerror(int code);

@@ -75,6 +75,8 @@ def load_library():
         lib.espo_version.restype = C.c_int
         lib.espo_debug_set_score_margin_scale.restype = C.c_int
         lib.espo_debug_set_score_margin_scale.argtypes = [f32]
+        lib.espo_debug_math_errors.restype = C.c_int
+        lib.espo_debug_math_errors.argtypes = [C.c_void_p, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -100,6 +102,13 @@ def _stream(stream):
 def espo_debug_set_score_margin_scale(scale: float) -> None:
     """Diagnostics: widen the fp32 score margin of espo_step (see include/espo.h)."""
     _check(load_library().espo_debug_set_score_margin_scale(float(scale)))
+
+
+def espo_debug_math_errors(out: torch.Tensor, stream=None) -> None:
+    """Diagnostics: accuracy of the hardware ln / exp on this device (see include/espo.h); `out` = 3 zeroed floats."""
+    if out.numel() < 3:
+        raise ValueError("out: need 3 floats")
+    _check(load_library().espo_debug_math_errors(_dev(out, torch.float32, "out"), _stream(stream)))
 
 
 def espo_step_workspace_bytes(B: int, V: int, dtype: torch.dtype) -> int:

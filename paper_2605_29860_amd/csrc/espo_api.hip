@@ -27,6 +27,11 @@ int espo_debug_set_score_margin_scale(float scale) {
   return ESPO_OK;
 }
 
+int espo_debug_math_errors(float* out, void* stream) {
+  if (!out) return ESPO_EINVAL;
+  return espo::launch_math_errors(out, (hipStream_t)stream);
+}
+
 const char* espo_strerror(int code) {
   switch (code) {
     case ESPO_OK: return "success";

@@ -19,6 +19,8 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
                 float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
                 hipStream_t stream);
 
+int launch_math_errors(float* out, hipStream_t stream);
+
 int launch_advantages(const float* rewards, const float* values, const int32_t* lengths,
                       const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
                       float lambda, float* td, float* adv, hipStream_t stream);

@@ -714,7 +714,46 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   }
 }
 
+// Measures what score_margin assumes about the hardware transcendentals: the largest relative
+// error of flog over every u(w) and over positive floats from 2^-26 to 64, and of fexp over
+// [-40, 8], against the double-precision library functions.  out[0..2] hold the maxima as
+// float bit patterns (non-negative floats order like unsigned integers).
+__global__ void math_error_kernel(uint32_t* out) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;  // 2^23 threads
+  float e_u = 0.0f, e_ln = 0.0f, e_exp = 0.0f;
+  {
+    const float u = (float)(2u * i + 1u) * (1.0f / 16777216.0f);  // every value u(w) takes
+    const double ref = log((double)u);
+    e_u = (float)fabs(((double)flog(u) - ref) / ref);
+  }
+  {
+    // exponents -26..5 (32 of them), 2^18 mantissas each, spread over the 2^23 mantissa values
+    const uint32_t bits = ((101u + (i >> 18)) << 23) | ((i & 0x3ffffu) * 32u + (i >> 18));
+    const float x = __builtin_bit_cast(float, bits);
+    const double ref = log((double)x);
+    if (x != 1.0f) e_ln = (float)fabs(((double)flog(x) - ref) / ref);
+  }
+  {
+    const float x = -40.0f + 48.0f * ((float)i * (1.0f / 8388608.0f));
+    const double ref = exp((double)x);
+    e_exp = (float)fabs(((double)fexp(x) - ref) / ref);
+  }
+  e_u = wave_max(e_u);
+  e_ln = wave_max(e_ln);
+  e_exp = wave_max(e_exp);
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    atomicMax(out + 0, __builtin_bit_cast(uint32_t, e_u));
+    atomicMax(out + 1, __builtin_bit_cast(uint32_t, e_ln));
+    atomicMax(out + 2, __builtin_bit_cast(uint32_t, e_exp));
+  }
+}
+
 }  // namespace
+
+int launch_math_errors(float* out, hipStream_t stream) {
+  hipLaunchKernelGGL(math_error_kernel, dim3(1u << 15), dim3(256), 0, stream, (uint32_t*)out);
+  return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
+}
 
 size_t step_shared_bytes(int dt, int64_t V) { return step_lds_bytes(dt, (int)((V + kTile - 1) / kTile)); }
 

@@ -287,3 +287,69 @@ def test_determinism_resume_and_batch_independence():
     d = run(allrows[:7], 0, steps, H.GpuState(7))
     for k in d[-1]:
         np.testing.assert_array_equal(d[-1][k].view(np.uint8), a[-1][k][:7].view(np.uint8))
+
+
+# --------------------------------------------------------------------------- fp32 scores: margin and exact fallback
+def test_hardware_ln_exp_within_the_margin_assumptions():
+    _say("[case] hardware ln / exp accuracy")
+    # The fp32 scores of espo_step are built from the hardware log2 / exp2; their margin assumes
+    # relative errors of at most 1.7e-7 (ln, also of every u(w)) and 2e-6 (exp).  Measured here
+    # on the device against the double-precision functions.
+    out = torch.zeros(3, dtype=torch.float32, device="cuda")
+    espo.espo_debug_math_errors(out)
+    torch.cuda.synchronize()
+    e_u, e_ln, e_exp = out.cpu().tolist()
+    _say(f"  max relative error: ln u(w) {e_u:.3e}, ln x {e_ln:.3e}, exp x {e_exp:.3e}")
+    assert 0 < e_u <= 1.7e-7 and 0 < e_ln <= 1.7e-7 and 0 < e_exp <= 2e-6
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_exact_fallback_decides_every_row_like_the_oracle(dtype):
+    _say(f"[case] double-precision fallback forced, dtype={dtype}")
+    # A huge margin makes the fp32 search "uncertain" for every row, so every token below is
+    # decided by the double-precision search; it must agree with the oracle, and with the
+    # tokens the default margin gives.
+    B = 6
+    gp, op = H.params_pair(stop_enabled=0)
+    for V, tau in ((37, 1.0), (8200, 0.6), (40000, 1.3)):
+        stride = ((V + 7) // 8) * 8
+        logits = _rand_logits(B, V, stride, dtype, seed=100 + V)
+        vals = torch.zeros(B, device="cuda")
+        tokens = {}
+        for scale in (1.0, 1e12):
+            espo.espo_debug_set_score_margin_scale(scale)
+            try:
+                st = H.GpuState(B)
+                for step in range(3):
+                    got = H.compare_step(logits, tau, 23, step, vals, gp, op, st, V=V)
+                    tokens[(scale, step)] = got["tokens"].copy()
+            finally:
+                espo.espo_debug_set_score_margin_scale(1.0)
+        for step in range(3):
+            np.testing.assert_array_equal(tokens[(1.0, step)], tokens[(1e12, step)])
+
+
+def test_exact_fallback_at_full_width_matches_default_margin():
+    _say("[case] double-precision fallback forced, B=512 x V=152064")
+    B, V = 512, W.QWEN_VOCAB
+    gen = W.ZipfLogits(V=V, seed=11, device="cuda")
+    logits = gen.rows(B, step=0)
+    plant = W.RegretPlant.make(B, V, 0.25, 0, 0, 11)     # flat, tie-heavy rows among them
+    plant.apply(logits, 0)
+    vals = torch.zeros(B, device="cuda")
+    gp, op = H.params_pair(stop_enabled=0)
+    res = {}
+    for scale in (1.0, 1e12):
+        espo.espo_debug_set_score_margin_scale(scale)
+        try:
+            st = H.GpuState(B)
+            H.gpu_step(logits, 0.6, 11, 0, vals, gp, st)
+            torch.cuda.synchronize()
+            res[scale] = st.host()
+        finally:
+            espo.espo_debug_set_score_margin_scale(1.0)
+    for k in ("tokens", "regret", "z"):
+        np.testing.assert_array_equal(res[1.0][k].view(np.uint32), res[1e12][k].view(np.uint32))
+    assert np.abs(res[1.0]["logprob"] - res[1e12]["logprob"]).max() == 0
+    with pytest.raises(espo.EspoError):
+        espo.espo_debug_set_score_margin_scale(0.5)
