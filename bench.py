@@ -47,6 +47,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--adv-reps", type=int, default=60)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copies", type=int, default=0,
+                    help="also launch this many plain 1 GiB copies (known traffic, for counter calibration; untimed)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -96,6 +98,14 @@ def main() -> int:
         run(0, Wm, z, alive, ss)                 # warmup steps are the first steps of the trajectory
         torch.cuda.synchronize()
         return z, alive, ss
+
+    if args.calibration_copies:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(args.calibration_copies):
+            espo.espo_debug_copy(dst, src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ timed region: exactly K steps
     z, alive, ss = fresh_state()

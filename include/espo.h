@@ -192,6 +192,13 @@ int espo_debug_set_score_margin_scale(float scale);
  */
 int espo_debug_math_errors(float* out, void* stream);
 
+/*
+ * Diagnostics: a plain copy kernel (reads `bytes` once, writes them once; device pointers,
+ * 16-byte aligned, bytes a multiple of 16).  It exists so that hardware traffic counters can
+ * be calibrated against a launch whose memory traffic is known exactly.
+ */
+int espo_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* espo_strerror(int code);
 

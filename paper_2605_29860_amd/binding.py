@@ -77,6 +77,8 @@ def load_library():
         lib.espo_debug_set_score_margin_scale.argtypes = [f32]
         lib.espo_debug_math_errors.restype = C.c_int
         lib.espo_debug_math_errors.argtypes = [C.c_void_p, C.c_void_p]
+        lib.espo_debug_copy.restype = C.c_int
+        lib.espo_debug_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = lib
     return _lib
 
@@ -109,6 +111,14 @@ def espo_debug_math_errors(out: torch.Tensor, stream=None) -> None:
     if out.numel() < 3:
         raise ValueError("out: need 3 floats")
     _check(load_library().espo_debug_math_errors(_dev(out, torch.float32, "out"), _stream(stream)))
+
+
+def espo_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:
+    """Diagnostics: plain copy kernel of known traffic, for calibrating hardware counters (see include/espo.h)."""
+    if dst.dtype != src.dtype or dst.numel() != src.numel():
+        raise ValueError("dst and src must match")
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().espo_debug_copy(_dev(dst, dst.dtype, "dst"), _dev(src, src.dtype, "src"), nbytes, _stream(stream)))
 
 
 def espo_step_workspace_bytes(B: int, V: int, dtype: torch.dtype) -> int:

@@ -12,6 +12,13 @@ namespace {
 
 bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// Plain streaming copy, 16 bytes per lane: reads n16*16 bytes once and writes them once.
+typedef unsigned int copy_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void copy_kernel(copy_u32x4* __restrict__ dst, const copy_u32x4* __restrict__ src, size_t n16) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n16) dst[i] = src[i];
+}
+
 std::atomic<float> g_margin_scale{1.0f};
 
 }  // namespace
@@ -30,6 +37,16 @@ int espo_debug_set_score_margin_scale(float scale) {
 int espo_debug_math_errors(float* out, void* stream) {
   if (!out) return ESPO_EINVAL;
   return espo::launch_math_errors(out, (hipStream_t)stream);
+}
+
+int espo_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (!dst || !src || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) return ESPO_EINVAL;
+  if (bytes == 0) return ESPO_OK;
+  const size_t n16 = bytes / 16;
+  if ((n16 + 255) / 256 > 0x7fffffffu) return ESPO_ERANGE;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)((n16 + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     (copy_u32x4*)dst, (const copy_u32x4*)src, n16);
+  return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 
 const char* espo_strerror(int code) {
