@@ -42,6 +42,7 @@ struct StepArgs {
   int64_t row_stride;
   int32_t V, ntiles, nblocks;
   float inv_tau, k2;   // 1/temperature (fp32 division) and inv_tau * log2(e)
+  float ref_lead;      // a lane's softmax reference is advanced once a logit tops it by this much (2^64 in the sum)
   float margin_scale;  // scales the fp32 score margin (1 in production)
   uint32_t key0, key1;
   int32_t step;
@@ -82,6 +83,21 @@ __device__ __forceinline__ Raw<DT> load_raw(const void* row, uint32_t e0, uint32
       const u32x4 u = __builtin_nontemporal_load((const u32x4*)(p + 16));
       r.w[4] = u.x; r.w[5] = u.y; r.w[6] = u.z; r.w[7] = u.w;
     }
+  }
+  return r;
+}
+
+// The same for a tile that lies wholly inside the row: `tile` is the tile's first element
+// (wave-uniform, so the address stays a scalar base plus a constant lane offset).
+template <int DT>
+__device__ __forceinline__ Raw<DT> load_raw_inner(const void* tile, uint32_t lane_bytes) {
+  Raw<DT> r;
+  const char* p = (const char*)tile + lane_bytes;
+  const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
+  r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
+  if constexpr (DT == ESPO_F32) {
+    const u32x4 u = __builtin_nontemporal_load((const u32x4*)(p + 16));
+    r.w[4] = u.x; r.w[5] = u.y; r.w[6] = u.z; r.w[7] = u.w;
   }
   return r;
 }
@@ -261,10 +277,12 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, flo
 
 // ---------------------------------------------------------------- shared memory
 struct StepShared {
-  float* mub;       // [nslots] upper bound of M_q per block slot (tile * 8 + group); phase 1 only
-  int* surv;        // [nslots] survivor list of phase 2 (same memory as mub)
+  float* mu;        // [nslots][2] per block slot (tile * 8 + group): upper bound of M_q (phase 1 only; phase 2
+                    //   keeps its survivor list there), and the bound of the block's best score
   uint32_t* wq;     // [nslots] the block's word of the random stream
-  float* ub;        // [nslots] upper bound of the block's best score
+  __device__ __forceinline__ float& mub(int b) const { return mu[2 * b]; }
+  __device__ __forceinline__ float& ub(int b) const { return mu[2 * b + 1]; }
+  __device__ __forceinline__ int& surv(int k) const { return ((int*)mu)[2 * k]; }
   void* top_raw;    // [kSlots][64 elements] data of each lane group's best block
   int* top_q;       // [kSlots] which block each lane group kept
   float* m;         // [kStepWaves] wave maxima
@@ -300,9 +318,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.fres = (float*)take(5 * kStepWaves * 4);
   s.nsurv = (int*)take(16);
   s.bkey = s.nsurv + 1;
-  s.mub = (float*)take((size_t)nslots * 4);
-  s.surv = (int*)s.mub;
-  s.ub = (float*)take((size_t)nslots * 4);
+  s.mu = (float*)take((size_t)nslots * 8);
   s.wq = (uint32_t*)take((size_t)nslots * 4);
   return s;
 }
@@ -311,8 +327,12 @@ size_t step_lds_bytes(int dt, int ntiles) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
   return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 12 * kStepWaves * 4 + 16 +
-         3 * ((nslots * 4 + 15) & ~(size_t)15);
+         ((nslots * 8 + 15) & ~(size_t)15) + ((nslots * 4 + 15) & ~(size_t)15);
 }
+
+// The streaming loop stores a block's bound as the plain fma(y_max, 1/tau, bound of M_q); what
+// that fma may have rounded away (2^-24 relative) is added back where bounds are compared.
+__device__ __forceinline__ float ub_rounded_up(float u) { return fmaf(fabsf(u), 2e-7f, u); }
 
 // Slot (wave, group) that streamed block q in phase 1.
 __device__ __forceinline__ int slot_of(int q) { return ((q >> 3) & (kStepWaves - 1)) * kGroups + (q & (kGroups - 1)); }
@@ -374,8 +394,8 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
       for (int w = 1; w < kStepWaves; ++w) bound_f = fmaxf(bound_f, sh.lo[w]);
       // blocks whose bound reaches the best score found so far
       for (int b = tid; b < nslots; b += kStepThreads) {
-        const float u = sh.ub[b];
-        if (u > -1e30f && u >= bound_f && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv[atomicAdd(sh.nsurv, 1)] = b;
+        const float u = sh.ub(b);
+        if (u > -1e30f && ub_rounded_up(u) >= bound_f && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       __syncthreads();
       nsurv = *sh.nsurv;
@@ -384,7 +404,7 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
       k += kStepWaves;
     }
     if (k >= nsurv) break;
-    q = sh.surv[k];
+    q = sh.surv(k);
   }
   st = wave_merge(st);
   if (lane == 0) {
@@ -505,8 +525,8 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
       between();
       const float bound = wave_max(lane < kStepWaves ? sh.lo[lane] : kNegInf);
       for (int b = tid; b < nslots; b += kStepThreads) {  // blocks whose bound reaches the best score found so far
-        const float u = sh.ub[b];
-        if (u > -1e30f && u >= bound && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv[atomicAdd(sh.nsurv, 1)] = b;
+        const float u = sh.ub(b);
+        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       if (tid == 0) *sh.bkey = float_key(bound);
       __syncthreads();
@@ -520,8 +540,8 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
     }
     q = -1;
     while (k < nsurv) {  // this wave's next survivor that can still matter
-      const int c = sh.surv[k];
-      if (nsurv <= kStepWaves || sh.ub[c] >= key_float(*sh.bkey)) { q = c; break; }
+      const int c = sh.surv(k);
+      if (nsurv <= kStepWaves || ub_rounded_up(sh.ub(c)) >= key_float(*sh.bkey)) { q = c; break; }
       k += kStepWaves;
     }
     if (q < 0) break;
@@ -574,13 +594,16 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   const int my_tiles = wave < ntiles ? (ntiles - wave + kStepWaves - 1) / kStepWaves : 0;
   const uint32_t last_group = (uint32_t)(a.V - 1) & ~7u;
   const uint32_t lane_off = (uint32_t)lane * 8u;
+  const uint32_t lane_bytes = lane_off * (uint32_t)elem_bytes<DT>();
+  auto load_tile = [&](int t) {  // t is wave-uniform
+    if (t != ntiles - 1) return load_raw_inner<DT>((const char*)rowp + (size_t)t * kTile * elem_bytes<DT>(), lane_bytes);
+    const uint32_t e0 = (uint32_t)t * kTile + lane_off;  // last tile: may be ragged
+    return load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
+  };
   Raw<DT> ring[kRing];
 #pragma unroll
   for (int d = 0; d < kRing; ++d)
-    if (d < my_tiles) {
-      const uint32_t e0 = (uint32_t)(d * kStepWaves + wave) * kTile + lane_off;
-      ring[d] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
-    }
+    if (d < my_tiles) ring[d] = load_tile(d * kStepWaves + wave);
   // While the first loads are in flight: M_q bounds of all blocks, four per Philox call.
   for (int c = tid; c * 4 < nslots; c += kStepThreads) {
     const Philox4 p = philox4x32_10((uint32_t)c, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
@@ -594,7 +617,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         mub += 1e-5f + 4e-7f * fabsf(mub);  // room for the rounding of y_max + M_q below
       }
       if (b < nslots) {
-        sh.mub[b] = mub;
+        sh.mub(b) = mub;
         sh.wq[b] = p.w[j];
       }
     }
@@ -603,13 +626,16 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
 
   // Softmax sum against a lazily advanced per-lane reference: the lane accumulates
   // sum_v 2^(x_v k2 + nrk) with nrk = -(reference logit) * k2; the final combine multiplies
-  // by 2^-(m k2 + nrk), so the rounding of nrk itself cancels.
+  // by 2^-(m k2 + nrk), so the rounding of nrk itself cancels.  `lead` is the logit beyond
+  // which the reference has to move up (the sum would grow past 2^64 per term otherwise).
   float nrk = 1e30f;
+  float lead = kNegInf;
   float sum = 0.0f;
   float mx = kNegInf;        // largest logit this lane group has seen
   float top_ub = kNegInf;    // largest block bound this lane group has seen, and its block
   int top_q = -1;
   char* const my_raw = (char*)sh.top_raw + ((size_t)(wave * kGroups + grp) * kDrawBlock + (lane & 7) * 8) * elem_bytes<DT>();
+  float* const mu_lane = sh.mu + 2 * (wave * kGroups + grp);  // this lane group's entry of tile `wave`; 256 floats per iteration
 
 #pragma unroll 1
   for (int i0 = 0; i0 < my_tiles; i0 += kRing) {
@@ -627,38 +653,36 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
             if (e0 + j >= a.V) x[j] = kNegInf;
         }
         const float gm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        if (__builtin_amdgcn_ballot_w64(fmaf(gm, a.k2, nrk) > kRescaleAt) != 0) {  // rare after the first tile
+        if (__builtin_amdgcn_ballot_w64(gm > lead) != 0) {  // rare after the first tile
           asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
-          if (fmaf(gm, a.k2, nrk) > kRescaleAt) {  // move this lane's reference up to gm
+          if (gm > lead) {  // move this lane's reference up to gm
             const float nrk_new = -gm * a.k2;
             sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
             nrk = nrk_new;
+            lead = gm + a.ref_lead;
           }
         }
-        float acc0 = 0.0f, acc1 = 0.0f;
+        float acc0 = __builtin_amdgcn_exp2f(fmaf(x[0], a.k2, nrk));
+        float acc1 = __builtin_amdgcn_exp2f(fmaf(x[1], a.k2, nrk));
 #pragma unroll
-        for (int j = 0; j < 8; j += 2) {
+        for (int j = 2; j < 8; j += 2) {
           acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
           acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
         }
         sum += acc0 + acc1;
-        // upper bound of every perturbed score in the lane group's block: y_max + M_q, rounded up
+        // upper bound of every perturbed score in the lane group's block: y_max + M_q
         const float bm = group8_max(gm);
-        const int q = t * kGroups + grp;
-        float ub = fmaf(fmaxf(bm, -1e30f), a.inv_tau, sh.mub[q]);
-        ub = fmaf(fabsf(ub), 4e-7f, ub);
-        sh.ub[q] = ub;  // the 8 lanes of the group store the same value
+        float* const mu = mu_lane + (size_t)i * (2 * kStepWaves * kGroups);
+        const float ub = fmaf(bm, a.inv_tau, mu[0]);
+        mu[1] = ub;  // the 8 lanes of the group store the same value
         mx = fmaxf(mx, bm);
         if (ub > top_ub) {  // keep the data of the block with the group's largest bound
           top_ub = ub;
-          top_q = q;
+          top_q = t * kGroups + grp;
           *(u32x4*)my_raw = u32x4{ring[d].w[0], ring[d].w[1], ring[d].w[2], ring[d].w[3]};
           if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{ring[d].w[4], ring[d].w[5], ring[d].w[6], ring[d].w[7]};
         }
-        if (i + kRing < my_tiles) {  // refill this ring slot
-          const uint32_t en = (uint32_t)(t + kRing * kStepWaves) * kTile + lane_off;
-          ring[d] = load_raw<DT>(rowp, en < last_group ? en : last_group, (uint32_t)a.V);
-        }
+        if (i + kRing < my_tiles) ring[d] = load_tile(t + kRing * kStepWaves);  // refill this ring slot
       }
     }
   }
@@ -769,6 +793,7 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.nblocks = (int)((V + kDrawBlock - 1) / kDrawBlock);
   a.inv_tau = 1.0f / temperature;
   a.k2 = a.inv_tau * kLog2e;
+  a.ref_lead = kRescaleAt / a.k2;
   a.margin_scale = margin_scale;
   a.key0 = (uint32_t)(seed & 0xffffffffu);
   a.key1 = (uint32_t)(seed >> 32);
