@@ -22,6 +22,8 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "../../include/espo.h"
 #include "espo_device.h"
 #include "espo_host.h"
@@ -637,54 +639,68 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   char* const my_raw = (char*)sh.top_raw + ((size_t)(wave * kGroups + grp) * kDrawBlock + (lane & 7) * 8) * elem_bytes<DT>();
   float* const mu_lane = sh.mu + 2 * (wave * kGroups + grp);  // this lane group's entry of tile `wave`; 256 floats per iteration
 
-#pragma unroll 1
-  for (int i0 = 0; i0 < my_tiles; i0 += kRing) {
+  // One wave iteration over ring slot d, tile index i of this wave.  `Steady` iterations are
+  // those that need no checks: the tile is whole, not the row's last, and its ring slot is
+  // refilled with a tile that is not the last either.
+  auto iteration = [&](auto steady, int d, int i) {
+    constexpr bool Steady = decltype(steady)::value;
+    const int t = i * kStepWaves + wave;
+    float x[8];
+    unpack<DT>(ring[d], x);
+    if (!Steady && (t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
+      const int32_t e0 = t * kTile + (int32_t)lane_off;
 #pragma unroll
-    for (int d = 0; d < kRing; ++d) {
-      const int i = i0 + d;
-      if (i < my_tiles) {  // wave-uniform
-        const int t = i * kStepWaves + wave;
-        float x[8];
-        unpack<DT>(ring[d], x);
-        if ((t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
-          const int32_t e0 = t * kTile + (int32_t)lane_off;
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            if (e0 + j >= a.V) x[j] = kNegInf;
-        }
-        const float gm = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-        if (__builtin_amdgcn_ballot_w64(gm > lead) != 0) {  // rare after the first tile
-          asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
-          if (gm > lead) {  // move this lane's reference up to gm
-            const float nrk_new = -gm * a.k2;
-            sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
-            nrk = nrk_new;
-            lead = gm + a.ref_lead;
-          }
-        }
-        float acc0 = __builtin_amdgcn_exp2f(fmaf(x[0], a.k2, nrk));
-        float acc1 = __builtin_amdgcn_exp2f(fmaf(x[1], a.k2, nrk));
-#pragma unroll
-        for (int j = 2; j < 8; j += 2) {
-          acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
-          acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
-        }
-        sum += acc0 + acc1;
-        // upper bound of every perturbed score in the lane group's block: y_max + M_q
-        const float bm = group8_max(gm);
-        float* const mu = mu_lane + (size_t)i * (2 * kStepWaves * kGroups);
-        const float ub = fmaf(bm, a.inv_tau, mu[0]);
-        mu[1] = ub;  // the 8 lanes of the group store the same value
-        mx = fmaxf(mx, bm);
-        if (ub > top_ub) {  // keep the data of the block with the group's largest bound
-          top_ub = ub;
-          top_q = t * kGroups + grp;
-          *(u32x4*)my_raw = u32x4{ring[d].w[0], ring[d].w[1], ring[d].w[2], ring[d].w[3]};
-          if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{ring[d].w[4], ring[d].w[5], ring[d].w[6], ring[d].w[7]};
-        }
-        if (i + kRing < my_tiles) ring[d] = load_tile(t + kRing * kStepWaves);  // refill this ring slot
+      for (int j = 0; j < 8; ++j)
+        if (e0 + j >= a.V) x[j] = kNegInf;
+    }
+    const float gm = fmaxf(fmaxf(fmaxf(fmaxf(fmaxf(x[0], x[1]), x[2]), fmaxf(fmaxf(x[3], x[4]), x[5])), x[6]), x[7]);
+    if (__builtin_amdgcn_ballot_w64(gm > lead) != 0) {  // rare after the first tile
+      asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
+      if (gm > lead) {  // move this lane's reference up to gm
+        const float nrk_new = -gm * a.k2;
+        sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
+        nrk = nrk_new;
+        lead = gm + a.ref_lead;
       }
     }
+    float acc0 = __builtin_amdgcn_exp2f(fmaf(x[0], a.k2, nrk));
+    float acc1 = __builtin_amdgcn_exp2f(fmaf(x[1], a.k2, nrk));
+#pragma unroll
+    for (int j = 2; j < 8; j += 2) {
+      acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
+      acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
+    }
+    sum += acc0 + acc1;
+    // upper bound of every perturbed score in the lane group's block: y_max + M_q
+    const float bm = group8_max(gm);
+    float* const mu = mu_lane + (size_t)i * (2 * kStepWaves * kGroups);
+    const float ub = fmaf(bm, a.inv_tau, mu[0]);
+    mu[1] = ub;  // the 8 lanes of the group store the same value
+    mx = fmaxf(mx, bm);
+    if (ub > top_ub) {  // keep the data of the block with the group's largest bound
+      top_ub = ub;
+      top_q = t * kGroups + grp;
+      *(u32x4*)my_raw = u32x4{ring[d].w[0], ring[d].w[1], ring[d].w[2], ring[d].w[3]};
+      if constexpr (DT == ESPO_F32) *(u32x4*)(my_raw + 16) = u32x4{ring[d].w[4], ring[d].w[5], ring[d].w[6], ring[d].w[7]};
+    }
+    if (Steady)  // refill this ring slot
+      ring[d] = load_raw_inner<DT>((const char*)rowp + (size_t)(t + kRing * kStepWaves) * kTile * elem_bytes<DT>(), lane_bytes);
+    else if (i + kRing < my_tiles)
+      ring[d] = load_tile(t + kRing * kStepWaves);
+  };
+  // Steady passes: all kRing tiles and their refills lie before this wave's last tile.
+  const int steady_end = my_tiles > 2 * kRing ? ((my_tiles - kRing - 1) / kRing) * kRing : 0;
+  int i0 = 0;
+#pragma unroll 1
+  for (; i0 < steady_end; i0 += kRing) {
+#pragma unroll
+    for (int d = 0; d < kRing; ++d) iteration(std::true_type{}, d, i0 + d);
+  }
+#pragma unroll 1
+  for (; i0 < my_tiles; i0 += kRing) {
+#pragma unroll
+    for (int d = 0; d < kRing; ++d)
+      if (i0 + d < my_tiles) iteration(std::false_type{}, d, i0 + d);  // wave-uniform
   }
   // The wave's largest logit, and the block with its largest bound (lowest block among equals).
   const float mw = wave_max(mx);
