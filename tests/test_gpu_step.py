@@ -353,3 +353,22 @@ def test_exact_fallback_at_full_width_matches_default_margin():
     assert np.abs(res[1.0]["logprob"] - res[1e12]["logprob"]).max() == 0
     with pytest.raises(espo.EspoError):
         espo.espo_debug_set_score_margin_scale(0.5)
+
+
+# --------------------------------------------------------------------------- largest supported vocabulary
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_largest_vocabulary_and_range_error(dtype):
+    _say(f"[case] V = 400000 (more than 64 KB of LDS per workgroup), dtype={dtype}")
+    B, V = 3, 400000
+    logits = _rand_logits(B, V, V, dtype, seed=77)
+    logits[1, 399999] = 25.0                                  # the mode in the very last block
+    gp, op = H.params_pair(stop_enabled=0)
+    st = H.GpuState(B)
+    vals = torch.zeros(B, device="cuda")
+    for step in range(2):
+        got = H.compare_step(logits, 1.0, 31, step, vals, gp, op, st)
+        assert ((got["tokens"] >= 0) & (got["tokens"] < V)).all()
+    big = torch.zeros(1, 400008, dtype=dtype, device="cuda")
+    with pytest.raises(espo.EspoError) as e:
+        H.gpu_step(big, 1.0, 0, 0, vals[:1], gp, H.GpuState(1), V=400001)
+    assert e.value.code == -5
