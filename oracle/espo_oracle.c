@@ -387,3 +387,63 @@ int oracle_gae_bruteforce(const float* rewards, const float* values,
   }
   return 0;
 }
+
+/*
+ * Batch-boundary update of the frozen statistics and of the threshold multiplier
+ * (Section 4.2: EMA of the batch mean and variance of the regret; Eq. beta_update).
+ *
+ * The batch B is every valid token of every trajectory: regret[b,t] for t < L_b
+ * (L_b clamped to [0,T]); entries at t >= L_b are never read.  Mean and variance are the
+ * plain two-pass definitions in double, the variance with divisor n (the paper writes
+ * Var(g_B) without a correction).  The stop rate is the fraction of trajectories that the
+ * stop rule ended.  The three updated parameters are formed in double and rounded to
+ * float once, since they are float fields of the rollout parameters.
+ *   out[0] batch mean, out[1] batch variance, out[2] stop rate,
+ *   out[3] mu_g', out[4] var_g', out[5] beta' (each exactly a float), out[6] token count n.
+ * With n = 0 the two statistics are left as they are; with B = 0 beta as well.
+ */
+int oracle_batch_stats(const float* regret, const int32_t* lengths, const uint8_t* stopped,
+                       int64_t B, int64_t T, float mu_g, float var_g, float beta,
+                       float alpha_ema, float eta_beta, float target_rate, float beta_min, float beta_max,
+                       double* out) {
+  if (B < 0 || T < 0 || !out) return -1;
+  if (B > 0 && (!lengths || !stopped || (T > 0 && !regret))) return -1;
+  double n = 0.0, sum = 0.0;
+  int64_t nstop = 0;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    for (int64_t t = 0; t < L; ++t) sum += (double)regret[b * T + t];
+    n += (double)L;
+    if (stopped[b]) ++nstop;
+  }
+  const double mean = n > 0.0 ? sum / n : 0.0;
+  double ss = 0.0;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    for (int64_t t = 0; t < L; ++t) {
+      const double d = (double)regret[b * T + t] - mean;
+      ss += d * d;
+    }
+  }
+  const double var = n > 0.0 ? ss / n : 0.0;
+  const double rate = B > 0 ? (double)nstop / (double)B : 0.0;
+  const double a = (double)alpha_ema;
+  float mu_new = mu_g, var_new = var_g, beta_new = beta;
+  if (n > 0.0) {
+    mu_new = (float)(a * (double)mu_g + (1.0 - a) * mean);
+    var_new = (float)(a * (double)var_g + (1.0 - a) * var);
+  }
+  if (B > 0) {
+    double bt = (double)beta + (double)eta_beta * (rate - (double)target_rate);   /* Eq. beta_update */
+    if (bt < (double)beta_min) bt = (double)beta_min;
+    if (bt > (double)beta_max) bt = (double)beta_max;
+    beta_new = (float)bt;
+  }
+  out[0] = mean; out[1] = var; out[2] = rate;
+  out[3] = (double)mu_new; out[4] = (double)var_new; out[5] = (double)beta_new; out[6] = n;
+  return 0;
+}

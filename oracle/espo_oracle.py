@@ -70,6 +70,8 @@ def _load():
         lib.oracle_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
         lib.oracle_gae_bruteforce.restype = C.c_int
         lib.oracle_gae_bruteforce.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp]
+        lib.oracle_batch_stats.restype = C.c_int
+        lib.oracle_batch_stats.argtypes = [vp, vp, vp, i64, i64, f32, f32, f32, f32, f32, f32, f32, f32, vp]
         lib.oracle_philox4x32_10.restype = None
         lib.oracle_philox4x32_10.argtypes = [vp, vp, vp]
         lib.oracle_stream_word.restype = C.c_uint32
@@ -236,3 +238,23 @@ def gae_bruteforce(rewards: np.ndarray, values: np.ndarray, lengths: np.ndarray,
     if rc != 0:
         raise ValueError("oracle_gae_bruteforce: invalid arguments")
     return adv
+
+
+def batch_stats(regret: np.ndarray, lengths: np.ndarray, stopped: np.ndarray, mu_g: float, var_g: float,
+                beta: float, alpha_ema: float, eta_beta: float, target_rate: float, beta_min: float,
+                beta_max: float) -> dict:
+    """Batch mean / variance of the regret over valid tokens, stop rate, and the updated
+    (mu_g, var_g, beta) of Section 4.2 and Eq. beta_update."""
+    assert regret.ndim == 2
+    B, T = regret.shape
+    _chk(regret, np.float32, (B, T), "regret")
+    _chk(lengths, np.int32, (B,), "lengths")
+    _chk(stopped, np.uint8, (B,), "stopped")
+    out = np.zeros(7, np.float64)
+    rc = _load().oracle_batch_stats(_ptr(regret), _ptr(lengths), _ptr(stopped), B, T, float(mu_g), float(var_g),
+                                    float(beta), float(alpha_ema), float(eta_beta), float(target_rate),
+                                    float(beta_min), float(beta_max), _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle_batch_stats: invalid arguments")
+    return {"mean": out[0], "var": out[1], "stop_rate": out[2], "mu_g": np.float32(out[3]),
+            "var_g": np.float32(out[4]), "beta": np.float32(out[5]), "tokens": int(out[6])}
