@@ -164,6 +164,26 @@ def main() -> int:
     adv_bytes = valid * 16 + (B_ADV * T_ADV - valid) * 8 + B_ADV * 5
     adv_gbs = float(adv_bytes.sum() / (adv_region_ms * 1e-3) / 1e9)
 
+    # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
+    bs_sets = [W.regret_batch(512, 8192, seed=70 + i, device=dev) for i in range(nbuf)]   # 134 MB in rotation
+    bs_out = torch.zeros(espo.BATCH_RESULT_BYTES, dtype=torch.uint8, device=dev)
+    bs_ws = torch.zeros(espo.espo_batch_stats_workspace_bytes(512, 8192), dtype=torch.uint8, device=dev)
+    def bs_call(i):
+        g, L, s = bs_sets[i % nbuf]
+        espo.espo_batch_stats(g, L, s, 1.0, 2.0, 7.0, bs_out, bs_ws)
+    for i in range(nbuf):
+        bs_call(i)
+    torch.cuda.synchronize()
+    bregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    bregion[0].record()
+    for i in range(args.adv_reps):
+        bs_call(i)
+    bregion[1].record()
+    torch.cuda.synchronize()
+    bs_us = bregion[0].elapsed_time(bregion[1]) / args.adv_reps * 1e3
+    bs_bytes = float(np.mean([int(bs_sets[i % nbuf][1].sum()) * 4 + 512 * 5 for i in range(args.adv_reps)]))
+    bs_res = espo.read_batch_result(bs_out)
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample (context only)
     cpu = None
     if not args.no_cpu_baseline:
@@ -213,6 +233,10 @@ def main() -> int:
                                     "avg_launch_us_event_pair_each": float(adv_ms.mean() * 1e3),
                                     "algorithmic_bytes_per_launch": float(adv_bytes.mean()),
                                     "traffic": _traffic_from_profiles("espo_advantages")}},
+        "batch_stats": {"workload": "B=512, T=8192 fp32 regrets, lengths U[64,8192], 25% stopped, 8 rotated sets",
+                        "us_per_call": bs_us, "algorithmic_bytes_per_call": bs_bytes,
+                        "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,
+                        "mu_g": bs_res["mu_g"], "var_g": bs_res["var_g"], "beta": bs_res["beta"]},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

@@ -9,9 +9,10 @@
  * the failure reward placed at the stop step (Section 4.4, Eq. failure_reward,
  * Eq. gae).
  *
- * Two operations are exported:
- *   espo_step        one decode step for a batch of trajectories (Algorithm 1 body)
- *   espo_advantages  TD errors + GAE over the truncated trajectories (Section 3, 4.4)
+ * Three operations are exported:
+ *   espo_step         one decode step for a batch of trajectories (Algorithm 1 body)
+ *   espo_advantages   TD errors + GAE over the truncated trajectories (Section 3, 4.4)
+ *   espo_batch_stats  update of the frozen statistics and of beta between batches (Section 4.2, 4.3)
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory owned by the caller; the library
@@ -169,6 +170,62 @@ int espo_advantages(const float* rewards, const float* values,
                     const int32_t* lengths, const uint8_t* stopped,
                     int64_t B, int64_t T, float r_fail, float gamma, float lambda,
                     float* td, float* adv, void* stream);
+
+/*
+ * espo_batch_stats -- the update at the boundary of a rollout batch: exponential moving
+ * averages of the batch mean and variance of the regret (Section 4.2) and the proportional
+ * controller of the threshold multiplier (Eq. beta_update).  The statistics stay frozen
+ * during a rollout; this call produces the values for the next one.
+ *
+ * The batch is every valid token of every trajectory, regret[b, t] for
+ * t < L_b = min(max(lengths[b], 0), T); entries at t >= L_b are never read.  With n = sum L_b:
+ *   mean = sum g / n,   var = sum (g - mean)^2 / n     (divisor n, accumulated in double)
+ *   rate = (number of rows with stopped[b] != 0) / B
+ *   mu_g'  = alpha_ema * mu_g  + (1 - alpha_ema) * mean
+ *   var_g' = alpha_ema * var_g + (1 - alpha_ema) * var
+ *   beta'  = min(max(beta + eta_beta * (rate - target_rate), beta_min), beta_max)
+ * each formed in double and rounded to float once.  With n = 0 mu_g and var_g are returned
+ * unchanged; with B = 0 beta as well.  The result does not depend on scheduling (fixed
+ * reduction order).
+ *
+ * Arguments
+ *   regret      device, [B, T] fp32 row-major (the per-step `regret` outputs of espo_step laid
+ *               out by trajectory), 16-byte aligned base.
+ *   lengths     device, [B] int32;  stopped  device, [B] uint8.
+ *   B, T        B >= 0, T >= 0.
+ *   mu_g, var_g, beta   the values the finished rollout used.
+ *   ctrl        host, read during the call.  alpha_ema in [0,1]; beta_min <= beta_max.
+ *   out         device, one espo_batch_result, written once the stream reaches the call.
+ *   workspace   device scratch of at least espo_batch_stats_workspace_bytes(B, T) bytes,
+ *               8-byte aligned; contents before and after the call are irrelevant.
+ *   stream      hipStream_t as void*.
+ */
+typedef struct {
+  float alpha_ema;   /* paper: 0.99 */
+  float eta_beta;    /* adjustment rate of beta, paper: 0.1 */
+  float target_rate; /* target termination rate, paper: 0.25 */
+  float beta_min;    /* paper: 0.0 */
+  float beta_max;    /* upper clip; the paper gives no value (its initial beta is 7.0) */
+} espo_batch_ctrl;
+
+typedef struct {
+  double mean_g;      /* batch mean of the regret over the valid tokens */
+  double var_g_batch; /* batch variance, divisor n */
+  double stop_rate;   /* fraction of trajectories ended by the stop rule */
+  int64_t tokens;     /* n */
+  float mu_g;         /* updated parameters for the next rollout */
+  float var_g;
+  float beta;
+  int32_t stopped;    /* number of trajectories ended by the stop rule */
+} espo_batch_result;
+
+int espo_batch_stats(const float* regret, const int32_t* lengths, const uint8_t* stopped,
+                     int64_t B, int64_t T, float mu_g, float var_g, float beta,
+                     const espo_batch_ctrl* ctrl, espo_batch_result* out,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace espo_batch_stats needs (at most 32 KiB). */
+size_t espo_batch_stats_workspace_bytes(int64_t B, int64_t T);
 
 /*
  * Diagnostics for the callers that test the library (not part of the method): espo_step

@@ -53,6 +53,20 @@ def library_path() -> str:
     return _LIB_PATH
 
 
+class _BatchCtrl(C.Structure):
+    _fields_ = [("alpha_ema", C.c_float), ("eta_beta", C.c_float), ("target_rate", C.c_float),
+                ("beta_min", C.c_float), ("beta_max", C.c_float)]
+
+
+class _BatchResult(C.Structure):
+    _fields_ = [("mean_g", C.c_double), ("var_g_batch", C.c_double), ("stop_rate", C.c_double),
+                ("tokens", C.c_int64), ("mu_g", C.c_float), ("var_g", C.c_float), ("beta", C.c_float),
+                ("stopped", C.c_int32)]
+
+
+BATCH_RESULT_BYTES = C.sizeof(_BatchResult)
+
+
 def load_library():
     """Loads libespo.so (built in-tree by `build.py`); raises if it is not there."""
     global _lib
@@ -77,6 +91,10 @@ def load_library():
         lib.espo_debug_set_score_margin_scale.argtypes = [f32]
         lib.espo_debug_math_errors.restype = C.c_int
         lib.espo_debug_math_errors.argtypes = [C.c_void_p, C.c_void_p]
+        lib.espo_batch_stats.restype = C.c_int
+        lib.espo_batch_stats.argtypes = [vp, vp, vp, i64, i64, f32, f32, f32, C.POINTER(_BatchCtrl), vp, vp, sz, vp]
+        lib.espo_batch_stats_workspace_bytes.restype = sz
+        lib.espo_batch_stats_workspace_bytes.argtypes = [i64, i64]
         lib.espo_debug_copy.restype = C.c_int
         lib.espo_debug_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         _lib = lib
@@ -111,6 +129,35 @@ def espo_debug_math_errors(out: torch.Tensor, stream=None) -> None:
     if out.numel() < 3:
         raise ValueError("out: need 3 floats")
     _check(load_library().espo_debug_math_errors(_dev(out, torch.float32, "out"), _stream(stream)))
+
+
+def espo_batch_stats_workspace_bytes(B: int, T: int) -> int:
+    return int(load_library().espo_batch_stats_workspace_bytes(B, T))
+
+
+def espo_batch_stats(regret: torch.Tensor, lengths: torch.Tensor, stopped: torch.Tensor, mu_g: float, var_g: float,
+                     beta: float, out: torch.Tensor, workspace: torch.Tensor, alpha_ema: float = 0.99,
+                     eta_beta: float = 0.1, target_rate: float = 0.25, beta_min: float = 0.0, beta_max: float = 7.0,
+                     stream=None) -> None:
+    """Batch-boundary update (Section 4.2, Eq. beta_update).  `out`: uint8 GPU tensor of BATCH_RESULT_BYTES bytes
+    (decode a host copy with `read_batch_result`); `workspace`: uint8 GPU tensor of the size the library asks for."""
+    if regret.dim() != 2:
+        raise ValueError("regret must be [B, T]")
+    B, T = regret.shape
+    if out.numel() * out.element_size() < BATCH_RESULT_BYTES:
+        raise ValueError("out is too small")
+    ctrl = _BatchCtrl(alpha_ema, eta_beta, target_rate, beta_min, beta_max)
+    _check(load_library().espo_batch_stats(
+        _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
+        B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out"),
+        _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def read_batch_result(out: torch.Tensor) -> dict:
+    """Host view of an espo_batch_result that `espo_batch_stats` wrote (synchronises through the copy)."""
+    raw = bytes(out.cpu().numpy().tobytes()[:BATCH_RESULT_BYTES])
+    r = _BatchResult.from_buffer_copy(raw)
+    return {name: getattr(r, name) for name, _ in _BatchResult._fields_}
 
 
 def espo_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> None:

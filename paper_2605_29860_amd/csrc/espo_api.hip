@@ -39,6 +39,28 @@ int espo_debug_math_errors(float* out, void* stream) {
   return espo::launch_math_errors(out, (hipStream_t)stream);
 }
 
+size_t espo_batch_stats_workspace_bytes(int64_t B, int64_t T) {
+  (void)T;
+  return espo::batch_stats_workspace(B);
+}
+
+int espo_batch_stats(const float* regret, const int32_t* lengths, const uint8_t* stopped, int64_t B, int64_t T,
+                     float mu_g, float var_g, float beta, const espo_batch_ctrl* ctrl, espo_batch_result* out,
+                     void* workspace, size_t workspace_bytes, void* stream) {
+  if (B < 0 || T < 0 || !ctrl || !out) return ESPO_EINVAL;
+  if (!(ctrl->alpha_ema >= 0.0f && ctrl->alpha_ema <= 1.0f) || !(ctrl->beta_min <= ctrl->beta_max)) return ESPO_EINVAL;
+  if (!isfinite(ctrl->eta_beta) || !isfinite(ctrl->target_rate) || !isfinite(mu_g) || !isfinite(var_g) || !isfinite(beta))
+    return ESPO_EINVAL;
+  if (B > 0 && (!lengths || !stopped || (T > 0 && !regret))) return ESPO_EINVAL;
+  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (regret && !aligned16(regret)) return ESPO_EALIGN;
+  if (((uintptr_t)out & 7u) != 0) return ESPO_EALIGN;
+  if (B > 0 && (!workspace || workspace_bytes < espo::batch_stats_workspace(B) || ((uintptr_t)workspace & 7u) != 0))
+    return ESPO_EWORKSPACE;
+  return espo::launch_batch_stats(regret, lengths, stopped, B, T, mu_g, var_g, beta, *ctrl, out, workspace,
+                                  (hipStream_t)stream);
+}
+
 int espo_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) return ESPO_EINVAL;
   if (bytes == 0) return ESPO_OK;

@@ -19,6 +19,12 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
                 float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
                 hipStream_t stream);
 
+size_t batch_stats_workspace(int64_t B);
+
+int launch_batch_stats(const float* regret, const int32_t* lengths, const uint8_t* stopped, int64_t B, int64_t T,
+                       float mu_g, float var_g, float beta, const espo_batch_ctrl& c, espo_batch_result* out,
+                       void* workspace, hipStream_t stream);
+
 int launch_math_errors(float* out, hipStream_t stream);
 
 int launch_advantages(const float* rewards, const float* values, const int32_t* lengths,

@@ -217,3 +217,25 @@ def advantage_batch(B: int = 1024, T: int = 16384, len_lo: int = 512, len_hi: in
         rewards[pad] = math.nan
     return (rewards, values, lengths.to(torch.int32).to(device),
             stopped.to(torch.uint8).to(device))
+
+
+# --------------------------------------------------------------------------- batch-boundary statistics
+def regret_batch(B: int = 512, T: int = 8192, len_lo: int = 64, stop_fraction: float = 0.25, seed: int = 0,
+                 device="cpu", poison: bool = False):
+    """Per-token regrets of a finished rollout batch, shaped like what espo_step emits on the
+    Qwen-vocabulary rows: zero when the mode was sampled (a bit more than half of the tokens),
+    otherwise exponential with mean 2.2; lengths ~ U{len_lo..T}; `stop_fraction` of the rows
+    ended by the stop rule.  With `poison` everything at t >= length is NaN.
+    Returns (regret [B,T] f32, lengths [B] i32, stopped [B] u8).
+    """
+    g = _gen("cpu", seed, 701)
+    lengths = torch.randint(min(len_lo, T), T + 1, (B,), generator=g, dtype=torch.int64)
+    stopped = torch.rand(B, generator=g) < stop_fraction
+    gd = _gen(device, seed, 702)
+    u = torch.rand(B, T, generator=gd, device=device, dtype=torch.float32)
+    e = torch.rand(B, T, generator=gd, device=device, dtype=torch.float32)
+    regret = torch.where(u < 0.55, torch.zeros_like(u), -2.2 * torch.log1p(-e))
+    if poison:
+        t = torch.arange(T, device=device)[None, :]
+        regret[t >= lengths.to(device)[:, None]] = float("nan")
+    return regret, lengths.to(torch.int32).to(device), stopped.to(torch.uint8).to(device)

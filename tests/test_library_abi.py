@@ -29,7 +29,8 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"espo_step", "espo_advantages", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
-            "espo_debug_set_score_margin_scale", "espo_debug_math_errors", "espo_debug_copy"} <= set(names)
+            "espo_debug_set_score_margin_scale", "espo_debug_math_errors", "espo_debug_copy", "espo_batch_stats",
+            "espo_batch_stats_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 
