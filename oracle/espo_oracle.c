@@ -44,6 +44,9 @@ typedef struct {
   float mu_g, var_g, delta, clip_c, alpha_s, beta, eps;
   int32_t stop_enabled;
   int32_t eos_id;
+  int32_t stop_mode;      /* 0 full rule; 1 value only; 2 regret only; 3 random (Section 6, variants D, E, F) */
+  float stop_threshold;   /* the fixed threshold of variants D and E; the per-step stop probability of F      */
+  int32_t simulate;       /* record the first stop step but keep decoding ("ESPO/Original", Section 7)        */
 } oracle_params;
 
 /* ------------------------------------------------------------------ Philox4x32-10 */
@@ -143,6 +146,48 @@ double oracle_gumbel_at(uint64_t seed, int64_t row, int32_t step, int64_t v, int
   int64_t pos;
   oracle_block_draw(seed, row, step, q, n, &M, &pos);
   return gumbel_in_block(seed, row, step, v, first, M, pos);
+}
+
+/*
+ * The stop decision of one live row at one step, after its state z has been advanced.
+ *   mode 0  Eq. stop_rule: z > beta * max(V, eps), strict, in fp32.
+ *   mode 1  the value alone: V < threshold (ablation D).
+ *   mode 2  the smoothed regret alone: z > threshold (ablation E).
+ *   mode 3  a coin: u < threshold with u = u(word 0 of Philox(counter (0, step, row,
+ *           0x53544F50), key)), independent of logits and values (ablation F).
+ * All are gated by stop_enabled.
+ */
+static int stop_decision(const oracle_params* p, float zn, float value, uint64_t seed, int64_t row, int32_t step) {
+  if (!p->stop_enabled) return 0;
+  switch (p->stop_mode) {
+    case 1: return value < p->stop_threshold;
+    case 2: return zn > p->stop_threshold;
+    case 3: {
+      const uint32_t ctr[4] = {0u, (uint32_t)step, (uint32_t)row, 0x53544F50u};
+      const uint32_t key[2] = {(uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32)};
+      uint32_t w[4];
+      oracle_philox4x32_10(ctr, key, w);
+      return oracle_uniform(w[0]) < (double)p->stop_threshold;
+    }
+    default: {
+      const float thr = p->beta * fmaxf(value, p->eps);
+      return zn > thr;                                   /* Eq. stop_rule, strict     */
+    }
+  }
+}
+
+/* What a stop (or the end-of-sequence token) does to the row's state. */
+static void apply_end(const oracle_params* p, int eos, int stop, int32_t step, uint8_t* alive, int32_t* stop_step) {
+  if (eos) {
+    *alive = 0;                                          /* natural end, not a failure */
+  } else if (stop) {
+    if (p->simulate) {
+      if (*stop_step < 0) *stop_step = step;             /* first stop only; decoding goes on */
+    } else {
+      *alive = 0;                                        /* absorbing failure          */
+      *stop_step = step;
+    }
+  }
 }
 
 static inline float load_logit(const void* base, int dtype, int64_t idx) {
@@ -253,19 +298,13 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
     const float gt = fminf(fmaxf(n, -p->clip_c), p->clip_c);   /* Eq. normalized_gap  */
     const float t = oma * gt;
     const float zn = fmaf(p->alpha_s, z[b], t);          /* Eq. smoothed_score        */
-    const float thr = p->beta * fmaxf(values[b], p->eps);
-    const int stop = p->stop_enabled && (zn > thr);      /* Eq. stop_rule, strict     */
+    const int stop = stop_decision(p, zn, values[b], seed, b, step);
 
     tokens[b] = (int32_t)a;
     regret[b] = g;
     z[b] = zn;
     if (logprob) logprob[b] = (float)(-(double)g - log(S));
-    if (p->eos_id >= 0 && a == (int64_t)p->eos_id) {
-      alive[b] = 0;                                      /* natural end, not a failure */
-    } else if (stop) {
-      alive[b] = 0;                                      /* absorbing failure          */
-      stop_step[b] = step;
-    }
+    apply_end(p, p->eos_id >= 0 && a == (int64_t)p->eos_id, stop, step, &alive[b], &stop_step[b]);
     if (best_score) best_score[b] = s1;
     if (second_score) second_score[b] = s2;
     if (second_token) second_token[b] = (int32_t)a2;
@@ -281,7 +320,7 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
  * row of a large batch from a recorded regret/token stream.
  */
 int oracle_state_update(int64_t B, const float* g, const int32_t* tokens, const float* values,
-                        const oracle_params* p, int32_t step,
+                        const oracle_params* p, uint64_t seed, int32_t step,
                         float* z, uint8_t* alive, int32_t* stop_step) {
   if (!g || !tokens || !values || !p || !z || !alive || !stop_step || B < 0) return -1;
   const float rsd = 1.0f / sqrtf(p->var_g + p->delta);
@@ -292,15 +331,9 @@ int oracle_state_update(int64_t B, const float* g, const int32_t* tokens, const 
     const float gt = fminf(fmaxf(n, -p->clip_c), p->clip_c);
     const float t = oma * gt;
     const float zn = fmaf(p->alpha_s, z[b], t);
-    const float thr = p->beta * fmaxf(values[b], p->eps);
-    const int stop = p->stop_enabled && (zn > thr);
+    const int stop = stop_decision(p, zn, values[b], seed, b, step);
     z[b] = zn;
-    if (p->eos_id >= 0 && tokens[b] == p->eos_id) {
-      alive[b] = 0;
-    } else if (stop) {
-      alive[b] = 0;
-      stop_step[b] = step;
-    }
+    apply_end(p, p->eos_id >= 0 && tokens[b] == p->eos_id, stop, step, &alive[b], &stop_step[b]);
   }
   return 0;
 }

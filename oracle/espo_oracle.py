@@ -31,7 +31,8 @@ def build_oracle(force: bool = False) -> str:
 class _Params(C.Structure):
     _fields_ = [("mu_g", C.c_float), ("var_g", C.c_float), ("delta", C.c_float),
                 ("clip_c", C.c_float), ("alpha_s", C.c_float), ("beta", C.c_float),
-                ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32)]
+                ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32),
+                ("stop_mode", C.c_int32), ("stop_threshold", C.c_float), ("simulate", C.c_int32)]
 
 
 @dataclass
@@ -46,10 +47,14 @@ class OracleParams:
     eps: float = 0.2
     stop_enabled: int = 1
     eos_id: int = -1
+    stop_mode: int = 0          # 0 Eq. stop_rule; 1 value only; 2 regret only; 3 random (ablations D, E, F)
+    stop_threshold: float = 0.0
+    simulate: int = 0           # record the first stop step, keep decoding
 
     def c_struct(self) -> _Params:
         return _Params(self.mu_g, self.var_g, self.delta, self.clip_c, self.alpha_s, self.beta,
-                       self.eps, int(self.stop_enabled), int(self.eos_id))
+                       self.eps, int(self.stop_enabled), int(self.eos_id), int(self.stop_mode),
+                       float(self.stop_threshold), int(self.simulate))
 
 
 _lib = None
@@ -65,7 +70,7 @@ def _load():
         lib.oracle_step.argtypes = [vp, C.c_int, i64, i64, i64, f32, u64, i32, vp, C.POINTER(_Params),
                                     vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.oracle_state_update.restype = C.c_int
-        lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), i32, vp, vp, vp]
+        lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), u64, i32, vp, vp, vp]
         lib.oracle_advantages.restype = C.c_int
         lib.oracle_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
         lib.oracle_gae_bruteforce.restype = C.c_int
@@ -188,8 +193,9 @@ def step(logits: np.ndarray, temperature: float, seed: int, step_: int, values: 
 
 
 def state_update(g: np.ndarray, tokens: np.ndarray, values: np.ndarray, params: OracleParams,
-                 step_: int, z: np.ndarray, alive: np.ndarray, stop_step: np.ndarray) -> None:
-    """Advance (z, alive, stop_step) in place from a given regret/token vector."""
+                 step_: int, z: np.ndarray, alive: np.ndarray, stop_step: np.ndarray, seed: int = 0) -> None:
+    """Advance (z, alive, stop_step) in place from a given regret/token vector (`seed` only
+    matters for the random stop mode)."""
     B = g.shape[0]
     _chk(g, np.float32, (B,), "g")
     _chk(tokens, np.int32, (B,), "tokens")
@@ -198,7 +204,7 @@ def state_update(g: np.ndarray, tokens: np.ndarray, values: np.ndarray, params: 
     _chk(alive, np.uint8, (B,), "alive")
     _chk(stop_step, np.int32, (B,), "stop_step")
     ps = params.c_struct()
-    rc = _load().oracle_state_update(B, _ptr(g), _ptr(tokens), _ptr(values), C.byref(ps), int(step_),
+    rc = _load().oracle_state_update(B, _ptr(g), _ptr(tokens), _ptr(values), C.byref(ps), int(seed), int(step_),
                                      _ptr(z), _ptr(alive), _ptr(stop_step))
     if rc != 0:
         raise ValueError("oracle_state_update: invalid arguments")

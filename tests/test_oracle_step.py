@@ -579,3 +579,72 @@ def test_invalid_arguments_are_rejected(oracle):
             oracle.step(logits, tau, 0, 0, np.zeros(1, np.float32), _params(oracle), z, a, s)
     with pytest.raises(ValueError):
         oracle.step(logits, 1.0, 0, 0, np.zeros(1, np.float32), _params(oracle), z, a, s, V=5)
+
+
+# --------------------------------------------------------------------------- stop modes of the ablations, simulate mode
+def _one_step(oracle, p, z0, value, seed=0, step=0, B=1):
+    """One oracle step on a row whose single dominant token makes the regret 0."""
+    x = np.full((B, 8), -40.0, np.float32)
+    x[:, 3] = 10.0
+    z = np.full(B, z0, np.float32)
+    alive = np.ones(B, np.uint8)
+    ss = np.full(B, -1, np.int32)
+    out = oracle.step(x, 1.0, seed, step, np.full(B, value, np.float32), p, z, alive, ss)
+    return out, z, alive, ss
+
+
+def test_value_only_and_regret_only_stop_modes(oracle):
+    # Section 6: variant D stops when V < threshold whatever the regret, variant E when z > threshold
+    # whatever the value.  With g = 0 and mu_g = 0 the state just decays: z' = 0.9 z.
+    base = dict(mu_g=0.0, var_g=1.0, alpha_s=0.9, beta=7.0, eps=0.2)
+    d = oracle.OracleParams(stop_mode=1, stop_threshold=0.3, **base)
+    for value, want in ((0.29, 0), (0.3, 1), (0.31, 1), (-5.0, 0)):
+        _, z, alive, ss = _one_step(oracle, d, 100.0, value)       # a huge z does not matter
+        assert alive[0] == want and (ss[0] == 0) == (want == 0), value
+    e = oracle.OracleParams(stop_mode=2, stop_threshold=0.9, **base)
+    for z0, want in ((1.0, 1), (1.01, 0), (0.5, 1)):        # z' = 0.9 z0 against 0.9, strict
+        _, z, alive, ss = _one_step(oracle, e, z0, -100.0)          # a hopeless value does not matter
+        assert alive[0] == want, z0
+    # the gate still applies
+    _, _, alive, _ = _one_step(oracle, oracle.OracleParams(stop_mode=1, stop_threshold=0.3, stop_enabled=0, **base), 0.0, 0.0)
+    assert alive[0] == 1
+
+
+def test_random_stop_mode_rate_and_independence(oracle):
+    # variant F: a coin per (row, step) with the given probability, keyed like the rest of the stream
+    base = dict(mu_g=0.0, var_g=1.0)
+    B, steps, prob = 4000, 3, 0.2
+    p = oracle.OracleParams(stop_mode=3, stop_threshold=prob, **base)
+    stops = []
+    for t in range(steps):
+        _, _, alive, ss = _one_step(oracle, p, 0.0, 0.5, seed=5, step=t, B=B)
+        stops.append(alive == 0)
+        assert (ss[alive == 0] == t).all() and (ss[alive == 1] == -1).all()
+    rate = np.mean(stops)
+    assert abs(rate - prob) < 4 * np.sqrt(prob * (1 - prob) / (B * steps))
+    assert 0.1 < np.mean(stops[0] ^ stops[1]) < 0.5          # different steps, different coins
+    _, _, again, _ = _one_step(oracle, p, 0.0, 0.5, seed=5, step=0, B=B)
+    assert ((again == 0) == stops[0]).all()                   # same key, same coins
+    _, _, other, _ = _one_step(oracle, p, 0.0, 0.5, seed=6, step=0, B=B)
+    assert ((other == 0) != stops[0]).any()
+    for prob_edge, want in ((0.0, 1), (1.0, 0)):              # never / always
+        _, _, alive, _ = _one_step(oracle, oracle.OracleParams(stop_mode=3, stop_threshold=prob_edge, **base), 0.0, 0.5, B=64)
+        assert (alive == want).all()
+
+
+def test_simulate_mode_records_the_first_stop_and_keeps_decoding(oracle):
+    # Section 7 ("ESPO/Original"): the first position that satisfies the rule is recorded, the
+    # sequence is not truncated.  Regret-only rule on a decaying state: z = 2, 1.8, 1.62, ...
+    p = oracle.OracleParams(mu_g=0.0, var_g=1.0, alpha_s=0.9, stop_mode=2, stop_threshold=1.5, simulate=1)
+    x = np.full((1, 8), -40.0, np.float32); x[:, 3] = 10.0
+    z = np.array([2.0 / 0.9], np.float32); alive = np.ones(1, np.uint8); ss = np.full(1, -1, np.int32)
+    for t in range(5):
+        out = oracle.step(x, 1.0, 0, t + 4, np.zeros(1, np.float32), p, z, alive, ss)
+        assert alive[0] == 1 and out["tokens"][0] == 3       # still decoding
+        assert ss[0] == 4                                     # the first step that fired, not the later ones
+    assert z[0] == pytest.approx(2.0 * 0.9 ** 4, rel=1e-6)
+    # end of sequence still ends the row
+    p2 = oracle.OracleParams(mu_g=0.0, var_g=1.0, stop_mode=2, stop_threshold=-1.0, simulate=1, eos_id=3)
+    alive = np.ones(1, np.uint8); ss = np.full(1, -1, np.int32)
+    oracle.step(x, 1.0, 0, 0, np.zeros(1, np.float32), p2, np.zeros(1, np.float32), alive, ss)
+    assert alive[0] == 0 and ss[0] == -1
