@@ -61,7 +61,30 @@ typedef struct {
   float eps;            /* floor on the value in Eq. stop_rule                        */
   int32_t stop_enabled; /* "warmup complete" gate of Algorithm 1; 0 = never stop      */
   int32_t eos_id;       /* token id that ends a trajectory naturally; -1 = none       */
+  int32_t stop_mode;    /* which stop test, see espo_stop_mode; 0 = Eq. stop_rule      */
+  float stop_threshold; /* the fixed threshold / probability of modes 1-3             */
+  int32_t simulate;     /* non-zero: record the first stop step but keep decoding     */
 } espo_params;
+
+/*
+ * Stop tests.  ESPO_STOP_RULE is the method (Eq. stop_rule); the others are the replacements
+ * studied in the ablations (Section 6, variants D, E and F).  All are gated by stop_enabled
+ * and all leave the update of z untouched.
+ *   ESPO_STOP_VALUE_ONLY   stop iff values[b] < stop_threshold
+ *   ESPO_STOP_REGRET_ONLY  stop iff z[b] > stop_threshold (after this step's update)
+ *   ESPO_STOP_RANDOM       stop iff u < stop_threshold with u = u(word 0 of
+ *                          Philox(counter (0, step, b, 0x53544F50), key)): a coin per row and
+ *                          step that looks at neither logits nor values
+ * With `simulate` set (the "ESPO/Original" bookkeeping of Section 7) a stop only writes
+ * stop_step[b] = step if stop_step[b] is still negative; alive[b] stays 1 and later steps
+ * keep decoding the row and updating z.  The end-of-sequence token ends the row either way.
+ */
+typedef enum {
+  ESPO_STOP_RULE = 0,
+  ESPO_STOP_VALUE_ONLY = 1,
+  ESPO_STOP_REGRET_ONLY = 2,
+  ESPO_STOP_RANDOM = 3
+} espo_stop_mode;
 
 /*
  * espo_step -- one decode step of Algorithm 1 for B trajectories.
@@ -94,7 +117,7 @@ typedef struct {
  *      the state before the first step is 0 and step 0 already updates it, as
  *      Algorithm 1 does).
  *   6. stop = stop_enabled && z[b] > beta * fmaxf(values[b], eps)   (Eq. stop_rule,
- *      strict).  If stop: alive[b] = 0 and stop_step[b] = step (the trajectory
+ *      strict; stop_mode selects the tests of the ablations instead, see espo_stop_mode).  If stop: alive[b] = 0 and stop_step[b] = step (the trajectory
  *      keeps the token of this step and has length step + 1; Eq. failure_reward).
  *      If eos_id >= 0 and a == eos_id the row ends naturally instead: alive[b] = 0
  *      and stop_step[b] is left alone.
@@ -154,7 +177,9 @@ size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt);
  *   td[b,t]  = r_t + gamma * values[b,t+1] - values[b,t]            for t < L,
  *   adv[b,t] = sum_{l=0}^{L-1-t} (gamma*lambda)^l td[b,t+l]          for t < L,
  * and td[b,t] = adv[b,t] = 0 for L <= t < T.  rewards and values are never read at
- * t >= L.
+ * t >= L.  (The ablation without the terminal failure penalty, Section 6 variant C, is this
+ * call with all `stopped` flags zero: the truncated trajectory then keeps its stored last
+ * reward.)
  *
  * Arguments
  *   rewards, values  device, [B, T] fp32 row-major, 16-byte aligned base; T*4 need

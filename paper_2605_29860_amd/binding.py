@@ -28,7 +28,8 @@ class EspoError(RuntimeError):
 class _Params(C.Structure):
     _fields_ = [("mu_g", C.c_float), ("var_g", C.c_float), ("delta", C.c_float),
                 ("clip_c", C.c_float), ("alpha_s", C.c_float), ("beta", C.c_float),
-                ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32)]
+                ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32),
+                ("stop_mode", C.c_int32), ("stop_threshold", C.c_float), ("simulate", C.c_int32)]
 
 
 @dataclass
@@ -43,10 +44,14 @@ class EspoParams:
     eps: float = 0.2
     stop_enabled: int = 1
     eos_id: int = -1
+    stop_mode: int = 0          # espo_stop_mode: 0 Eq. stop_rule, 1 value only, 2 regret only, 3 random
+    stop_threshold: float = 0.0
+    simulate: int = 0
 
     def _c(self) -> _Params:
         return _Params(self.mu_g, self.var_g, self.delta, self.clip_c, self.alpha_s, self.beta,
-                       self.eps, int(self.stop_enabled), int(self.eos_id))
+                       self.eps, int(self.stop_enabled), int(self.eos_id), int(self.stop_mode),
+                       float(self.stop_threshold), int(self.simulate))
 
 
 def library_path() -> str:

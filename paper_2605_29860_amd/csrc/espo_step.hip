@@ -50,7 +50,8 @@ struct StepArgs {
   int32_t step;
   const float* values;
   float mu_g, rsd, clip_c, alpha_s, oma, beta, eps;
-  int32_t stop_enabled, eos_id;
+  int32_t stop_enabled, eos_id, stop_mode, simulate;
+  float stop_threshold;
   float* z;
   uint8_t* alive;
   int32_t* stop_step;
@@ -265,7 +266,9 @@ struct ChainOut {
   bool stop;
 };
 
-__device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, float x_a, float z_prev, float value) {
+constexpr uint32_t kTagStop = 0x53544F50u;  // counter word 3 of the coin of the random stop mode
+
+__device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, int row, float m, float x_a, float z_prev, float value) {
 #pragma clang fp contract(off)
   const float d = m - x_a;
   const float g = d * a.inv_tau;                                    // Eq. step_gap
@@ -273,8 +276,19 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, float m, flo
   const float gt = fminf(fmaxf(n, -a.clip_c), a.clip_c);            // Eq. normalized_gap
   const float t = a.oma * gt;
   const float zn = __builtin_fmaf(a.alpha_s, z_prev, t);            // Eq. smoothed_score
-  const float thr = a.beta * fmaxf(value, a.eps);
-  return ChainOut{g, zn, a.stop_enabled && (zn > thr)};             // Eq. stop_rule (strict)
+  bool stop;
+  if (a.stop_mode == ESPO_STOP_VALUE_ONLY) {
+    stop = value < a.stop_threshold;
+  } else if (a.stop_mode == ESPO_STOP_REGRET_ONLY) {
+    stop = zn > a.stop_threshold;
+  } else if (a.stop_mode == ESPO_STOP_RANDOM) {
+    const Philox4 p = philox4x32_10(0u, (uint32_t)a.step, (uint32_t)row, kTagStop, a.key0, a.key1);
+    stop = (float)(2u * (p.w[0] >> 9) + 1u) * (1.0f / 16777216.0f) < a.stop_threshold;  // u(w) is exact in fp32
+  } else {
+    const float thr = a.beta * fmaxf(value, a.eps);
+    stop = zn > thr;                                                // Eq. stop_rule (strict)
+  }
+  return ChainOut{g, zn, a.stop_enabled && stop};
 }
 
 // ---------------------------------------------------------------- shared memory
@@ -739,7 +753,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     const float S = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // sum_v exp((x_v - m)/tau), fixed order
     if (lane == 0) {
       if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
-      const ChainOut c = scalar_chain(a, m, x_a, z_prev, value);
+      const ChainOut c = scalar_chain(a, row, m, x_a, z_prev, value);
       a.tokens[row] = tok;
       a.regret[row] = c.g;
       a.z[row] = c.z;
@@ -747,8 +761,12 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       if (a.eos_id >= 0 && tok == a.eos_id) {
         a.alive[row] = 0;  // natural end
       } else if (c.stop) {
-        a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
-        a.stop_step[row] = a.step;
+        if (a.simulate) {  // bookkeeping only: the first stop step is recorded, decoding goes on
+          if (a.stop_step[row] < 0) a.stop_step[row] = a.step;
+        } else {
+          a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
+          a.stop_step[row] = a.step;
+        }
       }
     }
   }
@@ -824,6 +842,9 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.eps = p.eps;
   a.stop_enabled = p.stop_enabled;
   a.eos_id = p.eos_id;
+  a.stop_mode = p.stop_mode;
+  a.simulate = p.simulate;
+  a.stop_threshold = p.stop_threshold;
   a.z = z;
   a.alive = alive;
   a.stop_step = stop_step;

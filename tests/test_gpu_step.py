@@ -372,3 +372,45 @@ def test_largest_vocabulary_and_range_error(dtype):
     with pytest.raises(espo.EspoError) as e:
         H.gpu_step(big, 1.0, 0, 0, vals[:1], gp, H.GpuState(1), V=400001)
     assert e.value.code == -5
+
+
+# --------------------------------------------------------------------------- ablation stop modes, simulate mode
+@pytest.mark.parametrize("mode,thr", [(1, 0.03), (2, 0.35), (3, 0.05)])
+def test_ablation_stop_modes_match_the_oracle(mode, thr):
+    _say(f"[case] stop mode {mode}")
+    B, V, steps = 48, 6000, 24
+    gen = W.ZipfLogits(V=V, seed=40 + mode, device="cuda")
+    gp, op = H.params_pair(mu_g=1.0, var_g=2.0, stop_mode=mode, stop_threshold=thr)
+    st = H.GpuState(B)
+    for t in range(steps):
+        vals = W.step_values(B, 40 + mode, t, 0.0, 1.0, device="cuda")
+        H.compare_step(gen.rows(B, step=t), 0.6, 40 + mode, t, vals, gp, op, st)
+    end = st.host()
+    stopped = end["stop_step"] >= 0
+    assert 0 < stopped.sum() < B                              # the rule fired for some rows, not for all
+    assert (end["alive"][stopped] == 0).all() and (end["alive"][~stopped] == 1).all()
+    bad, _ = H.params_pair(stop_mode=7)
+    with pytest.raises(espo.EspoError):
+        H.gpu_step(gen.rows(B, step=0), 0.6, 0, 0, vals, bad, H.GpuState(B))
+
+
+def test_simulate_mode_keeps_rows_alive_and_records_first_stop():
+    _say("[case] simulate mode")
+    B, V, steps = 32, 5000, 30
+    gen = W.ZipfLogits(V=V, seed=50, device="cuda")
+    kw = dict(mu_g=1.0, var_g=2.0, beta=1.0, eps=0.2)
+    gp, op = H.params_pair(simulate=1, **kw)
+    gp0, op0 = H.params_pair(**kw)
+    st, st0 = H.GpuState(B), H.GpuState(B)
+    for t in range(steps):
+        vals = W.step_values(B, 50, t, 0.0, 1.0, device="cuda")
+        x = gen.rows(B, step=t)
+        got = H.compare_step(x, 0.6, 50, t, vals, gp, op, st)
+        assert (got["alive"] == 1).all() and (got["tokens"] >= 0).all()     # nobody is truncated
+        H.gpu_step(x, 0.6, 50, t, vals, gp0, st0)
+    torch.cuda.synchronize()
+    sim, real = st.host(), st0.host()
+    # until a row's first stop both runs see the same stream, so the recorded step is the step
+    # at which the real run truncated the row
+    np.testing.assert_array_equal(sim["stop_step"], real["stop_step"])
+    assert (sim["stop_step"] >= 0).sum() > 0
