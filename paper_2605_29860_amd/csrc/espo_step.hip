@@ -73,19 +73,20 @@ struct Raw {
 template <int DT>
 constexpr int elem_bytes() { return DT == ESPO_BF16 ? 2 : 4; }
 
-// The lane's 8 consecutive elements starting at element e0 (a multiple of 8, e0 < V).
+// The lane's 8 consecutive elements starting at element e0 (a multiple of 8, e0 < V).  The row
+// pitch is a multiple of 4 floats only, so the second half of an fp32 group is read from the
+// row's last group of four if it would start at or beyond V (those elements are masked later).
 template <int DT>
 __device__ __forceinline__ Raw<DT> load_raw(const void* row, uint32_t e0, uint32_t V) {
   Raw<DT> r;
   const char* p = (const char*)row + (size_t)(e0 * (uint32_t)elem_bytes<DT>());
   const u32x4 t = __builtin_nontemporal_load((const u32x4*)p);
   r.w[0] = t.x; r.w[1] = t.y; r.w[2] = t.z; r.w[3] = t.w;
-  if constexpr (DT == ESPO_F32) {  // the row pitch is a multiple of 4 floats only: guard the second half
-    r.w[4] = r.w[5] = r.w[6] = r.w[7] = 0xFF800000u;
-    if (e0 + 4 < V) {
-      const u32x4 u = __builtin_nontemporal_load((const u32x4*)(p + 16));
-      r.w[4] = u.x; r.w[5] = u.y; r.w[6] = u.z; r.w[7] = u.w;
-    }
+  if constexpr (DT == ESPO_F32) {
+    const uint32_t last4 = (V - 1u) & ~3u;
+    const uint32_t e1 = e0 + 4u < last4 ? e0 + 4u : last4;
+    const u32x4 u = __builtin_nontemporal_load((const u32x4*)((const char*)row + (size_t)(e1 * 4u)));
+    r.w[4] = u.x; r.w[5] = u.y; r.w[6] = u.z; r.w[7] = u.w;
   }
   return r;
 }
@@ -616,10 +617,15 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     const uint32_t e0 = (uint32_t)t * kTile + lane_off;  // last tile: may be ragged
     return load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
   };
+  // The first ring of loads is issued by every wave, whether it has that many tiles or not
+  // (addresses beyond the row fall back on its last group): with a fixed number of loads in
+  // flight the compiler can wait for exactly the one a ring slot needs.
   Raw<DT> ring[kRing];
 #pragma unroll
-  for (int d = 0; d < kRing; ++d)
-    if (d < my_tiles) ring[d] = load_tile(d * kStepWaves + wave);
+  for (int d = 0; d < kRing; ++d) {
+    const uint32_t e0 = (uint32_t)(d * kStepWaves + wave) * kTile + lane_off;
+    ring[d] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
+  }
   // While the first loads are in flight: M_q bounds of all blocks, four per Philox call.
   for (int c = tid; c * 4 < nslots; c += kStepThreads) {
     const Philox4 p = philox4x32_10((uint32_t)c, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
