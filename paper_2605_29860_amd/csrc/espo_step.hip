@@ -37,6 +37,7 @@ constexpr int kTile = 512;                        // indices per wave iteration
 constexpr int kGroups = kTile / kDrawBlock;       // draw blocks per tile = lane groups per wave
 constexpr int kSlots = kStepWaves * kGroups;      // lane groups per workgroup
 constexpr int kRing = 4;                          // 16-byte loads kept in flight per lane
+constexpr int kCandCap = 1024;                    // candidate indices kept for a row with a long survivor list
 constexpr float kRescaleAt = 64.0f;               // advance a lane's softmax reference when topped by 2^64
 
 struct StepArgs {
@@ -312,6 +313,9 @@ struct StepShared {
   float* lo;        // [kStepWaves] score each wave knows to be attained
   int* visq;        // [kStepWaves] block each wave scored before the first barrier, or -1
   float* fres;      // [5][kStepWaves] per-wave results of the fp32 search: s, e, x, hi2, v
+  int32_t* cand_v;  // [kCandCap] long survivor lists: indices that can still win ...
+  float* cand_x;    // [kCandCap] ... and their logits
+  int* ncand;       // [1]
   int* nsurv;       // [1]
   int* bkey;        // [1] best attained score published during long survivor lists (order-preserving key)
 };
@@ -333,8 +337,11 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.lo = (float*)take(kStepWaves * 4);
   s.visq = (int*)take(kStepWaves * 4);
   s.fres = (float*)take(5 * kStepWaves * 4);
+  s.cand_v = (int32_t*)take(kCandCap * 4);
+  s.cand_x = (float*)take(kCandCap * 4);
   s.nsurv = (int*)take(16);
   s.bkey = s.nsurv + 1;
+  s.ncand = s.nsurv + 2;
   s.mu = (float*)take((size_t)nslots * 8);
   s.wq = (uint32_t*)take((size_t)nslots * 4);
   return s;
@@ -343,7 +350,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
 size_t step_lds_bytes(int dt, int ntiles) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
-  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 12 * kStepWaves * 4 + 16 +
+  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 12 * kStepWaves * 4 + 16 + 2 * kCandCap * 4 +
          ((nslots * 8 + 15) & ~(size_t)15) + ((nslots * 4 + 15) & ~(size_t)15);
 }
 
@@ -455,22 +462,16 @@ struct Best {
 
 __device__ __forceinline__ Best no_best() { return Best{kNegInf, 0.0f, 0.0f, kNegInf, -1}; }
 
-// Scores the 64 indices of block q in fp32, one per lane.  Every block is visited at most
-// once in this search, so a lane never meets the same index twice.
-template <int DT>
-__device__ __forceinline__ void fast_visit(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int q,
-                                           Best& st) {
-  const int lane = threadIdx.x & (kWave - 1);
+// Scores index v (logit x) in fp32 and offers it to the lane's state.  An index is scored at
+// most once in this search, so a lane never meets the same index twice.
+__device__ __forceinline__ void score_element(const StepArgs& a, const StepShared& sh, int row, int32_t v, float x,
+                                              bool valid, Best& st) {
+  const int32_t q = v >> 6;
   const int32_t first = q * kDrawBlock;
-  const int32_t v = first + lane;
   const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
   // the index's own word depends on nothing else here: its ten rounds overlap the loads
   const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
   const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
-  const int slot = slot_of(q);
-  const void* data = sh.top_q[slot] == q ? (const void*)((const char*)sh.top_raw + (size_t)slot * kDrawBlock * elem_bytes<DT>())
-                                         : (const void*)((const char*)rowp + (size_t)first * elem_bytes<DT>());
-  const float x = elem_at<DT>(data, lane < n ? lane : n - 1);
   const uint32_t wb = sh.wq[q];
   const float nlb = neg_log_uniform<float>(wb);
   const float M = flog((float)n) - flog(nlb);                 // M_q = ln n - ln(-ln u)
@@ -484,12 +485,71 @@ __device__ __forceinline__ void fast_visit(const StepArgs& a, const StepShared& 
   const float y = x * a.inv_tau;
   const float sc = y + G;
   const float e = score_margin(a, y);
-  if (lane < n && x > kNegInf) {  // masked (-inf) entries never win
+  if (valid && x > kNegInf) {  // masked (-inf) entries never win
     if (sc > st.s) {
       st.hi2 = fmaxf(st.hi2, st.s + st.e);
       st.s = sc; st.e = e; st.x = x; st.v = v;
     } else {
       st.hi2 = fmaxf(st.hi2, sc + e);
+    }
+  }
+}
+
+// This lane's element of block q: from LDS if a lane group kept the block, else from the row.
+template <int DT>
+__device__ __forceinline__ float block_elem(const StepArgs& a, const StepShared& sh, const void* rowp, int q) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int32_t first = q * kDrawBlock;
+  const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
+  const int slot = slot_of(q);
+  const int idx = lane < n ? lane : n - 1;  // stay inside the row in a ragged last block
+  if (sh.top_q[slot] == q) return elem_at<DT>((const char*)sh.top_raw + (size_t)slot * kDrawBlock * elem_bytes<DT>(), idx);
+  return elem_at<DT>((const char*)rowp + (size_t)first * elem_bytes<DT>(), idx);
+}
+
+// Scores the 64 indices of block q, one per lane.
+template <int DT>
+__device__ __forceinline__ void fast_visit(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int q,
+                                           Best& st) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int32_t n = a.V - q * kDrawBlock < kDrawBlock ? a.V - q * kDrawBlock : kDrawBlock;
+  score_element(a, sh, row, q * kDrawBlock + lane, block_elem<DT>(a, sh, rowp, q), lane < n, st);
+}
+
+// For a row with a long survivor list: instead of scoring every index of every surviving
+// block, the blocks' logits are only compared with the bound (index v can win only if
+// y_v + M_q reaches it), four blocks per wave at a time so that their loads overlap; the few
+// indices that pass are collected and then scored by all threads at once.
+template <int DT>
+__device__ __forceinline__ void collect_candidates(const StepArgs& a, const StepShared& sh, const void* rowp, int nsurv,
+                                                   float bound) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+#pragma unroll 1
+  for (int base = wave; base < nsurv; base += 4 * kStepWaves) {
+    int qs[4];
+    float xs[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int k = base + j * kStepWaves;
+      qs[j] = k < nsurv ? __builtin_amdgcn_readfirstlane(sh.surv(k)) : -1;
+      xs[j] = kNegInf;
+      if (qs[j] >= 0) xs[j] = block_elem<DT>(a, sh, rowp, qs[j]);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (qs[j] < 0) continue;
+      const int32_t first = qs[j] * kDrawBlock;
+      const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
+      const float M = flog((float)n) - flog(neg_log_uniform<float>(sh.wq[qs[j]]));
+      const float y = xs[j] * a.inv_tau;
+      if (lane < n && xs[j] > kNegInf && (y + M) + 2.0f * score_margin(a, y) >= bound) {
+        const int i = atomicAdd(sh.ncand, 1);
+        if (i < kCandCap) {
+          sh.cand_v[i] = first + lane;
+          sh.cand_x[i] = xs[j];
+        }
+      }
     }
   }
 }
@@ -537,7 +597,10 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
         sh.lo[wave] = lo;
         sh.visq[wave] = q_own;
       }
-      if (tid == 0) *sh.nsurv = 0;
+      if (tid == 0) {
+        *sh.nsurv = 0;
+        *sh.ncand = 0;
+      }
       __syncthreads();
       between();
       const float bound = wave_max(lane < kStepWaves ? sh.lo[lane] : kNegInf);
@@ -548,6 +611,15 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
       if (tid == 0) *sh.bkey = float_key(bound);
       __syncthreads();
       nsurv = *sh.nsurv;
+      if (nsurv > kStepWaves) {  // long list
+        collect_candidates<DT>(a, sh, rowp, nsurv, bound);
+        __syncthreads();
+        const int ncand = *sh.ncand;
+        if (ncand <= kCandCap) {  // else (tie-heavy rows): block by block below
+          for (int i = tid; i < ncand; i += kStepThreads) score_element(a, sh, row, sh.cand_v[i], sh.cand_x[i], true, st);
+          k = nsurv;
+        }
+      }
     } else {
       if (nsurv > kStepWaves) {  // long list: publish what this wave has attained, later visits may then be skipped
         const float lo = wave_max(st.s - st.e);
