@@ -375,6 +375,33 @@ __device__ __forceinline__ float round_down_f32(F v) {
   return f;
 }
 
+// Merges the lanes' and then the waves' search states in a fixed order; returns the same
+// result in every thread.  All threads of the workgroup must call it.
+template <typename F>
+__device__ __forceinline__ Search<F> combine_search(const StepShared& sh, Search<F> st) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  st = wave_merge(st);
+  if (lane == 0) {
+    sh.res_s[wave] = (double)st.best.s;
+    sh.res_hi2[wave] = (double)st.hi2;
+    sh.res_e[wave] = st.best.e;
+    sh.res_v[wave] = st.best.v;
+    sh.res_x[wave] = st.best.x;
+  }
+  __syncthreads();
+  Search<F> all;
+  all.init();
+#pragma unroll 1
+  for (int w = 0; w < kStepWaves; ++w) {  // fixed order: deterministic
+    Search<F> o;
+    o.best = Cand<F>{(F)sh.res_s[w], sh.res_e[w], sh.res_v[w], sh.res_x[w]};
+    o.hi2 = (F)sh.res_hi2[w];
+    all.merge(o);
+  }
+  return all;
+}
+
 // Finds the argmax over the row in precision F.  `bound0` is a score that is known to be
 // attained or exceeded (prunes from the start); `q_own` is the block this wave scores
 // first, without waiting for the others (or -1).  Every block whose bound reaches the best
@@ -430,25 +457,7 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
     if (k >= nsurv) break;
     q = sh.surv(k);
   }
-  st = wave_merge(st);
-  if (lane == 0) {
-    sh.res_s[wave] = (double)st.best.s;
-    sh.res_hi2[wave] = (double)st.hi2;
-    sh.res_e[wave] = st.best.e;
-    sh.res_v[wave] = st.best.v;
-    sh.res_x[wave] = st.best.x;
-  }
-  __syncthreads();
-  Search<F> all;
-  all.init();
-#pragma unroll 1
-  for (int w = 0; w < kStepWaves; ++w) {  // fixed order: deterministic
-    Search<F> o;
-    o.best = Cand<F>{(F)sh.res_s[w], sh.res_e[w], sh.res_v[w], sh.res_x[w]};
-    o.hi2 = (F)sh.res_hi2[w];
-    all.merge(o);
-  }
-  return all;
+  return combine_search<F>(sh, st);
 }
 
 // ---------------------------------------------------------------- phase 2 in fp32
@@ -552,6 +561,40 @@ __device__ __forceinline__ void collect_candidates(const StepArgs& a, const Step
       }
     }
   }
+}
+
+// The exact decision for a row whose best fp32 scores overlap: `lower` is a score known to be
+// attained (the fp32 winner's lower end), so only indices with y_v + M_q at or above it can
+// be the maximum.  They are collected as above, usually two or three, and scored in double
+// by one thread each.  Returns false if they do not fit the candidate buffer (then the
+// caller searches block by block); all threads of the workgroup must call it.
+template <int DT>
+__device__ __forceinline__ bool exact_among_candidates(const StepArgs& a, const StepShared& sh, const void* rowp, int row,
+                                                       int nslots, float lower, Search<double>& out) {
+  const int tid = threadIdx.x;
+  if (tid == 0) {
+    *sh.nsurv = 0;
+    *sh.ncand = 0;
+  }
+  __syncthreads();
+  for (int b = tid; b < nslots; b += kStepThreads) {
+    const float u = sh.ub(b);
+    if (u > -1e30f && ub_rounded_up(u) >= lower) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
+  }
+  __syncthreads();
+  collect_candidates<DT>(a, sh, rowp, *sh.nsurv, lower);
+  __syncthreads();
+  const int ncand = *sh.ncand;
+  if (ncand > kCandCap) return false;
+  Search<double> st;
+  st.init();
+  for (int i = tid; i < ncand; i += kStepThreads) {
+    const int32_t v = sh.cand_v[i];
+    const BlockDraw<double> d = block_draw<double>(a, row, v >> 6);
+    score_index<double>(a, row, v, sh.cand_x[i], d, -__builtin_huge_val(), st);
+  }
+  out = combine_search<double>(sh, st);
+  return true;
 }
 
 // Combines the lanes' states into the wave's: highest score, lowest index among equals.
@@ -820,8 +863,11 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   if (fast.v >= 0 && !(fast.s - fast.e > fast.hi2)) {
     // the two best fp32 scores overlap within their margins: decide in double (rare)
     __syncthreads();  // everyone has read the fp32 results
-    const Search<double> exact =
-        find_argmax<DT, double>(a, sh, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
+    Search<double> exact;
+    if (!exact_among_candidates<DT>(a, sh, rowp, row, nslots, fast.s - fast.e, exact)) {
+      __syncthreads();
+      exact = find_argmax<DT, double>(a, sh, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
+    }
     tok = exact.best.v;
     x_a = exact.best.x;
   }

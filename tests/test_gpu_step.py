@@ -316,7 +316,7 @@ def test_exact_fallback_decides_every_row_like_the_oracle(dtype):
         logits = _rand_logits(B, V, stride, dtype, seed=100 + V)
         vals = torch.zeros(B, device="cuda")
         tokens = {}
-        for scale in (1.0, 1e12):
+        for scale in (1.0, 3e4, 1e12):  # 3e4: a few candidates per row, decided in double one by one; 1e12: block by block
             espo.espo_debug_set_score_margin_scale(scale)
             try:
                 st = H.GpuState(B)
@@ -326,6 +326,7 @@ def test_exact_fallback_decides_every_row_like_the_oracle(dtype):
             finally:
                 espo.espo_debug_set_score_margin_scale(1.0)
         for step in range(3):
+            np.testing.assert_array_equal(tokens[(1.0, step)], tokens[(3e4, step)])
             np.testing.assert_array_equal(tokens[(1.0, step)], tokens[(1e12, step)])
 
 
@@ -339,7 +340,7 @@ def test_exact_fallback_at_full_width_matches_default_margin():
     vals = torch.zeros(B, device="cuda")
     gp, op = H.params_pair(stop_enabled=0)
     res = {}
-    for scale in (1.0, 1e12):
+    for scale in (1.0, 3e4, 1e12):
         espo.espo_debug_set_score_margin_scale(scale)
         try:
             st = H.GpuState(B)
@@ -348,9 +349,10 @@ def test_exact_fallback_at_full_width_matches_default_margin():
             res[scale] = st.host()
         finally:
             espo.espo_debug_set_score_margin_scale(1.0)
-    for k in ("tokens", "regret", "z"):
-        np.testing.assert_array_equal(res[1.0][k].view(np.uint32), res[1e12][k].view(np.uint32))
-    assert np.abs(res[1.0]["logprob"] - res[1e12]["logprob"]).max() == 0
+    for scale in (3e4, 1e12):
+        for k in ("tokens", "regret", "z"):
+            np.testing.assert_array_equal(res[1.0][k].view(np.uint32), res[scale][k].view(np.uint32))
+        assert np.abs(res[1.0]["logprob"] - res[scale]["logprob"]).max() == 0
     with pytest.raises(espo.EspoError):
         espo.espo_debug_set_score_margin_scale(0.5)
 
