@@ -18,6 +18,10 @@
  *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
  *                      Section 4.4 (failure reward at the stop step, no bootstrap).
  *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
+ *   oracle_batch_stats Section 4.2 (EMA of the batch mean and variance of the regret) and
+ *                      Eq. beta_update, plain two-pass definitions.
+ *   stop_decision      Eq. stop_rule and the replacement tests of the ablations (Section 6,
+ *                      variants D, E, F); the simulate mode of Section 7 ("ESPO/Original").
  *
  * Pins (tests marked "not gpu"): hand values of the regret on 3-token rows, closed
  * forms of the smoothed state, stop rule never/always firing, softmax frequencies of
