@@ -416,3 +416,45 @@ def test_simulate_mode_keeps_rows_alive_and_records_first_stop():
     # at which the real run truncated the row
     np.testing.assert_array_equal(sim["stop_step"], real["stop_step"])
     assert (sim["stop_step"] >= 0).sum() > 0
+
+
+# --------------------------------------------------------------------------- seeded sweep over shapes, structures and search paths
+def test_seeded_sweep_of_shapes_structures_and_margins():
+    _say("[case] seeded sweep")
+    rng = np.random.default_rng(2024)
+    paths = {1.0: 0, 3e4: 0, 1e12: 0}
+    for case in range(48):
+        V = int(rng.choice([rng.integers(1, 600), rng.integers(600, 9000), rng.integers(9000, 70000)]))
+        B = int(rng.integers(1, 7))
+        dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
+        tau = float(rng.choice([0.3, 0.6, 1.0, 2.5]))
+        kind = rng.choice(["gauss", "flat", "plateau", "masked", "peaked"])
+        stride = ((V + 7) // 8) * 8 + int(rng.choice([0, 8, 64]))
+        g = torch.Generator().manual_seed(1000 + case)
+        x = torch.randn(B, stride, generator=g) * float(rng.choice([0.5, 3.0, 12.0]))
+        if kind == "flat":
+            x[:] = 1.5
+        elif kind == "plateau":                               # half of the vocabulary tied just below one peak
+            x[:, 0::2] = 20.0
+            x[:, min(V - 1, 7)] = 22.0
+        elif kind == "masked":
+            x[:, torch.rand(stride, generator=g) < 0.7] = float("-inf")
+            x[:, V // 2] = 0.25                                # at least one finite entry
+        elif kind == "peaked":
+            x[:, V - 1] = 40.0
+        x[:, V:] = 1e4                                         # beyond V must never matter
+        logits = x.to(dtype).cuda()
+        scale = float(rng.choice([1.0, 1.0, 3e4, 1e12]))
+        paths[scale] += 1
+        gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=float(rng.choice([0.5, 7.0])))
+        st = H.GpuState(B, z=torch.rand(B, generator=g) * 2 - 1)
+        vals = torch.rand(B, generator=g).cuda()
+        espo.espo_debug_set_score_margin_scale(scale)
+        try:
+            for step in range(2):
+                H.compare_step(logits, tau, 900 + case, step, vals, gp, op, st, V=V)
+        except AssertionError as err:
+            raise AssertionError(f"case {case}: V={V} B={B} {dtype} tau={tau} {kind} scale={scale}: {err}")
+        finally:
+            espo.espo_debug_set_score_margin_scale(1.0)
+    _say(f"  cases per margin scale: {paths}")
