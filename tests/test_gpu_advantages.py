@@ -84,3 +84,24 @@ def test_config5_full_size():
     espo.espo_advantages(r, v, L, s, -1.0, 1.0, 0.95, td2, adv2)
     torch.cuda.synchronize()
     assert torch.equal(td1, td2) and torch.equal(adv1, adv2)
+
+
+@pytest.mark.parametrize("B", [513, 1025, 2500, 4096, 4097])
+def test_many_rows(B):
+    _say(f"[case] advantages B={B}")
+    # More rows than workgroups fit on the chip at once: every row must still be processed
+    # exactly once (outputs are pre-filled with a sentinel by the check), also with many equal
+    # lengths, empty rows and lengths out of range.
+    T = 260
+    g = torch.Generator().manual_seed(B)
+    L = torch.randint(0, T + 1, (B,), generator=g)
+    L[::7] = T
+    L[3::11] = 0
+    L[5::13] = 17
+    r, v, Lt, s = _batch(B, T, seed=B, lengths=L.tolist())
+    H.check_advantages(r, v, Lt, s, -1.0, 1.0, 0.95)
+    Lt[1] = -4
+    Lt[2] = T + 100
+    r = torch.nan_to_num(r, nan=0.0)
+    v = torch.nan_to_num(v, nan=0.0)
+    H.check_advantages(r, v, Lt, s, -0.5, 0.97, 0.9)
