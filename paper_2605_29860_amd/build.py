@@ -31,5 +31,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+ABI_CHECK_SRC = os.path.join(os.path.dirname(_HERE), "tests", "native", "abi_check.cpp")
+ABI_CHECK = os.path.join(os.path.dirname(_HERE), "tests", "native", "abi_check")
+
+
+def build_abi_check() -> str:
+    """Builds the plain HIP host program that drives the C ABI without Python (used by a GPU test)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "-O2", "-std=c++17", ABI_CHECK_SRC, "-o", ABI_CHECK, "-L" + _HERE, "-lespo",
+           "-Wl,-rpath,$ORIGIN/../../paper_2605_29860_amd"]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        print(res.stdout + res.stderr)
+        raise RuntimeError("hipcc failed building abi_check")
+    return ABI_CHECK
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_abi_check())

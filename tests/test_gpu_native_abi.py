@@ -1,0 +1,74 @@
+"""The C ABI driven from a plain HIP host program (no Python binding, no PyTorch in that process),
+checked against the CPU oracle (needs an MI355X)."""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+import oracle  # noqa: E402
+from paper_2605_29860_amd import binding, build  # noqa: E402
+
+
+def test_native_program_matches_the_oracle(tmp_path):
+    print("[case] native ABI check", flush=True)
+    if not os.path.exists(build.ABI_CHECK):
+        build.build_abi_check()
+    rng = np.random.default_rng(7)
+    B, V, T, step, seed, tau = 6, 5003, 300, 4, 123456789012345, 0.8
+    V_pad = 5004                              # a pitch of 5003 floats is not a multiple of 16 bytes: pad the rows
+    logits = (rng.standard_normal((B, V_pad)) * 3).astype(np.float32)
+    logits[:, V:] = 1e4
+    values = rng.random(B).astype(np.float32)
+    z = (rng.random(B) * 2 - 1).astype(np.float32)
+    alive = np.array([1, 1, 0, 1, 1, 1], np.uint8)
+    stop_step = np.full(B, -1, np.int32)
+    rewards = rng.standard_normal((B, T)).astype(np.float32)
+    vals2 = (rng.random((B, T)) * 2 - 1).astype(np.float32)
+    lengths = rng.integers(0, T + 1, B).astype(np.int32)
+    stopped = (rng.random(B) < 0.5).astype(np.uint8)
+    op = oracle.OracleParams(mu_g=1.0, var_g=2.0, beta=1.0)
+    gp = binding.EspoParams(mu_g=1.0, var_g=2.0, beta=1.0)._c()
+
+    # the program takes V as the row pitch too, so hand it the padded width and mask the pad away
+    logits_in = logits.copy()
+    logits_in[:, V:] = -np.inf
+    fin, fout = tmp_path / "in.bin", tmp_path / "out.bin"
+    with open(fin, "wb") as f:
+        f.write(np.array([B, V_pad, T], np.int32).tobytes())
+        f.write(np.float32(tau).tobytes())
+        f.write(np.uint64(seed).tobytes())
+        f.write(np.int32(step).tobytes())
+        f.write(bytes(gp))
+        for a in (logits_in, values, z, alive, stop_step, rewards, vals2, lengths, stopped):
+            f.write(a.tobytes())
+    res = subprocess.run([build.ABI_CHECK, str(fin), str(fout)], capture_output=True, text=True, timeout=120)
+    print(res.stdout, res.stderr, flush=True)
+    assert res.returncode == 0
+
+    raw = open(fout, "rb").read()
+    off = 0
+    def take(dtype, n):
+        nonlocal off
+        a = np.frombuffer(raw, dtype, n, off)
+        off += a.nbytes
+        return a
+    tokens, regret, z_g, alive_g, ss_g, logprob = (take(np.int32, B), take(np.float32, B), take(np.float32, B),
+                                                   take(np.uint8, B), take(np.int32, B), take(np.float32, B))
+    td, adv = take(np.float32, B * T).reshape(B, T), take(np.float32, B * T).reshape(B, T)
+
+    z_o, alive_o, ss_o = z.copy(), alive.copy(), stop_step.copy()
+    ref = oracle.step(logits_in, tau, seed, step, values, op, z_o, alive_o, ss_o)
+    np.testing.assert_array_equal(tokens, ref["tokens"])
+    np.testing.assert_array_equal(regret.view(np.uint32), ref["regret"].view(np.uint32))
+    np.testing.assert_array_equal(z_g.view(np.uint32), z_o.view(np.uint32))
+    np.testing.assert_array_equal(alive_g, alive_o)
+    np.testing.assert_array_equal(ss_g, ss_o)
+    live = alive == 1
+    assert np.abs(logprob[live] - ref["logprob"][live]).max() <= 1e-5 * np.maximum(np.abs(ref["logprob"][live]), 1).max()
+    td_o, adv_o, scale = oracle.advantages(rewards, vals2, lengths, stopped, -1.0, 1.0, 0.95)
+    assert np.abs(td - td_o).max() <= 4e-7 * (np.abs(rewards).max() + 2 * np.abs(vals2).max() + 1)
+    assert (np.abs(adv - adv_o) <= 1e-5 * np.maximum(np.abs(adv_o), scale)).all()
