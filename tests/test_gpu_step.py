@@ -458,3 +458,38 @@ def test_seeded_sweep_of_shapes_structures_and_margins():
         finally:
             espo.espo_debug_set_score_margin_scale(1.0)
     _say(f"  cases per margin scale: {paths}")
+
+
+# --------------------------------------------------------------------------- concurrent streams
+def test_two_streams_do_not_interfere():
+    _say("[case] two streams")
+    # The library keeps no state between calls: rollouts interleaved on two streams give the bits
+    # of the same rollouts run one after the other.
+    B, V, steps = 96, 30000, 10
+    gens = [W.ZipfLogits(V=V, seed=60 + i, device="cuda") for i in range(2)]
+    data = [[g.rows(B, step=t) for t in range(steps)] for g in gens]
+    vals = [[W.step_values(B, 60 + i, t, 0.0, 1.0, device="cuda") for t in range(steps)] for i in range(2)]
+    gp, _ = H.params_pair(mu_g=1.0, var_g=2.0, beta=1.0)
+
+    def one(i, st, stream=None):
+        for t in range(steps):
+            espo.espo_step(data[i][t], 0.6, 60 + i, t, vals[i][t], gp, st.z, st.alive, st.stop_step,
+                           st.tokens, st.regret, st.logprob, stream=stream)
+
+    serial = [H.GpuState(B), H.GpuState(B)]
+    for i in range(2):
+        one(i, serial[i])
+    torch.cuda.synchronize()
+    inter = [H.GpuState(B), H.GpuState(B)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    torch.cuda.synchronize()
+    for t in range(steps):
+        for i in range(2):
+            st = inter[i]
+            espo.espo_step(data[i][t], 0.6, 60 + i, t, vals[i][t], gp, st.z, st.alive, st.stop_step,
+                           st.tokens, st.regret, st.logprob, stream=streams[i])
+    torch.cuda.synchronize()
+    for i in range(2):
+        a, b = serial[i].host(), inter[i].host()
+        for k in a:
+            np.testing.assert_array_equal(a[k].view(np.uint8), b[k].view(np.uint8), err_msg=f"stream {i} {k}")
