@@ -11,9 +11,12 @@
 //     the block with the largest bound it has seen, so that phase 2 seldom re-reads memory.
 //   phase 2 (a handful of blocks, lanes = the 64 indices of a block): every wave scores the
 //     block with the largest bound it has streamed, the best score found rules out every
-//     block with a lower bound, the few survivors are scored by the waves in parallel.
-//     Scores are first formed in fp32 with a proven error margin; if the best two cannot be
-//     told apart within that margin the search is repeated in double, which decides exactly.
+//     block with a lower bound, the few survivors are scored by the waves in parallel (a long
+//     list is first reduced to the indices whose own bound y_v + M_q still reaches the score
+//     attained, and those are scored one per thread).  Scores are first formed in fp32 with a
+//     proven error margin; if the best two cannot be told apart within that margin, the
+//     indices that reach the fp32 winner's lower end are scored again in double, which
+//     decides exactly.
 //   One lane then runs the scalar chain regret -> normalise/clip -> smoothed state -> stop
 //   test (Eq. step_gap, Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule).
 // Pruning only ever discards indices that provably cannot attain the maximum, so the
