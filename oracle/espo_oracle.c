@@ -15,6 +15,9 @@
  *                      iid standard Gumbel G_v, over a Philox4x32-10 stream (Salmon et
  *                      al., "Parallel random numbers: as easy as 1, 2, 3", SC'11); the
  *                      stream definition below is the one the GPU path implements too.
+ *                      Optional output: the entropy of that distribution (the quantity
+ *                      tracked in the section on policy entropy and diversity, Fig. 2b),
+ *                      by its definition.
  *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
  *                      Section 4.4 (failure reward at the stop step, no bootstrap).
  *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
@@ -25,7 +28,8 @@
  *
  * Pins (tests marked "not gpu"): hand values of the regret on 3-token rows, closed
  * forms of the smoothed state, stop rule never/always firing, softmax frequencies of
- * the sampler on tiny vocabularies, moments of the Gumbel variates, GAE against the
+ * the sampler on tiny vocabularies, moments of the Gumbel variates, closed forms of the
+ * entropy (uniform, two-token, masked rows) and a library routine on random rows, GAE against the
  * explicit double sum and against telescoping identities.
  * Parity unpinned by the paper: the identity of the sampled token on a large
  * vocabulary (the paper fixes no random stream); it is pinned by the distribution
@@ -225,7 +229,11 @@ void oracle_set_threads(int n) {
  *   best_score / second_score / second_token  the two largest perturbed scores of
  *                          the draw and the index of the runner-up;
  *   sum_exp                S = sum_v exp(y_v - y_max);
- *   row_max                the row maximum m.
+ *   row_max                the row maximum m;
+ *   entropy                H = -sum_v pi_v ln pi_v of the distribution the token is drawn
+ *                          from, pi_v = exp(y_v - y_max) / S (the policy entropy tracked in
+ *                          the section on policy entropy and diversity, Fig. 2b); indices
+ *                          with pi_v = 0 contribute nothing.
  * Returns 0, or -1 on invalid arguments.
  */
 int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row_stride,
@@ -235,7 +243,7 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
                 int32_t* tokens, float* regret, float* logprob,
                 const int32_t* forced_tokens,
                 double* best_score, double* second_score, int32_t* second_token,
-                double* sum_exp, float* row_max) {
+                double* sum_exp, float* row_max, float* entropy) {
   if (!logits || !values || !p || !z || !alive || !stop_step || !tokens || !regret) return -1;
   if (B < 0 || V < 1 || row_stride < V || !(temperature > 0.0f) || !isfinite(temperature)) return -1;
   if (dtype != 0 && dtype != 1) return -1;
@@ -255,6 +263,7 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
       if (second_token) second_token[b] = -1;
       if (sum_exp) sum_exp[b] = 0.0;
       if (row_max) row_max[b] = 0.0f;
+      if (entropy) entropy[b] = 0.0f;
       continue;
     }
     const int64_t base = b * row_stride;
@@ -314,6 +323,15 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
     if (second_token) second_token[b] = (int32_t)a2;
     if (sum_exp) sum_exp[b] = S;
     if (row_max) row_max[b] = m;
+    if (entropy) {                                       /* the definition, term by term */
+      double H = 0.0;
+      for (int64_t v = 0; v < V; ++v) {
+        const double y = (double)load_logit(logits, dtype, base + v) * (double)inv_tau;
+        const double pi = exp(y - y_max) / S;
+        if (pi > 0.0) H -= pi * log(pi);
+      }
+      entropy[b] = (float)H;
+    }
   }
   return 0;
 }

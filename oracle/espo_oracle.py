@@ -68,7 +68,7 @@ def _load():
         vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float
         lib.oracle_step.restype = C.c_int
         lib.oracle_step.argtypes = [vp, C.c_int, i64, i64, i64, f32, u64, i32, vp, C.POINTER(_Params),
-                                    vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+                                    vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.oracle_state_update.restype = C.c_int
         lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), u64, i32, vp, vp, vp]
         lib.oracle_advantages.restype = C.c_int
@@ -151,12 +151,14 @@ def block_draw(seed: int, row: int, step_: int, q: int, n: int):
 
 def step(logits: np.ndarray, temperature: float, seed: int, step_: int, values: np.ndarray,
          params: OracleParams, z: np.ndarray, alive: np.ndarray, stop_step: np.ndarray,
-         V: int | None = None, forced_tokens: np.ndarray | None = None, want_logprob: bool = True):
+         V: int | None = None, forced_tokens: np.ndarray | None = None, want_logprob: bool = True,
+         want_entropy: bool = False):
     """One decode step.  ``logits`` is [B, row_stride] float32, or uint16 holding bf16 bits.
 
     ``z``, ``alive``, ``stop_step`` are updated in place.  Returns a dict with tokens,
     regret, logprob and the diagnostics of the draw (best/second score, runner-up,
-    softmax sum, row maximum).
+    softmax sum, row maximum); with ``want_entropy`` also the entropy of the distribution
+    the token is drawn from.
     """
     lib = _load()
     if logits.dtype == np.float32:
@@ -180,13 +182,15 @@ def step(logits: np.ndarray, temperature: float, seed: int, step_: int, values: 
         "best_score": np.empty(B, np.float64), "second_score": np.empty(B, np.float64),
         "second_token": np.empty(B, np.int32), "sum_exp": np.empty(B, np.float64),
         "row_max": np.empty(B, np.float32),
+        "entropy": np.empty(B, np.float32) if want_entropy else None,
     }
     ps = params.c_struct()
     rc = lib.oracle_step(_ptr(logits), dt, B, V, stride, float(temperature), int(seed), int(step_),
                          _ptr(values), C.byref(ps), _ptr(z), _ptr(alive), _ptr(stop_step),
                          _ptr(out["tokens"]), _ptr(out["regret"]), _ptr(out["logprob"]),
                          _ptr(forced_tokens), _ptr(out["best_score"]), _ptr(out["second_score"]),
-                         _ptr(out["second_token"]), _ptr(out["sum_exp"]), _ptr(out["row_max"]))
+                         _ptr(out["second_token"]), _ptr(out["sum_exp"]), _ptr(out["row_max"]),
+                         _ptr(out["entropy"]))
     if rc != 0:
         raise ValueError("oracle_step: invalid arguments")
     return out

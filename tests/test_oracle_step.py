@@ -648,3 +648,57 @@ def test_simulate_mode_records_the_first_stop_and_keeps_decoding(oracle):
     alive = np.ones(1, np.uint8); ss = np.full(1, -1, np.int32)
     oracle.step(x, 1.0, 0, 0, np.zeros(1, np.float32), p2, np.zeros(1, np.float32), alive, ss)
     assert alive[0] == 0 and ss[0] == -1
+
+
+# ------------------------------------------------------------------ policy entropy (Fig. 2b)
+def _entropy(oracle, logits, tau, **kw):
+    B = logits.shape[0]
+    z, alive, ss = _state(B)
+    out = oracle.step(logits, tau, 3, 0, np.zeros(B, np.float32), _params(oracle, stop_enabled=0),
+                      z, alive, ss, want_entropy=True, **kw)
+    return out["entropy"].astype(np.float64)
+
+
+def test_entropy_closed_forms(oracle):
+    # uniform row: ln V, at any temperature
+    for V in (1, 2, 7, 64, 1000):
+        H = _entropy(oracle, np.full((1, V), 1.25, np.float32), 0.6)
+        assert H[0] == pytest.approx(math.log(V), abs=1e-6)
+    # two tokens with logit gap d at temperature tau: binary entropy of sigmoid(d / tau)
+    for d, tau in [(0.0, 1.0), (1.0, 1.0), (3.0, 0.5), (0.25, 2.0), (40.0, 1.0)]:
+        H = _entropy(oracle, np.array([[d, 0.0]], np.float32), tau)
+        p = special.expit(np.float64(np.float32(d)) * np.float64(np.float32(1.0) / np.float32(tau)))
+        want = -(p * math.log(p) + (1 - p) * math.log1p(-p)) if p < 1 else 0.0
+        assert H[0] == pytest.approx(want, rel=1e-6, abs=1e-7)
+    # k equal modes and the rest masked out: ln k, and a single finite entry gives exactly 0
+    row = np.full((1, 50), -np.inf, np.float32)
+    row[0, [3, 17, 44]] = 2.0
+    assert _entropy(oracle, row, 1.0)[0] == pytest.approx(math.log(3), abs=1e-6)
+    row[0, [3, 44]] = -np.inf
+    assert _entropy(oracle, row, 1.0)[0] == 0.0
+
+
+def test_entropy_matches_library_and_identities(oracle):
+    rng = np.random.default_rng(12)
+    B, V, tau = 16, 301, 0.6
+    logits = (rng.normal(0, 3, (B, V)) + 6.0 * (rng.random((B, V)) < 0.01)).astype(np.float32)
+    H = _entropy(oracle, logits, tau)
+    inv = np.float64(np.float32(1.0) / np.float32(tau))
+    y = logits.astype(np.float64) * inv
+    want = stats.entropy(special.softmax(y, axis=1), axis=1)            # library routine, nats
+    np.testing.assert_allclose(H, want, rtol=2e-6)
+    # H = -E_pi[ln pi]: the same number from the log-softmax the regret test uses
+    lsm = special.log_softmax(y, axis=1)
+    np.testing.assert_allclose(H, -(np.exp(lsm) * lsm).sum(1), rtol=2e-6)
+    # bounds, invariance under a shift of the row, and monotone growth with the temperature
+    assert (H > 0).all() and (H < math.log(V)).all()
+    np.testing.assert_allclose(_entropy(oracle, logits + np.float32(8.0), tau), H, rtol=1e-5)
+    assert (_entropy(oracle, logits, 1.5) > H).all()
+    # rows that are done report 0 and padding beyond V is not read
+    z, alive, ss = _state(B)
+    alive[::2] = 0
+    padded = np.concatenate([logits, np.full((B, 11), 50.0, np.float32)], axis=1)
+    out = oracle.step(padded, tau, 3, 0, np.zeros(B, np.float32), _params(oracle, stop_enabled=0),
+                      z, alive, ss, V=V, want_entropy=True)
+    assert (out["entropy"][::2] == 0).all()
+    np.testing.assert_allclose(out["entropy"][1::2], H[1::2], rtol=1e-6)
