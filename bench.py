@@ -85,11 +85,12 @@ def main() -> int:
     regret = torch.empty(B_STEP, dtype=torch.float32, device=dev)
     logprob = torch.empty(B_STEP, dtype=torch.float32, device=dev)
 
-    def run(first, last, z, alive, ss, events=None):
+    def run(first, last, z, alive, ss, events=None, entropy=None):
         for s in range(first, last):
             if events is not None:
                 events[s - first][0].record()
-            espo.espo_step(logits[s], tau, seed, s, values[s], params, z, alive, ss, tokens, regret, logprob)
+            espo.espo_step(logits[s], tau, seed, s, values[s], params, z, alive, ss, tokens, regret, logprob,
+                           entropy=entropy)
             if events is not None:
                 events[s - first][1].record()
 
@@ -130,6 +131,17 @@ def main() -> int:
     torch.cuda.synchronize()
     assert torch.equal(ss2, ss) and torch.equal(z2, z), "replay of the timed steps is not deterministic"
     kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+
+    # and once more with the optional entropy output (the kernel's other instantiation)
+    z3, alive3, ss3 = fresh_state()
+    entropy = torch.empty(B_STEP, dtype=torch.float32, device=dev)
+    eregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    eregion[0].record()
+    run(Wm, total, z3, alive3, ss3, entropy=entropy)
+    eregion[1].record()
+    torch.cuda.synchronize()
+    assert torch.equal(ss3, ss) and torch.equal(z3, z), "the entropy output changed the trajectory"
+    ent_us = eregion[0].elapsed_time(eregion[1]) / K * 1e3
     step_bytes = live * (V_STEP * 2 + STEP_SCALAR_BYTES) + (B_STEP - live) * 1
     step_gbs = float(step_bytes.sum() / (region_ms * 1e-3) / 1e9)   # events around the K back-to-back launches
 
@@ -225,6 +237,8 @@ def main() -> int:
                      "avg_launch_us_event_pair_each": float(kern_ms.mean() * 1e3),
                      "algorithmic_bytes_per_launch": float(step_bytes.mean()),
                      "traffic": _traffic_from_profiles("espo_step")},
+        "step_with_entropy": {"avg_launch_us": ent_us, "frac": step_gbs / HBM_PEAK_GBS * (region_ms / K * 1e3) / ent_us,
+                              "mean_entropy_last_step": float(entropy[alive3 > 0].mean()) if bool((alive3 > 0).any()) else None},
         "advantages": {"workload": "B=1024, T=16384 fp32, lengths U[512,16384], 30% stopped, 8 rotated buffer sets",
                        "tokens_per_s": float(valid.sum() / adv_wall), "ms_per_call": adv_wall / args.adv_reps * 1e3,
                        "roofline": {"kernel": "espo_advantages_kernel", "bound": "hbm", "achieved": adv_gbs,

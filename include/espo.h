@@ -121,12 +121,17 @@ typedef enum {
  *      keeps the token of this step and has length step + 1; Eq. failure_reward).
  *      If eos_id >= 0 and a == eos_id the row ends naturally instead: alive[b] = 0
  *      and stop_step[b] is left alone.
- *   Outputs: tokens[b] = a, regret[b] = g, logprob[b] = -g - ln S.
+ *   Outputs: tokens[b] = a, regret[b] = g, logprob[b] = -g - ln S, and on request
+ *   entropy[b] = -sum_v pi_v ln pi_v = ln S - sum_v pi_v (y_v - y_max), the entropy of
+ *   pi(.|s_t) that the section on policy entropy and diversity tracks (Fig. 2b), taken
+ *   here for the distribution the token is drawn from (temperature included); masked
+ *   entries contribute 0.  It comes out of the same single pass over the row.
  * Steps 3-6 are single correctly rounded fp32 operations in exactly the order
  * written, so a host re-computation reproduces z, the mask and the stop step bit
  * for bit.
  * For rows with alive[b] == 0 the logits are not read; tokens[b] = -1,
- * regret[b] = 0, logprob[b] = 0, and z, alive, stop_step are left untouched.
+ * regret[b] = 0, logprob[b] = 0, entropy[b] = 0, and z, alive, stop_step are left
+ * untouched.
  *
  * Arguments
  *   logits      device, [B, row_stride] elements of `dt` (row-major, row b starts
@@ -148,6 +153,8 @@ typedef enum {
  *   tokens      device, [B] int32 out.
  *   regret      device, [B] fp32 out.
  *   logprob     device, [B] fp32 out, may be NULL.
+ *   entropy     device, [B] fp32 out, may be NULL (then nothing is spent on it: the
+ *               pass with the entropy does two more vector operations per logit).
  *   workspace   device scratch of at least espo_step_workspace_bytes(B, V, dt) bytes.
  *               A row is handled by one workgroup, so that size is 0 in this version
  *               and NULL / 0 may be passed; the argument is kept so that the ABI need
@@ -158,7 +165,7 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
               float temperature, uint64_t seed, int32_t step,
               const float* values, const espo_params* params,
               float* z, uint8_t* alive, int32_t* stop_step,
-              int32_t* tokens, float* regret, float* logprob,
+              int32_t* tokens, float* regret, float* logprob, float* entropy,
               void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace espo_step needs for this shape (0 in this version). */

@@ -84,7 +84,7 @@ def load_library():
         vp, i64, i32, u64, f32, sz = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float, C.c_size_t
         lib.espo_step.restype = C.c_int
         lib.espo_step.argtypes = [vp, C.c_int, i64, i64, i64, f32, u64, i32, vp, C.POINTER(_Params),
-                                  vp, vp, vp, vp, vp, vp, vp, sz, vp]
+                                  vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.espo_step_workspace_bytes.restype = sz
         lib.espo_step_workspace_bytes.argtypes = [i64, i64, C.c_int]
         lib.espo_advantages.restype = C.c_int
@@ -181,7 +181,8 @@ def espo_step_workspace_bytes(B: int, V: int, dtype: torch.dtype) -> int:
 def espo_step(logits: torch.Tensor, temperature: float, seed: int, step: int, values: torch.Tensor,
               params: EspoParams, z: torch.Tensor, alive: torch.Tensor, stop_step: torch.Tensor,
               tokens: torch.Tensor, regret: torch.Tensor, logprob: torch.Tensor | None = None,
-              V: int | None = None, workspace: torch.Tensor | None = None, stream=None) -> None:
+              V: int | None = None, workspace: torch.Tensor | None = None, stream=None,
+              entropy: torch.Tensor | None = None) -> None:
     """One decode step; see `espo_step` in include/espo.h.  `logits` is [B, row_stride]."""
     lib = load_library()
     if logits.dtype == torch.bfloat16:
@@ -204,7 +205,7 @@ def espo_step(logits: torch.Tensor, temperature: float, seed: int, step: int, va
                        _dev(z, torch.float32, "z"), _dev(alive, torch.uint8, "alive"),
                        _dev(stop_step, torch.int32, "stop_step"), _dev(tokens, torch.int32, "tokens"),
                        _dev(regret, torch.float32, "regret"), _dev(logprob, torch.float32, "logprob"),
-                       ws_ptr, ws_bytes, _stream(stream))
+                       _dev(entropy, torch.float32, "entropy"), ws_ptr, ws_bytes, _stream(stream))
     _check(rc)
 
 

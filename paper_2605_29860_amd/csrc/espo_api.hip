@@ -91,8 +91,8 @@ size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt) {
 int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,
               float temperature, uint64_t seed, int32_t step, const float* values,
               const espo_params* params, float* z, uint8_t* alive, int32_t* stop_step,
-              int32_t* tokens, float* regret, float* logprob, void* workspace, size_t workspace_bytes,
-              void* stream) {
+              int32_t* tokens, float* regret, float* logprob, float* entropy, void* workspace,
+              size_t workspace_bytes, void* stream) {
   (void)workspace; (void)workspace_bytes;
   if (dt != ESPO_F32 && dt != ESPO_BF16) return ESPO_EINVAL;
   if (B < 0 || V < 1 || row_stride < V || step < 0) return ESPO_EINVAL;
@@ -109,7 +109,8 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
   const size_t esize = dt == ESPO_BF16 ? 2 : 4;
   if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
   return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params,
-                           g_margin_scale.load(), z, alive, stop_step, tokens, regret, logprob, (hipStream_t)stream);
+                           g_margin_scale.load(), z, alive, stop_step, tokens, regret, logprob, entropy,
+                           (hipStream_t)stream);
 }
 
 int espo_advantages(const float* rewards, const float* values, const int32_t* lengths,

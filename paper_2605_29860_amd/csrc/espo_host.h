@@ -17,7 +17,7 @@ size_t step_shared_bytes(int dt, int64_t V);
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
                 float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
-                hipStream_t stream);
+                float* entropy, hipStream_t stream);
 
 size_t batch_stats_workspace(int64_t B);
 

@@ -62,6 +62,7 @@ struct StepArgs {
   int32_t* tokens;
   float* regret;
   float* logprob;
+  float* entropy;
 };
 
 // ---------------------------------------------------------------- row access
@@ -308,6 +309,7 @@ struct StepShared {
   int* top_q;       // [kSlots] which block each lane group kept
   float* m;         // [kStepWaves] wave maxima
   float* sum;       // [kStepWaves] wave softmax sums (relative to the row maximum)
+  float* sumw;      // [kStepWaves] wave sums of 2^t t, t = (y_v - y_max) log2 e (entropy output only)
   double* res_s;    // [kStepWaves] per-wave search results
   double* res_hi2;
   float* res_e;
@@ -334,6 +336,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.top_q = (int*)take(kSlots * 4);
   s.m = (float*)take(kStepWaves * 4);
   s.sum = (float*)take(kStepWaves * 4);
+  s.sumw = (float*)take(kStepWaves * 4);
   s.res_e = (float*)take(kStepWaves * 4);
   s.res_v = (int*)take(kStepWaves * 4);
   s.res_x = (float*)take(kStepWaves * 4);
@@ -353,7 +356,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
 size_t step_lds_bytes(int dt, int ntiles) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
-  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 12 * kStepWaves * 4 + 16 + 2 * kCandCap * 4 +
+  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 13 * kStepWaves * 4 + 16 + 2 * kCandCap * 4 +
          ((nslots * 8 + 15) & ~(size_t)15) + ((nslots * 4 + 15) & ~(size_t)15);
 }
 
@@ -702,7 +705,7 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
 }
 
 // ---------------------------------------------------------------- the kernel
-template <int DT>
+template <int DT, bool Entropy>
 __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int row = blockIdx.x;
@@ -712,6 +715,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       a.tokens[row] = -1;
       a.regret[row] = 0.0f;
       if (a.logprob) a.logprob[row] = 0.0f;
+      if (Entropy) a.entropy[row] = 0.0f;
     }
     return;
   }
@@ -771,6 +775,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   float nrk = 1e30f;
   float lead = kNegInf;
   float sum = 0.0f;
+  float sumw = 0.0f;         // entropy output: sum_v 2^t_v t_v with t_v = x_v k2 + nrk (see below)
   float mx = kNegInf;        // largest logit this lane group has seen
   float top_ub = kNegInf;    // largest block bound this lane group has seen, and its block
   int top_q = -1;
@@ -796,19 +801,40 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
       if (gm > lead) {  // move this lane's reference up to gm
         const float nrk_new = -gm * a.k2;
-        sum *= __builtin_amdgcn_exp2f(nrk_new - nrk);
+        const float shift = nrk_new - nrk;  // every t_v moves by this much
+        const float f = __builtin_amdgcn_exp2f(shift);
+        if (Entropy) sumw = f * fmaf(shift, sum, sumw);
+        sum *= f;
         nrk = nrk_new;
         lead = gm + a.ref_lead;
       }
     }
-    float acc0 = __builtin_amdgcn_exp2f(fmaf(x[0], a.k2, nrk));
-    float acc1 = __builtin_amdgcn_exp2f(fmaf(x[1], a.k2, nrk));
+    if constexpr (!Entropy) {
+      float acc0 = __builtin_amdgcn_exp2f(fmaf(x[0], a.k2, nrk));
+      float acc1 = __builtin_amdgcn_exp2f(fmaf(x[1], a.k2, nrk));
 #pragma unroll
-    for (int j = 2; j < 8; j += 2) {
-      acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
-      acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
+      for (int j = 2; j < 8; j += 2) {
+        acc0 += __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk));
+        acc1 += __builtin_amdgcn_exp2f(fmaf(x[j + 1], a.k2, nrk));
+      }
+      sum += acc0 + acc1;
+    } else {
+      // The entropy needs sum_v pi_v ln pi_v = (ln 2 / S) sum_v 2^t_v t_v - ln S.  t_v is kept
+      // above -200: 2^t_v is 0 in fp32 from far above that, so the sum is unchanged and a
+      // masked logit (-inf) contributes 0 * -200 instead of 0 * -inf.
+      float acc0 = 0.0f, acc1 = 0.0f, w0 = 0.0f, w1 = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) {
+        const float t0 = fmaxf(fmaf(x[j], a.k2, nrk), -200.0f), t1 = fmaxf(fmaf(x[j + 1], a.k2, nrk), -200.0f);
+        const float e0 = __builtin_amdgcn_exp2f(t0), e1 = __builtin_amdgcn_exp2f(t1);
+        acc0 += e0;
+        acc1 += e1;
+        w0 = fmaf(e0, t0, w0);
+        w1 = fmaf(e1, t1, w1);
+      }
+      sum += acc0 + acc1;
+      sumw += w0 + w1;
     }
-    sum += acc0 + acc1;
     // upper bound of every perturbed score in the lane group's block: y_max + M_q
     const float bm = group8_max(gm);
     float* const mu = mu_lane + (size_t)i * (2 * kStepWaves * kGroups);
@@ -856,9 +882,15 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   float m = kNegInf;
   auto softmax_sum = [&]() {  // after the first barrier: row maximum, then the wave's share of the sum
     m = wave_max(lane < kStepWaves ? sh.m[lane] : kNegInf);
-    const float part = sum > 0.0f ? sum * __builtin_amdgcn_exp2f(-fmaf(m, a.k2, nrk)) : 0.0f;
+    const float shift = -fmaf(m, a.k2, nrk);  // from this lane's reference to the row maximum
+    const float f = __builtin_amdgcn_exp2f(shift);
+    const float part = sum > 0.0f ? sum * f : 0.0f;
     const float tot = wave_sum(part);
     if (lane == 0) sh.sum[wave] = tot;
+    if constexpr (Entropy) {
+      const float totw = wave_sum(sum > 0.0f ? f * fmaf(shift, sum, sumw) : 0.0f);
+      if (lane == 0) sh.sumw[wave] = totw;
+    }
   };
   const Best fast = fast_argmax<DT>(a, sh, rowp, row, nslots, q_own, softmax_sum);
   int32_t tok = fast.v;
@@ -878,6 +910,8 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   // ------------------------------------------------------------ finalize: one lane
   if (wave == 0) {
     const float S = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // sum_v exp((x_v - m)/tau), fixed order
+    float Sw = 0.0f;
+    if constexpr (Entropy) Sw = wave_sum(lane < kStepWaves ? sh.sumw[lane] : 0.0f);
     if (lane == 0) {
       if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
       const ChainOut c = scalar_chain(a, row, m, x_a, z_prev, value);
@@ -885,6 +919,8 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       a.regret[row] = c.g;
       a.z[row] = c.z;
       if (a.logprob) a.logprob[row] = -c.g - flog(S);
+      if constexpr (Entropy)  // H = ln S - E_pi[y - y_max] >= 0; rounding can leave S a few ulp below 1
+        a.entropy[row] = fmaxf(flog(S) - kLn2 * Sw / S, 0.0f);
       if (a.eos_id >= 0 && tok == a.eos_id) {
         a.alive[row] = 0;  // natural end
       } else if (c.stop) {
@@ -945,7 +981,7 @@ size_t step_shared_bytes(int dt, int64_t V) { return step_lds_bytes(dt, (int)((V
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
                 float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
-                hipStream_t stream) {
+                float* entropy, hipStream_t stream) {
   StepArgs a;
   a.logits = logits;
   a.V = (int32_t)V;
@@ -978,17 +1014,18 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.tokens = tokens;
   a.regret = regret;
   a.logprob = logprob;
+  a.entropy = entropy;
   const size_t lds = step_lds_bytes(dt, a.ntiles);
   if (lds > kMaxStepLds) return ESPO_ERANGE;
   const dim3 grid((unsigned)B), block(kStepThreads);
+  // the entropy output costs two more vector operations per logit: its own instantiation
+  void (*kernel)(StepArgs) = dt == ESPO_BF16 ? (entropy ? espo_step_kernel<ESPO_BF16, true> : espo_step_kernel<ESPO_BF16, false>)
+                                             : (entropy ? espo_step_kernel<ESPO_F32, true> : espo_step_kernel<ESPO_F32, false>);
   if (lds > 64 * 1024) {  // beyond the default limit the kernel has to be told (very large vocabularies)
-    const void* fn = dt == ESPO_BF16 ? (const void*)espo_step_kernel<ESPO_BF16> : (const void*)espo_step_kernel<ESPO_F32>;
-    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStepLds) != hipSuccess) return ESPO_EHIP;
+    if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStepLds) != hipSuccess)
+      return ESPO_EHIP;
   }
-  if (dt == ESPO_BF16)
-    hipLaunchKernelGGL(espo_step_kernel<ESPO_BF16>, grid, block, lds, stream, a);
-  else
-    hipLaunchKernelGGL(espo_step_kernel<ESPO_F32>, grid, block, lds, stream, a);
+  hipLaunchKernelGGL(kernel, grid, block, lds, stream, a);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 

@@ -6,6 +6,9 @@ bit-exact; tokens are bit-exact except where the oracle's two largest perturbed 
 lie within 1e-6 relative, in which case the runner-up is accepted and forced into the
 oracle so that the rest of the trajectory stays comparable; log-probabilities agree
 within rtol * max(|ref|, 1) with rtol 1e-5 for fp32 logits and 2e-3 for bf16 logits.
+The entropy output agrees within 1e-5 * max(ref, 1) for both types (bf16 logits are exact
+inputs to both sides; what differs is fp32 summation and the hardware exp2/log2, a few 1e-7
+relative on each of the two sums the entropy is formed from).
 """
 from __future__ import annotations
 
@@ -37,22 +40,25 @@ class GpuState:
         self.tokens = torch.full((B,), -7, dtype=torch.int32, device=device)
         self.regret = torch.full((B,), -7.0, dtype=torch.float32, device=device)
         self.logprob = torch.full((B,), -7.0, dtype=torch.float32, device=device)
+        self.entropy = torch.full((B,), -7.0, dtype=torch.float32, device=device)
 
     def host(self):
-        return {k: getattr(self, k).cpu().numpy() for k in ("z", "alive", "stop_step", "tokens", "regret", "logprob")}
+        return {k: getattr(self, k).cpu().numpy()
+                for k in ("z", "alive", "stop_step", "tokens", "regret", "logprob", "entropy")}
 
 
-def gpu_step(logits, tau, seed, step, values, gparams, st: GpuState, V=None):
+def gpu_step(logits, tau, seed, step, values, gparams, st: GpuState, V=None, entropy=False):
     espo.espo_step(logits, tau, seed, step, values, gparams, st.z, st.alive, st.stop_step,
-                   st.tokens, st.regret, st.logprob, V=V)
+                   st.tokens, st.regret, st.logprob, V=V, entropy=st.entropy if entropy else None)
 
 
 def compare_step(logits, tau, seed, step, values, gparams, oparams, st: GpuState, V=None, rows=None,
-                 stats=None):
+                 stats=None, entropy=False):
     """Runs one step on both sides from the GPU's current state and compares all outputs.
 
     `rows` restricts the oracle to a subset of rows (the GPU always runs the whole batch).
-    Returns the GPU's host-side outputs of the step.
+    With `entropy` the step is asked for its entropy output as well (the kernel's other
+    instantiation) and that is compared too.  Returns the GPU's host-side outputs of the step.
     """
     B = logits.shape[0]
     rows = np.arange(B) if rows is None else np.asarray(rows)
@@ -61,7 +67,7 @@ def compare_step(logits, tau, seed, step, values, gparams, oparams, st: GpuState
               "stop_step": st.stop_step[ridx].cpu().numpy()}
     vals_h = values[ridx].cpu().numpy()
     bits = np.ascontiguousarray(to_host_bits(logits[ridx]))
-    gpu_step(logits, tau, seed, step, values, gparams, st, V=V)
+    gpu_step(logits, tau, seed, step, values, gparams, st, V=V, entropy=entropy)
     torch.cuda.synchronize()
     got = st.host()
 
@@ -75,7 +81,7 @@ def compare_step(logits, tau, seed, step, values, gparams, oparams, st: GpuState
     ss = np.full(nfull, -1, np.int32); ss[rows] = before["stop_step"]
     vals = np.zeros(nfull, np.float32); vals[rows] = vals_h
     z0, alive0, ss0 = z.copy(), alive.copy(), ss.copy()
-    ref = oracle.step(full_bits, tau, seed, step, vals, oparams, z, alive, ss, V=V)
+    ref = oracle.step(full_bits, tau, seed, step, vals, oparams, z, alive, ss, V=V, want_entropy=entropy)
 
     tok_g = got["tokens"][rows]
     tok_o = ref["tokens"][rows]
@@ -91,7 +97,8 @@ def compare_step(logits, tau, seed, step, values, gparams, oparams, st: GpuState
         if stats is not None:
             stats["near_ties"] = stats.get("near_ties", 0) + len(mism)
         z, alive, ss = z0, alive0, ss0
-        ref = oracle.step(full_bits, tau, seed, step, vals, oparams, z, alive, ss, V=V, forced_tokens=forced)
+        ref = oracle.step(full_bits, tau, seed, step, vals, oparams, z, alive, ss, V=V, forced_tokens=forced,
+                          want_entropy=entropy)
 
     where = f"step {step}"
     np.testing.assert_array_equal(got["tokens"][rows], ref["tokens"][rows], err_msg=where)
@@ -103,6 +110,12 @@ def compare_step(logits, tau, seed, step, values, gparams, oparams, st: GpuState
     lp_g, lp_o = got["logprob"][rows].astype(np.float64), ref["logprob"][rows].astype(np.float64)
     err = np.abs(lp_g - lp_o)
     assert (err <= rtol * np.maximum(np.abs(lp_o), 1.0)).all(), (where, err.max(), lp_g[err.argmax()], lp_o[err.argmax()])
+    if entropy:
+        h_g, h_o = got["entropy"][rows].astype(np.float64), ref["entropy"][rows].astype(np.float64)
+        herr = np.abs(h_g - h_o)
+        assert (herr <= RTOL_F32 * np.maximum(h_o, 1.0)).all(), (where, herr.max(), h_g[herr.argmax()], h_o[herr.argmax()])
+        if stats is not None:
+            stats["max_entropy_err"] = max(stats.get("max_entropy_err", 0.0), float(herr.max()) if len(herr) else 0.0)
     if stats is not None:
         stats["max_logprob_err"] = max(stats.get("max_logprob_err", 0.0), float(err.max()) if len(err) else 0.0)
         stats["rows_checked"] = stats.get("rows_checked", 0) + int(before["alive"].sum())

@@ -7,7 +7,7 @@
 //   float logits[B*V]; float values[B]; float z[B]; uint8 alive[B]; int32 stop_step[B];
 //   float rewards[B*T]; float vals2[B*T]; int32 lengths[B]; uint8 stopped[B]
 // output file: int32 tokens[B]; float regret[B]; float z[B]; uint8 alive[B]; int32 stop_step[B];
-//   float logprob[B]; float td[B*T]; float adv[B*T]
+//   float logprob[B]; float entropy[B]; float td[B*T]; float adv[B*T]
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -60,7 +60,7 @@ int main(int argc, char** argv) {
     return 1;
   std::fclose(f);
 
-  float *d_logits, *d_values, *d_z, *d_rewards, *d_vals2, *d_regret, *d_logprob, *d_td, *d_adv;
+  float *d_logits, *d_values, *d_z, *d_rewards, *d_vals2, *d_regret, *d_logprob, *d_entropy, *d_td, *d_adv;
   uint8_t *d_alive, *d_stopped;
   int32_t *d_stop_step, *d_lengths, *d_tokens;
   if (to_device(&d_logits, logits) || to_device(&d_values, values) || to_device(&d_z, z) || to_device(&d_alive, alive) ||
@@ -70,30 +70,33 @@ int main(int argc, char** argv) {
   CK(hipMalloc((void**)&d_tokens, B * 4));
   CK(hipMalloc((void**)&d_regret, B * 4));
   CK(hipMalloc((void**)&d_logprob, B * 4));
+  CK(hipMalloc((void**)&d_entropy, B * 4));
   CK(hipMalloc((void**)&d_td, (size_t)B * T * 4));
   CK(hipMalloc((void**)&d_adv, (size_t)B * T * 4));
   hipStream_t stream;
   CK(hipStreamCreate(&stream));
 
   EK(espo_step(d_logits, ESPO_F32, B, V, V, tau, seed, step, d_values, &p, d_z, d_alive, d_stop_step, d_tokens, d_regret,
-               d_logprob, nullptr, 0, stream));
+               d_logprob, d_entropy, nullptr, 0, stream));
   EK(espo_advantages(d_rewards, d_vals2, d_lengths, d_stopped, B, T, -1.0f, 1.0f, 0.95f, d_td, d_adv, stream));
   CK(hipStreamSynchronize(stream));
 
   std::vector<int32_t> tokens(B);
-  std::vector<float> regret(B), logprob(B), td((size_t)B * T), adv((size_t)B * T);
+  std::vector<float> regret(B), logprob(B), entropy(B), td((size_t)B * T), adv((size_t)B * T);
   CK(hipMemcpy(tokens.data(), d_tokens, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(regret.data(), d_regret, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(z.data(), d_z, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(alive.data(), d_alive, B, hipMemcpyDeviceToHost));
   CK(hipMemcpy(stop_step.data(), d_stop_step, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(logprob.data(), d_logprob, B * 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(entropy.data(), d_entropy, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(td.data(), d_td, td.size() * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(adv.data(), d_adv, adv.size() * 4, hipMemcpyDeviceToHost));
   std::FILE* o = std::fopen(argv[2], "wb");
   if (!o) return 1;
   const bool ok = wr(o, tokens.data(), B) && wr(o, regret.data(), B) && wr(o, z.data(), B) && wr(o, alive.data(), B) &&
-                  wr(o, stop_step.data(), B) && wr(o, logprob.data(), B) && wr(o, td.data(), td.size()) &&
+                  wr(o, stop_step.data(), B) && wr(o, logprob.data(), B) && wr(o, entropy.data(), B) &&
+                  wr(o, td.data(), td.size()) &&
                   wr(o, adv.data(), adv.size());
   std::fclose(o);
   std::printf("abi_check: version %d, B=%d V=%d T=%d done\n", espo_version(), B, V, T);

@@ -58,10 +58,11 @@ def test_native_program_matches_the_oracle(tmp_path):
         return a
     tokens, regret, z_g, alive_g, ss_g, logprob = (take(np.int32, B), take(np.float32, B), take(np.float32, B),
                                                    take(np.uint8, B), take(np.int32, B), take(np.float32, B))
+    entropy = take(np.float32, B)
     td, adv = take(np.float32, B * T).reshape(B, T), take(np.float32, B * T).reshape(B, T)
 
     z_o, alive_o, ss_o = z.copy(), alive.copy(), stop_step.copy()
-    ref = oracle.step(logits_in, tau, seed, step, values, op, z_o, alive_o, ss_o)
+    ref = oracle.step(logits_in, tau, seed, step, values, op, z_o, alive_o, ss_o, want_entropy=True)
     np.testing.assert_array_equal(tokens, ref["tokens"])
     np.testing.assert_array_equal(regret.view(np.uint32), ref["regret"].view(np.uint32))
     np.testing.assert_array_equal(z_g.view(np.uint32), z_o.view(np.uint32))
@@ -69,6 +70,7 @@ def test_native_program_matches_the_oracle(tmp_path):
     np.testing.assert_array_equal(ss_g, ss_o)
     live = alive == 1
     assert np.abs(logprob[live] - ref["logprob"][live]).max() <= 1e-5 * np.maximum(np.abs(ref["logprob"][live]), 1).max()
+    assert (np.abs(entropy - ref["entropy"]) <= 1e-5 * np.maximum(ref["entropy"], 1)).all() and (entropy[~live] == 0).all()
     td_o, adv_o, scale = oracle.advantages(rewards, vals2, lengths, stopped, -1.0, 1.0, 0.95)
     assert np.abs(td - td_o).max() <= 4e-7 * (np.abs(rewards).max() + 2 * np.abs(vals2).max() + 1)
     assert (np.abs(adv - adv_o) <= 1e-5 * np.maximum(np.abs(adv_o), scale)).all()

@@ -460,6 +460,46 @@ def test_seeded_sweep_of_shapes_structures_and_margins():
     _say(f"  cases per margin scale: {paths}")
 
 
+# --------------------------------------------------------------------------- entropy output
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_entropy_output_matches_the_oracle(dtype):
+    _say(f"[case] entropy {dtype}")
+    stats = {}
+    rng = np.random.default_rng(77)
+    for case, (V, kind, tau) in enumerate([(1, "gauss", 1.0), (5, "gauss", 0.6), (513, "gauss", 0.6), (4099, "flat", 1.0),
+                                           (9000, "masked", 0.8), (20000, "peaked", 0.6), (33000, "gauss", 0.05),
+                                           (33000, "gauss", 4.0), (70001, "zipf", 0.6), (152064, "zipf", 0.6)]):
+        B = 4
+        stride = ((V + 7) // 8) * 8 + 8
+        g = torch.Generator().manual_seed(500 + case)
+        x = torch.randn(B, stride, generator=g) * 3.0
+        if kind == "flat":
+            x[:] = -2.0
+        elif kind == "masked":
+            x[:, torch.rand(stride, generator=g) < 0.8] = float("-inf")
+            x[:, V // 3] = 1.0
+        elif kind == "peaked":
+            x[:, V - 2] = 60.0                                  # far beyond the rest: entropy next to 0
+        elif kind == "zipf":
+            x[:, :V] += W.ZipfLogits(V=V, seed=case, device="cpu").boost   # the shape of the benchmark rows
+        x[:, V:] = 1e4
+        logits = x.to(dtype).cuda()
+        gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=3.0)
+        st = H.GpuState(B, alive=torch.tensor([1, 1, 0, 1], dtype=torch.uint8))
+        vals = torch.rand(B, generator=g).cuda()
+        # the same step without the entropy output: every other output must be the same bits
+        plain = H.GpuState(B, alive=torch.tensor([1, 1, 0, 1], dtype=torch.uint8))
+        H.gpu_step(logits, tau, 41, 0, vals, gp, plain, V=V)
+        got = H.compare_step(logits, tau, 41, 0, vals, gp, op, st, V=V, entropy=True, stats=stats)
+        ref = plain.host()
+        for k in ("tokens", "regret", "z", "alive", "stop_step", "logprob"):
+            np.testing.assert_array_equal(got[k].view(np.uint8), ref[k].view(np.uint8), err_msg=f"case {case} {k}")
+        assert got["entropy"][2] == 0 and (got["entropy"] >= 0).all() and (got["entropy"] <= np.log(V) * (1 + 1e-6) + 1e-6).all()
+        if kind == "flat":
+            np.testing.assert_allclose(got["entropy"][[0, 1, 3]], np.log(V), rtol=1e-6)
+    _say(f"  largest entropy error {stats.get('max_entropy_err', 0):.2e}")
+
+
 # --------------------------------------------------------------------------- concurrent streams
 def test_two_streams_do_not_interfere():
     _say("[case] two streams")

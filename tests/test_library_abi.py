@@ -51,7 +51,7 @@ def test_argument_checks_need_no_gpu(lib):
     fake = ctypes.c_void_p(0x1000)
     def step(B=1, V=8, stride=8, tau=1.0, logits=fake, params=ctypes.byref(p), dt=1, stepno=0):
         return lib.espo_step(logits, dt, B, V, stride, tau, 0, stepno, fake, params, fake, fake, fake, fake, fake,
-                             None, None, 0, None)
+                             None, None, None, 0, None)
     assert step(B=0) == 0                                   # empty batch is a no-op
     assert step(tau=0.0) == -1 and step(tau=float("nan")) == -1
     assert step(V=0) == -1 and step(stride=4) == -1 and step(B=-1) == -1 and step(stepno=-1) == -1
