@@ -21,6 +21,8 @@
  *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
  *                      Section 4.4 (failure reward at the stop step, no bootstrap).
  *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
+ *   oracle_advantages_terminal  the same for the reward structure of Algorithm 1 (zero
+ *                      until the last step), plus the value targets A_t + V(s_t).
  *   oracle_batch_stats Section 4.2 (EMA of the batch mean and variance of the regret) and
  *                      Eq. beta_update, plain two-pass definitions.
  *   stop_decision      Eq. stop_rule and the replacement tests of the ablations (Section 6,
@@ -438,6 +440,53 @@ int oracle_gae_bruteforce(const float* rewards, const float* values,
         acc += pow(c, (double)l) * delta;
       }
       adv[b * T + t] = (t < L) ? acc : 0.0;
+    }
+  }
+  return 0;
+}
+
+/*
+ * The trajectory that Algorithm 1 returns has r_t = 0 at every step that goes on and one
+ * reward at its last step: r_fail if the stop rule ended it (Eq. failure_reward), else the
+ * task's terminal reward.  This is TD error and GAE (Section 3) for that reward structure,
+ * given per row only the terminal reward, and also the critic's regression target
+ * R_t = A_t + V(s_t) (the lambda-return that PPO's value loss uses; the paper keeps "the
+ * standard PPO formulation").  Same recursion as above, written for this case on its own.
+ * Outputs in double; td, adv, ret (ret may be NULL) are zero at t >= L.
+ */
+int oracle_advantages_terminal(const float* values, const int32_t* lengths, const uint8_t* stopped,
+                               const float* terminal_reward, int64_t B, int64_t T,
+                               float r_fail, float gamma, float lambda,
+                               double* td, double* adv, double* ret) {
+  if (B < 0 || T < 0) return -1;
+  if (B == 0 || T == 0) return 0;
+  if (!values || !lengths || !stopped || !terminal_reward || !td || !adv) return -1;
+  const double gam = (double)gamma;
+  const double c = (double)gamma * (double)lambda;
+#pragma omp parallel for schedule(dynamic, 1)
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    const float* val = values + b * T;
+    for (int64_t t = L; t < T; ++t) {
+      td[b * T + t] = 0.0;
+      adv[b * T + t] = 0.0;
+      if (ret) ret[b * T + t] = 0.0;
+    }
+    double A = 0.0;
+    for (int64_t t = L - 1; t >= 0; --t) {
+      double delta;
+      if (t == L - 1) {                                   /* last step: its reward, no bootstrap */
+        const double r_end = stopped[b] ? (double)r_fail : (double)terminal_reward[b];
+        delta = r_end - (double)val[t];
+      } else {                                            /* a step that went on: r_t = 0        */
+        delta = gam * (double)val[t + 1] - (double)val[t];
+      }
+      A = delta + c * A;
+      td[b * T + t] = delta;
+      adv[b * T + t] = A;
+      if (ret) ret[b * T + t] = A + (double)val[t];
     }
   }
   return 0;

@@ -73,6 +73,8 @@ def _load():
         lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), u64, i32, vp, vp, vp]
         lib.oracle_advantages.restype = C.c_int
         lib.oracle_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
+        lib.oracle_advantages_terminal.restype = C.c_int
+        lib.oracle_advantages_terminal.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
         lib.oracle_gae_bruteforce.restype = C.c_int
         lib.oracle_gae_bruteforce.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp]
         lib.oracle_batch_stats.restype = C.c_int
@@ -232,6 +234,22 @@ def advantages(rewards: np.ndarray, values: np.ndarray, lengths: np.ndarray, sto
     if rc != 0:
         raise ValueError("oracle_advantages: invalid arguments")
     return td, adv, scale
+
+
+def advantages_terminal(values: np.ndarray, lengths: np.ndarray, stopped: np.ndarray,
+                        terminal_reward: np.ndarray, r_fail: float, gamma: float, lam: float):
+    """TD errors, GAE and value targets (double) when every reward but the last is zero."""
+    B, T = values.shape
+    _chk(values, np.float32, (B, T), "values")
+    _chk(lengths, np.int32, (B,), "lengths")
+    _chk(stopped, np.uint8, (B,), "stopped")
+    _chk(terminal_reward, np.float32, (B,), "terminal_reward")
+    td, adv, ret = (np.empty((B, T), np.float64) for _ in range(3))
+    rc = _load().oracle_advantages_terminal(_ptr(values), _ptr(lengths), _ptr(stopped), _ptr(terminal_reward), B, T,
+                                            float(r_fail), float(gamma), float(lam), _ptr(td), _ptr(adv), _ptr(ret))
+    if rc != 0:
+        raise ValueError("oracle_advantages_terminal: invalid arguments")
+    return td, adv, ret
 
 
 def gae_bruteforce(rewards: np.ndarray, values: np.ndarray, lengths: np.ndarray, stopped: np.ndarray,

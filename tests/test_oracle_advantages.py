@@ -134,3 +134,80 @@ def test_empty_shapes(oracle):
     e = np.zeros((3, 0), np.float32)
     td, adv, _ = oracle.advantages(e, e, np.zeros(3, np.int32), np.zeros(3, np.uint8), -1.0, 1.0, 0.95)
     assert adv.shape == (3, 0)
+
+
+# ------------------------------------------------------------------ terminal-reward form (Algorithm 1's rewards)
+def _terminal_batch(rng, B, T, stop_p=0.4):
+    values = rng.uniform(-1, 1, (B, T)).astype(np.float32)
+    lengths = rng.integers(0, T + 1, B).astype(np.int32)
+    stopped = (rng.random(B) < stop_p).astype(np.uint8)
+    term = rng.integers(0, 2, B).astype(np.float32) + rng.normal(0, 0.1, B).astype(np.float32)
+    return values, lengths, stopped, term
+
+
+def test_terminal_form_hand_examples(oracle):
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "gae_terminal_hand_example.txt"))
+            if l.strip() and not l.startswith("#")]
+    v = np.array([[0.5, 0.2, -0.1]], np.float32)
+    cases = {"A": (v, [3], [0], [1.0], -1.0, 1.0, 0.95), "B": (v, [2], [1], [9.0], -1.0, 1.0, 0.95),
+             "C": (np.array([[1, 2, 4]], np.float32), [3], [0], [2.0], -1.0, 0.5, 0.5)}
+    assert len(rows) == 9
+    for name, t, e_td, e_adv, e_ret in rows:
+        val, L, st, term, rf, gam, lam = cases[name]
+        td, adv, ret = oracle.advantages_terminal(val, np.array(L, np.int32), np.array(st, np.uint8),
+                                                  np.array(term, np.float32), rf, gam, lam)
+        t = int(t)
+        assert abs(td[0, t] - float(e_td)) < 1e-6 and abs(adv[0, t] - float(e_adv)) < 1e-6, (name, t)
+        assert abs(ret[0, t] - float(e_ret)) < 1e-6, (name, t)
+
+
+def test_terminal_form_equals_dense_form_and_bruteforce(oracle):
+    rng = np.random.default_rng(31)
+    B, T = 24, 41
+    values, lengths, stopped, term = _terminal_batch(rng, B, T)
+    lengths[:3] = [0, 1, T]
+    dense = np.zeros((B, T), np.float32)                    # the same rewards, spelled out per token
+    for b in range(B):
+        if lengths[b] > 0:
+            dense[b, lengths[b] - 1] = term[b]
+    for gam, lam in [(1.0, 0.95), (0.9, 0.8), (1.0, 1.0), (0.7, 0.0)]:
+        td, adv, ret = oracle.advantages_terminal(values, lengths, stopped, term, -1.0, gam, lam)
+        td_d, adv_d, _ = oracle.advantages(dense, values, lengths, stopped, -1.0, gam, lam)
+        brute = oracle.gae_bruteforce(dense, values, lengths, stopped, -1.0, gam, lam)
+        np.testing.assert_allclose(td, td_d, rtol=0, atol=1e-15)
+        np.testing.assert_allclose(adv, adv_d, rtol=1e-13, atol=1e-13)
+        np.testing.assert_allclose(adv, brute, rtol=1e-11, atol=1e-12)
+        mask = np.arange(T)[None, :] < lengths[:, None]
+        np.testing.assert_allclose(ret, np.where(mask, adv + values, 0.0), rtol=1e-15, atol=0)
+        assert (td[~mask] == 0).all() and (adv[~mask] == 0).all() and (ret[~mask] == 0).all()
+
+
+def test_terminal_form_textbook_targets(oracle):
+    rng = np.random.default_rng(32)
+    B, T = 16, 30
+    values, lengths, stopped, term = _terminal_batch(rng, B, T)
+    lengths = np.maximum(lengths, 1).astype(np.int32)
+    r_fail, gam = -1.0, 0.9
+    r_end = np.where(stopped == 1, np.float64(r_fail), term.astype(np.float64))
+    t = np.arange(T)[None, :]
+    mask = t < lengths[:, None]
+    # lambda = 1: the target is the discounted Monte-Carlo return, whatever the critic says
+    _, _, ret = oracle.advantages_terminal(values, lengths, stopped, term, r_fail, gam, 1.0)
+    mc = np.where(mask, r_end[:, None] * np.float64(np.float32(gam)) ** (lengths[:, None] - 1 - t).clip(0), 0.0)
+    np.testing.assert_allclose(ret, mc, rtol=1e-12, atol=1e-13)
+    # lambda = 0: the one-step TD target gamma V(s_{t+1}), and the terminal reward at the end
+    _, adv0, ret0 = oracle.advantages_terminal(values, lengths, stopped, term, r_fail, gam, 0.0)
+    nxt = np.concatenate([values[:, 1:], np.zeros((B, 1), np.float32)], axis=1).astype(np.float64)
+    want = np.where(t == lengths[:, None] - 1, r_end[:, None], np.float64(np.float32(gam)) * nxt)
+    np.testing.assert_allclose(ret0, np.where(mask, want, 0.0), rtol=1e-13, atol=1e-15)
+    # zero critic: A_t = r_end (gamma lambda)^(L-1-t), so early stopping reaches back geometrically
+    zero = np.zeros_like(values)
+    _, adv, _ = oracle.advantages_terminal(zero, lengths, stopped, term, r_fail, 1.0, 0.95)
+    geo = np.where(mask, r_end[:, None] * np.float64(np.float32(0.95)) ** (lengths[:, None] - 1 - t).clip(0), 0.0)
+    np.testing.assert_allclose(adv, geo, rtol=1e-12, atol=0)
+    # NaN beyond the lengths is never read
+    poisoned = values.copy()
+    poisoned[~mask] = np.nan
+    a, b, c = oracle.advantages_terminal(poisoned, lengths, stopped, term, r_fail, gam, 0.95)
+    a2, b2, c2 = oracle.advantages_terminal(values, lengths, stopped, term, r_fail, gam, 0.95)
+    assert np.array_equal(a, a2) and np.array_equal(b, b2) and np.array_equal(c, c2)
