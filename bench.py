@@ -176,6 +176,25 @@ def main() -> int:
     adv_bytes = valid * 16 + (B_ADV * T_ADV - valid) * 8 + B_ADV * 5
     adv_gbs = float(adv_bytes.sum() / (adv_region_ms * 1e-3) / 1e9)
 
+    # the same batches in the terminal-reward form (no reward array, padding left to the caller's mask)
+    rows_all = torch.arange(B_ADV, device=dev)
+    adv_term = [r[rows_all, (L - 1).clamp(min=0).long()].contiguous() for r, v, L, s in adv_in]
+    def advt_call(i):
+        r, v, L, s = adv_in[i % nbuf]
+        td, ad = adv_out[i % nbuf]
+        espo.espo_advantages_terminal(v, L, s, adv_term[i % nbuf], -1.0, 1.0, 0.95, td, ad, zero_padding=False)
+    for i in range(nbuf):
+        advt_call(i)
+    torch.cuda.synchronize()
+    tregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    tregion[0].record()
+    for i in range(args.adv_reps):
+        advt_call(i)
+    tregion[1].record()
+    torch.cuda.synchronize()
+    advt_us = tregion[0].elapsed_time(tregion[1]) / args.adv_reps * 1e3
+    advt_bytes = float(np.mean(valid * 12 + B_ADV * 9))
+
     # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
     bs_sets = [W.regret_batch(512, 8192, seed=70 + i, device=dev) for i in range(nbuf)]   # 134 MB in rotation
     bs_out = torch.zeros(espo.BATCH_RESULT_BYTES, dtype=torch.uint8, device=dev)
@@ -247,6 +266,10 @@ def main() -> int:
                                     "avg_launch_us_event_pair_each": float(adv_ms.mean() * 1e3),
                                     "algorithmic_bytes_per_launch": float(adv_bytes.mean()),
                                     "traffic": _traffic_from_profiles("espo_advantages")}},
+        "advantages_terminal": {"workload": "the same batches, terminal-reward form: reads V, writes td and A at t < L only",
+                                "us_per_call": advt_us, "tokens_per_s": float(valid.mean() / advt_us * 1e6),
+                                "algorithmic_bytes_per_call": advt_bytes, "gbs": advt_bytes / advt_us / 1e3,
+                                "frac": advt_bytes / advt_us / 1e3 / HBM_PEAK_GBS},
         "batch_stats": {"workload": "B=512, T=8192 fp32 regrets, lengths U[64,8192], 25% stopped, 8 rotated sets",
                         "us_per_call": bs_us, "algorithmic_bytes_per_call": bs_bytes,
                         "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,

@@ -204,6 +204,28 @@ int espo_advantages(const float* rewards, const float* values,
                     float* td, float* adv, void* stream);
 
 /*
+ * espo_advantages_terminal -- the same pass for the reward structure of Algorithm 1:
+ * r_t = 0 at every step that goes on and one reward at the last step,
+ *   r_{L-1} = stopped[b] ? r_fail : terminal_reward[b]       (Eq. failure_reward),
+ * so no [B, T] reward array is read (4 bytes per token instead of 8).  td and adv are
+ * as in espo_advantages with these rewards.  Two options for the training step that
+ * follows:
+ *   returns       if not NULL, returns[b,t] = adv[b,t] + values[b,t] for t < L: the
+ *                 lambda-return that the critic of the (standard) PPO update regresses on.
+ *   zero_padding  non-zero: td, adv (and returns) are 0 for L <= t < T, as in
+ *                 espo_advantages.  Zero: positions at t >= L are not part of the result;
+ *                 each is either left as it was or set to 0 (a caller that masks by
+ *                 `lengths` saves the 8 to 12 bytes per padded token of the zero fill).
+ * Other arguments, alignment rules and errors as for espo_advantages; terminal_reward is
+ * device, [B] fp32 (read only for rows with stopped[b] == 0 and L > 0); returns, if given,
+ * device [B, T] fp32 with a 16-byte aligned base.
+ */
+int espo_advantages_terminal(const float* values, const int32_t* lengths, const uint8_t* stopped,
+                             const float* terminal_reward, int64_t B, int64_t T,
+                             float r_fail, float gamma, float lambda, int32_t zero_padding,
+                             float* td, float* adv, float* returns, void* stream);
+
+/*
  * espo_batch_stats -- the update at the boundary of a rollout batch: exponential moving
  * averages of the batch mean and variance of the regret (Section 4.2) and the proportional
  * controller of the threshold multiplier (Eq. beta_update).  The statistics stay frozen

@@ -88,6 +88,8 @@ def load_library():
         lib.espo_step_workspace_bytes.restype = sz
         lib.espo_step_workspace_bytes.argtypes = [i64, i64, C.c_int]
         lib.espo_advantages.restype = C.c_int
+        lib.espo_advantages_terminal.restype = C.c_int
+        lib.espo_advantages_terminal.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, i32, vp, vp, vp, vp]
         lib.espo_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
         lib.espo_strerror.restype = C.c_char_p
         lib.espo_strerror.argtypes = [C.c_int]
@@ -221,4 +223,23 @@ def espo_advantages(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.
                              _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
                              B, T, float(r_fail), float(gamma), float(lam),
                              _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"), _stream(stream))
+    _check(rc)
+
+
+def espo_advantages_terminal(values: torch.Tensor, lengths: torch.Tensor, stopped: torch.Tensor,
+                             terminal_reward: torch.Tensor, r_fail: float, gamma: float, lam: float,
+                             td: torch.Tensor, adv: torch.Tensor, returns: torch.Tensor | None = None,
+                             zero_padding: bool = True, stream=None) -> None:
+    """The advantage pass when only the last reward of a row is non-zero; see
+    `espo_advantages_terminal` in include/espo.h."""
+    lib = load_library()
+    if values.dim() != 2:
+        raise TypeError("values: need [B, T]")
+    B, T = values.shape
+    rc = lib.espo_advantages_terminal(_dev(values, torch.float32, "values"), _dev(lengths, torch.int32, "lengths"),
+                                      _dev(stopped, torch.uint8, "stopped"),
+                                      _dev(terminal_reward, torch.float32, "terminal_reward"), B, T,
+                                      float(r_fail), float(gamma), float(lam), int(bool(zero_padding)),
+                                      _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"),
+                                      _dev(returns, torch.float32, "returns"), _stream(stream))
     _check(rc)

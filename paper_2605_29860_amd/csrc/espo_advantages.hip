@@ -12,6 +12,11 @@
 // totals are combined the same way after one trip through LDS, and a single scalar carries A
 // across the tile boundary.  Only that scalar depends on the previous tile, so the next
 // tile's loads are issued before the current one is reduced.
+//
+// The same kernel serves the terminal-reward form (the rewards of Algorithm 1: zero at every
+// step that goes on, one reward at the last): no reward array is read, the last token takes
+// r_fail or the row's terminal reward, and on request the value targets A_t + V(s_t) are
+// stored and the padding beyond the lengths is left alone.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -30,7 +35,10 @@ constexpr int kAdvTile = kAdvThreads * kPerLane;  // 4096 tokens
 constexpr int kDppWaveShr1 = 0x138;               // lane i takes lane i-1 across the whole wave
 
 struct AdvArgs {
-  const float* rewards;
+  const float* rewards;          // dense form: [B, T]
+  const float* terminal_reward;  // terminal form: [B]
+  float* returns;                // optional [B, T]: A_t + V(s_t)
+  int32_t zero_padding;          // write zeros at t >= L (else those positions are not written by whole lanes)
   const float* values;
   const int32_t* lengths;
   const uint8_t* stopped;
@@ -60,7 +68,7 @@ __device__ __forceinline__ float pow_from_table(const float* tab, int e) {
 
 // Loads the lane's 4 tokens starting at t0 and, in lane 0, the value at t0 + 4; tokens at or
 // beyond L are never read.
-template <bool VEC>
+template <bool VEC, bool Dense>
 __device__ __forceinline__ TileIn load_tile(const float* __restrict__ rrow, const float* __restrict__ vrow, int64_t t0,
                                             int64_t L, bool want_halo) {
   TileIn in;
@@ -68,14 +76,21 @@ __device__ __forceinline__ TileIn load_tile(const float* __restrict__ rrow, cons
   for (int j = 0; j < kPerLane; ++j) { in.r[j] = 0.0f; in.v[j] = 0.0f; }
   in.halo = 0.0f;
   if (VEC && t0 + kPerLane <= L) {
-    const f32x4 a = __builtin_nontemporal_load((const f32x4*)(rrow + t0));
+    if constexpr (Dense) {
+      const f32x4 a = __builtin_nontemporal_load((const f32x4*)(rrow + t0));
+#pragma unroll
+      for (int j = 0; j < kPerLane; ++j) in.r[j] = a[j];
+    }
     const f32x4 b = __builtin_nontemporal_load((const f32x4*)(vrow + t0));
 #pragma unroll
-    for (int j = 0; j < kPerLane; ++j) { in.r[j] = a[j]; in.v[j] = b[j]; }
+    for (int j = 0; j < kPerLane; ++j) in.v[j] = b[j];
   } else {
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j)
-      if (t0 + j < L) { in.r[j] = rrow[t0 + j]; in.v[j] = vrow[t0 + j]; }
+      if (t0 + j < L) {
+        if constexpr (Dense) in.r[j] = rrow[t0 + j];
+        in.v[j] = vrow[t0 + j];
+      }
   }
   if (want_halo && t0 + kPerLane < L) in.halo = vrow[t0 + kPerLane];
   return in;
@@ -98,7 +113,7 @@ __device__ __forceinline__ float scan_step(float s, float w) {
   return fmaf(w, dpp_f32<Ctrl, RowMask>(0.0f, s), s);
 }
 
-template <bool VEC>
+template <bool VEC, bool Dense>
 __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs a) {
   __shared__ float s_tot[2][kAdvWaves];  // wave totals, double-buffered by tile parity
   const int row = blockIdx.x;
@@ -109,10 +124,16 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
   int64_t L = a.lengths[row];
   L = L < 0 ? 0 : (L > T ? T : L);
   const bool stopped = a.stopped[row] != 0;
-  const float* rrow = a.rewards + (int64_t)row * T;
+  // reward of the last token where it does not come from the reward array: r_fail after a stop
+  // (Eq. failure_reward), the row's terminal reward in the terminal form
+  const bool last_given = stopped || !Dense;
+  float r_last = a.r_fail;
+  if (!Dense && !stopped) r_last = a.terminal_reward[row];
+  const float* rrow = Dense ? a.rewards + (int64_t)row * T : nullptr;
   const float* vrow = a.values + (int64_t)row * T;
   float* drow = a.td + (int64_t)row * T;
   float* arow = a.adv + (int64_t)row * T;
+  float* trow = a.returns ? a.returns + (int64_t)row * T : nullptr;
 
   const int64_t ntiles = (T + kAdvTile - 1) / kAdvTile;
   const int64_t nvalid = (L + kAdvTile - 1) / kAdvTile;  // tiles that hold at least one valid token
@@ -120,9 +141,12 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
 
   // tiles wholly beyond the trajectory: outputs are exactly zero
   const float zero[kPerLane] = {0, 0, 0, 0};
-  for (int64_t k = ntiles - 1; k >= nvalid; --k) {
-    store4<VEC>(drow, k * kAdvTile + lane_off, T, zero);
-    store4<VEC>(arow, k * kAdvTile + lane_off, T, zero);
+  if (a.zero_padding) {
+    for (int64_t k = ntiles - 1; k >= nvalid; --k) {
+      store4<VEC>(drow, k * kAdvTile + lane_off, T, zero);
+      store4<VEC>(arow, k * kAdvTile + lane_off, T, zero);
+      if (trow) store4<VEC>(trow, k * kAdvTile + lane_off, T, zero);
+    }
   }
   if (nvalid == 0) return;
 
@@ -133,11 +157,11 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
   const float w_wave = pow_from_table<4>(a.cwave, wave);            // c^(256 wave): the tile's carry-in seen from this wave
 
   float carry = 0.0f;  // A at the first token of the tile processed before (the later one)
-  TileIn cur = load_tile<VEC>(rrow, vrow, (nvalid - 1) * kAdvTile + lane_off, L, lane == 0);
+  TileIn cur = load_tile<VEC, Dense>(rrow, vrow, (nvalid - 1) * kAdvTile + lane_off, L, lane == 0);
   for (int64_t k = nvalid - 1; k >= 0; --k) {
     const int64_t t0 = k * kAdvTile + lane_off;
     TileIn nxt;
-    if (k > 0) nxt = load_tile<VEC>(rrow, vrow, t0 - kAdvTile, L, lane == 0);  // the earlier tile, in flight during the scan
+    if (k > 0) nxt = load_tile<VEC, Dense>(rrow, vrow, t0 - kAdvTile, L, lane == 0);  // the earlier tile, in flight during the scan
 
     // V_{t+1} of the lane's last token: first value of the lane that holds the following tokens
     float vnext = dpp_f32<kDppWaveShr1, 0xf>(0.0f, cur.v[0]);
@@ -161,7 +185,7 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
         float vn = (j == kPerLane - 1) ? vnext : cur.v[j + 1];
         if (j + 1 >= rem) vn = 0.0f;                        // no bootstrap beyond the last token
         float r = cur.r[j];
-        if (stopped && j + 1 == rem) r = a.r_fail;          // Eq. failure_reward
+        if (last_given && j + 1 == rem) r = r_last;
         float dj = (r + a.gamma * vn) - cur.v[j];
         if (j >= rem) dj = 0.0f;
         d[j] = dj;
@@ -198,19 +222,30 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
     float outA[kPerLane];
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j) outA[j] = (j < rem) ? fmaf(a.cj[kPerLane - j], a_next, loc[j]) : 0.0f;
-    store4<VEC>(drow, t0, T, d);
-    store4<VEC>(arow, t0, T, outA);
+    if (a.zero_padding || rem > 0) {  // lanes wholly beyond L only ever hold zeros
+      store4<VEC>(drow, t0, T, d);
+      store4<VEC>(arow, t0, T, outA);
+      if (trow) {  // value targets: the lambda-return A_t + V(s_t)
+        float outR[kPerLane];
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j) outR[j] = (j < rem) ? outA[j] + cur.v[j] : 0.0f;
+        store4<VEC>(trow, t0, T, outR);
+      }
+    }
     if (k > 0) cur = nxt;
   }
 }
 
 }  // namespace
 
-int launch_advantages(const float* rewards, const float* values, const int32_t* lengths,
+int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
                       const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
-                      float lambda, float* td, float* adv, hipStream_t stream) {
+                      float lambda, int zero_padding, float* td, float* adv, float* returns, hipStream_t stream) {
   AdvArgs a;
   a.rewards = rewards;
+  a.terminal_reward = terminal_reward;
+  a.returns = returns;
+  a.zero_padding = zero_padding;
   a.values = values;
   a.lengths = lengths;
   a.stopped = stopped;
@@ -226,10 +261,9 @@ int launch_advantages(const float* rewards, const float* values, const int32_t* 
   a.adv = adv;
   const bool vec = (T % 4 == 0);
   const dim3 grid((unsigned)B), block(kAdvThreads);
-  if (vec)
-    hipLaunchKernelGGL(espo_advantages_kernel<true>, grid, block, 0, stream, a);
-  else
-    hipLaunchKernelGGL(espo_advantages_kernel<false>, grid, block, 0, stream, a);
+  void (*kernel)(AdvArgs) = rewards ? (vec ? espo_advantages_kernel<true, true> : espo_advantages_kernel<false, true>)
+                                    : (vec ? espo_advantages_kernel<true, false> : espo_advantages_kernel<false, false>);
+  hipLaunchKernelGGL(kernel, grid, block, 0, stream, a);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 

@@ -122,8 +122,22 @@ int espo_advantages(const float* rewards, const float* values, const int32_t* le
   if (!rewards || !values || !lengths || !stopped || !td || !adv) return ESPO_EINVAL;
   if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
   if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv)) return ESPO_EALIGN;
-  return espo::launch_advantages(rewards, values, lengths, stopped, B, T, r_fail, gamma, lambda, td, adv,
-                                 (hipStream_t)stream);
+  return espo::launch_advantages(rewards, nullptr, values, lengths, stopped, B, T, r_fail, gamma, lambda, 1, td, adv,
+                                 nullptr, (hipStream_t)stream);
+}
+
+int espo_advantages_terminal(const float* values, const int32_t* lengths, const uint8_t* stopped,
+                             const float* terminal_reward, int64_t B, int64_t T, float r_fail, float gamma,
+                             float lambda, int32_t zero_padding, float* td, float* adv, float* returns,
+                             void* stream) {
+  if (B < 0 || T < 0) return ESPO_EINVAL;
+  if (!isfinite(gamma) || !isfinite(lambda) || isnan(r_fail)) return ESPO_EINVAL;
+  if (B == 0 || T == 0) return ESPO_OK;
+  if (!values || !lengths || !stopped || !terminal_reward || !td || !adv) return ESPO_EINVAL;
+  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (!aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns)) return ESPO_EALIGN;
+  return espo::launch_advantages(nullptr, terminal_reward, values, lengths, stopped, B, T, r_fail, gamma, lambda,
+                                 zero_padding != 0, td, adv, returns, (hipStream_t)stream);
 }
 
 }  // extern "C"

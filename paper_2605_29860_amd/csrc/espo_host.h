@@ -27,8 +27,9 @@ int launch_batch_stats(const float* regret, const int32_t* lengths, const uint8_
 
 int launch_math_errors(float* out, hipStream_t stream);
 
-int launch_advantages(const float* rewards, const float* values, const int32_t* lengths,
+// rewards != nullptr: dense form; else the terminal form with terminal_reward[B].
+int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
                       const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
-                      float lambda, float* td, float* adv, hipStream_t stream);
+                      float lambda, int zero_padding, float* td, float* adv, float* returns, hipStream_t stream);
 
 }  // namespace espo

@@ -150,3 +150,48 @@ def check_advantages(rewards, values, lengths, stopped, r_fail, gamma, lam, rtol
     tol = rtol * np.maximum(np.abs(adv_o), scale)
     assert (e_adv <= tol).all(), (e_adv.max(), np.unravel_index((e_adv - tol).argmax(), e_adv.shape))
     return float((e_adv / np.maximum(scale, 1e-30))[~pad].max()) if (~pad).any() else 0.0
+
+
+def check_advantages_terminal(values, lengths, stopped, term, r_fail, gamma, lam, zero_padding=True, want_returns=True,
+                              rtol=RTOL_F32):
+    """The terminal-reward form against its oracle.  Same tolerances as `check_advantages`; the
+    value targets carry one more fp32 addition.  Without zero padding every position at or
+    beyond a row's length must be either untouched or zero, and nothing else is required of it.
+    """
+    B, T = values.shape
+    FILL = 7.0
+    td = torch.full((B, T), FILL, dtype=torch.float32, device=values.device)
+    adv = torch.full((B, T), FILL, dtype=torch.float32, device=values.device)
+    ret = torch.full((B, T), FILL, dtype=torch.float32, device=values.device) if want_returns else None
+    espo.espo_advantages_terminal(values, lengths, stopped, term, r_fail, gamma, lam, td, adv, returns=ret,
+                                  zero_padding=zero_padding)
+    torch.cuda.synchronize()
+    v_h, L_h, s_h, t_h = values.cpu().numpy(), lengths.cpu().numpy(), stopped.cpu().numpy(), term.cpu().numpy()
+    td_o, adv_o, ret_o = oracle.advantages_terminal(v_h, L_h, s_h, t_h, r_fail, gamma, lam)
+    Lc = np.clip(L_h, 0, T)
+    pad = np.arange(T)[None, :] >= Lc[:, None]
+    # magnitude of the terms: the dense-form oracle's scale on the same rewards spelled out
+    dense = np.zeros((B, T), np.float32)
+    rows = np.nonzero(Lc > 0)[0]
+    dense[rows, Lc[rows] - 1] = t_h[rows]
+    v_clean = np.where(pad, 0, v_h).astype(np.float32)
+    _, _, scale = oracle.advantages(dense, v_clean, L_h, s_h, r_fail, gamma, lam)
+    outs = [("td", td, td_o), ("adv", adv, adv_o)] + ([("returns", ret, ret_o)] if want_returns else [])
+    worst = 0.0
+    for name, g, o in outs:
+        g = g.cpu().numpy().astype(np.float64)
+        if zero_padding:
+            assert (g[pad] == 0).all(), f"{name}: padding must be exactly zero"
+        else:
+            assert ((g[pad] == 0) | (g[pad] == FILL)).all(), f"{name}: padding is neither untouched nor zero"
+        assert np.isfinite(g[~pad]).all()
+        err = np.abs(g - o)[~pad]
+        if name == "td":
+            mag = (np.abs(dense.astype(np.float64)) + abs(r_fail) + np.abs(v_clean.astype(np.float64)) * 2 + 1)[~pad]
+            assert (err <= 4e-7 * mag).all(), (name, err.max())
+        else:
+            tol = (rtol * np.maximum(np.abs(o), scale))[~pad]
+            assert (err <= tol).all(), (name, err.max())
+            if len(err):
+                worst = max(worst, float((err / np.maximum(scale[~pad], 1e-30)).max()))
+    return worst

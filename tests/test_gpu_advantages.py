@@ -105,3 +105,62 @@ def test_many_rows(B):
     r = torch.nan_to_num(r, nan=0.0)
     v = torch.nan_to_num(v, nan=0.0)
     H.check_advantages(r, v, Lt, s, -0.5, 0.97, 0.9)
+
+
+# --------------------------------------------------------------------------- terminal-reward form
+def _terminal_batch(B, T, seed, lengths=None, stop_p=0.4):
+    g = torch.Generator().manual_seed(seed)
+    values = torch.rand(B, T, generator=g) * 2 - 1
+    L = torch.randint(0, T + 1, (B,), generator=g) if lengths is None else torch.as_tensor(lengths)
+    stopped = (torch.rand(B, generator=g) < stop_p).to(torch.uint8)
+    term = torch.randint(0, 2, (B,), generator=g).float() + 0.25 * torch.randn(B, generator=g)
+    values[torch.arange(T)[None, :] >= L.clamp(0, T)[:, None]] = float("nan")   # never to be read
+    return values.cuda(), L.to(torch.int32).cuda(), stopped.cuda(), term.cuda()
+
+
+@pytest.mark.parametrize("T", [1, 3, 4, 7, 8, 9, 64, 511, 512, 2047, 2048, 2049, 4100, 6151, 8192, 9000])
+def test_terminal_form_shapes_and_options(T):
+    _say(f"[case] advantages, terminal form T={T}")
+    L = [0, T, 1, max(T - 1, 0), T // 2, min(T, 2048), min(T, 2049), min(T, 513), T, min(T, 4096), min(T, 4097)]
+    v, Lt, s, term = _terminal_batch(len(L), T, seed=T, lengths=L)
+    for gamma, lam in ((1.0, 0.95), (0.99, 0.9), (1.0, 1.0), (0.9, 0.0)):
+        H.check_advantages_terminal(v, Lt, s, term, -1.0, gamma, lam, zero_padding=True, want_returns=True)
+    H.check_advantages_terminal(v, Lt, s, term, -1.0, 1.0, 0.95, zero_padding=False, want_returns=True)
+    H.check_advantages_terminal(v, Lt, s, term, -0.5, 1.0, 0.95, zero_padding=False, want_returns=False)
+    H.check_advantages_terminal(v, Lt, s, term, -0.5, 1.0, 0.95, zero_padding=True, want_returns=False)
+
+
+def test_terminal_form_equals_dense_form_bit_for_bit():
+    _say("[case] advantages, terminal form vs dense form")
+    B, T = 64, 9001
+    v, L, s, term = _terminal_batch(B, T, seed=77)
+    dense = torch.zeros(B, T, device="cuda")
+    rows = torch.nonzero(L > 0).flatten()
+    dense[rows, (L[rows] - 1).long()] = term[rows]
+    td_d, adv_d = torch.empty_like(dense), torch.empty_like(dense)
+    td_t, adv_t, ret = torch.empty_like(dense), torch.empty_like(dense), torch.empty_like(dense)
+    espo.espo_advantages(dense, v, L, s, -1.0, 0.99, 0.95, td_d, adv_d)
+    espo.espo_advantages_terminal(v, L, s, term, -1.0, 0.99, 0.95, td_t, adv_t, returns=ret)
+    torch.cuda.synchronize()
+    assert torch.equal(td_d, td_t) and torch.equal(adv_d, adv_t)
+    valid = torch.arange(T, device="cuda")[None, :] < L[:, None]
+    assert torch.equal(ret[valid], (adv_t + torch.nan_to_num(v))[valid]) and (ret[~valid] == 0).all()
+    # lambda = 1: the value target is the discounted terminal reward, whatever the critic says
+    espo.espo_advantages_terminal(v, L, s, term, -1.0, 0.999, 1.0, td_t, adv_t, returns=ret)
+    torch.cuda.synchronize()
+    r_end = torch.where(s > 0, torch.full_like(term, -1.0), term).double()
+    dist = (L[:, None] - 1 - torch.arange(T, device="cuda")[None, :]).clamp(min=0).double()
+    want = r_end[:, None] * float(np.float32(0.999)) ** dist
+    err = (ret.double() - want).abs()[valid]
+    assert float(err.max()) < 2e-4, float(err.max())     # ~9000 fp32 steps through values of size 1
+
+
+def test_terminal_form_config5_full_size():
+    _say("[case] config 5 in the terminal form (B=1024, T=16384)")
+    r, v, L, s = W.advantage_batch(device="cuda", poison=True, seed=5)
+    rows = torch.arange(r.shape[0], device="cuda")
+    term = torch.nan_to_num(r[rows, (L - 1).clamp(min=0).long()])    # the survivors' terminal reward in {0, 1}
+    worst = H.check_advantages_terminal(v, L, s, term, -1.0, 1.0, 0.95, zero_padding=False, want_returns=True)
+    _say(f"  worst scaled error {worst:.2e}")
+    worst = H.check_advantages_terminal(v, L, s, term, -1.0, 1.0, 0.95, zero_padding=True, want_returns=False)
+    _say(f"  worst scaled error {worst:.2e}")

@@ -28,7 +28,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
-    assert {"espo_step", "espo_advantages", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
+    assert {"espo_step", "espo_advantages", "espo_advantages_terminal", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
             "espo_debug_set_score_margin_scale", "espo_debug_math_errors", "espo_debug_copy", "espo_batch_stats",
             "espo_batch_stats_workspace_bytes"} <= set(names)
     for n in names:
@@ -62,4 +62,9 @@ def test_argument_checks_need_no_gpu(lib):
     adv = lambda B=1, T=8, g=1.0: lib.espo_advantages(fake, fake, fake, fake, B, T, -1.0, g, 0.95, fake, fake, None)
     assert adv(B=0) == 0 and adv(T=0) == 0
     assert adv(B=-1) == -1 and adv(g=float("inf")) == -1
+    term = lambda B=1, T=8, g=1.0, ret=None, values=fake: lib.espo_advantages_terminal(
+        values, fake, fake, fake, B, T, -1.0, g, 0.95, 1, fake, fake, ret, None)
+    assert term(B=0) == 0 and term(T=0) == 0
+    assert term(B=-1) == -1 and term(g=float("nan")) == -1 and term(values=None) == -1
+    assert term(ret=ctypes.c_void_p(0x1004)) == -2          # misaligned optional output
     assert lib.espo_step_workspace_bytes(512, 152064, 1) == 0
