@@ -1,0 +1,83 @@
+"""Host-side contracts that need no GPU: the benchmark's one-GPU rule, the product path's
+refusal to run without its HIP library, the separation between the oracle and the GPU path,
+and the determinism of the seeded input generators."""
+import ast
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    for argv, env in ((["--gpus", "2"], {}), ([], {"WORLD_SIZE": "4"})):
+        res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), *argv], capture_output=True, text=True,
+                             env={**os.environ, **env}, timeout=120)
+        assert res.returncode != 0
+        assert "one GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_product_path_fails_loudly_without_its_library(monkeypatch, tmp_path):
+    from paper_2605_29860_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "libespo.so"))
+    with pytest.raises(FileNotFoundError, match="no fallback"):
+        binding.load_library()
+    with pytest.raises(FileNotFoundError):
+        binding.espo_step_workspace_bytes(1, 8, torch.float32)
+
+
+def _imports(path):
+    tree = ast.parse(open(path).read())
+    names = set()
+    for node in ast.walk(tree):
+        if isinstance(node, ast.Import):
+            names.update(a.name.split(".")[0] for a in node.names)
+        elif isinstance(node, ast.ImportFrom) and node.level == 0 and node.module:
+            names.add(node.module.split(".")[0])
+    return names
+
+
+def test_oracle_and_gpu_path_do_not_import_each_other():
+    pkg = os.path.join(ROOT, "paper_2605_29860_amd")
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            assert "oracle" not in _imports(os.path.join(pkg, f)), f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            assert "paper_2605_29860_amd" not in _imports(os.path.join(ROOT, "oracle", f)), f
+    # no shared sources either: the GPU sources include nothing from oracle/ and the oracle nothing from csrc/
+    for d, banned in ((os.path.join(pkg, "csrc"), "oracle"), (os.path.join(ROOT, "oracle"), "csrc")):
+        for f in os.listdir(d):
+            if f.endswith((".hip", ".h", ".c")):
+                for line in open(os.path.join(d, f)):
+                    if line.lstrip().startswith("#include"):
+                        assert banned not in line, (f, line)
+    # nothing that ships reads the working folder or the paper's text at run time
+    for f in ("bench.py", "__graft_entry__.py"):
+        text = open(os.path.join(ROOT, f)).read()
+        assert "_work/" not in text and '"_work"' not in text and "/root/reference" not in text
+
+
+def test_input_generators_are_seeded_and_hold_no_method_arithmetic():
+    from paper_2605_29860_amd import workloads as W
+    a = W.ZipfLogits(V=4096, seed=5).rows(3, step=2)
+    b = W.ZipfLogits(V=4096, seed=5).rows(3, step=2)
+    c = W.ZipfLogits(V=4096, seed=6).rows(3, step=2)
+    assert torch.equal(a, b) and not torch.equal(a, c) and a.dtype == torch.bfloat16
+    r1 = W.advantage_batch(B=8, T=64, len_lo=4, seed=1)
+    r2 = W.advantage_batch(B=8, T=64, len_lo=4, seed=1)
+    assert all(torch.equal(x, y) for x, y in zip(r1, r2))
+    rewards, values, lengths, stopped = r1
+    last = rewards[torch.arange(8), (lengths - 1).long()]
+    assert ((rewards != 0).sum(1) <= 1).all() and set(last.tolist()) <= {0.0, 1.0}      # terminal reward only
+    assert (last[stopped > 0] == 0).all() and float(values.abs().max()) <= 1.0
+    g1 = W.regret_batch(4, 32, seed=3)
+    g2 = W.regret_batch(4, 32, seed=3)
+    assert all(torch.equal(x, y) for x, y in zip(g1, g2))
+    bits = W.to_host_bits(a)
+    assert bits.dtype == np.uint16 and bits.shape == (3, 4096)
