@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="also launch this many plain 1 GiB copies (known traffic, for counter calibration; untimed)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
+    ap.add_argument("--live-curve", action="store_true",
+                    help="also run the heavy-termination rollout (B=1024, 256 steps, 60%% of rows planted to stop) "
+                         "and report the launch duration against the number of live rows")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; rows shard over GPUs without any exchange, "
@@ -215,6 +218,41 @@ def main() -> int:
     bs_bytes = float(np.mean([int(bs_sets[i % nbuf][1].sum()) * 4 + 512 * 5 for i in range(args.adv_reps)]))
     bs_res = espo.read_batch_result(bs_out)
 
+    # ------------------------------------------------------------------ optional: launch duration vs live rows (B=1024)
+    curve = None
+    if args.live_curve:
+        Bc, Sc, seed_c = 1024, 256, 4
+        plant_c = W.RegretPlant.make(Bc, V_STEP, 0.6, 12, 190, seed_c)
+        gen_c = W.ZipfLogits(V=V_STEP, seed=seed_c, device=dev)
+        logits_c = torch.empty(Sc, Bc, V_STEP, dtype=torch.bfloat16, device=dev)   # 80 GB, all steps resident
+        values_c = torch.empty(Sc, Bc, dtype=torch.float32, device=dev)
+        for t in range(Sc):                                                # generation: untimed
+            gen_c.rows(Bc, step=t, out=logits_c[t])
+            plant_c.apply(logits_c[t], t)
+            values_c[t] = W.step_values(Bc, seed_c, t, 0.2, 1.0, device=dev)
+        torch.cuda.synchronize()
+        zc_, ac_, sc_ = W.initial_state(Bc, device=dev)
+        tok_c = torch.empty(Bc, dtype=torch.int32, device=dev)
+        reg_c = torch.empty(Bc, dtype=torch.float32, device=dev)
+        cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(Sc)]
+        for t in range(Sc):
+            cev[t][0].record()
+            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, None)
+            cev[t][1].record()
+        torch.cuda.synchronize()
+        ss_c = sc_.cpu().numpy()
+        live_c = ((ss_c[None, :] < 0) | (ss_c[None, :] >= np.arange(Sc)[:, None])).sum(1)   # rows decoded at each step
+        cus = np.array([a.elapsed_time(b) * 1e3 for a, b in cev])
+        curve = []
+        for lo in range(400, 1025, 104):                                   # six bins of live rows
+            sel = (live_c > lo - 104) & (live_c <= lo)
+            if sel.any():
+                rows_m, us_m = float(live_c[sel].mean()), float(cus[sel].mean())
+                curve.append({"live_rows": rows_m, "steps": int(sel.sum()), "us_per_launch_event_pair": us_m,
+                              "rows_per_s": rows_m / us_m * 1e6,
+                              "gbs": (rows_m * (V_STEP * 2 + STEP_SCALAR_BYTES) + (Bc - rows_m)) / us_m / 1e3})
+        del logits_c
+
     # ------------------------------------------------------------------ CPU oracle on a bounded sample (context only)
     cpu = None
     if not args.no_cpu_baseline:
@@ -226,6 +264,8 @@ def main() -> int:
         while cpu_s < args.cpu_seconds and cpu_steps < total:      # the first steps of the same trajectory
             bits = W.to_host_bits(logits[cpu_steps])               # copy to the host: untimed
             vals_h = values[cpu_steps].cpu().numpy()
+            if cpu_steps == 0:
+                cpu_first_bits, cpu_first_vals = bits, vals_h
             cpu_rows += int(ac.sum())
             tc = time.perf_counter()
             oracle.step(bits, tau, seed, cpu_steps, vals_h, op, zc, ac, sc)
@@ -235,10 +275,24 @@ def main() -> int:
         tc = time.perf_counter()
         oracle.advantages(r, v, L, s, -1.0, 1.0, 0.95, want_scale=False)
         cpu_adv_s = time.perf_counter() - tc
+        # the same oracle on one thread, on a slice of the first step (it is deliberately plain code)
+        nthreads = oracle.num_threads()
+        oracle.set_threads(1)
+        n1 = 96
+        z1, a1, s1 = (np.zeros(n1, np.float32), np.ones(n1, np.uint8), np.full(n1, -1, np.int32))
+        tc = time.perf_counter()
+        oracle.step(np.ascontiguousarray(cpu_first_bits[:n1]), tau, seed, 0, cpu_first_vals[:n1], op, z1, a1, s1)
+        cpu_1t_rows = n1 / (time.perf_counter() - tc)
+        tc = time.perf_counter()
+        oracle.advantages(r[:64], v[:64], L[:64], s[:64], -1.0, 1.0, 0.95, want_scale=False)
+        cpu_1t_adv = float(L[:64].clip(0, T_ADV).sum() / (time.perf_counter() - tc))
+        oracle.set_threads(nthreads)
         cpu = {"value": cpu_rows / cpu_s, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"the first {cpu_steps} steps of the same workload ({cpu_rows} live rows x 152064 bf16 "
                          f"logits), {cpu_s:.1f} s of oracle time",
-               "advantages_tokens_per_s": float(L.clip(0, T_ADV).sum() / cpu_adv_s)}
+               "advantages_tokens_per_s": float(L.clip(0, T_ADV).sum() / cpu_adv_s),
+               "one_thread": {"rows_per_s": cpu_1t_rows, "advantages_tokens_per_s": cpu_1t_adv,
+                              "sample": f"{n1} rows of the first step; 64 rows of the advantage batch"}}
 
     out = {
         "metric": "logit rows/sec & HBM GB/s (fused step, V=152064 bf16); advantages tokens/sec",
@@ -276,6 +330,10 @@ def main() -> int:
                         "mu_g": bs_res["mu_g"], "var_g": bs_res["var_g"], "beta": bs_res["beta"]},
         "cpu_baseline": cpu,
     }
+    if curve is not None:
+        out["live_curve"] = {"workload": "heavy termination: B=1024, V=152064 bf16, 256 steps, 60% of rows planted to stop in "
+                                         "[16,200]; every step's logits resident, one event pair per launch",
+                             "bins": curve}
     print(json.dumps(out))
     return 0
 
