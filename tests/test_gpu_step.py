@@ -533,3 +533,63 @@ def test_two_streams_do_not_interfere():
         a, b = serial[i].host(), inter[i].host()
         for k in a:
             np.testing.assert_array_equal(a[k].view(np.uint8), b[k].view(np.uint8), err_msg=f"stream {i} {k}")
+
+
+# --------------------------------------------------------------------------- HIP graph capture
+def test_steps_captured_in_a_graph_replay_like_eager_launches():
+    _say("[case] graph capture and replay")
+    # The library allocates nothing and synchronises nothing, so its launches can be captured.
+    # A graph of three consecutive steps plus the advantage pass is replayed several times, with
+    # eager work and synchronisations in between, from a restored state; every replay must give
+    # the bits of the eager run.
+    B, V, T = 48, 30000, 700
+    gen = W.ZipfLogits(V=V, seed=21, device="cuda")
+    logits = [gen.rows(B, step=s) for s in range(3)]
+    vals = [W.step_values(B, 21, s, 0.2, 1.0, device="cuda") for s in range(3)]
+    gp, _ = H.params_pair(mu_g=1.0, var_g=2.0, beta=0.6)
+    r, v, L, stp = W.advantage_batch(B=B, T=T, len_lo=1, seed=8, device="cuda")
+    z0 = torch.rand(B, device="cuda") - 0.5
+
+    def fresh():
+        st = H.GpuState(B, z=z0)
+        st.out = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(3)]
+        st.td, st.adv = torch.empty(B, T, device="cuda"), torch.empty(B, T, device="cuda")
+        return st
+
+    def work(st):
+        for s in range(3):
+            espo.espo_step(logits[s], 0.6, 77, s, vals[s], gp, st.z, st.alive, st.stop_step, st.out[s], st.regret,
+                           st.logprob, entropy=st.entropy)
+        espo.espo_advantages(r, v, L, stp, -1.0, 1.0, 0.95, st.td, st.adv)
+
+    eager = fresh()
+    work(eager)
+    torch.cuda.synchronize()
+    want = {k: getattr(eager, k).clone() for k in ("z", "alive", "stop_step", "regret", "logprob", "entropy", "td", "adv")}
+    want_tok = [t.clone() for t in eager.out]
+    assert int(want["alive"].sum()) < B                      # some rows stop inside the graph
+
+    st = fresh()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        work(st)                                             # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        work(st)
+    for replay in range(4):
+        st.z.copy_(z0); st.alive.fill_(1); st.stop_step.fill_(-1)       # restore the state the graph starts from
+        st.td.fill_(7.0); st.adv.fill_(7.0); st.regret.fill_(-7.0)
+        for t in st.out:
+            t.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, w in want.items():
+            assert torch.equal(getattr(st, k), w), (replay, k)
+        for a, b in zip(st.out, want_tok):
+            assert torch.equal(a, b), replay
+        H.gpu_step(logits[0], 0.6, 5, replay, vals[0], gp, fresh())      # unrelated eager work between replays
+        torch.cuda.synchronize()
