@@ -9,9 +9,11 @@
  * the failure reward placed at the stop step (Section 4.4, Eq. failure_reward,
  * Eq. gae).
  *
- * Three operations are exported:
+ * Four operations are exported:
  *   espo_step         one decode step for a batch of trajectories (Algorithm 1 body)
  *   espo_advantages   TD errors + GAE over the truncated trajectories (Section 3, 4.4)
+ *   espo_advantages_terminal  the same for the rewards Algorithm 1 produces (zero until
+ *                     the last step), optionally with the critic's value targets
  *   espo_batch_stats  update of the frozen statistics and of beta between batches (Section 4.2, 4.3)
  *
  * Conventions for every entry point
@@ -25,6 +27,10 @@
  *     has been enqueued.
  *   - No global mutable state: calls from several host threads on different
  *     streams are safe as long as they do not share output or workspace buffers.
+ *   - A call consists of kernel launches only (no allocation, no copy, no memset,
+ *     no synchronisation), so it may be recorded while its stream is being captured
+ *     into a HIP graph; scalar arguments (seed, step, parameters) are then fixed in
+ *     the recorded nodes.
  */
 #ifndef ESPO_H_
 #define ESPO_H_
