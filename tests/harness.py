@@ -141,10 +141,11 @@ def check_advantages(rewards, values, lengths, stopped, r_fail, gamma, lam, rtol
     pad = np.arange(T)[None, :] >= np.clip(L_h, 0, T)[:, None]
     assert (td_g[pad] == 0).all() and (adv_g[pad] == 0).all(), "padding must be exactly zero"
     assert np.isfinite(td_g).all() and np.isfinite(adv_g).all()
-    # delta_t is three fp32 operations on exact inputs
+    # delta_t is three fp32 operations on exact inputs: judged against |r_t| + |V_t| + |V_{t+1}|
     e_td = np.abs(td_g - td_o)
-    mag = np.abs(r_h.astype(np.float64)) + np.abs(v_h.astype(np.float64)) * 2 + 1
-    mag[pad] = 1
+    v_abs = np.where(pad, 0.0, np.abs(v_h.astype(np.float64)))
+    v_next = np.concatenate([v_abs[:, 1:], np.zeros((B, 1))], axis=1)
+    mag = np.where(pad, 0.0, np.abs(r_h.astype(np.float64))) + abs(r_fail) + v_abs + v_next + 1
     assert (e_td <= 4e-7 * mag).all(), e_td.max()
     e_adv = np.abs(adv_g - adv_o)
     tol = rtol * np.maximum(np.abs(adv_o), scale)
@@ -187,7 +188,9 @@ def check_advantages_terminal(values, lengths, stopped, term, r_fail, gamma, lam
         assert np.isfinite(g[~pad]).all()
         err = np.abs(g - o)[~pad]
         if name == "td":
-            mag = (np.abs(dense.astype(np.float64)) + abs(r_fail) + np.abs(v_clean.astype(np.float64)) * 2 + 1)[~pad]
+            v_abs = np.abs(v_clean.astype(np.float64))
+            v_next = np.concatenate([v_abs[:, 1:], np.zeros((B, 1))], axis=1)
+            mag = (np.abs(dense.astype(np.float64)) + abs(r_fail) + v_abs + v_next + 1)[~pad]
             assert (err <= 4e-7 * mag).all(), (name, err.max())
         else:
             tol = (rtol * np.maximum(np.abs(o), scale))[~pad]

@@ -164,3 +164,32 @@ def test_terminal_form_config5_full_size():
     _say(f"  worst scaled error {worst:.2e}")
     worst = H.check_advantages_terminal(v, L, s, term, -1.0, 1.0, 0.95, zero_padding=True, want_returns=False)
     _say(f"  worst scaled error {worst:.2e}")
+
+
+def test_seeded_sweep_of_both_forms():
+    _say("[case] advantages, seeded sweep")
+    rng = np.random.default_rng(4242)
+    worst = 0.0
+    for case in range(150):
+        T = int(rng.choice([rng.integers(1, 64), rng.integers(64, 5000), rng.integers(5000, 20000)]))
+        B = int(rng.integers(1, 12))
+        g = torch.Generator().manual_seed(7000 + case)
+        v = (torch.rand(B, T, generator=g) * 2 - 1) * float(rng.choice([1.0, 30.0]))
+        r = torch.randn(B, T, generator=g)
+        L = torch.randint(0, T + 1, (B,), generator=g)
+        pad = torch.arange(T)[None, :] >= L[:, None]
+        v[pad] = float("nan")
+        r[pad] = float("nan")
+        s = (torch.rand(B, generator=g) < 0.4).to(torch.uint8)
+        term = torch.randn(B, generator=g)
+        gamma, lam = float(rng.choice([1.0, 0.99, 0.9])), float(rng.choice([0.95, 1.0, 0.0, 0.5]))
+        r_fail = float(rng.choice([-1.0, -0.25, 0.0]))
+        args = (v.cuda(), L.to(torch.int32).cuda(), s.cuda())
+        try:
+            worst = max(worst, H.check_advantages(r.cuda(), *args, r_fail, gamma, lam))
+            worst = max(worst, H.check_advantages_terminal(*args, term.cuda(), r_fail, gamma, lam,
+                                                           zero_padding=bool(rng.random() < 0.5),
+                                                           want_returns=bool(rng.random() < 0.5)))
+        except AssertionError as err:
+            raise AssertionError(f"case {case}: T={T} B={B} gamma={gamma} lambda={lam} r_fail={r_fail}: {err}")
+    _say(f"  worst scaled error {worst:.2e}")

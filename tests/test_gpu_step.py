@@ -421,19 +421,23 @@ def test_simulate_mode_keeps_rows_alive_and_records_first_stop():
 # --------------------------------------------------------------------------- seeded sweep over shapes, structures and search paths
 def test_seeded_sweep_of_shapes_structures_and_margins():
     _say("[case] seeded sweep")
+    # Random shapes, logit structures, temperatures, margin scales (1 = production; larger ones send
+    # more rows through the long-list and the double-precision paths), stop modes, simulate mode,
+    # end-of-sequence ids, partly dead batches, with and without the entropy output.
     rng = np.random.default_rng(2024)
-    paths = {1.0: 0, 3e4: 0, 1e12: 0}
-    for case in range(48):
-        V = int(rng.choice([rng.integers(1, 600), rng.integers(600, 9000), rng.integers(9000, 70000)]))
+    paths, stats = {1.0: 0, 3e4: 0, 1e12: 0}, {}
+    for case in range(400):
+        V = int(rng.choice([rng.integers(1, 600), rng.integers(600, 9000), rng.integers(9000, 70000),
+                            rng.integers(70000, 200000)], p=[0.3, 0.3, 0.3, 0.1]))
         B = int(rng.integers(1, 7))
         dtype = torch.bfloat16 if rng.random() < 0.5 else torch.float32
-        tau = float(rng.choice([0.3, 0.6, 1.0, 2.5]))
-        kind = rng.choice(["gauss", "flat", "plateau", "masked", "peaked"])
+        tau = float(rng.choice([0.05, 0.3, 0.6, 1.0, 2.5, 8.0]))
+        kind = str(rng.choice(["gauss", "flat", "plateau", "masked", "peaked", "twopeak", "ramp"]))
         stride = ((V + 7) // 8) * 8 + int(rng.choice([0, 8, 64]))
         g = torch.Generator().manual_seed(1000 + case)
         x = torch.randn(B, stride, generator=g) * float(rng.choice([0.5, 3.0, 12.0]))
         if kind == "flat":
-            x[:] = 1.5
+            x[:] = float(rng.choice([1.5, -3.0, 0.0]))
         elif kind == "plateau":                               # half of the vocabulary tied just below one peak
             x[:, 0::2] = 20.0
             x[:, min(V - 1, 7)] = 22.0
@@ -442,22 +446,32 @@ def test_seeded_sweep_of_shapes_structures_and_margins():
             x[:, V // 2] = 0.25                                # at least one finite entry
         elif kind == "peaked":
             x[:, V - 1] = 40.0
+        elif kind == "twopeak":                               # two equal modes, first and last index
+            x[:, 0] = 30.0
+            x[:, V - 1] = 30.0
+        elif kind == "ramp":
+            x[:] = torch.arange(stride).float()[None, :] * (10.0 / V)
         x[:, V:] = 1e4                                         # beyond V must never matter
         logits = x.to(dtype).cuda()
-        scale = float(rng.choice([1.0, 1.0, 3e4, 1e12]))
+        scale = float(rng.choice([1.0, 1.0, 1.0, 3e4, 1e12]))
         paths[scale] += 1
-        gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=float(rng.choice([0.5, 7.0])))
-        st = H.GpuState(B, z=torch.rand(B, generator=g) * 2 - 1)
+        mode, simulate = int(rng.choice([0, 0, 0, 1, 2, 3])), int(rng.random() < 0.15)
+        gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=float(rng.choice([0.5, 7.0])), stop_mode=mode,
+                               stop_threshold=float(rng.choice([0.05, 0.3, 1.0])), simulate=simulate,
+                               eos_id=int(rng.choice([-1, -1, 0, V - 1])))
+        st = H.GpuState(B, z=torch.rand(B, generator=g) * 2 - 1, alive=(torch.rand(B, generator=g) < 0.85).to(torch.uint8))
         vals = torch.rand(B, generator=g).cuda()
+        entropy = bool(rng.random() < 0.4)
         espo.espo_debug_set_score_margin_scale(scale)
         try:
             for step in range(2):
-                H.compare_step(logits, tau, 900 + case, step, vals, gp, op, st, V=V)
+                H.compare_step(logits, tau, 900 + case, step, vals, gp, op, st, V=V, stats=stats, entropy=entropy)
         except AssertionError as err:
-            raise AssertionError(f"case {case}: V={V} B={B} {dtype} tau={tau} {kind} scale={scale}: {err}")
+            raise AssertionError(f"case {case}: V={V} B={B} {dtype} tau={tau} {kind} scale={scale} mode={mode} "
+                                 f"simulate={simulate} entropy={entropy}: {err}")
         finally:
             espo.espo_debug_set_score_margin_scale(1.0)
-    _say(f"  cases per margin scale: {paths}")
+    _say(f"  cases per margin scale: {paths}; {stats}")
 
 
 # --------------------------------------------------------------------------- entropy output
