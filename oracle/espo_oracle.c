@@ -18,6 +18,9 @@
  *                      Optional output: the entropy of that distribution (the quantity
  *                      tracked in the section on policy entropy and diversity, Fig. 2b),
  *                      by its definition.
+ *                      Optional filters on the draw: top-p (nucleus) as in the evaluation
+ *                      set-up of Section 5, and top-k; the kept set by its definition over a
+ *                      library sort, the draw over the kept set with the same stream.
  *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
  *                      Section 4.4 (failure reward at the stop step, no bootstrap).
  *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
@@ -31,7 +34,9 @@
  * Pins (tests marked "not gpu"): hand values of the regret on 3-token rows, closed
  * forms of the smoothed state, stop rule never/always firing, softmax frequencies of
  * the sampler on tiny vocabularies, moments of the Gumbel variates, closed forms of the
- * entropy (uniform, two-token, masked rows) and a library routine on random rows, GAE against the
+ * entropy (uniform, two-token, masked rows) and a library routine on random rows, the kept
+ * set of top-p / top-k against its O(V^2) definition and a sorted cumulative sum, frequencies of
+ * filtered draws against the renormalised distribution, GAE against the
  * explicit double sum and against telescoping identities.
  * Parity unpinned by the paper: the identity of the sampled token on a large
  * vocabulary (the paper fixes no random stream); it is pinned by the distribution
@@ -45,6 +50,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
 #include <omp.h>
@@ -57,6 +63,8 @@ typedef struct {
   int32_t stop_mode;      /* 0 full rule; 1 value only; 2 regret only; 3 random (Section 6, variants D, E, F) */
   float stop_threshold;   /* the fixed threshold of variants D and E; the per-step stop probability of F      */
   int32_t simulate;       /* record the first stop step but keep decoding ("ESPO/Original", Section 7)        */
+  float top_p;            /* nucleus sampling, as in the evaluation set-up of Section 5 (p = 0.7 there); 0 or >= 1: off */
+  int32_t top_k;          /* keep the k largest logits; <= 0: off (the paper's evaluation leaves it off)       */
 } oracle_params;
 
 /* ------------------------------------------------------------------ Philox4x32-10 */
@@ -225,6 +233,44 @@ void oracle_set_threads(int n) {
 }
 
 /*
+ * The kept set of filtered sampling, as the smallest logit it contains.
+ *   top-p: the tokens of largest probability whose mass reaches p; tokens of equal logit stay
+ *          together, so v is kept iff the mass of all tokens with a strictly larger logit is
+ *          below p (the most probable token is always kept);
+ *   top-k: v is kept iff fewer than k tokens have a strictly larger logit.
+ * `ys` are the row's V tempered logits, `S` the softmax sum relative to y_max.  Returns the
+ * smallest kept y and the number of kept tokens.
+ */
+static int cmp_desc(const void* a, const void* b) {
+  const double x = *(const double*)a, y = *(const double*)b;
+  return (x < y) - (x > y);
+}
+
+static double kept_threshold(const double* ys, int64_t V, double y_max, double S, double top_p, int64_t top_k,
+                             int64_t* kept) {
+  double* sorted = (double*)malloc((size_t)V * sizeof(double));
+  memcpy(sorted, ys, (size_t)V * sizeof(double));
+  qsort(sorted, (size_t)V, sizeof(double), cmp_desc);      /* library sort, descending */
+  double mass_above = 0.0, thr = sorted[0];
+  int64_t count_above = 0, n = 0, i = 0;
+  while (i < V) {                                          /* groups of equal logit, largest first */
+    int64_t j = i;
+    double group = 0.0;
+    while (j < V && sorted[j] == sorted[i]) { group += exp(sorted[j] - y_max); ++j; }
+    const int keep = top_k > 0 ? (count_above < top_k) : (mass_above < top_p * S);
+    if (!keep) break;
+    thr = sorted[i];
+    n = j;
+    mass_above += group;
+    count_above = j;
+    i = j;
+  }
+  free(sorted);
+  *kept = n;
+  return thr;
+}
+
+/*
  * One decode step for B rows.  Arrays are host memory with the same meaning and
  * layout as the GPU entry point's.  Extra, optional (NULL-able) arguments:
  *   forced_tokens[b] >= 0  use that token instead of the draw (near-tie protocol);
@@ -232,6 +278,7 @@ void oracle_set_threads(int n) {
  *                          the draw and the index of the runner-up;
  *   sum_exp                S = sum_v exp(y_v - y_max);
  *   row_max                the row maximum m;
+ *   kept                   number of tokens the top-p / top-k filter keeps (V without filter);
  *   entropy                H = -sum_v pi_v ln pi_v of the distribution the token is drawn
  *                          from, pi_v = exp(y_v - y_max) / S (the policy entropy tracked in
  *                          the section on policy entropy and diversity, Fig. 2b); indices
@@ -245,10 +292,12 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
                 int32_t* tokens, float* regret, float* logprob,
                 const int32_t* forced_tokens,
                 double* best_score, double* second_score, int32_t* second_token,
-                double* sum_exp, float* row_max, float* entropy) {
+                double* sum_exp, float* row_max, float* entropy, int64_t* kept) {
   if (!logits || !values || !p || !z || !alive || !stop_step || !tokens || !regret) return -1;
   if (B < 0 || V < 1 || row_stride < V || !(temperature > 0.0f) || !isfinite(temperature)) return -1;
   if (dtype != 0 && dtype != 1) return -1;
+  if (!(p->top_p >= 0.0f && p->top_p <= 1.0f) || p->top_k < 0) return -1;
+  if (p->top_p > 0.0f && p->top_p < 1.0f && p->top_k > 0) return -1;   /* one filter at a time */
 
   const float inv_tau = 1.0f / temperature;              /* one fp32 division        */
   const float rsd = 1.0f / sqrtf(p->var_g + p->delta);   /* 1/sqrt(sigma_g^2+delta)  */
@@ -266,6 +315,7 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
       if (sum_exp) sum_exp[b] = 0.0;
       if (row_max) row_max[b] = 0.0f;
       if (entropy) entropy[b] = 0.0f;
+      if (kept) kept[b] = 0;
       continue;
     }
     const int64_t base = b * row_stride;
@@ -277,6 +327,21 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
       if (x > m) m = x;
     }
     const double y_max = (double)m * (double)inv_tau;
+
+    /* filtered sampling (the evaluation set-up's top-p; top-k): the kept set is {v : y_v >= y_keep} */
+    const int filter_p = p->top_p > 0.0f && p->top_p < 1.0f, filter_k = p->top_k > 0;
+    double y_keep = -INFINITY;
+    int64_t n_kept = V;
+    if ((filter_p || filter_k) && m > -INFINITY) {
+      double* ys = (double*)malloc((size_t)V * sizeof(double));
+      double S0 = 0.0;
+      for (int64_t v = 0; v < V; ++v) {
+        ys[v] = (double)load_logit(logits, dtype, base + v) * (double)inv_tau;
+        S0 += exp(ys[v] - y_max);
+      }
+      y_keep = kept_threshold(ys, V, y_max, S0, (double)p->top_p, filter_k ? p->top_k : 0, &n_kept);
+      free(ys);
+    }
 
     /* softmax normaliser and Gumbel-max draw, in index order */
     double S = 0.0;
@@ -294,6 +359,7 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
       double y = (double)x * (double)inv_tau;            /* tempered logit           */
       S += exp(y - y_max);
       double s = y + gumbel_in_block(seed, b, step, v, first_q, M_q, pos_q);
+      if (y < y_keep) continue;                          /* filtered out: cannot be drawn */
       if (s > s1) {                                      /* strict: lowest index wins */
         s2 = s1; a2 = a1;
         s1 = s; a1 = v;
@@ -325,6 +391,7 @@ int oracle_step(const void* logits, int dtype, int64_t B, int64_t V, int64_t row
     if (second_token) second_token[b] = (int32_t)a2;
     if (sum_exp) sum_exp[b] = S;
     if (row_max) row_max[b] = m;
+    if (kept) kept[b] = n_kept;
     if (entropy) {                                       /* the definition, term by term */
       double H = 0.0;
       for (int64_t v = 0; v < V; ++v) {

@@ -32,7 +32,8 @@ class _Params(C.Structure):
     _fields_ = [("mu_g", C.c_float), ("var_g", C.c_float), ("delta", C.c_float),
                 ("clip_c", C.c_float), ("alpha_s", C.c_float), ("beta", C.c_float),
                 ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32),
-                ("stop_mode", C.c_int32), ("stop_threshold", C.c_float), ("simulate", C.c_int32)]
+                ("stop_mode", C.c_int32), ("stop_threshold", C.c_float), ("simulate", C.c_int32),
+                ("top_p", C.c_float), ("top_k", C.c_int32)]
 
 
 @dataclass
@@ -50,11 +51,13 @@ class OracleParams:
     stop_mode: int = 0          # 0 Eq. stop_rule; 1 value only; 2 regret only; 3 random (ablations D, E, F)
     stop_threshold: float = 0.0
     simulate: int = 0           # record the first stop step, keep decoding
+    top_p: float = 0.0          # nucleus sampling (0 or >= 1: off)
+    top_k: int = 0              # keep the k largest logits (<= 0: off)
 
     def c_struct(self) -> _Params:
         return _Params(self.mu_g, self.var_g, self.delta, self.clip_c, self.alpha_s, self.beta,
                        self.eps, int(self.stop_enabled), int(self.eos_id), int(self.stop_mode),
-                       float(self.stop_threshold), int(self.simulate))
+                       float(self.stop_threshold), int(self.simulate), float(self.top_p), int(self.top_k))
 
 
 _lib = None
@@ -68,7 +71,7 @@ def _load():
         vp, i64, i32, u64, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64, C.c_float
         lib.oracle_step.restype = C.c_int
         lib.oracle_step.argtypes = [vp, C.c_int, i64, i64, i64, f32, u64, i32, vp, C.POINTER(_Params),
-                                    vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+                                    vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         lib.oracle_state_update.restype = C.c_int
         lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), u64, i32, vp, vp, vp]
         lib.oracle_advantages.restype = C.c_int
@@ -185,6 +188,7 @@ def step(logits: np.ndarray, temperature: float, seed: int, step_: int, values: 
         "second_token": np.empty(B, np.int32), "sum_exp": np.empty(B, np.float64),
         "row_max": np.empty(B, np.float32),
         "entropy": np.empty(B, np.float32) if want_entropy else None,
+        "kept": np.empty(B, np.int64),
     }
     ps = params.c_struct()
     rc = lib.oracle_step(_ptr(logits), dt, B, V, stride, float(temperature), int(seed), int(step_),
@@ -192,7 +196,7 @@ def step(logits: np.ndarray, temperature: float, seed: int, step_: int, values: 
                          _ptr(out["tokens"]), _ptr(out["regret"]), _ptr(out["logprob"]),
                          _ptr(forced_tokens), _ptr(out["best_score"]), _ptr(out["second_score"]),
                          _ptr(out["second_token"]), _ptr(out["sum_exp"]), _ptr(out["row_max"]),
-                         _ptr(out["entropy"]))
+                         _ptr(out["entropy"]), _ptr(out["kept"]))
     if rc != 0:
         raise ValueError("oracle_step: invalid arguments")
     return out

@@ -702,3 +702,97 @@ def test_entropy_matches_library_and_identities(oracle):
                       z, alive, ss, V=V, want_entropy=True)
     assert (out["entropy"][::2] == 0).all()
     np.testing.assert_allclose(out["entropy"][1::2], H[1::2], rtol=1e-6)
+
+
+# ------------------------------------------------------------------ filtered sampling (top-p, top-k)
+def _filtered(oracle, logits, tau, seed=5, step=0, **kw):
+    B = logits.shape[0]
+    z, alive, ss = _state(B)
+    return oracle.step(logits, tau, seed, step, np.zeros(B, np.float32), _params(oracle, stop_enabled=0, **kw), z, alive, ss)
+
+
+def _kept_by_definition(y, p=None, k=None):
+    """v is kept iff the mass (count) of strictly larger logits is below p (k): O(V^2), no sort."""
+    pi = special.softmax(y)
+    keep = np.zeros(len(y), bool)
+    for v in range(len(y)):
+        above = y > y[v]
+        keep[v] = (pi[above].sum() < p) if p is not None else (above.sum() < k)
+    return keep
+
+
+def test_kept_set_matches_its_definition_and_a_sorted_cumsum(oracle):
+    rng = np.random.default_rng(41)
+    for trial in range(30):
+        V = int(rng.integers(2, 90))
+        tau = float(rng.choice([0.6, 1.0, 2.0]))
+        x = rng.normal(0, 2.5, (1, V)).astype(np.float32)
+        if trial % 3 == 0:
+            x = np.round(x * 2) / 2                           # many exact ties
+        y = x[0].astype(np.float64) * np.float64(np.float32(1.0) / np.float32(tau))
+        for p in (0.05, 0.5, 0.7, 0.95):
+            out = _filtered(oracle, x, tau, top_p=p)
+            keep = _kept_by_definition(y, p=np.float64(np.float32(p)))
+            assert out["kept"][0] == keep.sum() and keep[out["tokens"][0]]
+            # the same set from a library sort: shortest prefix of the sorted probabilities that reaches p,
+            # extended over the ties of its last element
+            order = np.argsort(-y, kind="stable")
+            cum = np.cumsum(special.softmax(y)[order])
+            n = int(np.searchsorted(cum, np.float64(np.float32(p)), side="left")) + 1
+            n = min(n, V)
+            thr = y[order[n - 1]]
+            assert (y >= thr).sum() == keep.sum() or abs(cum[n - 1] - p) < 1e-12
+        for k in (1, 2, 5, V, V + 3):
+            out = _filtered(oracle, x, tau, top_k=k)
+            keep = _kept_by_definition(y, k=k)
+            assert out["kept"][0] == keep.sum() and keep[out["tokens"][0]]
+            assert keep.sum() >= min(k, V)                    # ties at the k-th value are all kept
+
+
+def test_filters_that_keep_everything_or_only_the_mode(oracle):
+    rng = np.random.default_rng(42)
+    B, V = 32, 300
+    x = rng.normal(0, 3, (B, V)).astype(np.float32)
+    plain = _filtered(oracle, x, 0.8)
+    assert (plain["kept"] == V).all()
+    for kw in (dict(top_p=1.0), dict(top_p=0.0), dict(top_k=V), dict(top_k=0), dict(top_k=10 * V)):
+        out = _filtered(oracle, x, 0.8, **kw)
+        np.testing.assert_array_equal(out["tokens"], plain["tokens"])
+        np.testing.assert_array_equal(out["regret"], plain["regret"])
+    mode = x.argmax(1)
+    for kw in (dict(top_k=1), dict(top_p=1e-6)):
+        out = _filtered(oracle, x, 0.8, **kw)
+        np.testing.assert_array_equal(out["tokens"], mode)
+        assert (out["regret"] == 0).all() and (out["kept"] == 1).all()
+    # tied modes are kept together and the draw chooses among them
+    x[:, 7] = x[:, 99] = 50.0
+    toks = np.concatenate([_filtered(oracle, x, 0.8, seed=s, top_k=1)["tokens"] for s in range(8)])
+    assert set(toks.tolist()) == {7, 99}
+    # the statistics of the unfiltered distribution are not touched by the filter
+    a, b = _filtered(oracle, x, 0.8, top_p=0.7), _filtered(oracle, x, 0.8)
+    np.testing.assert_array_equal(a["sum_exp"], b["sum_exp"])
+    np.testing.assert_array_equal(a["row_max"], b["row_max"])
+    with pytest.raises(ValueError):
+        _filtered(oracle, x, 0.8, top_p=0.7, top_k=5)
+    with pytest.raises(ValueError):
+        _filtered(oracle, x, 0.8, top_p=1.5)
+
+
+def test_filtered_draws_follow_the_renormalised_distribution(oracle):
+    V, tau, p = 12, 1.0, 0.7
+    x = np.array([[2.0, 1.5, 1.5, 0.5, 0.0, -0.5, 3.0, -1.0, 1.0, 0.2, -2.0, 0.8]], np.float32)
+    y = x[0].astype(np.float64)
+    keep = _kept_by_definition(y, p=np.float64(np.float32(p)))
+    assert 1 < keep.sum() < V
+    n = 6000
+    rows = np.repeat(x, n, axis=0)
+    z, alive, ss = _state(n)
+    out = oracle.step(rows, tau, 123, 0, np.zeros(n, np.float32), _params(oracle, stop_enabled=0, top_p=p), z, alive, ss)
+    counts = np.bincount(out["tokens"], minlength=V)
+    assert counts[~keep].sum() == 0                           # nothing outside the kept set is ever drawn
+    want = special.softmax(y[keep])
+    chi2 = stats.chisquare(counts[keep], want * n)
+    assert chi2.pvalue > 1e-4
+    # the kept set grows with p
+    sizes = [_filtered(oracle, x, tau, top_p=q)["kept"][0] for q in (0.1, 0.3, 0.5, 0.7, 0.9, 0.999)]
+    assert sizes == sorted(sizes) and sizes[-1] >= sizes[0]
