@@ -70,7 +70,26 @@ typedef struct {
   int32_t stop_mode;    /* which stop test, see espo_stop_mode; 0 = Eq. stop_rule      */
   float stop_threshold; /* the fixed threshold / probability of modes 1-3             */
   int32_t simulate;     /* non-zero: record the first stop step but keep decoding     */
+  float top_p;          /* nucleus filter on the draw, active for 0 < top_p < 1       */
+  int32_t top_k;        /* top-k filter on the draw, active for top_k > 0             */
 } espo_params;
+
+/*
+ * Filtered draws.  Rollouts for training draw from the whole vocabulary (both fields 0).  The
+ * evaluation set-up of Section 5 draws with a nucleus of 0.7 at temperature 1 and top-k off;
+ * for that, step 2 of espo_step below draws from a kept subset of the vocabulary instead:
+ *   top_p  v is kept iff the tokens with a strictly larger logit hold less than top_p of the
+ *          probability mass: the most probable tokens whose mass reaches top_p, with tokens
+ *          of equal logit kept or dropped together (the most probable token is always kept);
+ *   top_k  v is kept iff fewer than top_k tokens have a strictly larger logit (ties at the
+ *          k-th value are all kept).
+ * The token is argmax (y_v + G_v) over the kept set, with the same G_v as without a filter, so
+ * it is distributed as the renormalised distribution on the kept set.  regret, logprob, entropy
+ * and the state update are as without a filter (logprob and entropy refer to the unfiltered
+ * distribution; the regret of a kept token does not depend on the renormalisation).  At most
+ * one of the two may be active (ESPO_EINVAL otherwise).  A filtered step reads the row more than
+ * once (the later passes mostly from the caches) and runs as its own kernel instantiation.
+ */
 
 /*
  * Stop tests.  ESPO_STOP_RULE is the method (Eq. stop_rule); the others are the replacements

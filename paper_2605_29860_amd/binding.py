@@ -29,7 +29,8 @@ class _Params(C.Structure):
     _fields_ = [("mu_g", C.c_float), ("var_g", C.c_float), ("delta", C.c_float),
                 ("clip_c", C.c_float), ("alpha_s", C.c_float), ("beta", C.c_float),
                 ("eps", C.c_float), ("stop_enabled", C.c_int32), ("eos_id", C.c_int32),
-                ("stop_mode", C.c_int32), ("stop_threshold", C.c_float), ("simulate", C.c_int32)]
+                ("stop_mode", C.c_int32), ("stop_threshold", C.c_float), ("simulate", C.c_int32),
+                ("top_p", C.c_float), ("top_k", C.c_int32)]
 
 
 @dataclass
@@ -47,11 +48,13 @@ class EspoParams:
     stop_mode: int = 0          # espo_stop_mode: 0 Eq. stop_rule, 1 value only, 2 regret only, 3 random
     stop_threshold: float = 0.0
     simulate: int = 0
+    top_p: float = 0.0          # nucleus filter on the draw (0 or >= 1: off)
+    top_k: int = 0              # top-k filter on the draw (<= 0: off)
 
     def _c(self) -> _Params:
         return _Params(self.mu_g, self.var_g, self.delta, self.clip_c, self.alpha_s, self.beta,
                        self.eps, int(self.stop_enabled), int(self.eos_id), int(self.stop_mode),
-                       float(self.stop_threshold), int(self.simulate))
+                       float(self.stop_threshold), int(self.simulate), float(self.top_p), int(self.top_k))
 
 
 def library_path() -> str:

@@ -103,6 +103,8 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
   if (!(params->clip_c >= 0.0f) || !(params->beta >= 0.0f) || isnan(params->eps) || isnan(params->mu_g)) return ESPO_EINVAL;
   if (params->stop_mode < ESPO_STOP_RULE || params->stop_mode > ESPO_STOP_RANDOM) return ESPO_EINVAL;
   if (params->stop_mode != ESPO_STOP_RULE && isnan(params->stop_threshold)) return ESPO_EINVAL;
+  if (!(params->top_p >= 0.0f && params->top_p <= 1.0f) || params->top_k < 0) return ESPO_EINVAL;
+  if (params->top_p > 0.0f && params->top_p < 1.0f && params->top_k > 0) return ESPO_EINVAL;  // one filter at a time
   if (B == 0) return ESPO_OK;
   if (!logits || !values || !z || !alive || !stop_step || !tokens || !regret) return ESPO_EINVAL;
   if (V > espo::kMaxVocab || B > 0x7fffffff || espo::step_shared_bytes(dt, V) > espo::kMaxStepLds) return ESPO_ERANGE;

@@ -56,6 +56,8 @@ struct StepArgs {
   float mu_g, rsd, clip_c, alpha_s, oma, beta, eps;
   int32_t stop_enabled, eos_id, stop_mode, simulate;
   float stop_threshold;
+  float top_p;    // nucleus filter on the draw, active for 0 < top_p < 1
+  int32_t top_k;  // top-k filter on the draw, active for top_k > 0
   float* z;
   uint8_t* alive;
   int32_t* stop_step;
@@ -237,13 +239,14 @@ __device__ __forceinline__ BlockDraw<F> block_draw(const StepArgs& a, int row, i
 }
 
 // Scores index v (logit x) of a block with draw d and offers it to the search, unless its
-// upper bound y + M_q (+ margins) cannot reach `bound`, a score already known to be attained.
+// upper bound y + M_q (+ margins) cannot reach `bound`, a score already known to be attained,
+// or its logit is not above `floor` (-inf: only masked entries are left out).
 template <typename F>
 __device__ __forceinline__ void score_index(const StepArgs& a, int row, int32_t v, float x, const BlockDraw<F>& d,
-                                            F bound, Search<F>& st) {
+                                            F bound, float floor, Search<F>& st) {
   const F y = (F)x * (F)a.inv_tau;
   const float e = sizeof(F) == 4 ? score_margin(a, (float)y) : 0.0f;
-  if (x > kNegInf && (y + d.M) + (F)(2.0f * e) >= bound) {   // masked (-inf) entries never win
+  if (x > floor && (y + d.M) + (F)(2.0f * e) >= bound) {   // masked (-inf) and filtered entries never win
     F G = d.M;
     if (v != d.vpos) {
       const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
@@ -257,11 +260,12 @@ __device__ __forceinline__ void score_index(const StepArgs& a, int row, int32_t 
 // Scores the 64 indices of block q, one per lane.  `data` points at the block's 64 elements
 // (LDS copy or the row itself).
 template <int DT, typename F>
-__device__ __forceinline__ void visit_block(const StepArgs& a, int row, int q, const void* data, F bound, Search<F>& st) {
+__device__ __forceinline__ void visit_block(const StepArgs& a, int row, int q, const void* data, F bound, float floor,
+                                            Search<F>& st) {
   const int lane = threadIdx.x & (kWave - 1);
   const BlockDraw<F> d = block_draw<F>(a, row, q);
   const int32_t v = q * kDrawBlock + lane;
-  if (v < a.V) score_index<F>(a, row, v, elem_at<DT>(data, lane), d, bound, st);
+  if (v < a.V) score_index<F>(a, row, v, elem_at<DT>(data, lane), d, bound, floor, st);
 }
 
 // The scalar chain regret -> normalised, clipped regret -> smoothed state -> stop test.
@@ -323,11 +327,13 @@ struct StepShared {
   int* ncand;       // [1]
   int* nsurv;       // [1]
   int* bkey;        // [1] best attained score published during long survivor lists (order-preserving key)
+  float floor;      // only logits above this take part in the search (-inf unless the draw is filtered)
 };
 
 template <int DT>
 __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   StepShared s;
+  s.floor = kNegInf;
   size_t off = 0;
   auto take = [&](size_t bytes) { void* p = base + off; off += (bytes + 15) & ~(size_t)15; return p; };
   s.res_s = (double*)take(kStepWaves * 8);
@@ -433,7 +439,7 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
 #pragma unroll 1
   while (true) {  // one visit site for the wave's own block and for the survivors
     if (q >= 0) {
-      visit_block<DT, F>(a, row, q, data_of(q), bound, st);
+      visit_block<DT, F>(a, row, q, data_of(q), bound, sh.floor, st);
       const float lo = wave_max(round_down_f32(st.lower()));  // best score this wave has seen, rounded down
       bound = bound > (F)lo ? bound : (F)lo;
     }
@@ -500,7 +506,7 @@ __device__ __forceinline__ void score_element(const StepArgs& a, const StepShare
   const float y = x * a.inv_tau;
   const float sc = y + G;
   const float e = score_margin(a, y);
-  if (valid && x > kNegInf) {  // masked (-inf) entries never win
+  if (valid && x > sh.floor) {  // masked (-inf) and filtered entries never win
     if (sc > st.s) {
       st.hi2 = fmaxf(st.hi2, st.s + st.e);
       st.s = sc; st.e = e; st.x = x; st.v = v;
@@ -558,7 +564,7 @@ __device__ __forceinline__ void collect_candidates(const StepArgs& a, const Step
       const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
       const float M = flog((float)n) - flog(neg_log_uniform<float>(sh.wq[qs[j]]));
       const float y = xs[j] * a.inv_tau;
-      if (lane < n && xs[j] > kNegInf && (y + M) + 2.0f * score_margin(a, y) >= bound) {
+      if (lane < n && xs[j] > sh.floor && (y + M) + 2.0f * score_margin(a, y) >= bound) {
         const int i = atomicAdd(sh.ncand, 1);
         if (i < kCandCap) {
           sh.cand_v[i] = first + lane;
@@ -597,7 +603,7 @@ __device__ __forceinline__ bool exact_among_candidates(const StepArgs& a, const 
   for (int i = tid; i < ncand; i += kStepThreads) {
     const int32_t v = sh.cand_v[i];
     const BlockDraw<double> d = block_draw<double>(a, row, v >> 6);
-    score_index<double>(a, row, v, sh.cand_x[i], d, -__builtin_huge_val(), st);
+    score_index<double>(a, row, v, sh.cand_x[i], d, -__builtin_huge_val(), sh.floor, st);
   }
   out = combine_search<double>(sh, st);
   return true;
@@ -705,7 +711,7 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
 }
 
 // ---------------------------------------------------------------- the kernel
-template <int DT, bool Entropy>
+template <int DT, bool Entropy, bool Filter>
 __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int row = blockIdx.x;
@@ -892,19 +898,123 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       if (lane == 0) sh.sumw[wave] = totw;
     }
   };
-  const Best fast = fast_argmax<DT>(a, sh, rowp, row, nslots, q_own, softmax_sum);
-  int32_t tok = fast.v;
-  float x_a = fast.x;
-  if (fast.v >= 0 && !(fast.s - fast.e > fast.hi2)) {
-    // the two best fp32 scores overlap within their margins: decide in double (rare)
-    __syncthreads();  // everyone has read the fp32 results
-    Search<double> exact;
-    if (!exact_among_candidates<DT>(a, sh, rowp, row, nslots, fast.s - fast.e, exact)) {
-      __syncthreads();
-      exact = find_argmax<DT, double>(a, sh, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
+  int32_t tok;
+  float x_a;
+  // the argmax over the indices whose logit is above shx.floor: fp32 search, decided in double where needed
+  auto search = [&](const StepShared& shx, auto between) {
+    const Best fast = fast_argmax<DT>(a, shx, rowp, row, nslots, q_own, between);
+    tok = fast.v;
+    x_a = fast.x;
+    if (fast.v >= 0 && !(fast.s - fast.e > fast.hi2)) {
+      // the two best fp32 scores overlap within their margins: decide in double (rare)
+      __syncthreads();  // everyone has read the fp32 results
+      Search<double> exact;
+      if (!exact_among_candidates<DT>(a, shx, rowp, row, nslots, fast.s - fast.e, exact)) {
+        __syncthreads();
+        exact = find_argmax<DT, double>(a, shx, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
+      }
+      tok = exact.best.v;
+      x_a = exact.best.x;
     }
-    tok = exact.best.v;
-    x_a = exact.best.x;
+  };
+  search(sh, softmax_sum);
+
+  if constexpr (Filter) {
+    // Filtered draw (top-p of the evaluation set-up in Section 5, or top-k).  The kept set is
+    // {v : the mass (the number) of strictly larger logits is below p (k)}, an upper set in the
+    // logit, so the filtered draw is the argmax of y + G over it.  The unfiltered winner is
+    // tested first: if it is kept it is also the winner among the kept.  If not, nothing at or
+    // below its logit is kept either, the search is repeated over the logits above it, and so
+    // on; the floor rises strictly, so this ends, after 1/p rounds on average.  The test
+    // is one more pass over the row (from the caches): sum of 2^t over the logits above the
+    // floor against p times the sum over all, formed by the same arithmetic in the same pass;
+    // within 1e-5 of equality the pass is repeated in double, in the oracle's arithmetic.
+    const bool by_count = a.top_k > 0;
+    const float nrk_row = -m * a.k2;
+    while (tok >= 0) {
+      const float floor_x = x_a;
+      float acc_m = 0.0f, acc_s = 0.0f, acc_n = 0.0f;
+#pragma unroll 1
+      for (int i = 0; i < my_tiles; ++i) {
+        const int t = i * kStepWaves + wave;
+        const Raw<DT> raw = load_tile(t);
+        float x[8];
+        unpack<DT>(raw, x);
+        const int32_t e0 = t * kTile + (int32_t)lane_off;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          if (e0 + j >= a.V) x[j] = kNegInf;  // ragged last tile
+          const float e = __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk_row));
+          const bool above = x[j] > floor_x;
+          acc_s += e;
+          acc_m += above ? e : 0.0f;
+          acc_n += above ? 1.0f : 0.0f;  // counts stay exact in fp32: V < 2^24
+        }
+      }
+      acc_m = wave_sum(acc_m);
+      acc_s = wave_sum(acc_s);
+      acc_n = wave_sum(acc_n);
+      __syncthreads();  // the search is over in every wave: its scratch can be reused
+      if (lane == 0) {
+        sh.res_s[wave] = (double)acc_m;
+        sh.res_hi2[wave] = (double)acc_s;
+        sh.fres[wave] = acc_n;
+      }
+      __syncthreads();
+      float mass = 0.0f, total = 0.0f, count = 0.0f;
+      for (int w = 0; w < kStepWaves; ++w) {  // fixed order, the same in every thread
+        mass += (float)sh.res_s[w];
+        total += (float)sh.res_hi2[w];
+        count += sh.fres[w];
+      }
+      bool kept;
+      if (by_count) {
+        kept = count < (float)a.top_k;
+      } else if (fabsf(mass - a.top_p * total) > 1e-5f * total) {
+        kept = mass < a.top_p * total;
+      } else {  // too close for fp32: the same two sums in double, y and y_max formed as the oracle forms them
+        const double inv = (double)a.inv_tau, y_max = (double)m * inv;
+        double dm = 0.0, ds = 0.0;
+#pragma unroll 1
+        for (int i = 0; i < my_tiles; ++i) {
+          const int t = i * kStepWaves + wave;
+          const Raw<DT> raw = load_tile(t);
+          float x[8];
+          unpack<DT>(raw, x);
+          const int32_t e0 = t * kTile + (int32_t)lane_off;
+#pragma unroll 1
+          for (int j = 0; j < 8; ++j) {
+            if (e0 + j < a.V && x[j] > kNegInf) {
+              const double e = exp((double)x[j] * inv - y_max);
+              ds += e;
+              if (x[j] > floor_x) dm += e;
+            }
+          }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+          dm += __shfl_xor(dm, off);
+          ds += __shfl_xor(ds, off);
+        }
+        __syncthreads();
+        if (lane == 0) {
+          sh.res_s[wave] = dm;
+          sh.res_hi2[wave] = ds;
+        }
+        __syncthreads();
+        double dmass = 0.0, dtotal = 0.0;
+        for (int w = 0; w < kStepWaves; ++w) {
+          dmass += sh.res_s[w];
+          dtotal += sh.res_hi2[w];
+        }
+        kept = dmass < (double)a.top_p * dtotal;
+      }
+      __syncthreads();  // everyone has read the sums
+      if (kept) break;
+      StepShared above = sh;
+      above.floor = floor_x;
+      search(above, [] {});
+    }
   }
 
   // ------------------------------------------------------------ finalize: one lane
@@ -1008,6 +1118,8 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.stop_mode = p.stop_mode;
   a.simulate = p.simulate;
   a.stop_threshold = p.stop_threshold;
+  a.top_p = p.top_p;
+  a.top_k = p.top_k;
   a.z = z;
   a.alive = alive;
   a.stop_step = stop_step;
@@ -1019,8 +1131,15 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   if (lds > kMaxStepLds) return ESPO_ERANGE;
   const dim3 grid((unsigned)B), block(kStepThreads);
   // the entropy output costs two more vector operations per logit: its own instantiation
-  void (*kernel)(StepArgs) = dt == ESPO_BF16 ? (entropy ? espo_step_kernel<ESPO_BF16, true> : espo_step_kernel<ESPO_BF16, false>)
-                                             : (entropy ? espo_step_kernel<ESPO_F32, true> : espo_step_kernel<ESPO_F32, false>);
+  // and so does a filtered draw (more passes over the row)
+  const bool filter = (p.top_p > 0.0f && p.top_p < 1.0f) || p.top_k > 0;
+  void (*kernel)(StepArgs);
+  if (dt == ESPO_BF16)
+    kernel = filter ? (entropy ? espo_step_kernel<ESPO_BF16, true, true> : espo_step_kernel<ESPO_BF16, false, true>)
+                    : (entropy ? espo_step_kernel<ESPO_BF16, true, false> : espo_step_kernel<ESPO_BF16, false, false>);
+  else
+    kernel = filter ? (entropy ? espo_step_kernel<ESPO_F32, true, true> : espo_step_kernel<ESPO_F32, false, true>)
+                    : (entropy ? espo_step_kernel<ESPO_F32, true, false> : espo_step_kernel<ESPO_F32, false, false>);
   if (lds > 64 * 1024) {  // beyond the default limit the kernel has to be told (very large vocabularies)
     if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStepLds) != hipSuccess)
       return ESPO_EHIP;

@@ -456,9 +456,10 @@ def test_seeded_sweep_of_shapes_structures_and_margins():
         scale = float(rng.choice([1.0, 1.0, 1.0, 3e4, 1e12]))
         paths[scale] += 1
         mode, simulate = int(rng.choice([0, 0, 0, 1, 2, 3])), int(rng.random() < 0.15)
+        filt = [dict(), dict(), dict(top_p=float(rng.choice([0.3, 0.7, 0.95]))), dict(top_k=int(rng.choice([1, 3, 40])))][int(rng.integers(0, 4))]
         gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=float(rng.choice([0.5, 7.0])), stop_mode=mode,
                                stop_threshold=float(rng.choice([0.05, 0.3, 1.0])), simulate=simulate,
-                               eos_id=int(rng.choice([-1, -1, 0, V - 1])))
+                               eos_id=int(rng.choice([-1, -1, 0, V - 1])), **filt)
         st = H.GpuState(B, z=torch.rand(B, generator=g) * 2 - 1, alive=(torch.rand(B, generator=g) < 0.85).to(torch.uint8))
         vals = torch.rand(B, generator=g).cuda()
         entropy = bool(rng.random() < 0.4)
@@ -468,7 +469,7 @@ def test_seeded_sweep_of_shapes_structures_and_margins():
                 H.compare_step(logits, tau, 900 + case, step, vals, gp, op, st, V=V, stats=stats, entropy=entropy)
         except AssertionError as err:
             raise AssertionError(f"case {case}: V={V} B={B} {dtype} tau={tau} {kind} scale={scale} mode={mode} "
-                                 f"simulate={simulate} entropy={entropy}: {err}")
+                                 f"simulate={simulate} entropy={entropy} {filt}: {err}")
         finally:
             espo.espo_debug_set_score_margin_scale(1.0)
     _say(f"  cases per margin scale: {paths}; {stats}")
@@ -547,6 +548,85 @@ def test_two_streams_do_not_interfere():
         a, b = serial[i].host(), inter[i].host()
         for k in a:
             np.testing.assert_array_equal(a[k].view(np.uint8), b[k].view(np.uint8), err_msg=f"stream {i} {k}")
+
+
+# --------------------------------------------------------------------------- filtered draws
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_top_p_and_top_k_draws_match_the_oracle(dtype):
+    _say(f"[case] filtered draws {dtype}")
+    import oracle
+    stats = {}
+    cases = [(7, "gauss", 1.0), (513, "gauss", 0.6), (4099, "flat", 1.0), (9000, "masked", 0.8), (20000, "peaked", 1.0),
+             (33000, "gauss", 2.5), (40000, "ties", 1.0), (152064, "zipf", 1.0), (152064, "zipf", 0.6)]
+    filters = [dict(top_p=0.7), dict(top_p=0.1), dict(top_p=0.97), dict(top_k=1), dict(top_k=5), dict(top_k=50)]
+    for case, (V, kind, tau) in enumerate(cases):
+        B = 6
+        stride = ((V + 7) // 8) * 8 + 8
+        g = torch.Generator().manual_seed(800 + case)
+        x = torch.randn(B, stride, generator=g) * 3.0
+        if kind == "flat":
+            x[:] = 0.5
+        elif kind == "masked":
+            x[:, torch.rand(stride, generator=g) < 0.8] = float("-inf")
+            x[:, V // 3] = 1.0
+        elif kind == "peaked":
+            x[:, V - 2] = 30.0
+        elif kind == "ties":
+            x = torch.round(x)                                   # a handful of distinct values, huge tie groups
+        elif kind == "zipf":
+            x[:, :V] += W.ZipfLogits(V=V, seed=case, device="cpu").boost
+        x[:, V:] = 1e4
+        logits = x.to(dtype).cuda()
+        vals = torch.rand(B, generator=g).cuda()
+        for f in filters:
+            gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=3.0, **f)
+            st = H.GpuState(B, alive=torch.tensor([1, 1, 0, 1, 1, 1], dtype=torch.uint8))
+            for step in range(3):
+                try:
+                    got = H.compare_step(logits, tau, 61, step, vals, gp, op, st, V=V, stats=stats, entropy=(step == 1))
+                except AssertionError as err:
+                    raise AssertionError(f"case {case} V={V} {kind} tau={tau} {f} step {step}: {err}")
+            if f.get("top_k") == 1:
+                live = got["tokens"] >= 0
+                assert (got["regret"][live] == 0).all()          # only modes are kept
+    # a filter that keeps everything gives the bits of the plain step
+    V, B = 5000, 4
+    logits = _rand_logits(B, V, V, dtype, seed=3)
+    vals = torch.zeros(B, device="cuda")
+    outs = []
+    for f in (dict(), dict(top_p=1.0), dict(top_k=V), dict(top_p=0.999999)):
+        gp, _ = H.params_pair(stop_enabled=0, **f)
+        st = H.GpuState(B)
+        H.gpu_step(logits, 0.9, 8, 0, vals, gp, st)
+        outs.append(st.host())
+    for o in outs[1:3]:
+        for k in ("tokens", "regret", "z", "logprob"):
+            np.testing.assert_array_equal(o[k].view(np.uint8), outs[0][k].view(np.uint8))
+    with pytest.raises(espo.EspoError):
+        gp, _ = H.params_pair(top_p=0.5, top_k=3)
+        H.gpu_step(logits, 0.9, 8, 0, vals, gp, H.GpuState(B))
+    _say(f"  {stats}")
+
+
+def test_top_p_at_the_edge_of_the_kept_set_is_decided_like_the_oracle():
+    _say("[case] filtered draws, mass next to p")
+    # One tall token and many equal ones: the equal ones are kept iff the tall one's probability is below p.
+    # p is set to that probability rounded to fp32, so the comparison is closer than fp32 sums can tell
+    # and the kernel has to repeat it in double.
+    B = 16
+    for V, a, tau in [(1000, 5.0, 1.0), (30000, 9.5, 1.0), (152064, 11.0, 0.6)]:
+        x = torch.zeros(B, V)
+        x[:, 17] = a
+        inv = np.float64(np.float32(1.0) / np.float32(tau))
+        pa = 1.0 / (1.0 + (V - 1) * np.exp(-np.float64(np.float32(a)) * inv))
+        for p_val in (float(np.float32(pa)), float(np.nextafter(np.float32(pa), np.float32(1))),
+                      float(np.nextafter(np.float32(pa), np.float32(0)))):
+            if not 0.0 < p_val < 1.0:
+                continue
+            gp, op = H.params_pair(stop_enabled=0, top_p=p_val)
+            st = H.GpuState(B)
+            for step in range(2):
+                H.compare_step(x.cuda(), tau, 99, step, torch.zeros(B, device="cuda"), gp, op, st)
 
 
 # --------------------------------------------------------------------------- HIP graph capture
