@@ -166,7 +166,8 @@ typedef enum {
  *               supported (results for that row are unspecified, no fault).
  *   dt          ESPO_F32 or ESPO_BF16.
  *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 400000
- *               (ESPO_ERANGE beyond: the per-block bounds of a row live in LDS).
+ *               (ESPO_ERANGE beyond: the per-block bounds of a row live in LDS; a filtered
+ *               draw keeps one more table there and stops at about 350000 for fp32 logits).
  *   row_stride  elements between rows, >= V.
  *   temperature > 0 and finite.
  *   seed, step  key and counter word of the random stream; step >= 0.

@@ -107,7 +107,8 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
   if (params->top_p > 0.0f && params->top_p < 1.0f && params->top_k > 0) return ESPO_EINVAL;  // one filter at a time
   if (B == 0) return ESPO_OK;
   if (!logits || !values || !z || !alive || !stop_step || !tokens || !regret) return ESPO_EINVAL;
-  if (V > espo::kMaxVocab || B > 0x7fffffff || espo::step_shared_bytes(dt, V) > espo::kMaxStepLds) return ESPO_ERANGE;
+  if (V > espo::kMaxVocab || B > 0x7fffffff || espo::step_shared_bytes(dt, V, (params->top_p > 0.0f && params->top_p < 1.0f) || params->top_k > 0) > espo::kMaxStepLds)
+    return ESPO_ERANGE;
   const size_t esize = dt == ESPO_BF16 ? 2 : 4;
   if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
   return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params,

@@ -12,7 +12,7 @@ constexpr size_t kMaxStepLds = 128 * 1024;         // dynamic LDS a step workgro
 constexpr int64_t kMaxVocab = 400000;               // 96 bytes of LDS per 512-index tile plus 26-42 KB fixed
 
 // Bytes of dynamic LDS a step workgroup needs for this dtype and vocabulary.
-size_t step_shared_bytes(int dt, int64_t V);
+size_t step_shared_bytes(int dt, int64_t V, bool filter);  // filter: a top-p / top-k draw (one more table per row)
 
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,

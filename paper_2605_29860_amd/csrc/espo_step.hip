@@ -328,9 +328,10 @@ struct StepShared {
   int* nsurv;       // [1]
   int* bkey;        // [1] best attained score published during long survivor lists (order-preserving key)
   float floor;      // only logits above this take part in the search (-inf unless the draw is filtered)
+  float* bmx;       // [nslots] largest logit of every block (filtered draws only, else null)
 };
 
-template <int DT>
+template <int DT, bool Filter>
 __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   StepShared s;
   s.floor = kNegInf;
@@ -356,19 +357,24 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   s.ncand = s.nsurv + 2;
   s.mu = (float*)take((size_t)nslots * 8);
   s.wq = (uint32_t*)take((size_t)nslots * 4);
+  s.bmx = Filter ? (float*)take((size_t)nslots * 4) : nullptr;
   return s;
 }
 
-size_t step_lds_bytes(int dt, int ntiles) {
+size_t step_lds_bytes(int dt, int ntiles, bool filter) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups;
   return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 13 * kStepWaves * 4 + 16 + 2 * kCandCap * 4 +
-         ((nslots * 8 + 15) & ~(size_t)15) + ((nslots * 4 + 15) & ~(size_t)15);
+         ((nslots * 8 + 15) & ~(size_t)15) + (filter ? 2 : 1) * ((nslots * 4 + 15) & ~(size_t)15);
 }
 
 // The streaming loop stores a block's bound as the plain fma(y_max, 1/tau, bound of M_q); what
 // that fma may have rounded away (2^-24 relative) is added back where bounds are compared.
 __device__ __forceinline__ float ub_rounded_up(float u) { return fmaf(fabsf(u), 2e-7f, u); }
+
+// Whether block b can hold a logit that takes part in the search: always, unless the draw is
+// filtered; then only if its largest logit is above the floor.
+__device__ __forceinline__ bool holds_eligible(const StepShared& sh, int b) { return sh.bmx == nullptr || sh.bmx[b] > sh.floor; }
 
 // Slot (wave, group) that streamed block q in phase 1.
 __device__ __forceinline__ int slot_of(int q) { return ((q >> 3) & (kStepWaves - 1)) * kGroups + (q & (kGroups - 1)); }
@@ -458,7 +464,8 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
       // blocks whose bound reaches the best score found so far
       for (int b = tid; b < nslots; b += kStepThreads) {
         const float u = sh.ub(b);
-        if (u > -1e30f && ub_rounded_up(u) >= bound_f && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
+        if (u > -1e30f && ub_rounded_up(u) >= bound_f && sh.visq[(b >> 3) & (kStepWaves - 1)] != b && holds_eligible(sh, b))
+          sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       __syncthreads();
       nsurv = *sh.nsurv;
@@ -591,7 +598,7 @@ __device__ __forceinline__ bool exact_among_candidates(const StepArgs& a, const 
   __syncthreads();
   for (int b = tid; b < nslots; b += kStepThreads) {
     const float u = sh.ub(b);
-    if (u > -1e30f && ub_rounded_up(u) >= lower) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
+    if (u > -1e30f && ub_rounded_up(u) >= lower && holds_eligible(sh, b)) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
   }
   __syncthreads();
   collect_candidates<DT>(a, sh, rowp, *sh.nsurv, lower);
@@ -661,7 +668,8 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
       const float bound = wave_max(lane < kStepWaves ? sh.lo[lane] : kNegInf);
       for (int b = tid; b < nslots; b += kStepThreads) {  // blocks whose bound reaches the best score found so far
         const float u = sh.ub(b);
-        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[(b >> 3) & (kStepWaves - 1)] != b) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
+        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[(b >> 3) & (kStepWaves - 1)] != b && holds_eligible(sh, b))
+          sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       if (tid == 0) *sh.bkey = float_key(bound);
       __syncthreads();
@@ -730,7 +738,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   const int grp = lane >> 3;
   const int ntiles = a.ntiles;
   const int nslots = ntiles * kGroups;  // block slots incl. the non-existent ones of the last tile
-  const StepShared sh = carve<DT>(smem_raw, nslots);
+  const StepShared sh = carve<DT, Filter>(smem_raw, nslots);
   const void* rowp = (const char*)a.logits + (size_t)row * (size_t)a.row_stride * elem_bytes<DT>();
 
   // ------------------------------------------------------------ phase 1: stream the row
@@ -786,6 +794,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   float top_ub = kNegInf;    // largest block bound this lane group has seen, and its block
   int top_q = -1;
   char* const my_raw = (char*)sh.top_raw + ((size_t)(wave * kGroups + grp) * kDrawBlock + (lane & 7) * 8) * elem_bytes<DT>();
+  float* const bmx_lane = Filter ? sh.bmx + (wave * kGroups + grp) : nullptr;
   float* const mu_lane = sh.mu + 2 * (wave * kGroups + grp);  // this lane group's entry of tile `wave`; 256 floats per iteration
 
   // One wave iteration over ring slot d, tile index i of this wave.  `Steady` iterations are
@@ -846,6 +855,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     float* const mu = mu_lane + (size_t)i * (2 * kStepWaves * kGroups);
     const float ub = fmaf(bm, a.inv_tau, mu[0]);
     mu[1] = ub;  // the 8 lanes of the group store the same value
+    if constexpr (Filter) bmx_lane[(size_t)i * (kStepWaves * kGroups)] = bm;
     mx = fmaxf(mx, bm);
     if (ub > top_ub) {  // keep the data of the block with the group's largest bound
       top_ub = ub;
@@ -920,58 +930,208 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   search(sh, softmax_sum);
 
   if constexpr (Filter) {
-    // Filtered draw (top-p of the evaluation set-up in Section 5, or top-k).  The kept set is
+    // Filtered draw (top-p as in the evaluation set-up of Section 5, or top-k).  The kept set is
     // {v : the mass (the number) of strictly larger logits is below p (k)}, an upper set in the
-    // logit, so the filtered draw is the argmax of y + G over it.  The unfiltered winner is
-    // tested first: if it is kept it is also the winner among the kept.  If not, nothing at or
-    // below its logit is kept either, the search is repeated over the logits above it, and so
-    // on; the floor rises strictly, so this ends, after 1/p rounds on average.  The test
-    // is one more pass over the row (from the caches): sum of 2^t over the logits above the
-    // floor against p times the sum over all, formed by the same arithmetic in the same pass;
-    // within 1e-5 of equality the pass is repeated in double, in the oracle's arithmetic.
+    // logit, so the filtered draw is the argmax of y + G over it: the unfiltered winner if it is
+    // kept, else the winner of one more search above the kept set's edge.  What is needed is the
+    // mass (number) of the logits above a given floor, and those logits themselves when they are
+    // few.  A table of the blocks' largest logits, filled while streaming, names the blocks that
+    // hold any; a handful of blocks is read again directly, more of them by one more pass over
+    // the row.  First a floor that leaves about 32 blocks above it is tried: on rows like a
+    // language model's the kept set lies above it, its smallest logit is then read off the
+    // collected logits (the smallest whose strictly larger ones hold less than p, number fewer
+    // than k) and the token follows.  Otherwise (flat rows) the winner itself is tested, and
+    // while it is not kept the search is repeated above it; that floor rises strictly, so the
+    // loop ends.  Sums within 1e-5 of p times the softmax sum are not trusted in fp32: the
+    // candidate path is then left for the loop, whose test repeats them in double over the
+    // whole row, in the oracle's arithmetic.
+    const auto nothing = [] {};
     const bool by_count = a.top_k > 0;
     const float nrk_row = -m * a.k2;
-    while (tok >= 0) {
-      const float floor_x = x_a;
-      float acc_m = 0.0f, acc_s = 0.0f, acc_n = 0.0f;
+    const float total = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // S, as the last step forms it
+    const float want = a.top_p * total;
+    float* const cand_e = (float*)sh.cand_v;  // the candidates' 2^t, beside their logits in cand_x
+    float mass = 0.0f, count = 0.0f;
+    int ncand = 0;
+
+    // mass and number of the logits above floor_x; the logits themselves in cand_x / cand_e if they fit
+    auto measure = [&](float floor_x) {
+      __syncthreads();  // whatever used the scratch before is over in every wave
+      if (tid == 0) {
+        *sh.nsurv = 0;
+        *sh.ncand = 0;
+      }
+      __syncthreads();
+      for (int b = tid; b < nslots; b += kStepThreads)  // blocks that hold a logit above the floor
+        if (sh.bmx[b] > floor_x) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
+      __syncthreads();
+      const int nabove = *sh.nsurv;
+      float acc_m = 0.0f, acc_n = 0.0f;
+      if (nabove <= 8 * kStepWaves) {  // the usual case: one block per wave visit, one index per lane, four loads in flight
 #pragma unroll 1
-      for (int i = 0; i < my_tiles; ++i) {
-        const int t = i * kStepWaves + wave;
-        const Raw<DT> raw = load_tile(t);
-        float x[8];
-        unpack<DT>(raw, x);
-        const int32_t e0 = t * kTile + (int32_t)lane_off;
+        for (int base = wave; base < nabove; base += 4 * kStepWaves) {
+          float xs[4];
+          int32_t ns[4];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          if (e0 + j >= a.V) x[j] = kNegInf;  // ragged last tile
-          const float e = __builtin_amdgcn_exp2f(fmaf(x[j], a.k2, nrk_row));
-          const bool above = x[j] > floor_x;
-          acc_s += e;
-          acc_m += above ? e : 0.0f;
-          acc_n += above ? 1.0f : 0.0f;  // counts stay exact in fp32: V < 2^24
+          for (int u = 0; u < 4; ++u) {
+            const int k = base + u * kStepWaves;
+            xs[u] = kNegInf;
+            ns[u] = 0;
+            if (k < nabove) {
+              const int q = __builtin_amdgcn_readfirstlane(sh.surv(k));
+              ns[u] = a.V - q * kDrawBlock < kDrawBlock ? a.V - q * kDrawBlock : kDrawBlock;
+              xs[u] = block_elem<DT>(a, sh, rowp, q);
+            }
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            if (lane < ns[u] && xs[u] > floor_x) {
+              const float e = __builtin_amdgcn_exp2f(fmaf(xs[u], a.k2, nrk_row));
+              acc_m += e;
+              acc_n += 1.0f;  // counts stay exact in fp32: V < 2^24
+              const int c = atomicAdd(sh.ncand, 1);
+              if (c < kCandCap) {
+                sh.cand_x[c] = xs[u];
+                cand_e[c] = e;
+              }
+            }
+          }
+        }
+      } else {  // many blocks: stream the row once more, six loads in flight per lane
+        constexpr int kDeep = 6;
+#pragma unroll 1
+        for (int i0 = 0; i0 < my_tiles; i0 += kDeep) {
+          Raw<DT> raw[kDeep];
+#pragma unroll
+          for (int d = 0; d < kDeep; ++d)
+            if (i0 + d < my_tiles) raw[d] = load_tile((i0 + d) * kStepWaves + wave);
+#pragma unroll
+          for (int d = 0; d < kDeep; ++d) {
+            if (i0 + d < my_tiles) {
+              float x[8];
+              unpack<DT>(raw[d], x);
+              const int32_t e0 = ((i0 + d) * kStepWaves + wave) * kTile + (int32_t)lane_off;
+              const bool room = *sh.ncand <= kCandCap;  // once the buffer has overflowed nothing more is kept
+#pragma unroll
+              for (int u = 0; u < 8; ++u) {
+                const bool above = e0 + u < a.V && x[u] > floor_x;
+                const float e = __builtin_amdgcn_exp2f(fmaf(x[u], a.k2, nrk_row));
+                acc_m += above ? e : 0.0f;
+                acc_n += above ? 1.0f : 0.0f;
+                const uint64_t who = __builtin_amdgcn_ballot_w64(above);
+                if (who != 0 && room) {  // one counter update per wave, the lanes take consecutive entries
+                  int base = 0;
+                  if (lane == (int)__builtin_ctzll(who)) base = atomicAdd(sh.ncand, (int)__builtin_popcountll(who));
+                  base = __builtin_amdgcn_readlane(base, (int)__builtin_ctzll(who));
+                  const int c = base + (int)__builtin_popcountll(who & ((1ull << lane) - 1ull));
+                  if (above && c < kCandCap) {
+                    sh.cand_x[c] = x[u];
+                    cand_e[c] = e;
+                  }
+                }
+              }
+            }
+          }
         }
       }
       acc_m = wave_sum(acc_m);
-      acc_s = wave_sum(acc_s);
       acc_n = wave_sum(acc_n);
-      __syncthreads();  // the search is over in every wave: its scratch can be reused
       if (lane == 0) {
         sh.res_s[wave] = (double)acc_m;
-        sh.res_hi2[wave] = (double)acc_s;
         sh.fres[wave] = acc_n;
       }
       __syncthreads();
-      float mass = 0.0f, total = 0.0f, count = 0.0f;
+      mass = 0.0f;
+      count = 0.0f;
       for (int w = 0; w < kStepWaves; ++w) {  // fixed order, the same in every thread
         mass += (float)sh.res_s[w];
-        total += (float)sh.res_hi2[w];
         count += sh.fres[w];
       }
+      ncand = *sh.ncand;
+    };
+
+    // The smallest kept logit among the collected ones (all logits above some floor below the kept
+    // set): the smallest candidate whose strictly larger candidates hold less than p (number fewer
+    // than k).  False if a sum is too close to p to tell in fp32.
+    auto kept_edge = [&](float& edge_all) {
+      float mine_x = __builtin_huge_valf();  // this thread's candidate if it is kept, else +inf
+      bool unsure = false;
+      for (int c = tid; c < ncand; c += kStepThreads) {  // at most one per thread
+        const float xc = sh.cand_x[c];
+        float m_above = 0.0f, n_above = 0.0f;
+        for (int o = 0; o < ncand; ++o) {  // every thread reads the same entry: LDS broadcasts
+          const bool larger = sh.cand_x[o] > xc;
+          m_above += larger ? cand_e[o] : 0.0f;
+          n_above += larger ? 1.0f : 0.0f;
+        }
+        const bool keep = by_count ? n_above < (float)a.top_k : m_above < want;
+        unsure = !by_count && fabsf(m_above - want) <= 1e-5f * total;
+        if (keep) mine_x = xc;
+      }
+      const float edge = -wave_max(-mine_x);  // smallest kept candidate of the wave
+      const bool any_unsure = __builtin_amdgcn_ballot_w64(unsure) != 0;
+      __syncthreads();  // the sums of the measurement have been read by everyone
+      if (lane == 0) {
+        sh.fres[wave] = edge;
+        sh.fres[kStepWaves + wave] = any_unsure ? 1.0f : 0.0f;
+      }
+      __syncthreads();
+      edge_all = __builtin_huge_valf();
+      float unsure_all = 0.0f;
+      for (int w = 0; w < kStepWaves; ++w) {
+        edge_all = fminf(edge_all, sh.fres[w]);
+        unsure_all += sh.fres[kStepWaves + w];
+      }
+      return unsure_all == 0.0f && edge_all < __builtin_huge_valf();
+    };
+
+    // the token once the smallest kept logit is known: the winner so far if it is kept, else the winner above the edge
+    auto settle = [&](float edge) {
+      if (x_a >= edge) return;
+      StepShared kept_only = sh;  // everything at or above the edge: the floor is the next float below it
+      const int32_t bits = __builtin_bit_cast(int32_t, edge);
+      kept_only.floor = edge == 0.0f ? -1.401298464e-45f : __builtin_bit_cast(float, bits + (edge > 0.0f ? -1 : 1));
+      search(kept_only, nothing);
+    };
+
+    bool done = tok < 0;
+    if (!done) {
+      // a floor with about 32 blocks above it (32 + k for top-k, which needs k logits above it): the 32nd
+      // largest of the 128 lane groups' largest logits
+      __syncthreads();
+      if ((lane & 7) == 0) sh.cand_x[wave * kGroups + grp] = mx;
+      __syncthreads();
+      float trial = kNegInf;
+      const int trial_rank = by_count ? (a.top_k < kSlots - 32 ? 31 + a.top_k : kSlots - 1) : 31;
+      if (tid < kSlots) {
+        const float mine = sh.cand_x[tid];
+        int rank = 0;
+        for (int o = 0; o < kSlots; ++o) {
+          const float other = sh.cand_x[o];
+          rank += (other > mine || (other == mine && o < tid)) ? 1 : 0;
+        }
+        if (rank == trial_rank) sh.fres[2 * kStepWaves] = mine;
+      }
+      __syncthreads();
+      trial = sh.fres[2 * kStepWaves];  // -inf if fewer than 32 lane groups saw a finite logit
+      measure(trial);
+      const bool below_edge = by_count ? count >= (float)a.top_k : mass - want > 1e-5f * total;
+      if (below_edge && ncand <= kCandCap) {
+        float edge;
+        if (kept_edge(edge)) {
+          settle(edge);
+          done = true;
+        }
+      }
+    }
+    while (!done && tok >= 0) {
+      const float floor_x = x_a;
+      measure(floor_x);
       bool kept;
       if (by_count) {
         kept = count < (float)a.top_k;
-      } else if (fabsf(mass - a.top_p * total) > 1e-5f * total) {
-        kept = mass < a.top_p * total;
+      } else if (fabsf(mass - want) > 1e-5f * total) {
+        kept = mass < want;
       } else {  // too close for fp32: the same two sums in double, y and y_max formed as the oracle forms them
         const double inv = (double)a.inv_tau, y_max = (double)m * inv;
         double dm = 0.0, ds = 0.0;
@@ -982,12 +1142,12 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
           float x[8];
           unpack<DT>(raw, x);
           const int32_t e0 = t * kTile + (int32_t)lane_off;
-#pragma unroll 1
-          for (int j = 0; j < 8; ++j) {
-            if (e0 + j < a.V && x[j] > kNegInf) {
-              const double e = exp((double)x[j] * inv - y_max);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) {
+            if (e0 + u < a.V && x[u] > kNegInf) {
+              const double e = exp((double)x[u] * inv - y_max);
               ds += e;
-              if (x[j] > floor_x) dm += e;
+              if (x[u] > floor_x) dm += e;
             }
           }
         }
@@ -1009,11 +1169,17 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         }
         kept = dmass < (double)a.top_p * dtotal;
       }
-      __syncthreads();  // everyone has read the sums
       if (kept) break;
-      StepShared above = sh;
+      if (ncand <= kCandCap) {  // every logit above the winner's is at hand
+        float edge;
+        if (kept_edge(edge)) {
+          settle(edge);
+          break;  // that winner is kept by construction
+        }
+      }
+      StepShared above = sh;  // the bulk case, or a sum too close to tell: the next winner above the floor
       above.floor = floor_x;
-      search(above, [] {});
+      search(above, nothing);
     }
   }
 
@@ -1086,7 +1252,7 @@ int launch_math_errors(float* out, hipStream_t stream) {
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 
-size_t step_shared_bytes(int dt, int64_t V) { return step_lds_bytes(dt, (int)((V + kTile - 1) / kTile)); }
+size_t step_shared_bytes(int dt, int64_t V, bool filter) { return step_lds_bytes(dt, (int)((V + kTile - 1) / kTile), filter); }
 
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
@@ -1127,12 +1293,13 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.regret = regret;
   a.logprob = logprob;
   a.entropy = entropy;
-  const size_t lds = step_lds_bytes(dt, a.ntiles);
-  if (lds > kMaxStepLds) return ESPO_ERANGE;
+
   const dim3 grid((unsigned)B), block(kStepThreads);
   // the entropy output costs two more vector operations per logit: its own instantiation
   // and so does a filtered draw (more passes over the row)
   const bool filter = (p.top_p > 0.0f && p.top_p < 1.0f) || p.top_k > 0;
+  const size_t lds = step_lds_bytes(dt, a.ntiles, filter);
+  if (lds > kMaxStepLds) return ESPO_ERANGE;
   void (*kernel)(StepArgs);
   if (dt == ESPO_BF16)
     kernel = filter ? (entropy ? espo_step_kernel<ESPO_BF16, true, true> : espo_step_kernel<ESPO_BF16, false, true>)
