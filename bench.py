@@ -88,7 +88,7 @@ def main() -> int:
     regret = torch.empty(B_STEP, dtype=torch.float32, device=dev)
     logprob = torch.empty(B_STEP, dtype=torch.float32, device=dev)
 
-    def run(first, last, z, alive, ss, events=None, entropy=None):
+    def run(first, last, z, alive, ss, events=None, entropy=None, params=params):
         for s in range(first, last):
             if events is not None:
                 events[s - first][0].record()
@@ -145,6 +145,19 @@ def main() -> int:
     torch.cuda.synchronize()
     assert torch.equal(ss3, ss) and torch.equal(z3, z), "the entropy output changed the trajectory"
     ent_us = eregion[0].elapsed_time(eregion[1]) / K * 1e3
+
+    # and with the nucleus filter of the paper's evaluation set-up (top-p 0.7) on the same logits
+    params_p = espo.EspoParams(**{**W.RolloutParams().as_dict(), "top_p": 0.7})
+    z4, alive4, ss4 = W.initial_state(B_STEP, device=dev)
+    run(0, Wm, z4, alive4, ss4, params=params_p)
+    torch.cuda.synchronize()
+    pregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    pregion[0].record()
+    run(Wm, total, z4, alive4, ss4, params=params_p)
+    pregion[1].record()
+    torch.cuda.synchronize()
+    topp_us = pregion[0].elapsed_time(pregion[1]) / K * 1e3
+    topp_live = float((alive4 > 0).sum())
     step_bytes = live * (V_STEP * 2 + STEP_SCALAR_BYTES) + (B_STEP - live) * 1
     step_gbs = float(step_bytes.sum() / (region_ms * 1e-3) / 1e9)   # events around the K back-to-back launches
 
@@ -312,6 +325,8 @@ def main() -> int:
                      "traffic": _traffic_from_profiles("espo_step")},
         "step_with_entropy": {"avg_launch_us": ent_us, "frac": step_gbs / HBM_PEAK_GBS * (region_ms / K * 1e3) / ent_us,
                               "mean_entropy_last_step": float(entropy[alive3 > 0].mean()) if bool((alive3 > 0).any()) else None},
+        "step_top_p_0.7": {"avg_launch_us": topp_us, "live_rows_last": topp_live,
+                           "note": "filtered draw: own kernel instantiation, reads parts of the row again"},
         "advantages": {"workload": "B=1024, T=16384 fp32, lengths U[512,16384], 30% stopped, 8 rotated buffer sets",
                        "tokens_per_s": float(valid.sum() / adv_wall), "ms_per_call": adv_wall / args.adv_reps * 1e3,
                        "roofline": {"kernel": "espo_advantages_kernel", "bound": "hbm", "achieved": adv_gbs,

@@ -967,7 +967,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       __syncthreads();
       const int nabove = *sh.nsurv;
       float acc_m = 0.0f, acc_n = 0.0f;
-      if (nabove <= 8 * kStepWaves) {  // the usual case: one block per wave visit, one index per lane, four loads in flight
+      if (nabove <= 16 * kStepWaves) {  // the usual case: one block per wave visit, one index per lane, four loads in flight
 #pragma unroll 1
         for (int base = wave; base < nabove; base += 4 * kStepWaves) {
           float xs[4];
