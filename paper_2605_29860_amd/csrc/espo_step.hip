@@ -21,6 +21,11 @@
 //   test (Eq. step_gap, Eq. normalized_gap, Eq. smoothed_score, Eq. stop_rule).
 // Pruning only ever discards indices that provably cannot attain the maximum, so the
 // token equals the exhaustive double-precision argmax with lowest-index tie-break.
+//
+// Two optional features are template parameters, so that the plain step pays nothing for them:
+// the entropy of the sampling distribution (one more accumulator in phase 1) and filtered
+// draws (top-p / top-k: a table of block maxima in phase 1, and after phase 2 the search for
+// the edge of the kept set, see the comment at `if constexpr (Filter)`).
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -742,7 +747,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   const void* rowp = (const char*)a.logits + (size_t)row * (size_t)a.row_stride * elem_bytes<DT>();
 
   // ------------------------------------------------------------ phase 1: stream the row
-  // Wave iteration i handles tile i*16 + wave.  Lanes whose 16-byte group starts at or beyond
+  // Wave iteration i handles tile i*kStepWaves + wave.  Lanes whose 16-byte group starts at or beyond
   // V (last tile only) read the last valid group instead and are masked below.
   const int my_tiles = wave < ntiles ? (ntiles - wave + kStepWaves - 1) / kStepWaves : 0;
   const uint32_t last_group = (uint32_t)(a.V - 1) & ~7u;
