@@ -25,7 +25,8 @@
  *     stream has reached the point of the call.
  *   - Return value: ESPO_OK (0) or a negative espo_status.  On any error nothing
  *     has been enqueued.
- *   - No global mutable state: calls from several host threads on different
+ *   - No global mutable state (apart from the margin scale of the diagnostics at the
+ *     end of this file, an atomic): calls from several host threads on different
  *     streams are safe as long as they do not share output or workspace buffers.
  *   - A call consists of kernel launches only (no allocation, no copy, no memset,
  *     no synchronisation), so it may be recorded while its stream is being captured
