@@ -81,3 +81,20 @@ def test_input_generators_are_seeded_and_hold_no_method_arithmetic():
     assert all(torch.equal(x, y) for x, y in zip(g1, g2))
     bits = W.to_host_bits(a)
     assert bits.dtype == np.uint16 and bits.shape == (3, 4096)
+
+
+def test_parameter_structs_of_both_sides_have_the_same_layout():
+    # The two sides define their parameter structs separately (they share no code); the fields, their
+    # order, types and defaults must still agree, and both must match the C header's declaration order.
+    import dataclasses
+    import re
+    import oracle.espo_oracle as o
+    from paper_2605_29860_amd import binding as b
+    assert [(n, t) for n, t in b._Params._fields_] == [(n, t) for n, t in o._Params._fields_]
+    gd = {f.name: f.default for f in dataclasses.fields(b.EspoParams)}
+    od = {f.name: f.default for f in dataclasses.fields(o.OracleParams)}
+    assert gd == od and list(gd) == [n for n, _ in b._Params._fields_]
+    header = open(os.path.join(ROOT, "include", "espo.h")).read()
+    body = header[header.index("typedef struct {", header.index("frozen for a whole rollout batch")):header.index("} espo_params;")]
+    declared = re.findall(r"^\s*(?:float|int32_t)\s+(\w+);", body, flags=re.M)
+    assert declared == list(gd)
