@@ -146,6 +146,17 @@ def main() -> int:
     assert torch.equal(ss3, ss) and torch.equal(z3, z), "the entropy output changed the trajectory"
     ent_us = eregion[0].elapsed_time(eregion[1]) / K * 1e3
 
+    # and without the log-probability output (no softmax sum is formed then)
+    z5, alive5, ss5 = fresh_state()
+    nregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    nregion[0].record()
+    for s in range(Wm, total):
+        espo.espo_step(logits[s], tau, seed, s, values[s], params, z5, alive5, ss5, tokens, regret, None)
+    nregion[1].record()
+    torch.cuda.synchronize()
+    assert torch.equal(ss5, ss) and torch.equal(z5, z), "dropping the log-probability output changed the trajectory"
+    nolp_us = nregion[0].elapsed_time(nregion[1]) / K * 1e3
+
     # and with the nucleus filter of the paper's evaluation set-up (top-p 0.7) on the same logits
     params_p = espo.EspoParams(**{**W.RolloutParams().as_dict(), "top_p": 0.7})
     z4, alive4, ss4 = W.initial_state(B_STEP, device=dev)
@@ -325,6 +336,8 @@ def main() -> int:
                      "traffic": _traffic_from_profiles("espo_step")},
         "step_with_entropy": {"avg_launch_us": ent_us, "frac": step_gbs / HBM_PEAK_GBS * (region_ms / K * 1e3) / ent_us,
                               "mean_entropy_last_step": float(entropy[alive3 > 0].mean()) if bool((alive3 > 0).any()) else None},
+        "step_without_logprob": {"avg_launch_us": nolp_us, "frac": step_gbs / HBM_PEAK_GBS * (region_ms / K * 1e3) / nolp_us,
+                                 "note": "logprob = NULL: token, regret, state and masks only, no softmax sum"},
         "step_top_p_0.7": {"avg_launch_us": topp_us, "live_rows_last": topp_live,
                            "note": "filtered draw: own kernel instantiation, reads parts of the row again"},
         "advantages": {"workload": "B=1024, T=16384 fp32, lengths U[512,16384], 30% stopped, 8 rotated buffer sets",

@@ -724,8 +724,9 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
 }
 
 // ---------------------------------------------------------------- the kernel
-template <int DT, bool Entropy, bool Filter>
+template <int DT, bool Entropy, bool Filter, bool Sum>
 __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) {
+  static_assert(Sum || (!Entropy && !Filter), "entropy and filtered draws need the softmax sum");
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
@@ -817,19 +818,24 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
         if (e0 + j >= a.V) x[j] = kNegInf;
     }
     const float gm = fmaxf(fmaxf(fmaxf(fmaxf(fmaxf(x[0], x[1]), x[2]), fmaxf(fmaxf(x[3], x[4]), x[5])), x[6]), x[7]);
-    if (__builtin_amdgcn_ballot_w64(gm > lead) != 0) {  // rare after the first tile
-      asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
-      if (gm > lead) {  // move this lane's reference up to gm
-        const float nrk_new = -gm * a.k2;
-        const float shift = nrk_new - nrk;  // every t_v moves by this much
-        const float f = __builtin_amdgcn_exp2f(shift);
-        if (Entropy) sumw = f * fmaf(shift, sum, sumw);
-        sum *= f;
-        nrk = nrk_new;
-        lead = gm + a.ref_lead;
+    if constexpr (Sum) {
+      if (__builtin_amdgcn_ballot_w64(gm > lead) != 0) {  // rare after the first tile
+        asm volatile("" ::: "memory");  // keep this rare path out of the straight-line code
+        if (gm > lead) {  // move this lane's reference up to gm
+          const float nrk_new = -gm * a.k2;
+          const float shift = nrk_new - nrk;  // every t_v moves by this much
+          const float f = __builtin_amdgcn_exp2f(shift);
+          if (Entropy) sumw = f * fmaf(shift, sum, sumw);
+          sum *= f;
+          nrk = nrk_new;
+          lead = gm + a.ref_lead;
+        }
       }
     }
-    if constexpr (!Entropy) {
+    if constexpr (!Sum) {
+      // nobody asked for the log-probability, the entropy or a filtered draw: token, regret and
+      // state need the row maximum only, and the eight fma / exp2 / add per lane are left out
+    } else if constexpr (!Entropy) {
       float acc0 = __builtin_amdgcn_exp2f(fmaf(x[0], a.k2, nrk));
       float acc1 = __builtin_amdgcn_exp2f(fmaf(x[1], a.k2, nrk));
 #pragma unroll
@@ -903,6 +909,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   float m = kNegInf;
   auto softmax_sum = [&]() {  // after the first barrier: row maximum, then the wave's share of the sum
     m = wave_max(lane < kStepWaves ? sh.m[lane] : kNegInf);
+    if constexpr (!Sum) return;
     const float shift = -fmaf(m, a.k2, nrk);  // from this lane's reference to the row maximum
     const float f = __builtin_amdgcn_exp2f(shift);
     const float part = sum > 0.0f ? sum * f : 0.0f;
@@ -1199,7 +1206,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       a.tokens[row] = tok;
       a.regret[row] = c.g;
       a.z[row] = c.z;
-      if (a.logprob) a.logprob[row] = -c.g - flog(S);
+      if (Sum && a.logprob) a.logprob[row] = -c.g - flog(S);
       if constexpr (Entropy)  // H = ln S - E_pi[y - y_max] >= 0; rounding can leave S a few ulp below 1
         a.entropy[row] = fmaxf(flog(S) - kLn2 * Sw / S, 0.0f);
       if (a.eos_id >= 0 && tok == a.eos_id) {
@@ -1305,13 +1312,17 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   const bool filter = (p.top_p > 0.0f && p.top_p < 1.0f) || p.top_k > 0;
   const size_t lds = step_lds_bytes(dt, a.ntiles, filter);
   if (lds > kMaxStepLds) return ESPO_ERANGE;
+  // and a step that is asked for neither log-probabilities nor either of these needs no softmax sum at all
+  const bool sum = logprob != nullptr || entropy != nullptr || filter;
   void (*kernel)(StepArgs);
   if (dt == ESPO_BF16)
-    kernel = filter ? (entropy ? espo_step_kernel<ESPO_BF16, true, true> : espo_step_kernel<ESPO_BF16, false, true>)
-                    : (entropy ? espo_step_kernel<ESPO_BF16, true, false> : espo_step_kernel<ESPO_BF16, false, false>);
+    kernel = !sum     ? espo_step_kernel<ESPO_BF16, false, false, false>
+             : filter ? (entropy ? espo_step_kernel<ESPO_BF16, true, true, true> : espo_step_kernel<ESPO_BF16, false, true, true>)
+                      : (entropy ? espo_step_kernel<ESPO_BF16, true, false, true> : espo_step_kernel<ESPO_BF16, false, false, true>);
   else
-    kernel = filter ? (entropy ? espo_step_kernel<ESPO_F32, true, true> : espo_step_kernel<ESPO_F32, false, true>)
-                    : (entropy ? espo_step_kernel<ESPO_F32, true, false> : espo_step_kernel<ESPO_F32, false, false>);
+    kernel = !sum     ? espo_step_kernel<ESPO_F32, false, false, false>
+             : filter ? (entropy ? espo_step_kernel<ESPO_F32, true, true, true> : espo_step_kernel<ESPO_F32, false, true, true>)
+                      : (entropy ? espo_step_kernel<ESPO_F32, true, false, true> : espo_step_kernel<ESPO_F32, false, false, true>);
   if (lds > 64 * 1024) {  // beyond the default limit the kernel has to be told (very large vocabularies)
     if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStepLds) != hipSuccess)
       return ESPO_EHIP;

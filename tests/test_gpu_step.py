@@ -550,6 +550,43 @@ def test_two_streams_do_not_interfere():
             np.testing.assert_array_equal(a[k].view(np.uint8), b[k].view(np.uint8), err_msg=f"stream {i} {k}")
 
 
+# --------------------------------------------------------------------------- no log-probability asked for
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_step_without_logprob_gives_the_same_token_and_state(dtype):
+    _say(f"[case] no logprob output {dtype}")
+    # Without the log-probability (and without entropy or a filter) the softmax sum is not formed at all:
+    # another instantiation of the kernel.  Everything else must be the same bits, and the oracle's.
+    import oracle
+    for case, (V, kind, tau) in enumerate([(1, "gauss", 1.0), (37, "gauss", 0.6), (513, "masked", 0.8), (8200, "flat", 1.0),
+                                           (40000, "gauss", 0.05), (152064, "zipf", 0.6)]):
+        B = 5
+        stride = ((V + 7) // 8) * 8 + 8
+        g = torch.Generator().manual_seed(300 + case)
+        x = torch.randn(B, stride, generator=g) * 3.0
+        if kind == "flat":
+            x[:] = 0.25
+        elif kind == "masked":
+            x[:, torch.rand(stride, generator=g) < 0.7] = float("-inf")
+            x[:, V // 2] = 1.0
+        elif kind == "zipf":
+            x[:, :V] += W.ZipfLogits(V=V, seed=case, device="cpu").boost
+        x[:, V:] = 1e4
+        logits = x.to(dtype).cuda()
+        vals = torch.rand(B, generator=g).cuda()
+        gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=0.8)
+        alive0 = torch.tensor([1, 0, 1, 1, 1], dtype=torch.uint8)
+        full, bare = H.GpuState(B, alive=alive0), H.GpuState(B, alive=alive0)
+        for step in range(3):
+            H.compare_step(logits, tau, 19, step, vals, gp, op, full, V=V)
+            espo.espo_step(logits, tau, 19, step, vals, gp, bare.z, bare.alive, bare.stop_step, bare.tokens, bare.regret,
+                           None, V=V)
+            torch.cuda.synchronize()
+            a, b = full.host(), bare.host()
+            for k in ("tokens", "regret", "z", "alive", "stop_step"):
+                np.testing.assert_array_equal(a[k].view(np.uint8), b[k].view(np.uint8), err_msg=f"case {case} step {step} {k}")
+            assert (b["logprob"] == -7.0).all()                  # not written
+
+
 # --------------------------------------------------------------------------- filtered draws
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 def test_top_p_and_top_k_draws_match_the_oracle(dtype):
