@@ -463,10 +463,19 @@ def test_seeded_sweep_of_shapes_structures_and_margins():
         st = H.GpuState(B, z=torch.rand(B, generator=g) * 2 - 1, alive=(torch.rand(B, generator=g) < 0.85).to(torch.uint8))
         vals = torch.rand(B, generator=g).cuda()
         entropy = bool(rng.random() < 0.4)
+        # where nothing needs the softmax sum, the same steps also run without the log-probability output
+        bare = H.GpuState(B, z=st.z, alive=st.alive) if not filt and not entropy else None
         espo.espo_debug_set_score_margin_scale(scale)
         try:
             for step in range(2):
-                H.compare_step(logits, tau, 900 + case, step, vals, gp, op, st, V=V, stats=stats, entropy=entropy)
+                got = H.compare_step(logits, tau, 900 + case, step, vals, gp, op, st, V=V, stats=stats, entropy=entropy)
+                if bare is not None:
+                    espo.espo_step(logits, tau, 900 + case, step, vals, gp, bare.z, bare.alive, bare.stop_step,
+                                   bare.tokens, bare.regret, None, V=V)
+                    torch.cuda.synchronize()
+                    other = bare.host()
+                    for k in ("tokens", "regret", "z", "alive", "stop_step"):
+                        np.testing.assert_array_equal(got[k].view(np.uint8), other[k].view(np.uint8), err_msg=f"no logprob: {k}")
         except AssertionError as err:
             raise AssertionError(f"case {case}: V={V} B={B} {dtype} tau={tau} {kind} scale={scale} mode={mode} "
                                  f"simulate={simulate} entropy={entropy} {filt}: {err}")
