@@ -258,10 +258,11 @@ def main() -> int:
         zc_, ac_, sc_ = W.initial_state(Bc, device=dev)
         tok_c = torch.empty(Bc, dtype=torch.int32, device=dev)
         reg_c = torch.empty(Bc, dtype=torch.float32, device=dev)
+        lp_c = torch.empty(Bc, dtype=torch.float32, device=dev)   # with the log-probability, as in the headline figure
         cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(Sc)]
         for t in range(Sc):
             cev[t][0].record()
-            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, None)
+            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, lp_c)
             cev[t][1].record()
         torch.cuda.synchronize()
         ss_c = sc_.cpu().numpy()
