@@ -8,6 +8,7 @@ from .espo_oracle import (  # noqa: F401
     build_oracle,
     gae_bruteforce,
     advantages,
+    advantages_packed,
     advantages_terminal,
     batch_stats,
     gumbel,

@@ -24,6 +24,7 @@
  *   oracle_advantages  Section 3 (TD error, Eq. gae) on the truncated trajectory of
  *                      Section 4.4 (failure reward at the stop step, no bootstrap).
  *   oracle_gae_bruteforce  Eq. gae written as the explicit double sum, O(L^2).
+ *   oracle_advantages_packed  both forms for trajectories stored back to back
  *   oracle_advantages_terminal  the same for the reward structure of Algorithm 1 (zero
  *                      until the last step), plus the value targets A_t + V(s_t).
  *   oracle_batch_stats Section 4.2 (EMA of the batch mean and variance of the regret) and
@@ -554,6 +555,50 @@ int oracle_advantages_terminal(const float* values, const int32_t* lengths, cons
       td[b * T + t] = delta;
       adv[b * T + t] = A;
       if (ret) ret[b * T + t] = A + (double)val[t];
+    }
+  }
+  return 0;
+}
+
+/*
+ * The same quantities for trajectories stored back to back: trajectory b occupies positions
+ * cu[b] .. cu[b+1]-1 of arrays of N tokens, so a truncated trajectory takes no padding.
+ * Section 3 and Eq. failure_reward on each slice, written out once more for this layout:
+ * rewards == NULL means the reward structure of Algorithm 1 (zero at every step that goes on,
+ * terminal_reward[b] at the last); with a stop the last reward is r_fail in both forms.
+ * An extent is clipped to [0, N] and an empty or reversed one holds no token.  Outputs in
+ * double, written only at the positions some trajectory owns; ret (optional) is A_t + V(s_t),
+ * scale (optional) the magnitude described at oracle_advantages.
+ */
+int oracle_advantages_packed(const float* rewards, const float* terminal_reward, const float* values,
+                             const int64_t* cu, const uint8_t* stopped, int64_t B, int64_t N,
+                             float r_fail, float gamma, float lambda,
+                             double* td, double* adv, double* ret, double* scale) {
+  if (B < 0 || N < 0) return -1;
+  if (B == 0 || N == 0) return 0;
+  if (!values || !cu || !stopped || !td || !adv) return -1;
+  if (!rewards && !terminal_reward) return -1;
+  const double gam = (double)gamma;
+  const double c = (double)gamma * (double)lambda;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t first = cu[b], end = cu[b + 1];
+    if (first < 0) first = 0;
+    if (first > N) first = N;
+    if (end > N) end = N;
+    double A = 0.0, S = 0.0;                     /* nothing follows the last token */
+    for (int64_t i = end - 1; i >= first; --i) {
+      const int is_last = (i == end - 1);
+      double r_i = rewards ? (double)rewards[i] : 0.0;
+      if (is_last && !rewards) r_i = (double)terminal_reward[b];
+      if (is_last && stopped[b]) r_i = (double)r_fail;
+      const double v_next = is_last ? 0.0 : (double)values[i + 1];   /* no bootstrap past the end */
+      const double delta = r_i + gam * v_next - (double)values[i];
+      A = delta + c * A;
+      S = (fabs(r_i) + fabs(gam * v_next) + fabs((double)values[i])) + fabs(c) * S;
+      td[i] = delta;
+      adv[i] = A;
+      if (ret) ret[i] = A + (double)values[i];
+      if (scale) scale[i] = S;
     }
   }
   return 0;

@@ -76,6 +76,8 @@ def _load():
         lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), u64, i32, vp, vp, vp]
         lib.oracle_advantages.restype = C.c_int
         lib.oracle_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
+        lib.oracle_advantages_packed.restype = C.c_int
+        lib.oracle_advantages_packed.argtypes = [vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp, vp]
         lib.oracle_advantages_terminal.restype = C.c_int
         lib.oracle_advantages_terminal.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
         lib.oracle_gae_bruteforce.restype = C.c_int
@@ -254,6 +256,31 @@ def advantages_terminal(values: np.ndarray, lengths: np.ndarray, stopped: np.nda
     if rc != 0:
         raise ValueError("oracle_advantages_terminal: invalid arguments")
     return td, adv, ret
+
+
+def advantages_packed(rewards, terminal_reward, values: np.ndarray, cu_seqlens: np.ndarray, stopped: np.ndarray,
+                      r_fail: float, gamma: float, lam: float):
+    """TD errors, GAE, value targets and the scale (double) for trajectories stored back to
+    back: trajectory b is values[cu_seqlens[b]:cu_seqlens[b+1]].  `rewards` (same layout) or,
+    if it is None, `terminal_reward` [B] with zero reward before the last step.  Positions no
+    trajectory owns come back as NaN."""
+    N = values.shape[0]
+    B = stopped.shape[0]
+    _chk(values, np.float32, (N,), "values")
+    _chk(cu_seqlens, np.int64, (B + 1,), "cu_seqlens")
+    _chk(stopped, np.uint8, (B,), "stopped")
+    if rewards is not None:
+        _chk(rewards, np.float32, (N,), "rewards")
+    if terminal_reward is not None:
+        _chk(terminal_reward, np.float32, (B,), "terminal_reward")
+    td, adv, ret, scale = (np.full(N, np.nan, np.float64) for _ in range(4))
+    rc = _load().oracle_advantages_packed(_ptr(rewards) if rewards is not None else None,
+                                          _ptr(terminal_reward) if terminal_reward is not None else None,
+                                          _ptr(values), _ptr(cu_seqlens), _ptr(stopped), B, N, float(r_fail),
+                                          float(gamma), float(lam), _ptr(td), _ptr(adv), _ptr(ret), _ptr(scale))
+    if rc != 0:
+        raise ValueError("oracle_advantages_packed: invalid arguments")
+    return td, adv, ret, scale
 
 
 def gae_bruteforce(rewards: np.ndarray, values: np.ndarray, lengths: np.ndarray, stopped: np.ndarray,

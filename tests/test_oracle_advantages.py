@@ -211,3 +211,147 @@ def test_terminal_form_textbook_targets(oracle):
     a, b, c = oracle.advantages_terminal(poisoned, lengths, stopped, term, r_fail, gam, 0.95)
     a2, b2, c2 = oracle.advantages_terminal(values, lengths, stopped, term, r_fail, gam, 0.95)
     assert np.array_equal(a, a2) and np.array_equal(b, b2) and np.array_equal(c, c2)
+
+
+# ------------------------------------------------------------------ trajectories stored back to back
+
+def _packed_batch(rng, B, max_len, gap=0):
+    """Random extents (some empty), optional unowned gaps between them."""
+    lens = rng.integers(0, max_len + 1, B)
+    lens[rng.random(B) < 0.15] = 0
+    cu = np.zeros(B + 1, np.int64)
+    starts = np.zeros(B, np.int64)
+    pos = 0
+    for b in range(B):
+        pos += int(rng.integers(0, gap + 1))
+        starts[b] = pos
+        pos += int(lens[b])
+    N = pos + gap
+    values = rng.uniform(-1, 1, N).astype(np.float32)
+    rewards = rng.normal(0, 1, N).astype(np.float32)
+    stopped = (rng.random(B) < 0.4).astype(np.uint8)
+    term = rng.choice(np.array([0.0, 1.0, -0.5], np.float32), B)
+    return lens.astype(np.int64), starts, values, rewards, stopped, term
+
+
+def test_packed_hand_worked_examples(oracle):
+    """The three worked examples of the padded layout, laid end to end (case B keeps 2 of its 3 tokens)."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "gae_hand_example.txt"))
+            if l.strip() and not l.startswith("#")]
+    exp = {}
+    for case, t, td, adv in rows:
+        exp.setdefault(case, []).append((int(t), float(td), float(adv)))
+    v = [0.5, 0.2, -0.1]
+    for gam, lam, names in ((1.0, 0.95, "AB"), (0.5, 0.5, "C")):
+        if names == "AB":
+            values = np.array(v + v[:2], np.float32)
+            rewards = np.array([0, 0, 1, 0, 7], np.float32)          # the stored 7 is replaced by r_fail
+            cu = np.array([0, 3, 5], np.int64)
+            stopped = np.array([0, 1], np.uint8)
+        else:
+            values = np.array([1, 2, 4], np.float32)
+            rewards = np.array([0, 0, 2], np.float32)
+            cu = np.array([0, 3], np.int64)
+            stopped = np.array([0], np.uint8)
+        td, adv, ret, _ = oracle.advantages_packed(rewards, None, values, cu, stopped, -1.0, gam, lam)
+        for k, name in enumerate(names):
+            for t, e_td, e_adv in exp[name]:
+                if cu[k] + t < cu[k + 1]:
+                    assert abs(td[cu[k] + t] - e_td) < 1e-6 and abs(adv[cu[k] + t] - e_adv) < 1e-6, (name, t)
+                    assert abs(ret[cu[k] + t] - (e_adv + float(values[cu[k] + t]))) < 1e-6
+
+
+@pytest.mark.parametrize("gamma,lam", [(1.0, 0.95), (0.99, 0.9), (1.0, 1.0), (0.9, 0.0)])
+def test_packed_equals_explicit_sum_per_slice(oracle, gamma, lam):
+    """Eq. gae written out as a double sum over each slice, both reward forms."""
+    rng = np.random.default_rng(41)
+    B = 20
+    lens, starts, values, rewards, stopped, term = _packed_batch(rng, B, 17)
+    cu = np.concatenate([starts, [starts[-1] + lens[-1]]]).astype(np.int64)
+    g, c = np.float64(np.float32(gamma)), np.float64(np.float32(gamma)) * np.float64(np.float32(lam))
+    for dense in (True, False):
+        td, adv, ret, _ = oracle.advantages_packed(rewards if dense else None, None if dense else term, values, cu,
+                                                   stopped, -1.0, gamma, lam)
+        for b in range(B):
+            s, L = int(cu[b]), int(lens[b])
+            v = values[s:s + L].astype(np.float64)
+            r = rewards[s:s + L].astype(np.float64) if dense else np.zeros(L)
+            if L and not dense:
+                r[-1] = term[b]
+            if L and stopped[b]:
+                r[-1] = -1.0
+            delta = r + g * np.append(v[1:], 0.0) - v if L else np.zeros(0)
+            for t in range(L):
+                want = sum(c ** l * delta[t + l] for l in range(L - t))
+                assert abs(adv[s + t] - want) <= 1e-12 * max(1.0, abs(want))
+                assert td[s + t] == delta[t] and ret[s + t] == adv[s + t] + v[t]
+
+
+def test_packed_agrees_with_the_padded_layout(oracle):
+    rng = np.random.default_rng(42)
+    B, T = 16, 33
+    lens, starts, values, rewards, stopped, term = _packed_batch(rng, B, T)
+    cu = np.concatenate([starts, [starts[-1] + lens[-1]]]).astype(np.int64)
+    pad_r, pad_v = np.zeros((B, T), np.float32), np.zeros((B, T), np.float32)
+    for b in range(B):
+        pad_r[b, :lens[b]] = rewards[cu[b]:cu[b + 1]]
+        pad_v[b, :lens[b]] = values[cu[b]:cu[b + 1]]
+    td_p, adv_p, sc_p = oracle.advantages(pad_r, pad_v, lens.astype(np.int32), stopped, -1.0, 1.0, 0.95)
+    td, adv, ret, sc = oracle.advantages_packed(rewards, None, values, cu, stopped, -1.0, 1.0, 0.95)
+    td_t, adv_t, ret_t = oracle.advantages_terminal(pad_v, lens.astype(np.int32), stopped, term, -1.0, 1.0, 0.95)
+    td2, adv2, ret2, _ = oracle.advantages_packed(None, term, values, cu, stopped, -1.0, 1.0, 0.95)
+    for b in range(B):
+        sl, L = slice(int(cu[b]), int(cu[b + 1])), int(lens[b])
+        assert np.array_equal(td[sl], td_p[b, :L]) and np.array_equal(adv[sl], adv_p[b, :L])
+        assert np.array_equal(sc[sl], sc_p[b, :L])
+        assert np.array_equal(td2[sl], td_t[b, :L]) and np.array_equal(adv2[sl], adv_t[b, :L])
+        assert np.array_equal(ret2[sl], ret_t[b, :L])
+
+
+def test_packed_extents_gaps_and_neighbours(oracle):
+    """Unowned positions are neither read nor written, a trajectory never sees its neighbour,
+    extents are clipped to the arrays and reversed ones are empty."""
+    rng = np.random.default_rng(43)
+    B = 12
+    lens, starts, values, rewards, stopped, term = _packed_batch(rng, B, 9, gap=3)
+    N = values.shape[0]
+    owned = np.zeros(N, bool)
+    for b in range(B):
+        owned[starts[b]:starts[b] + lens[b]] = True
+    values[~owned] = np.nan
+    # with gaps the extents are not a running sum: one call per trajectory, its own two offsets
+    for b in range(B):
+        cu = np.array([starts[b], starts[b] + lens[b]], np.int64)
+        td, adv, ret, _ = oracle.advantages_packed(None, term[b:b + 1], values, cu, stopped[b:b + 1], -1.0, 0.9, 0.95)
+        mine = np.zeros(N, bool)
+        mine[cu[0]:cu[1]] = True
+        assert np.isfinite(td[mine]).all() and np.isfinite(adv[mine]).all() and np.isnan(td[~mine]).all()
+        # the same trajectory on its own gives the same numbers: nothing leaks in from either side
+        alone = oracle.advantages_packed(None, term[b:b + 1], values[cu[0]:cu[1]].copy(), np.array([0, lens[b]], np.int64),
+                                         stopped[b:b + 1], -1.0, 0.9, 0.95)
+        assert np.array_equal(adv[mine], alone[1]) and np.array_equal(ret[mine], alone[2])
+    # clipping: an extent that runs past N ends at N, a negative start begins at 0, a reversed one is empty
+    v = rng.uniform(-1, 1, 10).astype(np.float32)
+    one = np.array([0], np.uint8)
+    ref = oracle.advantages_packed(None, np.ones(1, np.float32), v, np.array([4, 10], np.int64), one, -1.0, 1.0, 0.95)
+    got = oracle.advantages_packed(None, np.ones(1, np.float32), v, np.array([4, 99], np.int64), one, -1.0, 1.0, 0.95)
+    assert np.array_equal(ref[1][4:], got[1][4:])
+    got = oracle.advantages_packed(None, np.ones(1, np.float32), v, np.array([-5, 10], np.int64), one, -1.0, 1.0, 0.95)
+    ref = oracle.advantages_packed(None, np.ones(1, np.float32), v, np.array([0, 10], np.int64), one, -1.0, 1.0, 0.95)
+    assert np.array_equal(ref[1], got[1])
+    got = oracle.advantages_packed(None, np.ones(1, np.float32), v, np.array([7, 3], np.int64), one, -1.0, 1.0, 0.95)
+    assert np.isnan(got[0]).all() and np.isnan(got[1]).all()
+
+
+def test_packed_monte_carlo_return(oracle):
+    """lambda = 1 with the rewards of Algorithm 1: the target is r_end gamma^(L-1-t), whatever the critic says."""
+    rng = np.random.default_rng(44)
+    B = 10
+    lens, starts, values, rewards, stopped, term = _packed_batch(rng, B, 25)
+    cu = np.concatenate([starts, [starts[-1] + lens[-1]]]).astype(np.int64)
+    _, _, ret, _ = oracle.advantages_packed(None, term, values, cu, stopped, -2.0, 0.9, 1.0)
+    g = np.float64(np.float32(0.9))
+    for b in range(B):
+        r_end = -2.0 if stopped[b] else float(term[b])
+        want = r_end * g ** (lens[b] - 1 - np.arange(lens[b]))
+        np.testing.assert_allclose(ret[cu[b]:cu[b + 1]], want, rtol=1e-12, atol=1e-13)
