@@ -222,6 +222,37 @@ def main() -> int:
     advt_us = tregion[0].elapsed_time(tregion[1]) / args.adv_reps * 1e3
     advt_bytes = float(np.mean(valid * 12 + B_ADV * 9))
 
+    # the same trajectories stored back to back: nothing but the valid tokens is read or written
+    pk = []
+    for r, v, L, s in adv_in:
+        mask = torch.arange(T_ADV, device=dev)[None, :] < L[:, None]
+        cu = torch.zeros(B_ADV + 1, dtype=torch.int64, device=dev)
+        cu[1:] = torch.cumsum(L.long(), 0)
+        vp, rp = v[mask].contiguous(), r[mask].contiguous()
+        pk.append((vp, rp, cu, torch.empty_like(vp), torch.empty_like(vp)))
+    del mask
+    def pk_call(i, dense):
+        vp, rp, cu, td, ad = pk[i % nbuf]
+        s = adv_in[i % nbuf][3]
+        if dense:
+            espo.espo_advantages_packed(vp, cu, s, -1.0, 1.0, 0.95, td, ad, rewards=rp)
+        else:
+            espo.espo_advantages_packed(vp, cu, s, -1.0, 1.0, 0.95, td, ad, terminal_reward=adv_term[i % nbuf])
+    pk_us = {}
+    for dense in (True, False):
+        for i in range(nbuf):
+            pk_call(i, dense)
+        torch.cuda.synchronize()
+        kregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        kregion[0].record()
+        for i in range(args.adv_reps):
+            pk_call(i, dense)
+        kregion[1].record()
+        torch.cuda.synchronize()
+        pk_us[dense] = kregion[0].elapsed_time(kregion[1]) / args.adv_reps * 1e3
+    pk_bytes = {True: float(np.mean(valid * 16 + B_ADV * 9)), False: float(np.mean(valid * 12 + B_ADV * 13))}
+    del pk
+
     # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
     bs_sets = [W.regret_batch(512, 8192, seed=70 + i, device=dev) for i in range(nbuf)]   # 134 MB in rotation
     bs_out = torch.zeros(espo.BATCH_RESULT_BYTES, dtype=torch.uint8, device=dev)
@@ -353,6 +384,13 @@ def main() -> int:
                                 "us_per_call": advt_us, "tokens_per_s": float(valid.mean() / advt_us * 1e6),
                                 "algorithmic_bytes_per_call": advt_bytes, "gbs": advt_bytes / advt_us / 1e3,
                                 "frac": advt_bytes / advt_us / 1e3 / HBM_PEAK_GBS},
+        "advantages_packed": {"workload": "the same trajectories stored back to back (cu_seqlens), no padding",
+                              "dense": {"us_per_call": pk_us[True], "algorithmic_bytes_per_call": pk_bytes[True],
+                                        "gbs": pk_bytes[True] / pk_us[True] / 1e3,
+                                        "frac": pk_bytes[True] / pk_us[True] / 1e3 / HBM_PEAK_GBS},
+                              "terminal": {"us_per_call": pk_us[False], "algorithmic_bytes_per_call": pk_bytes[False],
+                                           "gbs": pk_bytes[False] / pk_us[False] / 1e3,
+                                           "frac": pk_bytes[False] / pk_us[False] / 1e3 / HBM_PEAK_GBS}},
         "batch_stats": {"workload": "B=512, T=8192 fp32 regrets, lengths U[64,8192], 25% stopped, 8 rotated sets",
                         "us_per_call": bs_us, "algorithmic_bytes_per_call": bs_bytes,
                         "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,

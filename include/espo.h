@@ -9,11 +9,12 @@
  * the failure reward placed at the stop step (Section 4.4, Eq. failure_reward,
  * Eq. gae).
  *
- * Four operations are exported:
+ * Four operations are exported (the advantage pass in three layouts):
  *   espo_step         one decode step for a batch of trajectories (Algorithm 1 body)
  *   espo_advantages   TD errors + GAE over the truncated trajectories (Section 3, 4.4)
  *   espo_advantages_terminal  the same for the rewards Algorithm 1 produces (zero until
  *                     the last step), optionally with the critic's value targets
+ *   espo_advantages_packed    both for trajectories stored back to back, without padding
  *   espo_batch_stats  update of the frozen statistics and of beta between batches (Section 4.2, 4.3)
  *
  * Conventions for every entry point
@@ -254,6 +255,37 @@ int espo_advantages_terminal(const float* values, const int32_t* lengths, const 
                              const float* terminal_reward, int64_t B, int64_t T,
                              float r_fail, float gamma, float lambda, int32_t zero_padding,
                              float* td, float* adv, float* returns, void* stream);
+
+/*
+ * espo_advantages_packed -- the same pass for trajectories stored back to back.  Early
+ * stopping makes trajectories end long before the horizon (Section 4.4: nothing is decoded
+ * after T_stop), so a [B, T] layout is mostly padding; here trajectory b owns positions
+ * cu_seqlens[b] .. cu_seqlens[b+1]-1 of arrays of N tokens and only those are read and
+ * written: delta_t, A_t (Section 3, Eq. gae) and optionally A_t + V(s_t) over each
+ * trajectory on its own, V := 0 after its last token, r_fail at the last token of a stopped
+ * one (Eq. failure_reward).
+ *
+ * Exactly one of rewards / terminal_reward is given (ESPO_EINVAL otherwise):
+ *   rewards          device, [N] fp32 in the same layout: the dense form of espo_advantages;
+ *   terminal_reward  device, [B] fp32: the form of espo_advantages_terminal (zero reward
+ *                    before the last token).
+ * Other arguments
+ *   values       device, [N] fp32.
+ *   cu_seqlens   device, [B + 1] int64, non-decreasing offsets.  Each extent is clipped to
+ *                [0, N] on the device and an empty or reversed one holds no token, so no
+ *                content of this array leads to an access outside the arrays; extents that
+ *                overlap give unspecified results in the overlap.
+ *   stopped      device, [B] uint8.
+ *   B, N         B >= 0, N >= 0 (either 0 is a no-op).
+ *   td, adv      device, [N] fp32 out; returns device [N] fp32 out or NULL.  Positions
+ *                that no trajectory owns are left as they are.
+ *   All [N] arrays need 16-byte aligned bases (ESPO_EALIGN); offsets need no alignment.
+ *   stream       hipStream_t as void*.
+ */
+int espo_advantages_packed(const float* rewards, const float* terminal_reward, const float* values,
+                           const int64_t* cu_seqlens, const uint8_t* stopped, int64_t B, int64_t N,
+                           float r_fail, float gamma, float lambda,
+                           float* td, float* adv, float* returns, void* stream);
 
 /*
  * espo_batch_stats -- the update at the boundary of a rollout batch: exponential moving

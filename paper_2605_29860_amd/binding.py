@@ -91,6 +91,8 @@ def load_library():
         lib.espo_step_workspace_bytes.restype = sz
         lib.espo_step_workspace_bytes.argtypes = [i64, i64, C.c_int]
         lib.espo_advantages.restype = C.c_int
+        lib.espo_advantages_packed.restype = C.c_int
+        lib.espo_advantages_packed.argtypes = [vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp, vp]
         lib.espo_advantages_terminal.restype = C.c_int
         lib.espo_advantages_terminal.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, i32, vp, vp, vp, vp]
         lib.espo_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
@@ -226,6 +228,30 @@ def espo_advantages(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.
                              _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
                              B, T, float(r_fail), float(gamma), float(lam),
                              _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"), _stream(stream))
+    _check(rc)
+
+
+def espo_advantages_packed(values: torch.Tensor, cu_seqlens: torch.Tensor, stopped: torch.Tensor,
+                           r_fail: float, gamma: float, lam: float, td: torch.Tensor, adv: torch.Tensor,
+                           rewards: torch.Tensor | None = None, terminal_reward: torch.Tensor | None = None,
+                           returns: torch.Tensor | None = None, stream=None) -> None:
+    """The advantage pass over trajectories stored back to back; see `espo_advantages_packed`
+    in include/espo.h.  Exactly one of `rewards` [N] and `terminal_reward` [B]."""
+    lib = load_library()
+    if values.dim() != 1 or cu_seqlens.dim() != 1 or cu_seqlens.numel() != stopped.numel() + 1:
+        raise TypeError("values: need [N]; cu_seqlens: need [B + 1]")
+    N, B = values.numel(), stopped.numel()
+    for name, t in (("td", td), ("adv", adv), ("returns", returns), ("rewards", rewards)):
+        if t is not None and t.numel() != N:
+            raise TypeError(f"{name}: need [N]")
+    if terminal_reward is not None and terminal_reward.numel() != B:
+        raise TypeError("terminal_reward: need [B]")
+    rc = lib.espo_advantages_packed(_dev(rewards, torch.float32, "rewards"),
+                                    _dev(terminal_reward, torch.float32, "terminal_reward"),
+                                    _dev(values, torch.float32, "values"), _dev(cu_seqlens, torch.int64, "cu_seqlens"),
+                                    _dev(stopped, torch.uint8, "stopped"), B, N, float(r_fail), float(gamma), float(lam),
+                                    _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"),
+                                    _dev(returns, torch.float32, "returns"), _stream(stream))
     _check(rc)
 
 

@@ -17,6 +17,12 @@
 // step that goes on, one reward at the last): no reward array is read, the last token takes
 // r_fail or the row's terminal reward, and on request the value targets A_t + V(s_t) are
 // stored and the padding beyond the lengths is left alone.
+//
+// It also serves trajectories stored back to back (extents from cu_seqlens): the workgroup
+// then works on the span that starts at the 16-byte boundary at or before the trajectory's
+// first token, so every lane still moves 16 aligned bytes; the up to three tokens before the
+// first one belong to the neighbour, come last in the backward scan (nothing valid depends on
+// them) and are not stored, and neither is anything at or after the trajectory's end.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -40,6 +46,8 @@ struct AdvArgs {
   float* returns;                // optional [B, T]: A_t + V(s_t)
   int32_t zero_padding;          // write zeros at t >= L (else those positions are not written by whole lanes)
   const float* values;
+  const int64_t* cu;             // packed form: [B + 1] extents into arrays of N tokens
+  int64_t N;
   const int32_t* lengths;
   const uint8_t* stopped;
   int64_t T;
@@ -108,32 +116,56 @@ __device__ __forceinline__ void store4(float* __restrict__ row, int64_t t0, int6
 }
 
 // One step of a weighted inclusive prefix sum over lanes: s += w * (s of the lane the DPP control names).
+// Stores x[j] at t0 + j for lo <= t0 + j < hi (t0 a multiple of 4, the row 16-byte aligned).
+__device__ __forceinline__ void store_span(float* __restrict__ row, int64_t t0, int64_t lo, int64_t hi, const float x[kPerLane]) {
+  if (t0 >= lo && t0 + kPerLane <= hi) {
+    __builtin_nontemporal_store(f32x4{x[0], x[1], x[2], x[3]}, (f32x4*)(row + t0));
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < kPerLane; ++j)
+    if (t0 + j >= lo && t0 + j < hi) row[t0 + j] = x[j];
+}
+
 template <int Ctrl, int RowMask>
 __device__ __forceinline__ float scan_step(float s, float w) {
   return fmaf(w, dpp_f32<Ctrl, RowMask>(0.0f, s), s);
 }
 
-template <bool VEC, bool Dense>
+template <bool VEC, bool Dense, bool Packed>
 __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs a) {
   __shared__ float s_tot[2][kAdvWaves];  // wave totals, double-buffered by tile parity
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int64_t T = a.T;
-  int64_t L = a.lengths[row];
-  L = L < 0 ? 0 : (L > T ? T : L);
+  int64_t T = a.T;
+  int64_t L, base = (int64_t)row * T, head = 0;
+  if constexpr (Packed) {
+    // extent clipped to the arrays; the span starts at the 16-byte boundary at or before it
+    int64_t first = a.cu[row], end = a.cu[row + 1];
+    first = first < 0 ? 0 : (first > a.N ? a.N : first);
+    end = end > a.N ? a.N : end;
+    if (end <= first) return;
+    base = first & ~(int64_t)(kPerLane - 1);
+    head = first - base;
+    L = end - base;
+    T = L;
+  } else {
+    L = a.lengths[row];
+    L = L < 0 ? 0 : (L > T ? T : L);
+  }
   const bool stopped = a.stopped[row] != 0;
   // reward of the last token where it does not come from the reward array: r_fail after a stop
   // (Eq. failure_reward), the row's terminal reward in the terminal form
   const bool last_given = stopped || !Dense;
   float r_last = a.r_fail;
   if (!Dense && !stopped) r_last = a.terminal_reward[row];
-  const float* rrow = Dense ? a.rewards + (int64_t)row * T : nullptr;
-  const float* vrow = a.values + (int64_t)row * T;
-  float* drow = a.td + (int64_t)row * T;
-  float* arow = a.adv + (int64_t)row * T;
-  float* trow = a.returns ? a.returns + (int64_t)row * T : nullptr;
+  const float* rrow = Dense ? a.rewards + base : nullptr;
+  const float* vrow = a.values + base;
+  float* drow = a.td + base;
+  float* arow = a.adv + base;
+  float* trow = a.returns ? a.returns + base : nullptr;
 
   const int64_t ntiles = (T + kAdvTile - 1) / kAdvTile;
   const int64_t nvalid = (L + kAdvTile - 1) / kAdvTile;  // tiles that hold at least one valid token
@@ -141,7 +173,7 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
 
   // tiles wholly beyond the trajectory: outputs are exactly zero
   const float zero[kPerLane] = {0, 0, 0, 0};
-  if (a.zero_padding) {
+  if (!Packed && a.zero_padding) {
     for (int64_t k = ntiles - 1; k >= nvalid; --k) {
       store4<VEC>(drow, k * kAdvTile + lane_off, T, zero);
       store4<VEC>(arow, k * kAdvTile + lane_off, T, zero);
@@ -222,15 +254,21 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
     float outA[kPerLane];
 #pragma unroll
     for (int j = 0; j < kPerLane; ++j) outA[j] = (j < rem) ? fmaf(a.cj[kPerLane - j], a_next, loc[j]) : 0.0f;
-    if (a.zero_padding || rem > 0) {  // lanes wholly beyond L only ever hold zeros
+    float outR[kPerLane] = {0, 0, 0, 0};  // value targets: the lambda-return A_t + V(s_t)
+    if (trow) {
+#pragma unroll
+      for (int j = 0; j < kPerLane; ++j) outR[j] = (j < rem) ? outA[j] + cur.v[j] : 0.0f;
+    }
+    if constexpr (Packed) {  // only what the trajectory owns
+      if (rem > 0 && t0 + kPerLane > head) {
+        store_span(drow, t0, head, L, d);
+        store_span(arow, t0, head, L, outA);
+        if (trow) store_span(trow, t0, head, L, outR);
+      }
+    } else if (a.zero_padding || rem > 0) {  // lanes wholly beyond L only ever hold zeros
       store4<VEC>(drow, t0, T, d);
       store4<VEC>(arow, t0, T, outA);
-      if (trow) {  // value targets: the lambda-return A_t + V(s_t)
-        float outR[kPerLane];
-#pragma unroll
-        for (int j = 0; j < kPerLane; ++j) outR[j] = (j < rem) ? outA[j] + cur.v[j] : 0.0f;
-        store4<VEC>(trow, t0, T, outR);
-      }
+      if (trow) store4<VEC>(trow, t0, T, outR);
     }
     if (k > 0) cur = nxt;
   }
@@ -239,7 +277,7 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
 }  // namespace
 
 int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
-                      const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
+                      const int64_t* cu, int64_t N, const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
                       float lambda, int zero_padding, float* td, float* adv, float* returns, hipStream_t stream) {
   AdvArgs a;
   a.rewards = rewards;
@@ -248,6 +286,8 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
   a.zero_padding = zero_padding;
   a.values = values;
   a.lengths = lengths;
+  a.cu = cu;
+  a.N = N;
   a.stopped = stopped;
   a.T = T;
   a.r_fail = r_fail;
@@ -261,8 +301,12 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
   a.adv = adv;
   const bool vec = (T % 4 == 0);
   const dim3 grid((unsigned)B), block(kAdvThreads);
-  void (*kernel)(AdvArgs) = rewards ? (vec ? espo_advantages_kernel<true, true> : espo_advantages_kernel<false, true>)
-                                    : (vec ? espo_advantages_kernel<true, false> : espo_advantages_kernel<false, false>);
+  void (*kernel)(AdvArgs);
+  if (cu)
+    kernel = rewards ? espo_advantages_kernel<true, true, true> : espo_advantages_kernel<true, false, true>;
+  else
+    kernel = rewards ? (vec ? espo_advantages_kernel<true, true, false> : espo_advantages_kernel<false, true, false>)
+                     : (vec ? espo_advantages_kernel<true, false, false> : espo_advantages_kernel<false, false, false>);
   hipLaunchKernelGGL(kernel, grid, block, 0, stream, a);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }

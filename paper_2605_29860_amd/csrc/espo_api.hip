@@ -125,7 +125,7 @@ int espo_advantages(const float* rewards, const float* values, const int32_t* le
   if (!rewards || !values || !lengths || !stopped || !td || !adv) return ESPO_EINVAL;
   if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
   if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv)) return ESPO_EALIGN;
-  return espo::launch_advantages(rewards, nullptr, values, lengths, stopped, B, T, r_fail, gamma, lambda, 1, td, adv,
+  return espo::launch_advantages(rewards, nullptr, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda, 1, td, adv,
                                  nullptr, (hipStream_t)stream);
 }
 
@@ -139,8 +139,23 @@ int espo_advantages_terminal(const float* values, const int32_t* lengths, const 
   if (!values || !lengths || !stopped || !terminal_reward || !td || !adv) return ESPO_EINVAL;
   if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
   if (!aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns)) return ESPO_EALIGN;
-  return espo::launch_advantages(nullptr, terminal_reward, values, lengths, stopped, B, T, r_fail, gamma, lambda,
+  return espo::launch_advantages(nullptr, terminal_reward, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda,
                                  zero_padding != 0, td, adv, returns, (hipStream_t)stream);
+}
+
+int espo_advantages_packed(const float* rewards, const float* terminal_reward, const float* values,
+                           const int64_t* cu_seqlens, const uint8_t* stopped, int64_t B, int64_t N, float r_fail,
+                           float gamma, float lambda, float* td, float* adv, float* returns, void* stream) {
+  if (B < 0 || N < 0) return ESPO_EINVAL;
+  if (!isfinite(gamma) || !isfinite(lambda) || isnan(r_fail)) return ESPO_EINVAL;
+  if (B == 0 || N == 0) return ESPO_OK;
+  if ((rewards != nullptr) == (terminal_reward != nullptr)) return ESPO_EINVAL;  // exactly one form
+  if (!values || !cu_seqlens || !stopped || !td || !adv) return ESPO_EINVAL;
+  if (B > 0x7fffffff) return ESPO_ERANGE;
+  if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns))
+    return ESPO_EALIGN;
+  return espo::launch_advantages(rewards, terminal_reward, values, nullptr, cu_seqlens, N, stopped, B, 0, r_fail, gamma,
+                                 lambda, 0, td, adv, returns, (hipStream_t)stream);
 }
 
 }  // extern "C"

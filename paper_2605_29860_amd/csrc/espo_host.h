@@ -28,8 +28,9 @@ int launch_batch_stats(const float* regret, const int32_t* lengths, const uint8_
 int launch_math_errors(float* out, hipStream_t stream);
 
 // rewards != nullptr: dense form; else the terminal form with terminal_reward[B].
+// cu != nullptr: trajectories stored back to back in arrays of N tokens (lengths, T, zero_padding unused).
 int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
-                      const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
+                      const int64_t* cu, int64_t N, const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
                       float lambda, int zero_padding, float* td, float* adv, float* returns, hipStream_t stream);
 
 }  // namespace espo

@@ -198,3 +198,41 @@ def check_advantages_terminal(values, lengths, stopped, term, r_fail, gamma, lam
             if len(err):
                 worst = max(worst, float((err / np.maximum(scale[~pad], 1e-30)).max()))
     return worst
+
+
+def check_advantages_packed(values, cu, stopped, r_fail, gamma, lam, rewards=None, term=None, want_returns=True,
+                            rtol=RTOL_F32):
+    """The packed layout against its oracle.  Tolerances as in `check_advantages`; positions that
+    no trajectory owns must keep what they held, bit for bit."""
+    N = values.numel()
+    FILL = 7.0
+    td = torch.full((N,), FILL, dtype=torch.float32, device=values.device)
+    adv = torch.full((N,), FILL, dtype=torch.float32, device=values.device)
+    ret = torch.full((N,), FILL, dtype=torch.float32, device=values.device) if want_returns else None
+    espo.espo_advantages_packed(values, cu, stopped, r_fail, gamma, lam, td, adv, rewards=rewards, terminal_reward=term,
+                                returns=ret)
+    torch.cuda.synchronize()
+    v_h, cu_h, s_h = values.cpu().numpy(), cu.cpu().numpy(), stopped.cpu().numpy()
+    r_h = rewards.cpu().numpy() if rewards is not None else None
+    t_h = term.cpu().numpy() if term is not None else None
+    td_o, adv_o, ret_o, scale = oracle.advantages_packed(r_h, t_h, v_h, cu_h, s_h, r_fail, gamma, lam)
+    owned = ~np.isnan(td_o)                                  # the oracle writes only what a trajectory owns
+    outs = [("td", td, td_o), ("adv", adv, adv_o)] + ([("returns", ret, ret_o)] if want_returns else [])
+    worst = 0.0
+    for name, g, o in outs:
+        g = g.cpu().numpy().astype(np.float64)
+        assert (g[~owned] == FILL).all(), f"{name}: a position that no trajectory owns was written"
+        assert np.isfinite(g[owned]).all(), name
+        err = np.abs(g - o)[owned]
+        if name == "td":
+            # delta_t is three fp32 operations on exact inputs, judged against the size of its terms
+            v_abs = np.abs(np.nan_to_num(v_h.astype(np.float64)))
+            r_abs = np.abs(np.nan_to_num(r_h.astype(np.float64))) if r_h is not None else np.abs(t_h.astype(np.float64)).max(initial=0.0)
+            mag = (r_abs + abs(r_fail) + v_abs + np.append(v_abs[1:], 0.0) + 1)[owned]
+            assert (err <= 4e-7 * mag).all(), (name, err.max())
+        else:
+            tol = (rtol * np.maximum(np.abs(o), scale))[owned]
+            assert (err <= tol).all(), (name, err.max(), int((err - tol).argmax()))
+            if len(err):
+                worst = max(worst, float((err / np.maximum(scale[owned], 1e-30)).max()))
+    return worst

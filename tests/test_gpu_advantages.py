@@ -193,3 +193,123 @@ def test_seeded_sweep_of_both_forms():
         except AssertionError as err:
             raise AssertionError(f"case {case}: T={T} B={B} gamma={gamma} lambda={lam} r_fail={r_fail}: {err}")
     _say(f"  worst scaled error {worst:.2e}")
+
+
+# ------------------------------------------------------------------ trajectories stored back to back
+
+def _packed(lens, seed, gaps=None, scale=1.0, stop_p=0.4):
+    """Values, rewards, extents for the given lengths; `gaps[b]` unowned tokens (NaN) before trajectory b."""
+    g = torch.Generator().manual_seed(seed)
+    B = len(lens)
+    gaps = [0] * B if gaps is None else gaps
+    starts, pos = [], 0
+    for b in range(B):
+        pos += gaps[b]
+        starts.append(pos)
+        pos += lens[b]
+    N = pos
+    values = (torch.rand(N, generator=g) * 2 - 1) * scale
+    rewards = torch.randn(N, generator=g)
+    owned = torch.zeros(N, dtype=torch.bool)
+    for b in range(B):
+        owned[starts[b]:starts[b] + lens[b]] = True
+    values[~owned] = float("nan")
+    rewards[~owned] = float("nan")
+    stopped = (torch.rand(B, generator=g) < stop_p).to(torch.uint8)
+    term = torch.randn(B, generator=g)
+    return values.cuda(), rewards.cuda(), starts, stopped.cuda(), term.cuda()
+
+
+def _check_packed_both_forms(lens, seed, gaps=None, gamma=1.0, lam=0.95, r_fail=-1.0, scale=1.0):
+    """With gaps the extents are not one running sum, so gapped layouts go one call per extent pair:
+    cu = [start_b, end_b] is a valid one-trajectory call into the same arrays."""
+    v, r, starts, s, term = _packed(lens, seed, gaps, scale)
+    worst = 0.0
+    if gaps is None:
+        cu = torch.tensor(starts + [starts[-1] + lens[-1]] if lens else [0], dtype=torch.int64).cuda()
+        worst = max(worst, H.check_advantages_packed(v, cu, s, r_fail, gamma, lam, rewards=r, want_returns=False))
+        worst = max(worst, H.check_advantages_packed(v, cu, s, r_fail, gamma, lam, term=term, want_returns=True))
+    else:
+        for b in range(len(lens)):
+            cu = torch.tensor([starts[b], starts[b] + lens[b]], dtype=torch.int64).cuda()
+            worst = max(worst, H.check_advantages_packed(v, cu, s[b:b + 1], r_fail, gamma, lam, rewards=r, want_returns=True))
+            worst = max(worst, H.check_advantages_packed(v, cu, s[b:b + 1], r_fail, gamma, lam, term=term[b:b + 1], want_returns=False))
+    return worst
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 4, 5, 7, 8, 63, 64, 257, 4093, 4096, 4097, 8191, 8200, 12289])
+def test_packed_every_alignment_of_start_and_end(L):
+    _say(f"[case] packed advantages, L={L}")
+    # neighbours of 1..3 tokens shift the start through all four alignments; each one is a trajectory itself
+    lens = [L, 1, L, 2, L, 3, L, 0, L, 5, 0, 0, L]
+    for gamma, lam in ((1.0, 0.95), (0.99, 0.9), (1.0, 1.0), (0.9, 0.0)):
+        _check_packed_both_forms(lens, seed=L, gamma=gamma, lam=lam)
+
+
+def test_packed_gaps_are_neither_read_nor_written():
+    _say("[case] packed advantages, unowned gaps")
+    lens = [5, 4096, 1, 300, 4099, 2, 8193]
+    gaps = [3, 1, 2, 5, 0, 7, 1]
+    _check_packed_both_forms(lens, seed=11, gaps=gaps)
+
+
+def test_packed_extents_are_clipped_and_empty_batches():
+    _say("[case] packed advantages, clipping / empty")
+    v, r, starts, s, term = _packed([100, 50], seed=12)
+    N = v.numel()
+    td, adv = torch.full((N,), 7.0, device="cuda"), torch.full((N,), 7.0, device="cuda")
+    ref_td, ref_adv = torch.full((N,), 7.0, device="cuda"), torch.full((N,), 7.0, device="cuda")
+    espo.espo_advantages_packed(v, torch.tensor([0, 100, 150]).cuda(), s, -1.0, 1.0, 0.95, ref_td, ref_adv, terminal_reward=term)
+    espo.espo_advantages_packed(v, torch.tensor([-9, 100, 10**12]).cuda(), s, -1.0, 1.0, 0.95, td, adv, terminal_reward=term)
+    torch.cuda.synchronize()
+    assert torch.equal(td, ref_td) and torch.equal(adv, ref_adv)
+    td.fill_(7.0)
+    espo.espo_advantages_packed(v, torch.tensor([120, 30, 10]).cuda(), s, -1.0, 1.0, 0.95, td, adv, terminal_reward=term)
+    torch.cuda.synchronize()
+    assert (td == 7.0).all()                                  # reversed extents hold no token
+    H.check_advantages_packed(v, torch.tensor([-9, 100, 10**12]).cuda(), s, -1.0, 1.0, 0.95, rewards=r)
+    e = torch.zeros(0, device="cuda")
+    espo.espo_advantages_packed(e, torch.zeros(1, dtype=torch.int64, device="cuda"), torch.zeros(0, dtype=torch.uint8, device="cuda"),
+                                -1.0, 1.0, 0.95, e.clone(), e.clone(), terminal_reward=e.clone())
+    with pytest.raises(espo.EspoError):                       # both reward forms at once
+        espo.espo_advantages_packed(v, torch.tensor([0, 100, 150]).cuda(), s, -1.0, 1.0, 0.95, td, adv, rewards=r, terminal_reward=term)
+    with pytest.raises(espo.EspoError):                       # a view that starts 4 bytes into an allocation
+        espo.espo_advantages_packed(v[1:], torch.tensor([0, 100, 149]).cuda(), s, -1.0, 1.0, 0.95, td[1:], adv[1:], terminal_reward=term)
+
+
+def test_packed_config5_full_size():
+    _say("[case] config 5 stored back to back (B=1024, lengths as in the padded workload)")
+    r, v, L, s = W.advantage_batch(device="cuda", poison=False, seed=5)
+    B, T = v.shape
+    valid = torch.arange(T, device="cuda")[None, :] < L[:, None]
+    cu = torch.zeros(B + 1, dtype=torch.int64, device="cuda")
+    cu[1:] = torch.cumsum(L.long(), 0)
+    vp, rp = v[valid].contiguous(), r[valid].contiguous()
+    rows = torch.arange(B, device="cuda")
+    term = r[rows, (L - 1).clamp(min=0).long()].contiguous()
+    _say(f"  N = {vp.numel()} of {B * T}")
+    worst = H.check_advantages_packed(vp, cu, s, -1.0, 1.0, 0.95, rewards=rp, want_returns=False)
+    _say(f"  dense form: worst scaled error {worst:.2e}")
+    worst = H.check_advantages_packed(vp, cu, s, -1.0, 1.0, 0.95, term=term, want_returns=True)
+    _say(f"  terminal form: worst scaled error {worst:.2e}")
+
+
+def test_packed_seeded_sweep():
+    _say("[case] packed advantages, seeded sweep")
+    rng = np.random.default_rng(5151)
+    worst = 0.0
+    for case in range(120):
+        B = int(rng.integers(1, 24))
+        top = int(rng.choice([8, 200, 5000, 14000]))
+        lens = [int(x) for x in rng.integers(0, top + 1, B)]
+        for b in range(B):
+            if rng.random() < 0.15:
+                lens[b] = 0
+        gamma, lam = float(rng.choice([1.0, 0.99, 0.9])), float(rng.choice([0.95, 1.0, 0.0, 0.5]))
+        r_fail = float(rng.choice([-1.0, -0.25, 0.0]))
+        try:
+            worst = max(worst, _check_packed_both_forms(lens, 9000 + case, gamma=gamma, lam=lam, r_fail=r_fail,
+                                                        scale=float(rng.choice([1.0, 30.0]))))
+        except AssertionError as err:
+            raise AssertionError(f"case {case}: lens={lens[:8]}... gamma={gamma} lambda={lam} r_fail={r_fail}: {err}")
+    _say(f"  worst scaled error {worst:.2e}")

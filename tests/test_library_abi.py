@@ -28,7 +28,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
-    assert {"espo_step", "espo_advantages", "espo_advantages_terminal", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
+    assert {"espo_step", "espo_advantages", "espo_advantages_terminal", "espo_advantages_packed", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
             "espo_debug_set_score_margin_scale", "espo_debug_math_errors", "espo_debug_copy", "espo_batch_stats",
             "espo_batch_stats_workspace_bytes"} <= set(names)
     for n in names:
@@ -67,4 +67,11 @@ def test_argument_checks_need_no_gpu(lib):
     assert term(B=0) == 0 and term(T=0) == 0
     assert term(B=-1) == -1 and term(g=float("nan")) == -1 and term(values=None) == -1
     assert term(ret=ctypes.c_void_p(0x1004)) == -2          # misaligned optional output
+    lib.espo_advantages_packed.argtypes = [ctypes.c_void_p] * 5 + [ctypes.c_int64] * 2 + [ctypes.c_float] * 3 + [ctypes.c_void_p] * 4
+    packed = lambda r=None, term=fake, B=1, N=8, g=1.0, cu=fake, ret=None: lib.espo_advantages_packed(
+        r, term, fake, cu, fake, B, N, -1.0, g, 0.95, fake, fake, ret, None)
+    assert packed(B=0) == 0 and packed(N=0) == 0
+    assert packed(B=-1) == -1 and packed(N=-1) == -1 and packed(g=float("nan")) == -1 and packed(cu=None) == -1
+    assert packed(r=fake, term=fake) == -1 and packed(r=None, term=None) == -1   # exactly one reward form
+    assert packed(ret=ctypes.c_void_p(0x1004)) == -2 and packed(r=ctypes.c_void_p(0x1008), term=None) == -2
     assert lib.espo_step_workspace_bytes(512, 152064, 1) == 0
