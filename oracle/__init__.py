@@ -21,4 +21,5 @@ from .espo_oracle import (  # noqa: F401
     step,
     stream_word,
     uniform,
+    whiten,
 )

@@ -27,6 +27,8 @@
  *   oracle_advantages_packed  both forms for trajectories stored back to back
  *   oracle_advantages_terminal  the same for the reward structure of Algorithm 1 (zero
  *                      until the last step), plus the value targets A_t + V(s_t).
+ *   oracle_whiten      advantage whitening over the valid tokens (standard PPO practice),
+ *                      two-pass definitions.
  *   oracle_batch_stats Section 4.2 (EMA of the batch mean and variance of the regret) and
  *                      Eq. beta_update, plain two-pass definitions.
  *   stop_decision      Eq. stop_rule and the replacement tests of the ablations (Section 6,
@@ -600,6 +602,58 @@ int oracle_advantages_packed(const float* rewards, const float* terminal_reward,
       if (ret) ret[i] = A + (double)values[i];
       if (scale) scale[i] = S;
     }
+  }
+  return 0;
+}
+
+/*
+ * Advantage whitening over the valid tokens of a batch, the normalisation that PPO
+ * implementations apply to the GAE output before the clipped objective (the paper keeps the
+ * standard PPO update, Section 3, and does not spell this step out): with n = sum_b L_b,
+ *   mean = sum A / n,   var = sum (A - mean)^2 / (n - ddof),
+ *   out[b,t] = (A[b,t] - (shift_mean ? mean : 0)) / sqrt(var + eps)        for t < L_b.
+ * Plain two-pass definitions in double.  Positions at t >= L_b are neither read nor written.
+ * With n - ddof <= 0 the variance is taken as 0.  stats (optional): mean, var, n.
+ */
+int oracle_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps,
+                  int shift_mean, int ddof, double* out, double* stats) {
+  if (B < 0 || T < 0 || ddof < 0 || ddof > 1) return -1;
+  if (stats) stats[0] = stats[1] = stats[2] = 0.0;
+  if (B == 0 || T == 0) return 0;
+  if (!adv || !lengths || !out) return -1;
+  double n = 0.0, sum = 0.0;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    for (int64_t t = 0; t < L; ++t) sum += (double)adv[b * T + t];
+    n += (double)L;
+  }
+  if (n == 0.0) return 0;
+  const double mean = sum / n;
+  double ss = 0.0;
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    for (int64_t t = 0; t < L; ++t) {
+      const double d = (double)adv[b * T + t] - mean;
+      ss += d * d;
+    }
+  }
+  const double var = (n - (double)ddof > 0.0) ? ss / (n - (double)ddof) : 0.0;
+  const double sd = sqrt(var + (double)eps);
+  for (int64_t b = 0; b < B; ++b) {
+    int64_t L = lengths[b];
+    if (L < 0) L = 0;
+    if (L > T) L = T;
+    for (int64_t t = 0; t < L; ++t)
+      out[b * T + t] = ((double)adv[b * T + t] - (shift_mean ? mean : 0.0)) / sd;
+  }
+  if (stats) {
+    stats[0] = mean;
+    stats[1] = var;
+    stats[2] = n;
   }
   return 0;
 }

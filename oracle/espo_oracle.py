@@ -76,6 +76,8 @@ def _load():
         lib.oracle_state_update.argtypes = [i64, vp, vp, vp, C.POINTER(_Params), u64, i32, vp, vp, vp]
         lib.oracle_advantages.restype = C.c_int
         lib.oracle_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
+        lib.oracle_whiten.restype = C.c_int
+        lib.oracle_whiten.argtypes = [vp, vp, i64, i64, f32, C.c_int, C.c_int, vp, vp]
         lib.oracle_advantages_packed.restype = C.c_int
         lib.oracle_advantages_packed.argtypes = [vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp, vp]
         lib.oracle_advantages_terminal.restype = C.c_int
@@ -281,6 +283,20 @@ def advantages_packed(rewards, terminal_reward, values: np.ndarray, cu_seqlens: 
     if rc != 0:
         raise ValueError("oracle_advantages_packed: invalid arguments")
     return td, adv, ret, scale
+
+
+def whiten(adv: np.ndarray, lengths: np.ndarray, eps: float = 1e-8, shift_mean: bool = True, unbiased: bool = False):
+    """Whitened advantages (double; NaN where t >= L) and (mean, var, n) over the valid tokens."""
+    B, T = adv.shape
+    _chk(adv, np.float32, (B, T), "adv")
+    _chk(lengths, np.int32, (B,), "lengths")
+    out = np.full((B, T), np.nan, np.float64)
+    stats = np.zeros(3, np.float64)
+    rc = _load().oracle_whiten(_ptr(adv), _ptr(lengths), B, T, float(eps), int(bool(shift_mean)), int(bool(unbiased)),
+                               _ptr(out), _ptr(stats))
+    if rc != 0:
+        raise ValueError("oracle_whiten: invalid arguments")
+    return out, stats
 
 
 def gae_bruteforce(rewards: np.ndarray, values: np.ndarray, lengths: np.ndarray, stopped: np.ndarray,
