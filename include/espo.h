@@ -9,13 +9,14 @@
  * the failure reward placed at the stop step (Section 4.4, Eq. failure_reward,
  * Eq. gae).
  *
- * Four operations are exported (the advantage pass in three layouts):
+ * Five operations are exported (the advantage pass in three layouts):
  *   espo_step         one decode step for a batch of trajectories (Algorithm 1 body)
  *   espo_advantages   TD errors + GAE over the truncated trajectories (Section 3, 4.4)
  *   espo_advantages_terminal  the same for the rewards Algorithm 1 produces (zero until
  *                     the last step), optionally with the critic's value targets
  *   espo_advantages_packed    both for trajectories stored back to back, without padding
  *   espo_batch_stats  update of the frozen statistics and of beta between batches (Section 4.2, 4.3)
+ *   espo_whiten       whitening of the advantages over the valid tokens (standard PPO step)
  *
  * Conventions for every entry point
  *   - "device" pointers are HIP device memory owned by the caller; the library
@@ -342,6 +343,38 @@ int espo_batch_stats(const float* regret, const int32_t* lengths, const uint8_t*
 
 /* Bytes of workspace espo_batch_stats needs (at most 32 KiB). */
 size_t espo_batch_stats_workspace_bytes(int64_t B, int64_t T);
+
+/*
+ * espo_whiten -- advantage whitening over the valid tokens of a batch: the normalisation
+ * that PPO implementations apply to the GAE output before the clipped objective.  (The paper
+ * keeps the standard PPO update, Section 3, and does not spell this step out; it belongs
+ * to the training step that consumes espo_advantages' output.)  With n = sum_b L_b,
+ * L_b = min(max(lengths[b], 0), T):
+ *   mean = sum A / n,    var = sum (A - mean)^2 / (n - (unbiased ? 1 : 0))   (0 if that divisor is <= 0)
+ *   out[b,t] = (A[b,t] - (shift_mean ? mean : 0)) / sqrt(var + eps)           for t < L_b,
+ * sums in double, each element normalised in double and rounded to float once.  Positions
+ * at t >= L_b are neither read nor written.  The result does not depend on scheduling
+ * (fixed reduction order).  With n = 0 nothing is written to out.
+ *
+ * Arguments
+ *   adv        device, [B, T] fp32 row-major, 16-byte aligned base.  Trajectories stored
+ *              back to back (espo_advantages_packed) are the case B = 1, T = N, lengths = {N}.
+ *   lengths    device, [B] int32.
+ *   B, T       B >= 0, T >= 0 (either 0 is a no-op).
+ *   eps        >= 0, finite (common choice: 1e-8).
+ *   shift_mean, unbiased   flags as above.
+ *   out        device, [B, T] fp32, 16-byte aligned base; may be the same array as adv.
+ *   stats      device, 3 doubles (mean, var, n) written by the call, or NULL; 8-byte aligned.
+ *   workspace  device scratch of at least espo_whiten_workspace_bytes(B, T) bytes, 8-byte
+ *              aligned; contents before and after the call are irrelevant.
+ *   stream     hipStream_t as void*.
+ */
+int espo_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps,
+                int32_t shift_mean, int32_t unbiased, float* out, double* stats,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace espo_whiten needs (at most 32 KiB). */
+size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
 
 /*
  * Diagnostics for the callers that test the library (not part of the method): espo_step

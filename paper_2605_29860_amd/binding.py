@@ -91,6 +91,10 @@ def load_library():
         lib.espo_step_workspace_bytes.restype = sz
         lib.espo_step_workspace_bytes.argtypes = [i64, i64, C.c_int]
         lib.espo_advantages.restype = C.c_int
+        lib.espo_whiten.restype = C.c_int
+        lib.espo_whiten.argtypes = [vp, vp, i64, i64, f32, i32, i32, vp, vp, vp, C.c_size_t, vp]
+        lib.espo_whiten_workspace_bytes.restype = C.c_size_t
+        lib.espo_whiten_workspace_bytes.argtypes = [i64, i64]
         lib.espo_advantages_packed.restype = C.c_int
         lib.espo_advantages_packed.argtypes = [vp, vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp, vp]
         lib.espo_advantages_terminal.restype = C.c_int
@@ -228,6 +232,32 @@ def espo_advantages(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.
                              _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
                              B, T, float(r_fail), float(gamma), float(lam),
                              _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"), _stream(stream))
+    _check(rc)
+
+
+def espo_whiten_workspace_bytes(B: int, T: int) -> int:
+    return int(load_library().espo_whiten_workspace_bytes(B, T))
+
+
+def espo_whiten(adv: torch.Tensor, lengths: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor, eps: float = 1e-8,
+                shift_mean: bool = True, unbiased: bool = False, stats: torch.Tensor | None = None, stream=None) -> None:
+    """Whitening of the advantages over the valid tokens; see `espo_whiten` in include/espo.h.
+    `adv` is [B, T] (or [N] with `lengths` = [N] for a packed batch); `out` may be `adv`."""
+    lib = load_library()
+    if adv.dim() == 1:
+        B, T = 1, adv.numel()
+    elif adv.dim() == 2:
+        B, T = adv.shape
+    else:
+        raise TypeError("adv: need [B, T] or [N]")
+    if out.shape != adv.shape or lengths.numel() != B:
+        raise TypeError("out: need the shape of adv; lengths: need [B]")
+    if stats is not None and stats.numel() < 3:
+        raise TypeError("stats: need 3 doubles")
+    rc = lib.espo_whiten(_dev(adv, torch.float32, "adv"), _dev(lengths, torch.int32, "lengths"), B, T, float(eps),
+                         int(bool(shift_mean)), int(bool(unbiased)), _dev(out, torch.float32, "out"),
+                         _dev(stats, torch.float64, "stats"), _dev(workspace, torch.uint8, "workspace"),
+                         workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(rc)
 
 

@@ -8,7 +8,7 @@ import tempfile
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libespo.so")
-SOURCES = ["espo_api.hip", "espo_step.hip", "espo_advantages.hip", "espo_batch_stats.hip"]
+SOURCES = ["espo_api.hip", "espo_step.hip", "espo_advantages.hip", "espo_batch_stats.hip", "espo_whiten.hip"]
 # packed-fp32 VALU forms are switched off for every device translation unit
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fvisibility=hidden",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -61,6 +61,24 @@ int espo_batch_stats(const float* regret, const int32_t* lengths, const uint8_t*
                                   (hipStream_t)stream);
 }
 
+size_t espo_whiten_workspace_bytes(int64_t B, int64_t T) {
+  if (B <= 0 || T <= 0) return 0;
+  return espo::whiten_workspace(B, T);
+}
+
+int espo_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps, int32_t shift_mean,
+                int32_t unbiased, float* out, double* stats, void* workspace, size_t workspace_bytes, void* stream) {
+  if (B < 0 || T < 0 || !(eps >= 0.0f) || !isfinite(eps)) return ESPO_EINVAL;
+  if (B == 0 || T == 0) return ESPO_OK;
+  if (!adv || !lengths || !out) return ESPO_EINVAL;
+  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (!aligned16(adv) || !aligned16(out) || ((uintptr_t)stats & 7u) != 0) return ESPO_EALIGN;
+  if (!workspace || workspace_bytes < espo::whiten_workspace(B, T) || ((uintptr_t)workspace & 7u) != 0)
+    return ESPO_EWORKSPACE;
+  return espo::launch_whiten(adv, lengths, B, T, eps, shift_mean != 0, unbiased != 0, out, stats, workspace,
+                             (hipStream_t)stream);
+}
+
 int espo_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
   if (!dst || !src || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) return ESPO_EINVAL;
   if (bytes == 0) return ESPO_OK;

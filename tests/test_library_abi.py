@@ -28,7 +28,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
-    assert {"espo_step", "espo_advantages", "espo_advantages_terminal", "espo_advantages_packed", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
+    assert {"espo_step", "espo_advantages", "espo_advantages_terminal", "espo_advantages_packed", "espo_whiten", "espo_whiten_workspace_bytes", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
             "espo_debug_set_score_margin_scale", "espo_debug_math_errors", "espo_debug_copy", "espo_batch_stats",
             "espo_batch_stats_workspace_bytes"} <= set(names)
     for n in names:
@@ -74,4 +74,16 @@ def test_argument_checks_need_no_gpu(lib):
     assert packed(B=-1) == -1 and packed(N=-1) == -1 and packed(g=float("nan")) == -1 and packed(cu=None) == -1
     assert packed(r=fake, term=fake) == -1 and packed(r=None, term=None) == -1   # exactly one reward form
     assert packed(ret=ctypes.c_void_p(0x1004)) == -2 and packed(r=ctypes.c_void_p(0x1008), term=None) == -2
+    lib.espo_whiten.argtypes = [ctypes.c_void_p] * 2 + [ctypes.c_int64] * 2 + [ctypes.c_float] + [ctypes.c_int32] * 2 + \
+        [ctypes.c_void_p] * 3 + [ctypes.c_size_t, ctypes.c_void_p]
+    lib.espo_whiten_workspace_bytes.restype = ctypes.c_size_t
+    lib.espo_whiten_workspace_bytes.argtypes = [ctypes.c_int64] * 2
+    need = lib.espo_whiten_workspace_bytes(4, 100)
+    assert 0 < need <= 32768 and lib.espo_whiten_workspace_bytes(1024, 16384) <= 32768 and lib.espo_whiten_workspace_bytes(0, 5) == 0
+    wh = lambda B=4, T=100, eps=1e-8, adv=fake, out=fake, stats=None, ws=fake, nws=need: lib.espo_whiten(
+        adv, fake, B, T, eps, 1, 0, out, stats, ws, nws, None)
+    assert wh(B=0) == 0 and wh(T=0) == 0
+    assert wh(B=-1) == -1 and wh(eps=-1.0) == -1 and wh(eps=float("nan")) == -1 and wh(adv=None) == -1
+    assert wh(out=ctypes.c_void_p(0x1004)) == -2 and wh(stats=ctypes.c_void_p(0x1004)) == -2
+    assert wh(ws=None) == -3 and wh(nws=need - 1) == -3
     assert lib.espo_step_workspace_bytes(512, 152064, 1) == 0
