@@ -253,6 +253,25 @@ def main() -> int:
     pk_bytes = {True: float(np.mean(valid * 16 + B_ADV * 9)), False: float(np.mean(valid * 12 + B_ADV * 13))}
     del pk
 
+    # whitening of the advantages over the valid tokens (two passes over A, one store)
+    wh_ws = torch.empty(espo.espo_whiten_workspace_bytes(B_ADV, T_ADV), dtype=torch.uint8, device=dev)
+    def wh_call(i):
+        td, ad = adv_out[i % nbuf]
+        espo.espo_whiten(ad, adv_in[i % nbuf][2], td, wh_ws)      # td serves as the output buffer here
+    for i in range(nbuf):
+        adv_call(i)                                               # the advantages these whiten
+    for i in range(nbuf):
+        wh_call(i)
+    torch.cuda.synchronize()
+    wregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    wregion[0].record()
+    for i in range(args.adv_reps):
+        wh_call(i)
+    wregion[1].record()
+    torch.cuda.synchronize()
+    wh_us = wregion[0].elapsed_time(wregion[1]) / args.adv_reps * 1e3
+    wh_bytes = float(np.mean(valid * 12 + B_ADV * 8))
+
     # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
     bs_sets = [W.regret_batch(512, 8192, seed=70 + i, device=dev) for i in range(nbuf)]   # 134 MB in rotation
     bs_out = torch.zeros(espo.BATCH_RESULT_BYTES, dtype=torch.uint8, device=dev)
@@ -391,6 +410,9 @@ def main() -> int:
                               "terminal": {"us_per_call": pk_us[False], "algorithmic_bytes_per_call": pk_bytes[False],
                                            "gbs": pk_bytes[False] / pk_us[False] / 1e3,
                                            "frac": pk_bytes[False] / pk_us[False] / 1e3 / HBM_PEAK_GBS}},
+        "whiten": {"workload": "whitening of the advantages of the same batches over their valid tokens",
+                   "us_per_call": wh_us, "launches_per_call": 2, "algorithmic_bytes_per_call": wh_bytes,
+                   "gbs": wh_bytes / wh_us / 1e3, "frac": wh_bytes / wh_us / 1e3 / HBM_PEAK_GBS},
         "batch_stats": {"workload": "B=512, T=8192 fp32 regrets, lengths U[64,8192], 25% stopped, 8 rotated sets",
                         "us_per_call": bs_us, "algorithmic_bytes_per_call": bs_bytes,
                         "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,

@@ -373,7 +373,7 @@ int espo_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, 
                 int32_t shift_mean, int32_t unbiased, float* out, double* stats,
                 void* workspace, size_t workspace_bytes, void* stream);
 
-/* Bytes of workspace espo_whiten needs (at most 32 KiB). */
+/* Bytes of workspace espo_whiten needs (at most 16 KiB). */
 size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
 
 /*

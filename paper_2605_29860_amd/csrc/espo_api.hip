@@ -71,7 +71,7 @@ int espo_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, 
   if (B < 0 || T < 0 || !(eps >= 0.0f) || !isfinite(eps)) return ESPO_EINVAL;
   if (B == 0 || T == 0) return ESPO_OK;
   if (!adv || !lengths || !out) return ESPO_EINVAL;
-  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (T > 0x7fffffff || B > 0x7fffffff || B * ((T + 4095) / 4096) > 0x7fffffff) return ESPO_ERANGE;  // 2^31 items of 4096 tokens
   if (!aligned16(adv) || !aligned16(out) || ((uintptr_t)stats & 7u) != 0) return ESPO_EALIGN;
   if (!workspace || workspace_bytes < espo::whiten_workspace(B, T) || ((uintptr_t)workspace & 7u) != 0)
     return ESPO_EWORKSPACE;

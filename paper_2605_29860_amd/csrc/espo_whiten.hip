@@ -3,13 +3,12 @@
 // update, Section 3):  out = (A - mean) / sqrt(var + eps), mean and var over all A[b, t < L_b].
 //
 // Two launches over the same decomposition.  The batch is cut into items of 4096 consecutive
-// tokens of one row; workgroup w takes items w, w + G, ... and every lane moves 16 bytes per
-// item.  The first launch reduces each workgroup's items to (n, sum d, sum d^2) in double, with
-// d = A - shift and shift the first valid token the workgroup sees: a shift that is itself a
-// data value keeps the one-pass variance free of cancellation however far the mean is from
-// zero.  The second launch starts by combining the at most 1024 partials (re-based to the
-// first non-empty partial's shift, added in a fixed tree, so every workgroup gets the same
-// bits whatever the scheduling), then rewrites its items.  Each element is normalised in
+// tokens of one row, numbered chunk position first so that a workgroup, which takes items
+// w, w + G, ..., sees every chunk position; every lane moves 16 bytes per item.  The first launch reduces each workgroup's items to (n, sum d, sum d^2) in double, with
+// d = A - shift and shift the first valid token of the batch: a shift that is itself a data
+// value keeps the one-pass variance free of cancellation however far the mean is from zero.
+// The second launch starts by adding the at most 512 partials in a fixed tree (every workgroup
+// gets the same bits whatever the scheduling), then rewrites its items.  Each element is normalised in
 // double and rounded to float once.  Positions at t >= L_b are neither read nor written.
 #include <hip/hip_runtime.h>
 #include <math.h>
@@ -25,7 +24,7 @@ namespace {
 constexpr int kWhThreads = 1024;
 constexpr int kWhWaves = kWhThreads / kWave;
 constexpr int kWhItem = kWhThreads * 4;  // tokens per item
-constexpr int kWhMaxGroups = 1024;
+constexpr int kWhMaxGroups = 512;  // one workgroup per slot of the chip
 
 struct WhPartial {
   double s1, s2, shift;
@@ -65,61 +64,85 @@ __device__ __forceinline__ double block_sum_all(double v, double* lds) {
   return t;
 }
 
-__device__ __forceinline__ int64_t clamped_length(const WhArgs& a, int64_t row) {
-  const int64_t L = a.lengths[row];
-  return L < 0 ? 0 : (L > a.T ? a.T : L);
+// One pass of a workgroup over its items, four at a time with their loads issued together.
+// An item is (row, first token); `whole(g, t)` gets the four tokens of a lane that lies wholly
+// inside the trajectory, `single(x, t)` a token of a lane that the trajectory's end cuts.
+constexpr int kWhUnroll = 4;  // eight spill: three 64-bit offsets per item in flight
+template <bool VEC, typename Whole, typename Single, typename Count>
+__device__ __forceinline__ void for_items(const WhArgs& a, Whole&& whole, Single&& single, Count&& count) {
+  const int tid = threadIdx.x;
+  for (uint32_t it0 = blockIdx.x; it0 < (uint32_t)a.items; it0 += kWhUnroll * (uint32_t)a.groups) {
+    int64_t base[kWhUnroll], t[kWhUnroll], L[kWhUnroll];
+#pragma unroll
+    for (int u = 0; u < kWhUnroll; ++u) {
+      const uint32_t it = it0 + (uint32_t)u * (uint32_t)a.groups;
+      L[u] = 0;
+      base[u] = 0;
+      t[u] = 0;
+      if (it < (uint32_t)a.items) {
+        const uint32_t ch = it / (uint32_t)a.B, row = it - ch * (uint32_t)a.B;  // chunk-major: a workgroup sees every chunk position
+        const int64_t len = a.lengths[row];
+        L[u] = len < 0 ? 0 : (len > a.T ? a.T : len);
+        base[u] = (int64_t)row * a.T;
+        t[u] = (int64_t)ch * kWhItem + (VEC ? tid * 4 : tid);
+        const int64_t left = L[u] - (int64_t)ch * kWhItem;
+        count(left < 0 ? 0 : (left < kWhItem ? left : kWhItem));  // valid tokens of the item
+      }
+    }
+    if (VEC) {  // T % 4 == 0: every row is 16-byte aligned
+      f32x4 g[kWhUnroll];
+#pragma unroll
+      for (int u = 0; u < kWhUnroll; ++u)
+        if (t[u] + 4 <= L[u]) g[u] = __builtin_nontemporal_load((const f32x4*)(a.adv + base[u] + t[u]));
+#pragma unroll
+      for (int u = 0; u < kWhUnroll; ++u) {
+        if (t[u] + 4 <= L[u]) {
+          whole(g[u], base[u] + t[u]);
+        } else {
+          for (int j = 0; j < 4 && t[u] + j < L[u]; ++j) single(a.adv[base[u] + t[u] + j], base[u] + t[u] + j);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kWhUnroll; ++u)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int64_t tt = t[u] + (int64_t)j * kWhThreads;
+          if (tt < L[u]) single(a.adv[base[u] + tt], base[u] + tt);
+        }
+    }
+  }
 }
 
 template <bool VEC>
 __global__ __launch_bounds__(kWhThreads) void whiten_partial_kernel(WhArgs a) {
   __shared__ double lds[kWhWaves];
   const int tid = threadIdx.x;
-  // the shift: the first valid token of this workgroup's items (the same address in every lane)
+  // the shift: the first valid token of the batch (the same in every workgroup)
   double shift = 0.0;
-  for (int64_t it = blockIdx.x; it < a.items; it += a.groups) {
-    const int64_t row = it / a.nch, t0 = (it % a.nch) * kWhItem;
-    if (t0 < clamped_length(a, row)) {
-      shift = (double)a.adv[row * a.T + t0];
+  for (int64_t b = 0; b < a.B; ++b)
+    if (a.lengths[b] > 0) {
+      shift = (double)a.adv[b * a.T];
       break;
     }
-  }
-  double s1 = 0.0, s2 = 0.0;
   long long n = 0;
-  for (int64_t it = blockIdx.x; it < a.items; it += a.groups) {
-    const int64_t row = it / a.nch, t0 = (it % a.nch) * kWhItem;
-    const int64_t L = clamped_length(a, row);
-    if (t0 >= L) continue;
-    const float* p = a.adv + row * a.T;
-    if (VEC) {  // T % 4 == 0: every row is 16-byte aligned
-      const int64_t t = t0 + (int64_t)tid * 4;
-      if (t + 4 <= L) {
-        const f32x4 g = __builtin_nontemporal_load((const f32x4*)(p + t));
+  double s1 = 0.0, s2 = 0.0;
+  for_items<VEC>(
+      a,
+      [&](const f32x4& g, int64_t) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const double d = (double)g[j] - shift;
           s1 += d;
           s2 += d * d;
         }
-      } else {
-        for (int j = 0; j < 4 && t + j < L; ++j) {
-          const double d = (double)p[t + j] - shift;
-          s1 += d;
-          s2 += d * d;
-        }
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int64_t t = t0 + tid + (int64_t)j * kWhThreads;
-        if (t < L) {
-          const double d = (double)p[t] - shift;
-          s1 += d;
-          s2 += d * d;
-        }
-      }
-    }
-    if (tid == 0) n += (L - t0 < kWhItem ? L - t0 : kWhItem);
-  }
+      },
+      [&](float x, int64_t) {
+        const double d = (double)x - shift;
+        s1 += d;
+        s2 += d * d;
+      },
+      [&](int64_t valid) { n += valid; });
   const double t1 = block_sum_all(s1, lds);
   const double t2 = block_sum_all(s2, lds);
   if (tid == 0) a.part[blockIdx.x] = WhPartial{t1, t2, shift, n};
@@ -127,28 +150,36 @@ __global__ __launch_bounds__(kWhThreads) void whiten_partial_kernel(WhArgs a) {
 
 template <bool VEC>
 __global__ __launch_bounds__(kWhThreads) void whiten_apply_kernel(WhArgs a) {
-  __shared__ double lds[kWhWaves];
-  __shared__ int s_first[kWhWaves];
+  __shared__ double lds[3 * kWhWaves];
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1), wave = tid >> 6;
-  // combine the partials: thread i holds partial i
+  // combine the partials (all about the same shift): thread i holds partial i
   WhPartial mine{0.0, 0.0, 0.0, 0};
   if (tid < a.groups) mine = a.part[tid];
-  const uint32_t first_w = wave_min_u32(mine.n > 0 ? (uint32_t)tid : 0xffffffffu);
-  if (lane == 0) s_first[wave] = (int)first_w;
+  double v0 = (double)mine.n, v1 = mine.s1, v2 = mine.s2;  // counts are below 2^53: exact
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    v0 += shfl_down_f64(v0, d);
+    v1 += shfl_down_f64(v1, d);
+    v2 += shfl_down_f64(v2, d);
+  }
+  if (lane == 0) {
+    lds[wave] = v0;
+    lds[kWhWaves + wave] = v1;
+    lds[2 * kWhWaves + wave] = v2;
+  }
   __syncthreads();
-  uint32_t first = 0xffffffffu;
-  for (int w = 0; w < kWhWaves; ++w) first = min(first, (uint32_t)s_first[w]);
-  if (first == 0xffffffffu) {  // no valid token in the batch: nothing to write
+  double n = 0.0, s1 = 0.0, s2 = 0.0;
+  for (int w = 0; w < kWhWaves; ++w) {  // fixed order: the same bits in every workgroup
+    n += lds[w];
+    s1 += lds[kWhWaves + w];
+    s2 += lds[2 * kWhWaves + w];
+  }
+  if (n == 0.0) {  // no valid token in the batch: nothing to write
     if (a.stats && blockIdx.x == 0 && tid < 3) a.stats[tid] = 0.0;
     return;
   }
-  const double shift = a.part[first].shift;
-  const double off = mine.shift - shift;  // re-base this partial: d' = d + off
-  const double nn = (double)mine.n;       // below 2^53: exact
-  const double n = block_sum_all(nn, lds);
-  const double s1 = block_sum_all(mine.n > 0 ? mine.s1 + nn * off : 0.0, lds);
-  const double s2 = block_sum_all(mine.n > 0 ? mine.s2 + 2.0 * off * mine.s1 + nn * off * off : 0.0, lds);
+  const double shift = a.part[0].shift;
   const double md = s1 / n;
   const double mean = shift + md;
   double ss = s2 - n * md * md;  // sum of squared deviations from the mean
@@ -162,32 +193,15 @@ __global__ __launch_bounds__(kWhThreads) void whiten_apply_kernel(WhArgs a) {
     a.stats[1] = var;
     a.stats[2] = n;
   }
-
-  for (int64_t it = blockIdx.x; it < a.items; it += a.groups) {
-    const int64_t row = it / a.nch, t0 = (it % a.nch) * kWhItem;
-    const int64_t L = clamped_length(a, row);
-    if (t0 >= L) continue;
-    const float* p = a.adv + row * a.T;
-    float* q = a.out + row * a.T;
-    if (VEC) {
-      const int64_t t = t0 + (int64_t)tid * 4;
-      if (t + 4 <= L) {
-        const f32x4 g = __builtin_nontemporal_load((const f32x4*)(p + t));
+  for_items<VEC>(
+      a,
+      [&](const f32x4& g, int64_t at) {
         f32x4 o;
 #pragma unroll
         for (int j = 0; j < 4; ++j) o[j] = (float)(((double)g[j] - sub) * rstd);
-        __builtin_nontemporal_store(o, (f32x4*)(q + t));
-      } else {
-        for (int j = 0; j < 4 && t + j < L; ++j) q[t + j] = (float)(((double)p[t + j] - sub) * rstd);
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        const int64_t t = t0 + tid + (int64_t)j * kWhThreads;
-        if (t < L) q[t] = (float)(((double)p[t] - sub) * rstd);
-      }
-    }
-  }
+        __builtin_nontemporal_store(o, (f32x4*)(a.out + at));
+      },
+      [&](float x, int64_t at) { a.out[at] = (float)(((double)x - sub) * rstd); }, [](int64_t) {});
 }
 
 int whiten_groups(int64_t B, int64_t T) {
