@@ -1,13 +1,15 @@
 // Calls the C ABI of libespo.so from a plain HIP host program (no Python, no PyTorch): reads a
-// binary file of inputs, runs one espo_step and one espo_advantages, writes the outputs to
-// another binary file.  The GPU test that drives it generates the inputs and compares the
+// binary file of inputs, runs one espo_step, one espo_advantages, one espo_whiten on its result
+// and one espo_advantages_packed (the [B, T] arrays taken as B full trajectories of T tokens
+// stored back to back, terminal reward values[b]), writes the outputs to another binary file.  The GPU test that drives it generates the inputs and compares the
 // outputs with the CPU oracle.
 //
 // input file (little endian): int32 B, V, T; float tau; uint64 seed; int32 step; espo_params;
 //   float logits[B*V]; float values[B]; float z[B]; uint8 alive[B]; int32 stop_step[B];
 //   float rewards[B*T]; float vals2[B*T]; int32 lengths[B]; uint8 stopped[B]
 // output file: int32 tokens[B]; float regret[B]; float z[B]; uint8 alive[B]; int32 stop_step[B];
-//   float logprob[B]; float entropy[B]; float td[B*T]; float adv[B*T]
+//   float logprob[B]; float entropy[B]; float td[B*T]; float adv[B*T];
+//   float whitened[B*T] (0 beyond the lengths); float td_packed[B*T]; float adv_packed[B*T]
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -73,16 +75,32 @@ int main(int argc, char** argv) {
   CK(hipMalloc((void**)&d_entropy, B * 4));
   CK(hipMalloc((void**)&d_td, (size_t)B * T * 4));
   CK(hipMalloc((void**)&d_adv, (size_t)B * T * 4));
+  float *d_wh, *d_tdp, *d_advp;
+  void* d_ws;
+  int64_t* d_cu;
+  std::vector<int64_t> cu(B + 1);
+  for (int b = 0; b <= B; ++b) cu[b] = (int64_t)b * T;
+  if (to_device(&d_cu, cu)) return 2;
+  CK(hipMalloc((void**)&d_wh, (size_t)B * T * 4));
+  CK(hipMemset(d_wh, 0, (size_t)B * T * 4));
+  CK(hipMalloc((void**)&d_tdp, (size_t)B * T * 4));
+  CK(hipMalloc((void**)&d_advp, (size_t)B * T * 4));
+  const size_t ws_bytes = espo_whiten_workspace_bytes(B, T);
+  CK(hipMalloc(&d_ws, ws_bytes));
   hipStream_t stream;
   CK(hipStreamCreate(&stream));
 
   EK(espo_step(d_logits, ESPO_F32, B, V, V, tau, seed, step, d_values, &p, d_z, d_alive, d_stop_step, d_tokens, d_regret,
                d_logprob, d_entropy, nullptr, 0, stream));
   EK(espo_advantages(d_rewards, d_vals2, d_lengths, d_stopped, B, T, -1.0f, 1.0f, 0.95f, d_td, d_adv, stream));
+  EK(espo_whiten(d_adv, d_lengths, B, T, 1e-8f, 1, 0, d_wh, nullptr, d_ws, ws_bytes, stream));
+  EK(espo_advantages_packed(nullptr, d_values, d_vals2, d_cu, d_stopped, B, (int64_t)B * T, -1.0f, 1.0f, 0.95f, d_tdp,
+                            d_advp, nullptr, stream));
   CK(hipStreamSynchronize(stream));
 
   std::vector<int32_t> tokens(B);
   std::vector<float> regret(B), logprob(B), entropy(B), td((size_t)B * T), adv((size_t)B * T);
+  std::vector<float> wh((size_t)B * T), tdp((size_t)B * T), advp((size_t)B * T);
   CK(hipMemcpy(tokens.data(), d_tokens, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(regret.data(), d_regret, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(z.data(), d_z, B * 4, hipMemcpyDeviceToHost));
@@ -92,12 +110,16 @@ int main(int argc, char** argv) {
   CK(hipMemcpy(entropy.data(), d_entropy, B * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(td.data(), d_td, td.size() * 4, hipMemcpyDeviceToHost));
   CK(hipMemcpy(adv.data(), d_adv, adv.size() * 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(wh.data(), d_wh, wh.size() * 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(tdp.data(), d_tdp, tdp.size() * 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(advp.data(), d_advp, advp.size() * 4, hipMemcpyDeviceToHost));
   std::FILE* o = std::fopen(argv[2], "wb");
   if (!o) return 1;
   const bool ok = wr(o, tokens.data(), B) && wr(o, regret.data(), B) && wr(o, z.data(), B) && wr(o, alive.data(), B) &&
                   wr(o, stop_step.data(), B) && wr(o, logprob.data(), B) && wr(o, entropy.data(), B) &&
                   wr(o, td.data(), td.size()) &&
-                  wr(o, adv.data(), adv.size());
+                  wr(o, adv.data(), adv.size()) && wr(o, wh.data(), wh.size()) && wr(o, tdp.data(), tdp.size()) &&
+                  wr(o, advp.data(), advp.size());
   std::fclose(o);
   std::printf("abi_check: version %d, B=%d V=%d T=%d done\n", espo_version(), B, V, T);
   return ok ? 0 : 1;

@@ -60,6 +60,7 @@ def test_native_program_matches_the_oracle(tmp_path):
                                                    take(np.uint8, B), take(np.int32, B), take(np.float32, B))
     entropy = take(np.float32, B)
     td, adv = take(np.float32, B * T).reshape(B, T), take(np.float32, B * T).reshape(B, T)
+    wh, td_p, adv_p = take(np.float32, B * T).reshape(B, T), take(np.float32, B * T), take(np.float32, B * T)
 
     z_o, alive_o, ss_o = z.copy(), alive.copy(), stop_step.copy()
     ref = oracle.step(logits_in, tau, seed, step, values, op, z_o, alive_o, ss_o, want_entropy=True)
@@ -74,3 +75,12 @@ def test_native_program_matches_the_oracle(tmp_path):
     td_o, adv_o, scale = oracle.advantages(rewards, vals2, lengths, stopped, -1.0, 1.0, 0.95)
     assert np.abs(td - td_o).max() <= 4e-7 * (np.abs(rewards).max() + 2 * np.abs(vals2).max() + 1)
     assert (np.abs(adv - adv_o) <= 1e-5 * np.maximum(np.abs(adv_o), scale)).all()
+    # whitening of the advantages the program itself produced (its fp32 output is the oracle's input)
+    wh_o, _ = oracle.whiten(adv, lengths)
+    mask = np.arange(T)[None, :] < np.clip(lengths, 0, T)[:, None]
+    assert (np.abs(wh[mask] - wh_o[mask]) <= 2e-7 * np.maximum(np.abs(wh_o[mask]), 1)).all() and (wh[~mask] == 0).all()
+    # the [B, T] values as B full trajectories stored back to back, terminal reward values[b]
+    cu = (np.arange(B + 1) * T).astype(np.int64)
+    tdp_o, advp_o, _, scale_p = oracle.advantages_packed(None, values, vals2.reshape(-1), cu, stopped, -1.0, 1.0, 0.95)
+    assert np.abs(td_p - tdp_o).max() <= 4e-7 * (np.abs(values).max() + 2 * np.abs(vals2).max() + 2)
+    assert (np.abs(adv_p - advp_o) <= 1e-5 * np.maximum(np.abs(advp_o), scale_p)).all()
