@@ -354,7 +354,8 @@ size_t espo_batch_stats_workspace_bytes(int64_t B, int64_t T);
  *   out[b,t] = (A[b,t] - (shift_mean ? mean : 0)) / sqrt(var + eps)           for t < L_b,
  * sums in double, each element normalised in double and rounded to float once.  Positions
  * at t >= L_b are neither read nor written.  The result does not depend on scheduling
- * (fixed reduction order).  With n = 0 nothing is written to out.
+ * (fixed reduction order).  With n = 0 nothing is written to out; with var + eps = 0 (a
+ * constant batch and eps = 0) every valid position of out is 0.
  *
  * Arguments
  *   adv        device, [B, T] fp32 row-major, 16-byte aligned base.  Trajectories stored

@@ -613,7 +613,8 @@ int oracle_advantages_packed(const float* rewards, const float* terminal_reward,
  *   mean = sum A / n,   var = sum (A - mean)^2 / (n - ddof),
  *   out[b,t] = (A[b,t] - (shift_mean ? mean : 0)) / sqrt(var + eps)        for t < L_b.
  * Plain two-pass definitions in double.  Positions at t >= L_b are neither read nor written.
- * With n - ddof <= 0 the variance is taken as 0.  stats (optional): mean, var, n.
+ * With n - ddof <= 0 the variance is taken as 0, and with var + eps = 0 (a constant batch
+ * and eps = 0) every output is 0 rather than 0/0.  stats (optional): mean, var, n.
  */
 int oracle_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps,
                   int shift_mean, int ddof, double* out, double* stats) {
@@ -643,12 +644,13 @@ int oracle_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T
   }
   const double var = (n - (double)ddof > 0.0) ? ss / (n - (double)ddof) : 0.0;
   const double sd = sqrt(var + (double)eps);
+  const double inv = sd > 0.0 ? 1.0 / sd : 0.0;   /* constant batch and eps = 0: nothing to scale by */
   for (int64_t b = 0; b < B; ++b) {
     int64_t L = lengths[b];
     if (L < 0) L = 0;
     if (L > T) L = T;
     for (int64_t t = 0; t < L; ++t)
-      out[b * T + t] = ((double)adv[b * T + t] - (shift_mean ? mean : 0.0)) / sd;
+      out[b * T + t] = inv > 0.0 ? ((double)adv[b * T + t] - (shift_mean ? mean : 0.0)) / sd : 0.0;
   }
   if (stats) {
     stats[0] = mean;

@@ -186,7 +186,8 @@ __global__ __launch_bounds__(kWhThreads) void whiten_apply_kernel(WhArgs a) {
   if (ss < 0.0) ss = 0.0;
   const double denom = n - (double)a.ddof;
   const double var = denom > 0.0 ? ss / denom : 0.0;
-  const double rstd = 1.0 / sqrt(var + (double)a.eps);
+  const double sd = sqrt(var + (double)a.eps);
+  const double rstd = sd > 0.0 ? 1.0 / sd : 0.0;  // a constant batch with eps = 0: every output is 0
   const double sub = a.shift_mean ? mean : 0.0;
   if (a.stats && blockIdx.x == 0 && tid == 0) {
     a.stats[0] = mean;
@@ -198,10 +199,10 @@ __global__ __launch_bounds__(kWhThreads) void whiten_apply_kernel(WhArgs a) {
       [&](const f32x4& g, int64_t at) {
         f32x4 o;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = (float)(((double)g[j] - sub) * rstd);
+        for (int j = 0; j < 4; ++j) o[j] = rstd > 0.0 ? (float)(((double)g[j] - sub) * rstd) : 0.0f;
         __builtin_nontemporal_store(o, (f32x4*)(a.out + at));
       },
-      [&](float x, int64_t at) { a.out[at] = (float)(((double)x - sub) * rstd); }, [](int64_t) {});
+      [&](float x, int64_t at) { a.out[at] = rstd > 0.0 ? (float)(((double)x - sub) * rstd) : 0.0f; }, [](int64_t) {});
 }
 
 int whiten_groups(int64_t B, int64_t T) {

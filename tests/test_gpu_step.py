@@ -679,7 +679,8 @@ def test_top_p_at_the_edge_of_the_kept_set_is_decided_like_the_oracle():
 def test_steps_captured_in_a_graph_replay_like_eager_launches():
     _say("[case] graph capture and replay")
     # The library allocates nothing and synchronises nothing, so its launches can be captured.
-    # A graph of three consecutive steps plus the advantage pass is replayed several times, with
+    # A graph of three consecutive steps plus the advantage pass (padded and packed) and the whitening
+    # of its result is replayed several times, with
     # eager work and synchronisations in between, from a restored state; every replay must give
     # the bits of the eager run.
     B, V, T = 48, 30000, 700
@@ -689,11 +690,18 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
     gp, _ = H.params_pair(mu_g=1.0, var_g=2.0, beta=0.6)
     r, v, L, stp = W.advantage_batch(B=B, T=T, len_lo=1, seed=8, device="cuda")
     z0 = torch.rand(B, device="cuda") - 0.5
+    cu = torch.zeros(B + 1, dtype=torch.int64, device="cuda")
+    cu[1:] = torch.cumsum(L.long(), 0)
+    vp = v[torch.arange(T, device="cuda")[None, :] < L[:, None]].contiguous()
+    term = torch.rand(B, device="cuda")
+    ws = torch.empty(espo.espo_whiten_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
 
     def fresh():
         st = H.GpuState(B, z=z0)
         st.out = [torch.empty(B, dtype=torch.int32, device="cuda") for _ in range(3)]
         st.td, st.adv = torch.empty(B, T, device="cuda"), torch.empty(B, T, device="cuda")
+        st.wh = torch.full((B, T), 7.0, device="cuda")
+        st.tdp, st.advp = torch.empty_like(vp), torch.empty_like(vp)
         return st
 
     def work(st):
@@ -701,11 +709,13 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
             espo.espo_step(logits[s], 0.6, 77, s, vals[s], gp, st.z, st.alive, st.stop_step, st.out[s], st.regret,
                            st.logprob, entropy=st.entropy)
         espo.espo_advantages(r, v, L, stp, -1.0, 1.0, 0.95, st.td, st.adv)
+        espo.espo_whiten(st.adv, L, st.wh, ws)
+        espo.espo_advantages_packed(vp, cu, stp, -1.0, 1.0, 0.95, st.tdp, st.advp, terminal_reward=term)
 
     eager = fresh()
     work(eager)
     torch.cuda.synchronize()
-    want = {k: getattr(eager, k).clone() for k in ("z", "alive", "stop_step", "regret", "logprob", "entropy", "td", "adv")}
+    want = {k: getattr(eager, k).clone() for k in ("z", "alive", "stop_step", "regret", "logprob", "entropy", "td", "adv", "wh", "tdp", "advp")}
     want_tok = [t.clone() for t in eager.out]
     assert int(want["alive"].sum()) < B                      # some rows stop inside the graph
 
@@ -722,6 +732,7 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
     for replay in range(4):
         st.z.copy_(z0); st.alive.fill_(1); st.stop_step.fill_(-1)       # restore the state the graph starts from
         st.td.fill_(7.0); st.adv.fill_(7.0); st.regret.fill_(-7.0)
+        st.wh.fill_(7.0); st.tdp.fill_(7.0); st.advp.fill_(7.0); ws.fill_(0x5a)
         for t in st.out:
             t.fill_(-7)
         torch.cuda.synchronize()

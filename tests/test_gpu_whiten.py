@@ -91,6 +91,8 @@ def test_degenerate_batches_and_errors():
     _check(a, L, eps=0.25, shift_mean=False)
     c = torch.full((4, 300), 2.5, device="cuda")
     _check(c, torch.tensor([300, 7, 0, 150], dtype=torch.int32, device="cuda"))   # constant: zeros
+    _check(c, torch.tensor([300, 7, 0, 150], dtype=torch.int32, device="cuda"), eps=0.0)   # var + eps = 0: zeros too
+    _check(c, torch.tensor([0, 1, 0, 0], dtype=torch.int32, device="cuda"), eps=0.0, shift_mean=False, unbiased=True)
     a, _ = _batch(4, 100, seed=7, lengths=[100] * 4)
     _check(a, torch.tensor([-3, 150, 0, 17], dtype=torch.int32, device="cuda"))   # lengths are clamped
     ws = torch.empty(espo.espo_whiten_workspace_bytes(4, 100), dtype=torch.uint8, device="cuda")

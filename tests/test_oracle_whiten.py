@@ -75,6 +75,10 @@ def test_degenerate_batches(oracle):
     assert st[1] == 0 and out[0, 0] == 0                                     # n - 1 = 0: variance taken as 0
     out, _ = oracle.whiten(a, np.array([1, 0], np.int32), eps=0.25, shift_mean=False)
     assert out[0, 0] == 6.0                                                  # 3 / sqrt(0 + 1/4)
+    out, _ = oracle.whiten(a, np.array([5, 2], np.int32), eps=0.0)          # var + eps = 0: zeros, not 0/0
+    assert (out[0] == 0).all() and (out[1, :2] == 0).all()
+    out, _ = oracle.whiten(a, np.array([1, 0], np.int32), eps=0.0, shift_mean=False, unbiased=True)
+    assert out[0, 0] == 0
     e = np.zeros((0, 4), np.float32)
     out, st = oracle.whiten(e, np.zeros(0, np.int32))
     assert out.shape == (0, 4) and st[2] == 0
