@@ -9,7 +9,7 @@
  * the failure reward placed at the stop step (Section 4.4, Eq. failure_reward,
  * Eq. gae).
  *
- * Five operations are exported (the advantage pass in three layouts):
+ * Four operations are exported, the advantage pass in three layouts:
  *   espo_step         one decode step for a batch of trajectories (Algorithm 1 body)
  *   espo_advantages   TD errors + GAE over the truncated trajectories (Section 3, 4.4)
  *   espo_advantages_terminal  the same for the rewards Algorithm 1 produces (zero until
