@@ -939,7 +939,27 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       x_a = exact.best.x;
     }
   };
-  search(sh, softmax_sum);
+  // the largest float below x (x finite or +inf): a floor that lets x itself through
+  const auto next_below = [](float x) {
+    const int32_t bits = __builtin_bit_cast(int32_t, x);
+    return x == 0.0f ? -1.401298464e-45f : __builtin_bit_cast(float, bits + (x > 0.0f ? -1 : 1));
+  };
+  bool greedy = false;
+  if constexpr (Filter) {
+    if (a.top_k == 1) {
+      // Greedy decoding up to ties: the kept set is the row's largest logit, so no search over
+      // the whole row is needed, only one over the blocks that hold that value.
+      __syncthreads();  // the waves' maxima are in place
+      softmax_sum();
+      if (m > kNegInf) {
+        StepShared top = sh;
+        top.floor = next_below(m);
+        search(top, [] {});
+        greedy = true;
+      }
+    }
+  }
+  if (!greedy) search(sh, softmax_sum);
 
   if constexpr (Filter) {
     // Filtered draw (top-p as in the evaluation set-up of Section 5, or top-k).  The kept set is
@@ -1101,12 +1121,11 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     auto settle = [&](float edge) {
       if (x_a >= edge) return;
       StepShared kept_only = sh;  // everything at or above the edge: the floor is the next float below it
-      const int32_t bits = __builtin_bit_cast(int32_t, edge);
-      kept_only.floor = edge == 0.0f ? -1.401298464e-45f : __builtin_bit_cast(float, bits + (edge > 0.0f ? -1 : 1));
+      kept_only.floor = next_below(edge);
       search(kept_only, nothing);
     };
 
-    bool done = tok < 0;
+    bool done = tok < 0 || greedy;
     if (!done) {
       // a floor with about 32 blocks above it (32 + k for top-k, which needs k logits above it): the 32nd
       // largest of the 128 lane groups' largest logits
