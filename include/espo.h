@@ -277,7 +277,7 @@ int espo_advantages_terminal(const float* values, const int32_t* lengths, const 
  *                content of this array leads to an access outside the arrays; extents that
  *                overlap give unspecified results in the overlap.
  *   stopped      device, [B] uint8.
- *   B, N         B >= 0, N >= 0 (either 0 is a no-op).
+ *   B, N         B >= 0, N >= 0 (either 0 is a no-op); B < 2^31 (ESPO_ERANGE), N any int64.
  *   td, adv      device, [N] fp32 out; returns device [N] fp32 out or NULL.  Positions
  *                that no trajectory owns are left as they are.
  *   All [N] arrays need 16-byte aligned bases (ESPO_EALIGN); offsets need no alignment.
@@ -361,7 +361,8 @@ size_t espo_batch_stats_workspace_bytes(int64_t B, int64_t T);
  *   adv        device, [B, T] fp32 row-major, 16-byte aligned base.  Trajectories stored
  *              back to back (espo_advantages_packed) are the case B = 1, T = N, lengths = {N}.
  *   lengths    device, [B] int32.
- *   B, T       B >= 0, T >= 0 (either 0 is a no-op).
+ *   B, T       B >= 0, T >= 0 (either 0 is a no-op); B, T and B * ceil(T / 4096) below 2^31
+ *              (ESPO_ERANGE).
  *   eps        >= 0, finite (common choice: 1e-8).
  *   shift_mean, unbiased   flags as above.
  *   out        device, [B, T] fp32, 16-byte aligned base; may be the same array as adv.
