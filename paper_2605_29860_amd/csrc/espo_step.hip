@@ -969,7 +969,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     // mass (number) of the logits above a given floor, and those logits themselves when they are
     // few.  A table of the blocks' largest logits, filled while streaming, names the blocks that
     // hold any; a handful of blocks is read again directly, more of them by one more pass over
-    // the row.  First a floor that leaves about 32 blocks above it is tried: on rows like a
+    // the row.  First a floor that leaves about 64 blocks above it is tried: on rows like a
     // language model's the kept set lies above it, its smallest logit is then read off the
     // collected logits (the smallest whose strictly larger ones hold less than p, number fewer
     // than k) and the token follows.  Otherwise (flat rows) the winner itself is tested, and
@@ -999,13 +999,14 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       __syncthreads();
       const int nabove = *sh.nsurv;
       float acc_m = 0.0f, acc_n = 0.0f;
-      if (nabove <= 16 * kStepWaves) {  // the usual case: one block per wave visit, one index per lane, four loads in flight
+      constexpr int kVisit = 8;
+      if (nabove <= 16 * kStepWaves) {  // the usual case: one block per wave visit, one index per lane, eight loads in flight
 #pragma unroll 1
-        for (int base = wave; base < nabove; base += 4 * kStepWaves) {
-          float xs[4];
-          int32_t ns[4];
+        for (int base = wave; base < nabove; base += kVisit * kStepWaves) {
+          float xs[kVisit];
+          int32_t ns[kVisit];
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < kVisit; ++u) {
             const int k = base + u * kStepWaves;
             xs[u] = kNegInf;
             ns[u] = 0;
@@ -1016,7 +1017,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
             }
           }
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
+          for (int u = 0; u < kVisit; ++u) {
             if (lane < ns[u] && xs[u] > floor_x) {
               const float e = __builtin_amdgcn_exp2f(fmaf(xs[u], a.k2, nrk_row));
               acc_m += e;
@@ -1091,7 +1092,20 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       for (int c = tid; c < ncand; c += kStepThreads) {  // at most one per thread
         const float xc = sh.cand_x[c];
         float m_above = 0.0f, n_above = 0.0f;
-        for (int o = 0; o < ncand; ++o) {  // every thread reads the same entry: LDS broadcasts
+        // every thread reads the same entries (LDS broadcasts), four at a time and several
+        // reads in flight: one entry per dependent read would cost a microsecond per ten candidates
+        const int whole = ncand & ~3;
+#pragma unroll 4
+        for (int o = 0; o < whole; o += 4) {
+          const f32x4 xo = *(const f32x4*)(sh.cand_x + o), eo = *(const f32x4*)(cand_e + o);
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const bool larger = xo[u] > xc;
+            m_above += larger ? eo[u] : 0.0f;
+            n_above += larger ? 1.0f : 0.0f;
+          }
+        }
+        for (int o = whole; o < ncand; ++o) {
           const bool larger = sh.cand_x[o] > xc;
           m_above += larger ? cand_e[o] : 0.0f;
           n_above += larger ? 1.0f : 0.0f;
@@ -1127,24 +1141,35 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
 
     bool done = tok < 0 || greedy;
     if (!done) {
-      // a floor with about 32 blocks above it (32 + k for top-k, which needs k logits above it): the 32nd
-      // largest of the 128 lane groups' largest logits
+      // a floor with about 64 blocks above it, the 64th largest of the 128 lane groups' largest logits
+      // (for top-k the (32 + k)-th: k logits have to lie above it).  Measured, 32 is 2 us faster on rows
+      // whose nucleus is a few dozen tokens and 10 to 30 us slower where it is a few hundred.
       __syncthreads();
       if ((lane & 7) == 0) sh.cand_x[wave * kGroups + grp] = mx;
+      if (tid < kSlots) sh.cand_v[tid] = 0;  // the ranks, summed from eight partial counts each
       __syncthreads();
       float trial = kNegInf;
-      const int trial_rank = by_count ? (a.top_k < kSlots - 32 ? 31 + a.top_k : kSlots - 1) : 31;
-      if (tid < kSlots) {
-        const float mine = sh.cand_x[tid];
-        int rank = 0;
-        for (int o = 0; o < kSlots; ++o) {
-          const float other = sh.cand_x[o];
-          rank += (other > mine || (other == mine && o < tid)) ? 1 : 0;
+      const int trial_rank = by_count ? (a.top_k < kSlots - 32 ? 31 + a.top_k : kSlots - 1) : 63;
+      {
+        static_assert(kStepThreads / kSlots == 8 && kSlots % 16 == 0, "eight threads per value, sixteen others each");
+        const int j = tid & (kSlots - 1), part = tid / kSlots;
+        const float mine = sh.cand_x[j];
+        int r = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const f32x4 o4 = ((const f32x4*)sh.cand_x)[part * 4 + q];
+#pragma unroll
+          for (int u = 0; u < 4; ++u) {
+            const int o = part * 16 + q * 4 + u;
+            r += (o4[u] > mine || (o4[u] == mine && o < j)) ? 1 : 0;
+          }
         }
-        if (rank == trial_rank) sh.fres[2 * kStepWaves] = mine;
+        atomicAdd(&sh.cand_v[j], r);
       }
       __syncthreads();
-      trial = sh.fres[2 * kStepWaves];  // -inf if fewer than 32 lane groups saw a finite logit
+      if (tid < kSlots && sh.cand_v[tid] == trial_rank) sh.fres[2 * kStepWaves] = sh.cand_x[tid];
+      __syncthreads();
+      trial = sh.fres[2 * kStepWaves];  // -inf if fewer lane groups than that saw a finite logit
       measure(trial);
       const bool below_edge = by_count ? count >= (float)a.top_k : mass - want > 1e-5f * total;
       if (below_edge && ncand <= kCandCap) {
