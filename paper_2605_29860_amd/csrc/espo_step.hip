@@ -944,22 +944,15 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     const int32_t bits = __builtin_bit_cast(int32_t, x);
     return x == 0.0f ? -1.401298464e-45f : __builtin_bit_cast(float, bits + (x > 0.0f ? -1 : 1));
   };
-  bool greedy = false;
-  if constexpr (Filter) {
-    if (a.top_k == 1) {
-      // Greedy decoding up to ties: the kept set is the row's largest logit, so no search over
-      // the whole row is needed, only one over the blocks that hold that value.
-      __syncthreads();  // the waves' maxima are in place
-      softmax_sum();
-      if (m > kNegInf) {
-        StepShared top = sh;
-        top.floor = next_below(m);
-        search(top, [] {});
-        greedy = true;
-      }
-    }
+  if constexpr (!Filter) {
+    search(sh, softmax_sum);
+  } else {
+    __syncthreads();  // the waves' maxima are in place
+    softmax_sum();    // m, and the waves' shares of S
+    __syncthreads();
+    tok = -1;         // a row without a finite logit keeps this
+    x_a = 0.0f;
   }
-  if (!greedy) search(sh, softmax_sum);
 
   if constexpr (Filter) {
     // Filtered draw (top-p as in the evaluation set-up of Section 5, or top-k).  The kept set is
@@ -972,9 +965,10 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     // the row.  First a floor that leaves about 64 blocks above it is tried: on rows like a
     // language model's the kept set lies above it, its smallest logit is then read off the
     // collected logits (the smallest whose strictly larger ones hold less than p, number fewer
-    // than k) and the token follows.  Otherwise (flat rows) the winner itself is tested, and
-    // while it is not kept the search is repeated above it; that floor rises strictly, so the
-    // loop ends.  Sums within 1e-5 of p times the softmax sum are not trusted in fp32: the
+    // than k) and one search above that edge gives the token; the unfiltered winner is not
+    // needed then and is not searched for.  Otherwise (flat rows) the unfiltered winner is found
+    // and tested, and while it is not kept the search is repeated above it; that floor rises
+    // strictly, so the loop ends.  Sums within 1e-5 of p times the softmax sum are not trusted in fp32: the
     // candidate path is then left for the loop, whose test repeats them in double over the
     // whole row, in the oracle's arithmetic.
     const auto nothing = [] {};
@@ -1139,8 +1133,13 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       search(kept_only, nothing);
     };
 
-    bool done = tok < 0 || greedy;
-    if (!done) {
+    bool done = !(m > kNegInf);
+    float edge_known = kNegInf;
+    bool have_edge = false;
+    if (!done && a.top_k == 1) {  // greedy decoding up to ties: the kept set is the row's largest logit
+      edge_known = m;
+      have_edge = true;
+    } else if (!done) {
       // a floor with about 64 blocks above it, the 64th largest of the 128 lane groups' largest logits
       // (for top-k the (32 + k)-th: k logits have to lie above it).  Measured, 32 is 2 us faster on rows
       // whose nucleus is a few dozen tokens and 10 to 30 us slower where it is a few hundred.
@@ -1172,13 +1171,15 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
       trial = sh.fres[2 * kStepWaves];  // -inf if fewer lane groups than that saw a finite logit
       measure(trial);
       const bool below_edge = by_count ? count >= (float)a.top_k : mass - want > 1e-5f * total;
-      if (below_edge && ncand <= kCandCap) {
-        float edge;
-        if (kept_edge(edge)) {
-          settle(edge);
-          done = true;
-        }
-      }
+      if (below_edge && ncand <= kCandCap) have_edge = kept_edge(edge_known);
+    }
+    if (have_edge) {  // the kept set is everything at or above the edge
+      StepShared kept_only = sh;
+      kept_only.floor = next_below(edge_known);
+      search(kept_only, nothing);
+      done = true;
+    } else if (!done) {
+      search(sh, nothing);  // the unfiltered winner, for the loop below
     }
     while (!done && tok >= 0) {
       const float floor_x = x_a;
