@@ -225,7 +225,7 @@ size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt);
  *                    not be a multiple of 16.
  *   lengths          device, [B] int32 (clamped to [0, T] on the device).
  *   stopped          device, [B] uint8, non-zero = ended by the stop rule.
- *   B, T             B >= 0, T >= 0 (either 0 is a no-op); T < 2^31.
+ *   B, T             B >= 0, T >= 0 (either 0 is a no-op); T < 2^31, B < 2^30 (ESPO_ERANGE).
  *   r_fail, gamma, lambda   scalars; gamma, lambda finite.
  *   td, adv          device, [B, T] fp32 out, 16-byte aligned base.
  *   stream           hipStream_t as void*.

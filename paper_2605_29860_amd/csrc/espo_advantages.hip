@@ -51,6 +51,7 @@ struct AdvArgs {
   const int32_t* lengths;
   const uint8_t* stopped;
   int64_t T;
+  int32_t B;  // rows; with zero padding the grid has 2 B workgroups, the second B only fill
   float r_fail, gamma, c;
   float cj[kPerLane + 1];  // c^0 .. c^4
   float clane[6];          // c^(4*2^k), k = 0..5: a distance of 2^k lanes
@@ -135,7 +136,14 @@ __device__ __forceinline__ float scan_step(float s, float w) {
 template <bool VEC, bool Dense, bool Packed>
 __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs a) {
   __shared__ float s_tot[2][kAdvWaves];  // wave totals, double-buffered by tile parity
-  const int row = blockIdx.x;
+  // With zero padding, the tiles wholly beyond a trajectory are filled by a workgroup of their
+  // own (the second half of the grid): the two kinds of work of a row are then dispatched
+  // separately, which evens out the rows (a row costs 16 bytes per valid and 8 per padded token):
+  // 2 to 3 us on the B = 1024, T = 16384 batches when their rows come in order of length, nothing
+  // when they come in random order.  (Ranking the rows by length inside every workgroup, 8 or 64
+  // classes, costs 3 to 5 us per launch, as much as the order gains.)
+  const bool fill_only = !Packed && (int)blockIdx.x >= a.B;
+  const int row = fill_only ? (int)blockIdx.x - a.B : (int)blockIdx.x;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -173,12 +181,13 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
 
   // tiles wholly beyond the trajectory: outputs are exactly zero
   const float zero[kPerLane] = {0, 0, 0, 0};
-  if (!Packed && a.zero_padding) {
+  if (fill_only) {
     for (int64_t k = ntiles - 1; k >= nvalid; --k) {
       store4<VEC>(drow, k * kAdvTile + lane_off, T, zero);
       store4<VEC>(arow, k * kAdvTile + lane_off, T, zero);
       if (trow) store4<VEC>(trow, k * kAdvTile + lane_off, T, zero);
     }
+    return;
   }
   if (nvalid == 0) return;
 
@@ -290,6 +299,7 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
   a.N = N;
   a.stopped = stopped;
   a.T = T;
+  a.B = (int32_t)B;
   a.r_fail = r_fail;
   a.gamma = gamma;
   const double c = (double)gamma * (double)lambda;
@@ -300,7 +310,7 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
   a.td = td;
   a.adv = adv;
   const bool vec = (T % 4 == 0);
-  const dim3 grid((unsigned)B), block(kAdvThreads);
+  const dim3 grid((unsigned)(cu == nullptr && zero_padding ? 2 * B : B)), block(kAdvThreads);
   void (*kernel)(AdvArgs);
   if (cu)
     kernel = rewards ? espo_advantages_kernel<true, true, true> : espo_advantages_kernel<true, false, true>;

@@ -141,7 +141,7 @@ int espo_advantages(const float* rewards, const float* values, const int32_t* le
   if (!isfinite(gamma) || !isfinite(lambda) || isnan(r_fail)) return ESPO_EINVAL;
   if (B == 0 || T == 0) return ESPO_OK;
   if (!rewards || !values || !lengths || !stopped || !td || !adv) return ESPO_EINVAL;
-  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (T > 0x7fffffff || B > 0x3fffffff) return ESPO_ERANGE;  // the grid has 2 B workgroups
   if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv)) return ESPO_EALIGN;
   return espo::launch_advantages(rewards, nullptr, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda, 1, td, adv,
                                  nullptr, (hipStream_t)stream);
@@ -155,7 +155,7 @@ int espo_advantages_terminal(const float* values, const int32_t* lengths, const 
   if (!isfinite(gamma) || !isfinite(lambda) || isnan(r_fail)) return ESPO_EINVAL;
   if (B == 0 || T == 0) return ESPO_OK;
   if (!values || !lengths || !stopped || !terminal_reward || !td || !adv) return ESPO_EINVAL;
-  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (T > 0x7fffffff || B > 0x3fffffff) return ESPO_ERANGE;  // with zero padding the grid has 2 B workgroups
   if (!aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns)) return ESPO_EALIGN;
   return espo::launch_advantages(nullptr, terminal_reward, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda,
                                  zero_padding != 0, td, adv, returns, (hipStream_t)stream);
