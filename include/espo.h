@@ -346,6 +346,24 @@ int espo_batch_stats(const float* regret, const int32_t* lengths, const uint8_t*
 size_t espo_batch_stats_workspace_bytes(int64_t B, int64_t T);
 
 /*
+ * espo_batch_stats_static -- espo_batch_stats for callers that cannot allocate device memory
+ * (code under HIP graph capture, serving loops, harnesses that forbid hipMalloc): the same
+ * kernels and the same result, bit for bit, but the partial sums go to a 32 KiB array that
+ * the library holds on every GPU it is loaded on, instead of a caller's workspace.  The call
+ * allocates and frees nothing.  Every B fits that array (a launch never has more than 1024
+ * partial sums of 32 bytes); the size is checked all the same and a batch that would not fit
+ * returns ESPO_ERANGE with nothing enqueued, as do B or T of 2^31 or more.  ESPO_EHIP if the
+ * runtime cannot give the array's address on the current device (the device that is current
+ * at the call must be the one `stream` belongs to).  All calls on one GPU share the array:
+ * two calls that can overlap there (different streams, or different host threads without
+ * ordering between their streams) race on it; calls on one stream are ordered and safe.
+ * Arguments, alignment rules and other errors as for espo_batch_stats.
+ */
+int espo_batch_stats_static(const float* regret, const int32_t* lengths, const uint8_t* stopped,
+                            int64_t B, int64_t T, float mu_g, float var_g, float beta,
+                            const espo_batch_ctrl* ctrl, espo_batch_result* out, void* stream);
+
+/*
  * espo_whiten -- advantage whitening over the valid tokens of a batch: the normalisation
  * that PPO implementations apply to the GAE output before the clipped objective.  (The paper
  * keeps the standard PPO update, Section 3, and does not spell this step out; it belongs

@@ -109,6 +109,8 @@ def load_library():
         lib.espo_debug_math_errors.argtypes = [C.c_void_p, C.c_void_p]
         lib.espo_batch_stats.restype = C.c_int
         lib.espo_batch_stats.argtypes = [vp, vp, vp, i64, i64, f32, f32, f32, C.POINTER(_BatchCtrl), vp, vp, sz, vp]
+        lib.espo_batch_stats_static.restype = C.c_int
+        lib.espo_batch_stats_static.argtypes = [vp, vp, vp, i64, i64, f32, f32, f32, C.POINTER(_BatchCtrl), vp, vp]
         lib.espo_batch_stats_workspace_bytes.restype = sz
         lib.espo_batch_stats_workspace_bytes.argtypes = [i64, i64]
         lib.espo_debug_copy.restype = C.c_int
@@ -167,6 +169,23 @@ def espo_batch_stats(regret: torch.Tensor, lengths: torch.Tensor, stopped: torch
         _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
         B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out"),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
+
+
+def espo_batch_stats_static(regret: torch.Tensor, lengths: torch.Tensor, stopped: torch.Tensor, mu_g: float, var_g: float,
+                            beta: float, out: torch.Tensor, alpha_ema: float = 0.99, eta_beta: float = 0.1,
+                            target_rate: float = 0.25, beta_min: float = 0.0, beta_max: float = 7.0, stream=None) -> None:
+    """`espo_batch_stats` on the library's own scratch (no workspace argument, nothing allocated)."""
+    if regret.dim() != 2:
+        raise ValueError("regret must be [B, T]")
+    B, T = regret.shape
+    if lengths.numel() != B or stopped.numel() != B:
+        raise ValueError("lengths and stopped must hold B elements")
+    if out.numel() * out.element_size() < BATCH_RESULT_BYTES:
+        raise ValueError("out is too small")
+    ctrl = _BatchCtrl(alpha_ema, eta_beta, target_rate, beta_min, beta_max)
+    _check(load_library().espo_batch_stats_static(
+        _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
+        B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out"), _stream(stream)))
 
 
 def read_batch_result(out: torch.Tensor) -> dict:

@@ -61,6 +61,25 @@ int espo_batch_stats(const float* regret, const int32_t* lengths, const uint8_t*
                                   (hipStream_t)stream);
 }
 
+int espo_batch_stats_static(const float* regret, const int32_t* lengths, const uint8_t* stopped, int64_t B, int64_t T,
+                            float mu_g, float var_g, float beta, const espo_batch_ctrl* ctrl, espo_batch_result* out,
+                            void* stream) {
+  if (B < 0 || T < 0 || !ctrl || !out) return ESPO_EINVAL;
+  if (!(ctrl->alpha_ema >= 0.0f && ctrl->alpha_ema <= 1.0f) || !(ctrl->beta_min <= ctrl->beta_max)) return ESPO_EINVAL;
+  if (!isfinite(ctrl->eta_beta) || !isfinite(ctrl->target_rate) || !isfinite(mu_g) || !isfinite(var_g) || !isfinite(beta))
+    return ESPO_EINVAL;
+  if (B > 0 && (!lengths || !stopped || (T > 0 && !regret))) return ESPO_EINVAL;
+  if (T > 0x7fffffff || B > 0x7fffffff) return ESPO_ERANGE;
+  if (regret && !aligned16(regret)) return ESPO_EALIGN;
+  if (((uintptr_t)out & 7u) != 0) return ESPO_EALIGN;
+  // the partial sums of this batch must fit the library's own scratch
+  if (B > 0 && espo::batch_stats_workspace(B) > espo::batch_stats_static_capacity()) return ESPO_ERANGE;
+  void* scratch_ptr = espo::batch_stats_static_scratch();
+  if (!scratch_ptr) return ESPO_EHIP;
+  return espo::launch_batch_stats(regret, lengths, stopped, B, T, mu_g, var_g, beta, *ctrl, out, scratch_ptr,
+                                  (hipStream_t)stream);
+}
+
 size_t espo_whiten_workspace_bytes(int64_t B, int64_t T) {
   if (B <= 0 || T <= 0) return 0;
   return espo::whiten_workspace(B, T);

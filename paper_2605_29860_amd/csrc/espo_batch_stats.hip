@@ -11,9 +11,16 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/espo.h"
 #include "espo_device.h"
 #include "espo_host.h"
+
+// Scratch of espo_batch_stats_static: room for the partial sums of the largest launch (1024
+// workgroups, 32 bytes each).  One copy per GPU, held from the moment the library is loaded.
+// In host code this name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[32768];
 
 namespace espo {
 namespace {
@@ -147,7 +154,28 @@ __global__ __launch_bounds__(kStatThreads) void batch_final_kernel(FinalArgs a) 
 
 int stat_groups(int64_t B) { return (int)(B < 1 ? 1 : (B > kMaxStatGroups ? kMaxStatGroups : B)); }
 
+// Device address of `scratch` on the current GPU: looked up once per device, with that device
+// current, and kept.  Returns nullptr if the runtime cannot name the device or the symbol.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void* g_scratch_ptr[kMaxDevices];
+
+void* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> hold(g_scratch_lock);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+
 }  // namespace
+
+size_t batch_stats_static_capacity() { return sizeof(scratch); }
+void* batch_stats_static_scratch() { return static_scratch(); }
 
 size_t batch_stats_workspace(int64_t B) { return (size_t)stat_groups(B) * sizeof(Partial); }
 

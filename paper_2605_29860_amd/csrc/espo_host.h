@@ -25,6 +25,11 @@ int launch_batch_stats(const float* regret, const int32_t* lengths, const uint8_
                        float mu_g, float var_g, float beta, const espo_batch_ctrl& c, espo_batch_result* out,
                        void* workspace, hipStream_t stream);
 
+// The library's own scratch for espo_batch_stats_static: its size, and its device address on the
+// current GPU (nullptr if the runtime cannot provide it).
+size_t batch_stats_static_capacity();
+void* batch_stats_static_scratch();
+
 size_t whiten_workspace(int64_t B, int64_t T);
 int launch_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps, int shift_mean,
                   int unbiased, float* out, double* stats, void* workspace, hipStream_t stream);
