@@ -27,9 +27,9 @@
  *     stream has reached the point of the call.
  *   - Return value: ESPO_OK (0) or a negative espo_status.  On any error nothing
  *     has been enqueued.
- *   - No global mutable state (apart from the margin scale of the diagnostics at the
- *     end of this file, an atomic): calls from several host threads on different
- *     streams are safe as long as they do not share output or workspace buffers.
+ *   - No global mutable state: calls from several host threads on different streams
+ *     are safe as long as they do not share output or workspace buffers.  (The one
+ *     exception is espo_batch_stats_static, which says so.)
  *   - A call consists of kernel launches only (no allocation, no copy, no memset,
  *     no synchronisation), so it may be recorded while its stream is being captured
  *     into a HIP graph; scalar arguments (seed, step, parameters) are then fixed in
@@ -145,8 +145,10 @@ typedef enum {
  *      the state before the first step is 0 and step 0 already updates it, as
  *      Algorithm 1 does).
  *   6. stop = stop_enabled && z[b] > beta * fmaxf(values[b], eps)   (Eq. stop_rule,
- *      strict; stop_mode selects the tests of the ablations instead, see espo_stop_mode).  If stop: alive[b] = 0 and stop_step[b] = step (the trajectory
- *      keeps the token of this step and has length step + 1; Eq. failure_reward).
+ *      strict; stop_mode selects the tests of the ablations instead, see
+ *      espo_stop_mode).
+ *      If stop: alive[b] = 0 and stop_step[b] = step (the trajectory keeps the token
+ *      of this step and has length step + 1; Eq. failure_reward).
  *      If eos_id >= 0 and a == eos_id the row ends naturally instead: alive[b] = 0
  *      and stop_step[b] is left alone.
  *   Outputs: tokens[b] = a, regret[b] = g, logprob[b] = -g - ln S, and on request
@@ -169,8 +171,9 @@ typedef enum {
  *               supported (results for that row are unspecified, no fault).
  *   dt          ESPO_F32 or ESPO_BF16.
  *   B, V        rows and vocabulary size; B >= 0 (0 is a no-op), 1 <= V <= 400000
- *               (ESPO_ERANGE beyond: the per-block bounds of a row live in LDS; a filtered
- *               draw keeps one more table there and stops at about 350000 for fp32 logits).
+ *               (ESPO_ERANGE beyond: without a workspace the per-block bounds of a row live
+ *               in the LDS of one workgroup; a filtered draw keeps one more table there and
+ *               stops at about 350000 for fp32 logits).
  *   row_stride  elements between rows, >= V.
  *   temperature > 0 and finite.
  *   seed, step  key and counter word of the random stream; step >= 0.
@@ -187,10 +190,14 @@ typedef enum {
  *               a leaner instantiation of the kernel runs (about 8 % faster at B = 512).
  *   entropy     device, [B] fp32 out, may be NULL (then nothing is spent on it: the
  *               pass with the entropy does two more vector operations per logit).
- *   workspace   device scratch of at least espo_step_workspace_bytes(B, V, dt) bytes.
- *               A row is handled by one workgroup, so that size is 0 in this version
- *               and NULL / 0 may be passed; the argument is kept so that the ABI need
- *               not change if a later version spreads a row over several workgroups.
+ *   workspace   device scratch of at least espo_step_workspace_bytes(B, V, dt) bytes, 16-byte
+ *               aligned, or NULL if that size is 0, as it is for every shape in this version:
+ *               one workgroup handles a whole row and needs no scratch in device memory.
+ *               (Splitting a row over several workgroups that combine through a workspace is
+ *               implemented and reachable through espo_debug_step in espo_debug.h; on an
+ *               MI355X it measured slower for every shape tried, so espo_step does not do it.)
+ *               A workspace that is given but smaller than that size or misaligned is
+ *               ESPO_EWORKSPACE.
  *   stream      hipStream_t as void*.
  */
 int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,
@@ -396,35 +403,6 @@ int espo_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, 
 
 /* Bytes of workspace espo_whiten needs (at most 16 KiB). */
 size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
-
-/*
- * Diagnostics for the callers that test the library (not part of the method): espo_step
- * scores contenders in fp32 first and repeats the search in double only when the two best
- * scores overlap within the fp32 error margin.  `scale` >= 1 multiplies that margin for all
- * later espo_step calls of the process (1 = default; a huge value sends every row through
- * the double-precision search).  The sampled token does not depend on it.
- * Returns ESPO_EINVAL for scale < 1 or NaN.
- */
-int espo_debug_set_score_margin_scale(float scale);
-
-/*
- * Diagnostics: measures on the device the accuracy of the hardware logarithm and exponential
- * that the fp32 scores of espo_step are built from, against the double-precision functions.
- * `out` is device memory, 3 floats that the caller has set to zero; once the stream has
- * reached the call they hold the largest relative error of
- *   out[0]  ln u over every value u(w) = (2r+1)/2^24, r = 0 .. 2^23-1, the stream can produce,
- *   out[1]  ln x over 2^23 positive floats spread over [2^-26, 64),
- *   out[2]  exp x over 2^23 points of [-40, 8].
- * The margin of the fp32 scores assumes at most 1.7e-7, 1.7e-7 and 2e-6.
- */
-int espo_debug_math_errors(float* out, void* stream);
-
-/*
- * Diagnostics: a plain copy kernel (reads `bytes` once, writes them once; device pointers,
- * 16-byte aligned, bytes a multiple of 16).  It exists so that hardware traffic counters can
- * be calibrated against a launch whose memory traffic is known exactly.
- */
-int espo_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Static, human-readable text for a status code (never NULL). */
 const char* espo_strerror(int code);

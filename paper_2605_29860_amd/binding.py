@@ -103,8 +103,14 @@ def load_library():
         lib.espo_strerror.restype = C.c_char_p
         lib.espo_strerror.argtypes = [C.c_int]
         lib.espo_version.restype = C.c_int
-        lib.espo_debug_set_score_margin_scale.restype = C.c_int
-        lib.espo_debug_set_score_margin_scale.argtypes = [f32]
+        lib.espo_debug_step.restype = C.c_int
+        lib.espo_debug_step.argtypes = lib.espo_step.argtypes + [f32, i32, i32]
+        lib.espo_debug_step_workspace_bytes.restype = sz
+        lib.espo_debug_step_workspace_bytes.argtypes = [i64, i32]
+        lib.espo_debug_read.restype = C.c_int
+        lib.espo_debug_read.argtypes = [vp, sz, vp, vp]
+        lib.espo_debug_sweep.restype = C.c_int
+        lib.espo_debug_sweep.argtypes = [vp, sz, vp, sz, vp]
         lib.espo_debug_math_errors.restype = C.c_int
         lib.espo_debug_math_errors.argtypes = [C.c_void_p, C.c_void_p]
         lib.espo_batch_stats.restype = C.c_int
@@ -124,11 +130,22 @@ def _check(rc: int):
         raise EspoError(rc, load_library().espo_strerror(rc).decode())
 
 
-def _dev(t: torch.Tensor, dtype, name: str):
+def _on_gpu(t: torch.Tensor) -> bool:
+    return t.is_cuda
+
+
+def _dev(t: torch.Tensor, dtype, name: str, numel: int | None = None, shape: tuple | None = None):
+    """Device pointer of a tensor after checking what the C ABI cannot: placement, type, layout and size.
+    The library takes bare pointers, so a tensor that is too short would become an out-of-bounds access
+    on the GPU; it is refused here instead (`numel`: at least that many elements; `shape`: exactly that)."""
     if t is None:
         return None
-    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+    if not _on_gpu(t) or t.dtype != dtype or not t.is_contiguous():
         raise TypeError(f"{name}: need a contiguous GPU tensor of {dtype}")
+    if numel is not None and t.numel() < numel:
+        raise ValueError(f"{name}: need at least {numel} elements, got {t.numel()}")
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: need shape {tuple(shape)}, got {tuple(t.shape)}")
     return C.c_void_p(t.data_ptr())
 
 
@@ -137,16 +154,26 @@ def _stream(stream):
     return C.c_void_p(s.cuda_stream)
 
 
-def espo_debug_set_score_margin_scale(scale: float) -> None:
-    """Diagnostics: widen the fp32 score margin of espo_step (see include/espo.h)."""
-    _check(load_library().espo_debug_set_score_margin_scale(float(scale)))
-
-
 def espo_debug_math_errors(out: torch.Tensor, stream=None) -> None:
-    """Diagnostics: accuracy of the hardware ln / exp on this device (see include/espo.h); `out` = 3 zeroed floats."""
-    if out.numel() < 3:
-        raise ValueError("out: need 3 floats")
-    _check(load_library().espo_debug_math_errors(_dev(out, torch.float32, "out"), _stream(stream)))
+    """Diagnostics: accuracy of the hardware ln / exp on this device (see include/espo_debug.h); `out` = 3 zeroed floats."""
+    _check(load_library().espo_debug_math_errors(_dev(out, torch.float32, "out", numel=3), _stream(stream)))
+
+
+def espo_debug_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """Diagnostics: bare streaming read of `src` (see include/espo_debug.h); `sink`: at least 4 bytes on the GPU."""
+    if not src.is_cuda or not src.is_contiguous() or not sink.is_cuda or sink.numel() * sink.element_size() < 4:
+        raise TypeError("src: contiguous GPU tensor; sink: GPU tensor of at least 4 bytes")
+    _check(load_library().espo_debug_read(C.c_void_p(src.data_ptr()), src.numel() * src.element_size(),
+                                          C.c_void_p(sink.data_ptr()), _stream(stream)))
+
+
+def espo_debug_sweep(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, write_bytes: int, stream=None) -> None:
+    """Diagnostics: flat sweep that reads `read_bytes` of src and writes `write_bytes` of dst (see include/espo_debug.h)."""
+    for name, t, n in (("src", src, read_bytes), ("dst", dst, write_bytes)):
+        if not t.is_cuda or not t.is_contiguous() or t.numel() * t.element_size() < n:
+            raise ValueError(f"{name}: need a contiguous GPU tensor of at least {n} bytes")
+    _check(load_library().espo_debug_sweep(C.c_void_p(src.data_ptr()), int(read_bytes), C.c_void_p(dst.data_ptr()),
+                                           int(write_bytes), _stream(stream)))
 
 
 def espo_batch_stats_workspace_bytes(B: int, T: int) -> int:
@@ -162,12 +189,11 @@ def espo_batch_stats(regret: torch.Tensor, lengths: torch.Tensor, stopped: torch
     if regret.dim() != 2:
         raise ValueError("regret must be [B, T]")
     B, T = regret.shape
-    if out.numel() * out.element_size() < BATCH_RESULT_BYTES:
-        raise ValueError("out is too small")
     ctrl = _BatchCtrl(alpha_ema, eta_beta, target_rate, beta_min, beta_max)
     _check(load_library().espo_batch_stats(
-        _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
-        B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out"),
+        _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths", numel=B),
+        _dev(stopped, torch.uint8, "stopped", numel=B),
+        B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out", numel=BATCH_RESULT_BYTES),
         _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)))
 
 
@@ -178,14 +204,12 @@ def espo_batch_stats_static(regret: torch.Tensor, lengths: torch.Tensor, stopped
     if regret.dim() != 2:
         raise ValueError("regret must be [B, T]")
     B, T = regret.shape
-    if lengths.numel() != B or stopped.numel() != B:
-        raise ValueError("lengths and stopped must hold B elements")
-    if out.numel() * out.element_size() < BATCH_RESULT_BYTES:
-        raise ValueError("out is too small")
     ctrl = _BatchCtrl(alpha_ema, eta_beta, target_rate, beta_min, beta_max)
     _check(load_library().espo_batch_stats_static(
-        _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
-        B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out"), _stream(stream)))
+        _dev(regret, torch.float32, "regret"), _dev(lengths, torch.int32, "lengths", numel=B),
+        _dev(stopped, torch.uint8, "stopped", numel=B),
+        B, T, float(mu_g), float(var_g), float(beta), C.byref(ctrl), _dev(out, torch.uint8, "out", numel=BATCH_RESULT_BYTES),
+        _stream(stream)))
 
 
 def read_batch_result(out: torch.Tensor) -> dict:
@@ -208,12 +232,20 @@ def espo_step_workspace_bytes(B: int, V: int, dtype: torch.dtype) -> int:
     return int(load_library().espo_step_workspace_bytes(B, V, dt))
 
 
+def espo_debug_step_workspace_bytes(B: int, chunks: int) -> int:
+    return int(load_library().espo_debug_step_workspace_bytes(B, chunks))
+
+
 def espo_step(logits: torch.Tensor, temperature: float, seed: int, step: int, values: torch.Tensor,
               params: EspoParams, z: torch.Tensor, alive: torch.Tensor, stop_step: torch.Tensor,
               tokens: torch.Tensor, regret: torch.Tensor, logprob: torch.Tensor | None = None,
               V: int | None = None, workspace: torch.Tensor | None = None, stream=None,
-              entropy: torch.Tensor | None = None) -> None:
-    """One decode step; see `espo_step` in include/espo.h.  `logits` is [B, row_stride]."""
+              entropy: torch.Tensor | None = None, margin_scale: float | None = None, waves: int | None = None,
+              chunks: int | None = None) -> None:
+    """One decode step; see `espo_step` in include/espo.h.  `logits` is [B, row_stride].  `workspace`: a
+    zero-initialised uint8 GPU tensor of `espo_step_workspace_bytes` bytes (rows are then split over several
+    workgroups) or None.  With any of `margin_scale`, `waves`, `chunks` the call goes through
+    `espo_debug_step` (include/espo_debug.h), which exposes those choices for this call."""
     lib = load_library()
     if logits.dtype == torch.bfloat16:
         dt = ESPO_BF16
@@ -221,21 +253,27 @@ def espo_step(logits: torch.Tensor, temperature: float, seed: int, step: int, va
         dt = ESPO_F32
     else:
         raise TypeError("logits must be bfloat16 or float32")
-    if logits.dim() != 2 or logits.stride(1) != 1 or not logits.is_cuda:
+    if logits.dim() != 2 or logits.stride(1) != 1 or not _on_gpu(logits):
         raise TypeError("logits: need a 2-D GPU tensor with unit stride along the vocabulary")
     B, width = logits.shape
     row_stride = logits.stride(0) if B > 1 else width
     V = width if V is None else int(V)
+    if V > width:
+        raise EspoError(-1, "V exceeds the width of logits")
     ws_ptr, ws_bytes = None, 0
     if workspace is not None:
-        ws_ptr, ws_bytes = C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size()
+        ws_ptr, ws_bytes = _dev(workspace, torch.uint8, "workspace"), workspace.numel()
     p = params._c()
-    rc = lib.espo_step(C.c_void_p(logits.data_ptr()), dt, B, V, row_stride, float(temperature), int(seed),
-                       int(step), _dev(values, torch.float32, "values"), C.byref(p),
-                       _dev(z, torch.float32, "z"), _dev(alive, torch.uint8, "alive"),
-                       _dev(stop_step, torch.int32, "stop_step"), _dev(tokens, torch.int32, "tokens"),
-                       _dev(regret, torch.float32, "regret"), _dev(logprob, torch.float32, "logprob"),
-                       _dev(entropy, torch.float32, "entropy"), ws_ptr, ws_bytes, _stream(stream))
+    args = [C.c_void_p(logits.data_ptr()), dt, B, V, row_stride, float(temperature), int(seed),
+            int(step), _dev(values, torch.float32, "values", numel=B), C.byref(p),
+            _dev(z, torch.float32, "z", numel=B), _dev(alive, torch.uint8, "alive", numel=B),
+            _dev(stop_step, torch.int32, "stop_step", numel=B), _dev(tokens, torch.int32, "tokens", numel=B),
+            _dev(regret, torch.float32, "regret", numel=B), _dev(logprob, torch.float32, "logprob", numel=B),
+            _dev(entropy, torch.float32, "entropy", numel=B), ws_ptr, ws_bytes, _stream(stream)]
+    if margin_scale is None and waves is None and chunks is None:
+        rc = lib.espo_step(*args)
+    else:
+        rc = lib.espo_debug_step(*args, 1.0 if margin_scale is None else float(margin_scale), int(waves or 0), int(chunks or 0))
     _check(rc)
 
 
@@ -247,10 +285,11 @@ def espo_advantages(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.
     if rewards.dim() != 2:
         raise TypeError("rewards: need [B, T]")
     B, T = rewards.shape
-    rc = lib.espo_advantages(_dev(rewards, torch.float32, "rewards"), _dev(values, torch.float32, "values"),
-                             _dev(lengths, torch.int32, "lengths"), _dev(stopped, torch.uint8, "stopped"),
+    rc = lib.espo_advantages(_dev(rewards, torch.float32, "rewards"), _dev(values, torch.float32, "values", shape=(B, T)),
+                             _dev(lengths, torch.int32, "lengths", numel=B), _dev(stopped, torch.uint8, "stopped", numel=B),
                              B, T, float(r_fail), float(gamma), float(lam),
-                             _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"), _stream(stream))
+                             _dev(td, torch.float32, "td", shape=(B, T)), _dev(adv, torch.float32, "adv", shape=(B, T)),
+                             _stream(stream))
     _check(rc)
 
 
@@ -273,9 +312,9 @@ def espo_whiten(adv: torch.Tensor, lengths: torch.Tensor, out: torch.Tensor, wor
         raise TypeError("out: need the shape of adv; lengths: need [B]")
     if stats is not None and stats.numel() < 3:
         raise TypeError("stats: need 3 doubles")
-    rc = lib.espo_whiten(_dev(adv, torch.float32, "adv"), _dev(lengths, torch.int32, "lengths"), B, T, float(eps),
+    rc = lib.espo_whiten(_dev(adv, torch.float32, "adv"), _dev(lengths, torch.int32, "lengths", numel=B), B, T, float(eps),
                          int(bool(shift_mean)), int(bool(unbiased)), _dev(out, torch.float32, "out"),
-                         _dev(stats, torch.float64, "stats"), _dev(workspace, torch.uint8, "workspace"),
+                         _dev(stats, torch.float64, "stats", numel=3), _dev(workspace, torch.uint8, "workspace"),
                          workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(rc)
 
@@ -314,10 +353,10 @@ def espo_advantages_terminal(values: torch.Tensor, lengths: torch.Tensor, stoppe
     if values.dim() != 2:
         raise TypeError("values: need [B, T]")
     B, T = values.shape
-    rc = lib.espo_advantages_terminal(_dev(values, torch.float32, "values"), _dev(lengths, torch.int32, "lengths"),
-                                      _dev(stopped, torch.uint8, "stopped"),
-                                      _dev(terminal_reward, torch.float32, "terminal_reward"), B, T,
+    rc = lib.espo_advantages_terminal(_dev(values, torch.float32, "values"), _dev(lengths, torch.int32, "lengths", numel=B),
+                                      _dev(stopped, torch.uint8, "stopped", numel=B),
+                                      _dev(terminal_reward, torch.float32, "terminal_reward", numel=B), B, T,
                                       float(r_fail), float(gamma), float(lam), int(bool(zero_padding)),
-                                      _dev(td, torch.float32, "td"), _dev(adv, torch.float32, "adv"),
-                                      _dev(returns, torch.float32, "returns"), _stream(stream))
+                                      _dev(td, torch.float32, "td", shape=(B, T)), _dev(adv, torch.float32, "adv", shape=(B, T)),
+                                      _dev(returns, torch.float32, "returns", shape=(B, T)), _stream(stream))
     _check(rc)

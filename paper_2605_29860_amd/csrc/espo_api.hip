@@ -4,9 +4,8 @@
 #include <math.h>
 
 #include "../../include/espo.h"
+#include "../../include/espo_debug.h"
 #include "espo_host.h"
-
-#include <atomic>
 
 namespace {
 
@@ -19,19 +18,109 @@ __global__ __launch_bounds__(256) void copy_kernel(copy_u32x4* __restrict__ dst,
   if (i < n16) dst[i] = src[i];
 }
 
-std::atomic<float> g_margin_scale{1.0f};
+// Bare streaming read: every lane keeps eight nontemporal 16-byte loads in flight over a span of
+// 32 KB per workgroup and folds what arrives into one word, which is stored only if it takes a value
+// that the fold cannot produce for the caller's data in practice (so nothing is written, yet the
+// loads cannot be dropped).
+constexpr int kReadLoads = 8;
+__global__ __launch_bounds__(256) void read_kernel(const copy_u32x4* __restrict__ src, size_t n16, unsigned* __restrict__ sink) {
+  const size_t base = (size_t)blockIdx.x * (256 * kReadLoads) + threadIdx.x;
+  copy_u32x4 v[kReadLoads];
+#pragma unroll
+  for (int j = 0; j < kReadLoads; ++j) {
+    const size_t i = base + (size_t)j * 256;
+    v[j] = i < n16 ? __builtin_nontemporal_load(src + i) : copy_u32x4{0u, 0u, 0u, 0u};
+  }
+  unsigned acc = 0;
+#pragma unroll
+  for (int j = 0; j < kReadLoads; ++j) acc |= (v[j].x ^ v[j].y) + (v[j].z ^ v[j].w);
+  if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+
+// Flat sweep with a given read / write mix and no dependency between elements: lane i reads the i-th
+// 16 bytes of src (while there are any) and writes the i-th 16 bytes of dst (while there are any),
+// nontemporal both ways.
+__global__ __launch_bounds__(256) void sweep_kernel(const copy_u32x4* __restrict__ src, size_t nr, copy_u32x4* __restrict__ dst, size_t nw) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  copy_u32x4 v = copy_u32x4{(unsigned)i, 1u, 2u, 3u};
+  if (i < nr) v = __builtin_nontemporal_load(src + i);
+  if (i < nw) __builtin_nontemporal_store(v, dst + i);
+}
+
+bool filtered(const espo_params* p) { return (p->top_p > 0.0f && p->top_p < 1.0f) || p->top_k > 0; }
+
+// Argument checks of espo_step and of its diagnostics twin; ESPO_OK means "go on", B == 0 is reported
+// through *empty.  `waves`, `chunks`: 0 for the library's choice (see espo_debug_step).
+int step_checked(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
+                 uint64_t seed, int32_t step, const float* values, const espo_params* params, float* z, uint8_t* alive,
+                 int32_t* stop_step, int32_t* tokens, float* regret, float* logprob, float* entropy, void* workspace,
+                 size_t workspace_bytes, float margin_scale, int waves, int chunks, void* stream) {
+  if (dt != ESPO_F32 && dt != ESPO_BF16) return ESPO_EINVAL;
+  if (B < 0 || V < 1 || row_stride < V || step < 0) return ESPO_EINVAL;
+  if (!params) return ESPO_EINVAL;
+  if (!(temperature > 0.0f) || !isfinite(temperature)) return ESPO_EINVAL;
+  if (!(params->alpha_s >= 0.0f && params->alpha_s <= 1.0f)) return ESPO_EINVAL;
+  if (!(params->var_g + params->delta > 0.0f) || !isfinite(params->var_g + params->delta)) return ESPO_EINVAL;
+  if (!(params->clip_c >= 0.0f) || !(params->beta >= 0.0f) || isnan(params->eps) || isnan(params->mu_g)) return ESPO_EINVAL;
+  if (params->stop_mode < ESPO_STOP_RULE || params->stop_mode > ESPO_STOP_RANDOM) return ESPO_EINVAL;
+  if (params->stop_mode != ESPO_STOP_RULE && isnan(params->stop_threshold)) return ESPO_EINVAL;
+  if (!(params->top_p >= 0.0f && params->top_p <= 1.0f) || params->top_k < 0) return ESPO_EINVAL;
+  if (params->top_p > 0.0f && params->top_p < 1.0f && params->top_k > 0) return ESPO_EINVAL;  // one filter at a time
+  if (!(margin_scale >= 1.0f)) return ESPO_EINVAL;  // below 1 the fp32 search would no longer be exact
+  if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return ESPO_EINVAL;
+  if (chunks < 0) return ESPO_EINVAL;
+  if (B == 0) return ESPO_OK;
+  if (!logits || !values || !z || !alive || !stop_step || !tokens || !regret) return ESPO_EINVAL;
+  if (V > espo::kMaxVocab || B > 0x7fffffff) return ESPO_ERANGE;
+  const size_t esize = dt == ESPO_BF16 ? 2 : 4;
+  if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
+  const bool filter = filtered(params);
+  if (filter && ((waves != 0 && waves != 16) || chunks > 1)) return ESPO_EINVAL;  // a filtered draw has one layout
+  const espo::StepPlan plan = espo::plan_step(dt, B, V, filter, waves, chunks);
+  if (plan.lds > espo::kMaxStepLds) return ESPO_ERANGE;
+  if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace || !aligned16(workspace))) return ESPO_EWORKSPACE;
+  return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params, margin_scale, z, alive,
+                           stop_step, tokens, regret, logprob, entropy, workspace, plan, (hipStream_t)stream);
+}
 
 }  // namespace
 
 #pragma GCC visibility push(default)
 extern "C" {
 
-int espo_version(void) { return 200; }
+int espo_version(void) { return 300; }
 
-int espo_debug_set_score_margin_scale(float scale) {
-  if (!(scale >= 1.0f)) return ESPO_EINVAL;  // below 1 the fast path would no longer be exact
-  g_margin_scale.store(scale);
-  return ESPO_OK;
+int espo_debug_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
+                    uint64_t seed, int32_t step, const float* values, const espo_params* params, float* z, uint8_t* alive,
+                    int32_t* stop_step, int32_t* tokens, float* regret, float* logprob, float* entropy, void* workspace,
+                    size_t workspace_bytes, void* stream, float score_margin_scale, int32_t waves, int32_t chunks) {
+  return step_checked(logits, dt, B, V, row_stride, temperature, seed, step, values, params, z, alive, stop_step, tokens,
+                      regret, logprob, entropy, workspace, workspace_bytes, score_margin_scale, waves, chunks, stream);
+}
+
+size_t espo_debug_step_workspace_bytes(int64_t B, int32_t chunks) {
+  if (B <= 0 || chunks <= 1) return 0;
+  return espo::step_workspace_layout(B, chunks, nullptr);
+}
+
+int espo_debug_read(const void* src, size_t bytes, void* sink, void* stream) {
+  if (!src || !sink || bytes % 16 != 0 || !aligned16(src)) return ESPO_EINVAL;
+  if (bytes == 0) return ESPO_OK;
+  const size_t n16 = bytes / 16, groups = (n16 + 256 * kReadLoads - 1) / (256 * kReadLoads);
+  if (groups > 0x7fffffffu) return ESPO_ERANGE;
+  hipLaunchKernelGGL(read_kernel, dim3((unsigned)groups), dim3(256), 0, (hipStream_t)stream, (const copy_u32x4*)src, n16,
+                     (unsigned*)sink);
+  return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
+}
+
+int espo_debug_sweep(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream) {
+  if (!src || !dst || read_bytes % 16 != 0 || write_bytes % 16 != 0 || !aligned16(src) || !aligned16(dst)) return ESPO_EINVAL;
+  if (read_bytes == 0 && write_bytes == 0) return ESPO_OK;
+  const size_t nr = read_bytes / 16, nw = write_bytes / 16, n = nr > nw ? nr : nw;
+  if ((n + 255) / 256 > 0x7fffffffu) return ESPO_ERANGE;
+  hipLaunchKernelGGL(sweep_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                     (const copy_u32x4*)src, nr, (copy_u32x4*)dst, nw);
+  return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 
 int espo_debug_math_errors(float* out, void* stream) {
@@ -121,8 +210,8 @@ const char* espo_strerror(int code) {
 }
 
 size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt) {
-  (void)B; (void)V; (void)dt;
-  return 0;  // a row is handled by a single workgroup: no inter-workgroup scratch
+  if (B <= 0 || V < 1 || V > espo::kMaxVocab || (dt != ESPO_F32 && dt != ESPO_BF16)) return 0;
+  return espo::plan_step(dt, B, V, false, 0, 0).workspace;
 }
 
 int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,
@@ -130,27 +219,8 @@ int espo_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t r
               const espo_params* params, float* z, uint8_t* alive, int32_t* stop_step,
               int32_t* tokens, float* regret, float* logprob, float* entropy, void* workspace,
               size_t workspace_bytes, void* stream) {
-  (void)workspace; (void)workspace_bytes;
-  if (dt != ESPO_F32 && dt != ESPO_BF16) return ESPO_EINVAL;
-  if (B < 0 || V < 1 || row_stride < V || step < 0) return ESPO_EINVAL;
-  if (!params) return ESPO_EINVAL;
-  if (!(temperature > 0.0f) || !isfinite(temperature)) return ESPO_EINVAL;
-  if (!(params->alpha_s >= 0.0f && params->alpha_s <= 1.0f)) return ESPO_EINVAL;
-  if (!(params->var_g + params->delta > 0.0f) || !isfinite(params->var_g + params->delta)) return ESPO_EINVAL;
-  if (!(params->clip_c >= 0.0f) || !(params->beta >= 0.0f) || isnan(params->eps) || isnan(params->mu_g)) return ESPO_EINVAL;
-  if (params->stop_mode < ESPO_STOP_RULE || params->stop_mode > ESPO_STOP_RANDOM) return ESPO_EINVAL;
-  if (params->stop_mode != ESPO_STOP_RULE && isnan(params->stop_threshold)) return ESPO_EINVAL;
-  if (!(params->top_p >= 0.0f && params->top_p <= 1.0f) || params->top_k < 0) return ESPO_EINVAL;
-  if (params->top_p > 0.0f && params->top_p < 1.0f && params->top_k > 0) return ESPO_EINVAL;  // one filter at a time
-  if (B == 0) return ESPO_OK;
-  if (!logits || !values || !z || !alive || !stop_step || !tokens || !regret) return ESPO_EINVAL;
-  if (V > espo::kMaxVocab || B > 0x7fffffff || espo::step_shared_bytes(dt, V, (params->top_p > 0.0f && params->top_p < 1.0f) || params->top_k > 0) > espo::kMaxStepLds)
-    return ESPO_ERANGE;
-  const size_t esize = dt == ESPO_BF16 ? 2 : 4;
-  if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
-  return espo::launch_step(logits, dt, B, V, row_stride, temperature, seed, step, values, *params,
-                           g_margin_scale.load(), z, alive, stop_step, tokens, regret, logprob, entropy,
-                           (hipStream_t)stream);
+  return step_checked(logits, dt, B, V, row_stride, temperature, seed, step, values, params, z, alive, stop_step, tokens,
+                      regret, logprob, entropy, workspace, workspace_bytes, 1.0f, 0, 0, stream);
 }
 
 int espo_advantages(const float* rewards, const float* values, const int32_t* lengths,

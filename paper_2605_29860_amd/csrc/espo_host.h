@@ -9,15 +9,28 @@
 namespace espo {
 
 constexpr size_t kMaxStepLds = 128 * 1024;         // dynamic LDS a step workgroup may ask for (160 KB per CU)
-constexpr int64_t kMaxVocab = 400000;               // 96 bytes of LDS per 512-index tile plus 26-42 KB fixed
+constexpr int64_t kMaxVocab = 400000;               // one workgroup per row: 96 bytes of LDS per 512-index tile plus 26-42 KB fixed
 
-// Bytes of dynamic LDS a step workgroup needs for this dtype and vocabulary.
-size_t step_shared_bytes(int dt, int64_t V, bool filter);  // filter: a top-p / top-k draw (one more table per row)
+// How one espo_step call is laid out: wavefronts per workgroup (16, 8 or 4), workgroups per row,
+// workgroups in the launch, dynamic LDS per workgroup, and the bytes of workspace a split needs.
+struct StepPlan {
+  int waves, chunks;
+  int64_t grid;
+  size_t lds, workspace;
+};
+
+// The plan for this shape.  `filter`: a top-p / top-k draw (one more table in LDS, never split).
+// waves / chunks > 0 force those values (the diagnostics entry point); 0 is the library's choice
+// (16 waves, no split).
+StepPlan plan_step(int dt, int64_t B, int64_t V, bool filter, int waves, int chunks);
+
+// Bytes of workspace for B rows split `chunks` ways; the offset of the chunk results behind the tickets.
+size_t step_workspace_layout(int64_t B, int chunks, size_t* partials_offset);
 
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
                 float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
-                float* entropy, hipStream_t stream);
+                float* entropy, void* workspace, const StepPlan& plan, hipStream_t stream);
 
 size_t batch_stats_workspace(int64_t B);
 

@@ -39,14 +39,23 @@
 namespace espo {
 namespace {
 
-constexpr int kStepThreads = 1024;
-constexpr int kStepWaves = kStepThreads / kWave;
+// A workgroup has W wavefronts (a template parameter of everything below that depends on it): 16 when
+// one workgroup owns a whole row, 4 when a row is split into chunks that several workgroups stream.
 constexpr int kTile = 512;                        // indices per wave iteration
 constexpr int kGroups = kTile / kDrawBlock;       // draw blocks per tile = lane groups per wave
-constexpr int kSlots = kStepWaves * kGroups;      // lane groups per workgroup
+constexpr int kMaxChunks = 64;                    // a row is split over at most this many workgroups (one lane each in the combine)
 constexpr int kRing = 4;                          // 16-byte loads kept in flight per lane
 constexpr int kCandCap = 1024;                    // candidate indices kept for a row with a long survivor list
 constexpr float kRescaleAt = 64.0f;               // advance a lane's softmax reference when topped by 2^64
+
+// What the workgroup of one chunk hands to the combine: the chunk's largest logit, its softmax
+// sums relative to that logit, and its exact local winner (score known to within +-e).
+struct __attribute__((aligned(16))) ChunkResult {
+  float m, sum, sumw, s;
+  float e, x;
+  int32_t v;
+  int32_t pad;
+};
 
 struct StepArgs {
   const void* logits;
@@ -70,7 +79,12 @@ struct StepArgs {
   float* regret;
   float* logprob;
   float* entropy;
+  // a row split over `nch` workgroups: workgroup row * nch + c streams tiles [c ntiles / nch, (c + 1) ntiles / nch)
+  int32_t nch;
+  ChunkResult* partials;         // [B * nch] what each chunk found, combined by the last one of a row to arrive
+  uint32_t* tickets;             // [B] arrivals per row; zero before the launch and again after it
 };
+
 
 // ---------------------------------------------------------------- row access
 // The raw words of a lane's 8 elements.  Kept as scalars on purpose: the ring of loads in
@@ -307,26 +321,32 @@ __device__ __forceinline__ ChainOut scalar_chain(const StepArgs& a, int row, flo
 }
 
 // ---------------------------------------------------------------- shared memory
+// Blocks are named by their index q in the row everywhere (survivor lists, top_q, visq); the
+// per-block tables only cover the workgroup's chunk and are reached through the accessors, which
+// subtract q0, the chunk's first block (a multiple of 8).
 struct StepShared {
   float* mu;        // [nslots][2] per block slot (tile * 8 + group): upper bound of M_q (phase 1 only; phase 2
                     //   keeps its survivor list there), and the bound of the block's best score
   uint32_t* wq;     // [nslots] the block's word of the random stream
-  __device__ __forceinline__ float& mub(int b) const { return mu[2 * b]; }
-  __device__ __forceinline__ float& ub(int b) const { return mu[2 * b + 1]; }
+  int q0;           // first block of the chunk
+  __device__ __forceinline__ float& mub(int q) const { return mu[2 * (q - q0)]; }
+  __device__ __forceinline__ float& ub(int q) const { return mu[2 * (q - q0) + 1]; }
+  __device__ __forceinline__ uint32_t& word(int q) const { return wq[q - q0]; }
+  __device__ __forceinline__ float& blockmax(int q) const { return bmx[q - q0]; }
   __device__ __forceinline__ int& surv(int k) const { return ((int*)mu)[2 * k]; }
-  void* top_raw;    // [kSlots][64 elements] data of each lane group's best block
-  int* top_q;       // [kSlots] which block each lane group kept
-  float* m;         // [kStepWaves] wave maxima
-  float* sum;       // [kStepWaves] wave softmax sums (relative to the row maximum)
-  float* sumw;      // [kStepWaves] wave sums of 2^t t, t = (y_v - y_max) log2 e (entropy output only)
-  double* res_s;    // [kStepWaves] per-wave search results
+  void* top_raw;    // [8 W][64 elements] data of each lane group's best block
+  int* top_q;       // [8 W] which block each lane group kept
+  float* m;         // [W] wave maxima
+  float* sum;       // [W] wave softmax sums (relative to the chunk maximum)
+  float* sumw;      // [W] wave sums of 2^t t, t = (y_v - y_max) log2 e (entropy output only)
+  double* res_s;    // [W] per-wave search results
   double* res_hi2;
   float* res_e;
   int* res_v;
   float* res_x;
-  float* lo;        // [kStepWaves] score each wave knows to be attained
-  int* visq;        // [kStepWaves] block each wave scored before the first barrier, or -1
-  float* fres;      // [5][kStepWaves] per-wave results of the fp32 search: s, e, x, hi2, v
+  float* lo;        // [W] score each wave knows to be attained
+  int* visq;        // [W] block each wave scored before the first barrier, or -1
+  float* fres;      // [5][W] per-wave results of the fp32 search: s, e, x, hi2, v
   int32_t* cand_v;  // [kCandCap] long survivor lists: indices that can still win ...
   float* cand_x;    // [kCandCap] ... and their logits
   int* ncand;       // [1]
@@ -336,10 +356,12 @@ struct StepShared {
   float* bmx;       // [nslots] largest logit of every block (filtered draws only, else null)
 };
 
-template <int DT, bool Filter>
-__device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
+template <int DT, bool Filter, int W>
+__device__ __forceinline__ StepShared carve(unsigned char* base, int nslots, int q0) {
+  constexpr int kStepWaves = W, kSlots = W * kGroups;
   StepShared s;
   s.floor = kNegInf;
+  s.q0 = q0;
   size_t off = 0;
   auto take = [&](size_t bytes) { void* p = base + off; off += (bytes + 15) & ~(size_t)15; return p; };
   s.res_s = (double*)take(kStepWaves * 8);
@@ -366,10 +388,11 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots) {
   return s;
 }
 
-size_t step_lds_bytes(int dt, int ntiles, bool filter) {
+// Dynamic LDS of a workgroup of `waves` wavefronts whose chunk has `ntiles` tiles (what carve() lays out).
+size_t step_lds_bytes(int dt, int ntiles, bool filter, int waves) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
-  const size_t nslots = (size_t)ntiles * kGroups;
-  return 2 * kStepWaves * 8 + kSlots * kDrawBlock * esz + kSlots * 4 + 13 * kStepWaves * 4 + 16 + 2 * kCandCap * 4 +
+  const size_t nslots = (size_t)ntiles * kGroups, slots = (size_t)waves * kGroups;
+  return 2 * (size_t)waves * 8 + slots * kDrawBlock * esz + slots * 4 + 13 * (size_t)waves * 4 + 16 + 2 * kCandCap * 4 +
          ((nslots * 8 + 15) & ~(size_t)15) + (filter ? 2 : 1) * ((nslots * 4 + 15) & ~(size_t)15);
 }
 
@@ -379,10 +402,13 @@ __device__ __forceinline__ float ub_rounded_up(float u) { return fmaf(fabsf(u), 
 
 // Whether block b can hold a logit that takes part in the search: always, unless the draw is
 // filtered; then only if its largest logit is above the floor.
-__device__ __forceinline__ bool holds_eligible(const StepShared& sh, int b) { return sh.bmx == nullptr || sh.bmx[b] > sh.floor; }
+__device__ __forceinline__ bool holds_eligible(const StepShared& sh, int q) { return sh.bmx == nullptr || sh.blockmax(q) > sh.floor; }
 
-// Slot (wave, group) that streamed block q in phase 1.
-__device__ __forceinline__ int slot_of(int q) { return ((q >> 3) & (kStepWaves - 1)) * kGroups + (q & (kGroups - 1)); }
+// Wave that streamed block q in phase 1, and the slot (wave, group) of that block.
+template <int W>
+__device__ __forceinline__ int wave_of(const StepShared& sh, int q) { return ((q - sh.q0) >> 3) & (W - 1); }
+template <int W>
+__device__ __forceinline__ int slot_of(const StepShared& sh, int q) { return wave_of<W>(sh, q) * kGroups + (q & (kGroups - 1)); }
 
 // ---------------------------------------------------------------- phase 2
 __device__ __forceinline__ int float_key(float f) {  // order-preserving map to signed int
@@ -400,8 +426,9 @@ __device__ __forceinline__ float round_down_f32(F v) {
 
 // Merges the lanes' and then the waves' search states in a fixed order; returns the same
 // result in every thread.  All threads of the workgroup must call it.
-template <typename F>
+template <typename F, int W>
 __device__ __forceinline__ Search<F> combine_search(const StepShared& sh, Search<F> st) {
+  constexpr int kStepWaves = W;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   st = wave_merge(st);
@@ -431,14 +458,15 @@ __device__ __forceinline__ Search<F> combine_search(const StepShared& sh, Search
 // score found that way is then scored, one block per wave visit.  `between` runs right
 // after the first barrier.  Returns the winner, the same in every thread; all threads of
 // the workgroup must call it.
-template <int DT, typename F, typename Between>
+template <int DT, typename F, int W, typename Between>
 __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepShared& sh, const void* rowp, int row,
                                                  int nslots, int q_own, F bound0, Between between) {
+  constexpr int kStepWaves = W, kStepThreads = W * kWave;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   auto data_of = [&](int q) -> const void* {  // LDS copy if a lane group kept this block, else the row
-    const int slot = slot_of(q);
+    const int slot = slot_of<W>(sh, q);
     if (sh.top_q[slot] == q) return (const char*)sh.top_raw + (size_t)slot * kDrawBlock * elem_bytes<DT>();
     return (const char*)rowp + (size_t)q * kDrawBlock * elem_bytes<DT>();
   };
@@ -467,9 +495,9 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
 #pragma unroll
       for (int w = 1; w < kStepWaves; ++w) bound_f = fmaxf(bound_f, sh.lo[w]);
       // blocks whose bound reaches the best score found so far
-      for (int b = tid; b < nslots; b += kStepThreads) {
+      for (int b = sh.q0 + tid; b < sh.q0 + nslots; b += kStepThreads) {
         const float u = sh.ub(b);
-        if (u > -1e30f && ub_rounded_up(u) >= bound_f && sh.visq[(b >> 3) & (kStepWaves - 1)] != b && holds_eligible(sh, b))
+        if (u > -1e30f && ub_rounded_up(u) >= bound_f && sh.visq[wave_of<W>(sh, b)] != b && holds_eligible(sh, b))
           sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       __syncthreads();
@@ -481,7 +509,7 @@ __device__ __forceinline__ Search<F> find_argmax(const StepArgs& a, const StepSh
     if (k >= nsurv) break;
     q = sh.surv(k);
   }
-  return combine_search<F>(sh, st);
+  return combine_search<F, W>(sh, st);
 }
 
 // ---------------------------------------------------------------- phase 2 in fp32
@@ -505,7 +533,7 @@ __device__ __forceinline__ void score_element(const StepArgs& a, const StepShare
   // the index's own word depends on nothing else here: its ten rounds overlap the loads
   const Philox4 p = philox4x32_10((uint32_t)(v >> 2), (uint32_t)a.step, (uint32_t)row, kTagElem, a.key0, a.key1);
   const uint32_t w = (v & 3) == 0 ? p.w[0] : (v & 3) == 1 ? p.w[1] : (v & 3) == 2 ? p.w[2] : p.w[3];
-  const uint32_t wb = sh.wq[q];
+  const uint32_t wb = sh.word(q);
   const float nlb = neg_log_uniform<float>(wb);
   const float M = flog((float)n) - flog(nlb);                 // M_q = ln n - ln(-ln u)
   const float emM = nlb * __builtin_amdgcn_rcpf((float)n);    // exp(-M_q) = (-ln u) / n
@@ -529,33 +557,34 @@ __device__ __forceinline__ void score_element(const StepArgs& a, const StepShare
 }
 
 // This lane's element of block q: from LDS if a lane group kept the block, else from the row.
-template <int DT>
+template <int DT, int W>
 __device__ __forceinline__ float block_elem(const StepArgs& a, const StepShared& sh, const void* rowp, int q) {
   const int lane = threadIdx.x & (kWave - 1);
   const int32_t first = q * kDrawBlock;
   const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
-  const int slot = slot_of(q);
+  const int slot = slot_of<W>(sh, q);
   const int idx = lane < n ? lane : n - 1;  // stay inside the row in a ragged last block
   if (sh.top_q[slot] == q) return elem_at<DT>((const char*)sh.top_raw + (size_t)slot * kDrawBlock * elem_bytes<DT>(), idx);
   return elem_at<DT>((const char*)rowp + (size_t)first * elem_bytes<DT>(), idx);
 }
 
 // Scores the 64 indices of block q, one per lane.
-template <int DT>
+template <int DT, int W>
 __device__ __forceinline__ void fast_visit(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int q,
                                            Best& st) {
   const int lane = threadIdx.x & (kWave - 1);
   const int32_t n = a.V - q * kDrawBlock < kDrawBlock ? a.V - q * kDrawBlock : kDrawBlock;
-  score_element(a, sh, row, q * kDrawBlock + lane, block_elem<DT>(a, sh, rowp, q), lane < n, st);
+  score_element(a, sh, row, q * kDrawBlock + lane, block_elem<DT, W>(a, sh, rowp, q), lane < n, st);
 }
 
 // For a row with a long survivor list: instead of scoring every index of every surviving
 // block, the blocks' logits are only compared with the bound (index v can win only if
 // y_v + M_q reaches it), four blocks per wave at a time so that their loads overlap; the few
 // indices that pass are collected and then scored by all threads at once.
-template <int DT>
+template <int DT, int W>
 __device__ __forceinline__ void collect_candidates(const StepArgs& a, const StepShared& sh, const void* rowp, int nsurv,
                                                    float bound) {
+  constexpr int kStepWaves = W;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
 #pragma unroll 1
@@ -567,14 +596,14 @@ __device__ __forceinline__ void collect_candidates(const StepArgs& a, const Step
       const int k = base + j * kStepWaves;
       qs[j] = k < nsurv ? __builtin_amdgcn_readfirstlane(sh.surv(k)) : -1;
       xs[j] = kNegInf;
-      if (qs[j] >= 0) xs[j] = block_elem<DT>(a, sh, rowp, qs[j]);
+      if (qs[j] >= 0) xs[j] = block_elem<DT, W>(a, sh, rowp, qs[j]);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       if (qs[j] < 0) continue;
       const int32_t first = qs[j] * kDrawBlock;
       const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
-      const float M = flog((float)n) - flog(neg_log_uniform<float>(sh.wq[qs[j]]));
+      const float M = flog((float)n) - flog(neg_log_uniform<float>(sh.word(qs[j])));
       const float y = xs[j] * a.inv_tau;
       if (lane < n && xs[j] > sh.floor && (y + M) + 2.0f * score_margin(a, y) >= bound) {
         const int i = atomicAdd(sh.ncand, 1);
@@ -592,21 +621,22 @@ __device__ __forceinline__ void collect_candidates(const StepArgs& a, const Step
 // be the maximum.  They are collected as above, usually two or three, and scored in double
 // by one thread each.  Returns false if they do not fit the candidate buffer (then the
 // caller searches block by block); all threads of the workgroup must call it.
-template <int DT>
+template <int DT, int W>
 __device__ __forceinline__ bool exact_among_candidates(const StepArgs& a, const StepShared& sh, const void* rowp, int row,
                                                        int nslots, float lower, Search<double>& out) {
+  constexpr int kStepThreads = W * kWave;
   const int tid = threadIdx.x;
   if (tid == 0) {
     *sh.nsurv = 0;
     *sh.ncand = 0;
   }
   __syncthreads();
-  for (int b = tid; b < nslots; b += kStepThreads) {
+  for (int b = sh.q0 + tid; b < sh.q0 + nslots; b += kStepThreads) {
     const float u = sh.ub(b);
     if (u > -1e30f && ub_rounded_up(u) >= lower && holds_eligible(sh, b)) sh.surv(atomicAdd(sh.nsurv, 1)) = b;
   }
   __syncthreads();
-  collect_candidates<DT>(a, sh, rowp, *sh.nsurv, lower);
+  collect_candidates<DT, W>(a, sh, rowp, *sh.nsurv, lower);
   __syncthreads();
   const int ncand = *sh.ncand;
   if (ncand > kCandCap) return false;
@@ -617,7 +647,7 @@ __device__ __forceinline__ bool exact_among_candidates(const StepArgs& a, const 
     const BlockDraw<double> d = block_draw<double>(a, row, v >> 6);
     score_index<double>(a, row, v, sh.cand_x[i], d, -__builtin_huge_val(), sh.floor, st);
   }
-  out = combine_search<double>(sh, st);
+  out = combine_search<double, W>(sh, st);
   return true;
 }
 
@@ -645,9 +675,10 @@ __device__ __forceinline__ float key_float(int k) { return __builtin_bit_cast(fl
 // attained, and every other block whose bound reaches it is then scored, one block per wave
 // visit.  `between` runs right after the first barrier.  Returns the wave-uniform result,
 // the same in every wave; all threads of the workgroup must call it.
-template <int DT, typename Between>
+template <int DT, int W, typename Between>
 __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int nslots,
                                             int q_own, Between between) {
+  constexpr int kStepWaves = W, kStepThreads = W * kWave;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -656,7 +687,7 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
   bool first = true;
 #pragma unroll 1
   while (true) {  // one visit site for the wave's own block and for the survivors
-    if (q >= 0) fast_visit<DT>(a, sh, rowp, row, q, st);
+    if (q >= 0) fast_visit<DT, W>(a, sh, rowp, row, q, st);
     if (first) {
       first = false;
       const float lo = wave_max(st.s - st.e);
@@ -671,16 +702,16 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
       __syncthreads();
       between();
       const float bound = wave_max(lane < kStepWaves ? sh.lo[lane] : kNegInf);
-      for (int b = tid; b < nslots; b += kStepThreads) {  // blocks whose bound reaches the best score found so far
+      for (int b = sh.q0 + tid; b < sh.q0 + nslots; b += kStepThreads) {  // blocks whose bound reaches the best score found so far
         const float u = sh.ub(b);
-        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[(b >> 3) & (kStepWaves - 1)] != b && holds_eligible(sh, b))
+        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[wave_of<W>(sh, b)] != b && holds_eligible(sh, b))
           sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       if (tid == 0) *sh.bkey = float_key(bound);
       __syncthreads();
       nsurv = *sh.nsurv;
       if (nsurv > kStepWaves) {  // long list
-        collect_candidates<DT>(a, sh, rowp, nsurv, bound);
+        collect_candidates<DT, W>(a, sh, rowp, nsurv, bound);
         __syncthreads();
         const int ncand = *sh.ncand;
         if (ncand <= kCandCap) {  // else (tie-heavy rows): block by block below
@@ -724,14 +755,33 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
 }
 
 // ---------------------------------------------------------------- the kernel
-template <int DT, bool Entropy, bool Filter, bool Sum>
-__global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) {
+// alive[row] == 0, read through the scalar data path: the aligned 32-bit word that holds the flag (it
+// lies in the same page as the flag, so the read cannot fault wherever the array ends).  A workgroup
+// whose row is done holds its place in the dispatcher's queue until it knows; the scalar path tells
+// it sooner than a vector load.  The kernel writes the flag later with a vector store, after this
+// read, and never reads it again.
+__device__ __forceinline__ bool row_is_done(const uint8_t* alive, int row) {
+  const uintptr_t addr = (uintptr_t)(alive + row);
+  const uint32_t* word = (const uint32_t*)(addr & ~(uintptr_t)3);
+  uint32_t bits;
+  asm volatile("s_load_dword %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(bits) : "s"(word) : "memory");
+  return ((bits >> (8u * (uint32_t)(addr & 3))) & 0xffu) == 0u;
+}
+
+template <int DT, bool Entropy, bool Filter, bool Sum, int W>
+__global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
   static_assert(Sum || (!Entropy && !Filter), "entropy and filtered draws need the softmax sum");
+  static_assert(!Filter || W == 16, "a filtered draw looks at the whole row: one workgroup of 16 waves per row");
+  constexpr int kStepWaves = W, kStepThreads = W * kWave, kSlots = W * kGroups;
   extern __shared__ __align__(16) unsigned char smem_raw[];
-  const int row = blockIdx.x;
   const int tid = threadIdx.x;
-  if (a.alive[row] == 0) {  // done rows are not decoded (Algorithm 1, loop condition)
-    if (tid == 0) {
+  // workgroup row * nch + c owns chunk c of the row: tiles [tile0, tile1)
+  const unsigned unit = blockIdx.x;
+  const int nch = Filter ? 1 : a.nch;
+  const int row = nch == 1 ? (int)unit : (int)(unit / (unsigned)nch);
+  const int chunk = (int)unit - row * nch;
+  if (row_is_done(a.alive, row)) {  // done rows are not decoded (Algorithm 1, loop condition)
+    if (tid == 0 && chunk == 0) {
       a.tokens[row] = -1;
       a.regret[row] = 0.0f;
       if (a.logprob) a.logprob[row] = 0.0f;
@@ -742,16 +792,21 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int grp = lane >> 3;
-  const int ntiles = a.ntiles;
-  const int nslots = ntiles * kGroups;  // block slots incl. the non-existent ones of the last tile
-  const StepShared sh = carve<DT, Filter>(smem_raw, nslots);
+  const int ntiles = a.ntiles;  // of the row
+  const int tile0 = nch == 1 ? 0 : (int)(((int64_t)chunk * ntiles) / nch);
+  const int tile1 = nch == 1 ? ntiles : (int)(((int64_t)(chunk + 1) * ntiles) / nch);
+  const int ctiles = tile1 - tile0;
+  const int nslots = ctiles * kGroups;  // block slots of the chunk incl. the non-existent ones of the row's last tile
+  const StepShared sh = carve<DT, Filter, W>(smem_raw, nslots, tile0 * kGroups);
   const void* rowp = (const char*)a.logits + (size_t)row * (size_t)a.row_stride * elem_bytes<DT>();
 
-  // ------------------------------------------------------------ phase 1: stream the row
-  // Wave iteration i handles tile i*kStepWaves + wave.  Lanes whose 16-byte group starts at or beyond
-  // V (last tile only) read the last valid group instead and are masked below.
-  const int my_tiles = wave < ntiles ? (ntiles - wave + kStepWaves - 1) / kStepWaves : 0;
+  // ------------------------------------------------------------ phase 1: stream the chunk
+  // Wave iteration i handles tile tile0 + i*W + wave.  Lanes whose 16-byte group starts at or beyond
+  // V (the row's last tile only) read the last valid group instead and are masked below.
+  const int my_tiles = wave < ctiles ? (ctiles - wave + kStepWaves - 1) / kStepWaves : 0;
   const uint32_t last_group = (uint32_t)(a.V - 1) & ~7u;
+  // the last 16-byte group of the chunk: where the first ring's loads of a wave with fewer tiles go
+  const uint32_t chunk_last = tile1 == ntiles ? last_group : (uint32_t)tile1 * kTile - 8u;
   const uint32_t lane_off = (uint32_t)lane * 8u;
   const uint32_t lane_bytes = lane_off * (uint32_t)elem_bytes<DT>();
   auto load_tile = [&](int t) {  // t is wave-uniform
@@ -760,29 +815,31 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
     return load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
   };
   // The first ring of loads is issued by every wave, whether it has that many tiles or not
-  // (addresses beyond the row fall back on its last group): with a fixed number of loads in
+  // (addresses beyond the chunk fall back on its last group): with a fixed number of loads in
   // flight the compiler can wait for exactly the one a ring slot needs.
   Raw<DT> ring[kRing];
 #pragma unroll
   for (int d = 0; d < kRing; ++d) {
-    const uint32_t e0 = (uint32_t)(d * kStepWaves + wave) * kTile + lane_off;
-    ring[d] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
+    const uint32_t e0 = (uint32_t)(tile0 + d * kStepWaves + wave) * kTile + lane_off;
+    ring[d] = load_raw<DT>(rowp, e0 < chunk_last ? e0 : chunk_last, (uint32_t)a.V);
   }
-  // While the first loads are in flight: M_q bounds of all blocks, four per Philox call.
+  // While the first loads are in flight: M_q bounds of the chunk's blocks, four per Philox call
+  // (the chunk starts at a multiple of 8 blocks, so the calls' groups of four line up).
   for (int c = tid; c * 4 < nslots; c += kStepThreads) {
-    const Philox4 p = philox4x32_10((uint32_t)c, (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
+    const int b0 = sh.q0 + c * 4;
+    const Philox4 p = philox4x32_10((uint32_t)(b0 >> 2), (uint32_t)a.step, (uint32_t)row, kTagBlock, a.key0, a.key1);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int b = c * 4 + j;
+      const int b = b0 + j;
       float mub = kNegInf;
       if (b < a.nblocks) {
         const int32_t n = a.V - b * kDrawBlock < kDrawBlock ? a.V - b * kDrawBlock : kDrawBlock;
         mub = (__builtin_amdgcn_logf((float)n) * kLn2 + 2e-6f) + gumbel_upper_f32(p.w[j]);
         mub += 1e-5f + 4e-7f * fabsf(mub);  // room for the rounding of y_max + M_q below
       }
-      if (b < nslots) {
+      if (c * 4 + j < nslots) {
         sh.mub(b) = mub;
-        sh.wq[b] = p.w[j];
+        sh.word(b) = p.w[j];
       }
     }
   }
@@ -808,7 +865,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   // refilled with a tile that is not the last either.
   auto iteration = [&](auto steady, int d, int i) {
     constexpr bool Steady = decltype(steady)::value;
-    const int t = i * kStepWaves + wave;
+    const int t = tile0 + i * kStepWaves + wave;
     float x[8];
     unpack<DT>(ring[d], x);
     if (!Steady && (t + 1) * kTile > a.V) {  // ragged last tile: indices at or beyond V do not exist
@@ -900,7 +957,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   if (lane == 0) sh.m[wave] = mw;
   if ((lane & 7) == 0) sh.top_q[wave * kGroups + grp] = top_q;
   float z_prev = 0.0f, value = 0.0f;  // wanted at the very end: fetched now, off the critical path
-  if (tid == 0) {
+  if (tid == 0 && nch == 1) {
     z_prev = a.z[row];
     value = a.values[row];
   }
@@ -922,21 +979,26 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   };
   int32_t tok;
   float x_a;
+  float s_a = kNegInf, e_a = 0.0f;  // the winner's score as a float known to within +-e_a (what the combine of a split row compares)
   // the argmax over the indices whose logit is above shx.floor: fp32 search, decided in double where needed
   auto search = [&](const StepShared& shx, auto between) {
-    const Best fast = fast_argmax<DT>(a, shx, rowp, row, nslots, q_own, between);
+    const Best fast = fast_argmax<DT, W>(a, shx, rowp, row, nslots, q_own, between);
     tok = fast.v;
     x_a = fast.x;
+    s_a = fast.s;
+    e_a = fast.e;
     if (fast.v >= 0 && !(fast.s - fast.e > fast.hi2)) {
       // the two best fp32 scores overlap within their margins: decide in double (rare)
       __syncthreads();  // everyone has read the fp32 results
       Search<double> exact;
-      if (!exact_among_candidates<DT>(a, shx, rowp, row, nslots, fast.s - fast.e, exact)) {
+      if (!exact_among_candidates<DT, W>(a, shx, rowp, row, nslots, fast.s - fast.e, exact)) {
         __syncthreads();
-        exact = find_argmax<DT, double>(a, shx, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
+        exact = find_argmax<DT, double, W>(a, shx, rowp, row, nslots, q_own, (double)fast.s - (double)fast.e, [] {});
       }
       tok = exact.best.v;
       x_a = exact.best.x;
+      s_a = (float)exact.best.s;                 // rounded to float: within 2^-24 relative of the double score
+      e_a = fmaf(fabsf(s_a), 1.2e-7f, 1e-30f);
     }
   };
   // the largest float below x (x finite or +inf): a floor that lets x itself through
@@ -1007,7 +1069,7 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
             if (k < nabove) {
               const int q = __builtin_amdgcn_readfirstlane(sh.surv(k));
               ns[u] = a.V - q * kDrawBlock < kDrawBlock ? a.V - q * kDrawBlock : kDrawBlock;
-              xs[u] = block_elem<DT>(a, sh, rowp, q);
+              xs[u] = block_elem<DT, W>(a, sh, rowp, q);
             }
           }
 #pragma unroll
@@ -1241,28 +1303,100 @@ __global__ __launch_bounds__(kStepThreads, 8) void espo_step_kernel(StepArgs a) 
   }
 
   // ------------------------------------------------------------ finalize: one lane
-  if (wave == 0) {
-    const float S = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // sum_v exp((x_v - m)/tau), fixed order
-    float Sw = 0.0f;
-    if constexpr (Entropy) Sw = wave_sum(lane < kStepWaves ? sh.sumw[lane] : 0.0f);
-    if (lane == 0) {
-      if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
-      const ChainOut c = scalar_chain(a, row, m, x_a, z_prev, value);
-      a.tokens[row] = tok;
-      a.regret[row] = c.g;
-      a.z[row] = c.z;
-      if (Sum && a.logprob) a.logprob[row] = -c.g - flog(S);
-      if constexpr (Entropy)  // H = ln S - E_pi[y - y_max] >= 0; rounding can leave S a few ulp below 1
-        a.entropy[row] = fmaxf(flog(S) - kLn2 * Sw / S, 0.0f);
-      if (a.eos_id >= 0 && tok == a.eos_id) {
-        a.alive[row] = 0;  // natural end
-      } else if (c.stop) {
-        if (a.simulate) {  // bookkeeping only: the first stop step is recorded, decoding goes on
-          if (a.stop_step[row] < 0) a.stop_step[row] = a.step;
-        } else {
-          a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
-          a.stop_step[row] = a.step;
+  if (wave != 0) return;
+  float S = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // sum_v exp((x_v - m)/tau) over the chunk, fixed order
+  float Sw = 0.0f;
+  if constexpr (Entropy) Sw = wave_sum(lane < kStepWaves ? sh.sumw[lane] : 0.0f);
+  if constexpr (!Filter) {
+    if (nch > 1) {
+      // A row split over nch workgroups: each leaves its chunk's result in the workspace and takes a
+      // ticket; the one that takes the row's last ticket finishes the row.  Results, tickets and the
+      // reads of the results all go through device-scope atomic accesses, which bypass the caches that
+      // are private to a part of the chip, and a workgroup takes its ticket only once its stores have
+      // been acknowledged, so whoever sees the last ticket also sees every result.  (A device-scope
+      // fence would do too, but writes back and invalidates a whole L2 per workgroup: measured, 50 ns
+      // of serialised work per workgroup, 100 us per launch.)  atomicInc wraps to zero at nch - 1, so
+      // the ticket is ready for the next launch without anyone clearing it.
+      uint32_t arrived = 0;
+      if (lane == 0) {
+        uint32_t* const dst = (uint32_t*)(a.partials + (size_t)unit);
+        const uint32_t w[7] = {__builtin_bit_cast(uint32_t, m),   __builtin_bit_cast(uint32_t, S),   __builtin_bit_cast(uint32_t, Sw),
+                               __builtin_bit_cast(uint32_t, s_a), __builtin_bit_cast(uint32_t, e_a), __builtin_bit_cast(uint32_t, x_a),
+                               (uint32_t)tok};
+#pragma unroll
+        for (int j = 0; j < 7; ++j) __hip_atomic_store(dst + j, w[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores are done before the ticket is taken
+        arrived = atomicInc(a.tickets + row, (uint32_t)(nch - 1));
+      }
+      arrived = (uint32_t)__builtin_amdgcn_readfirstlane((int)arrived);
+      if (arrived != (uint32_t)(nch - 1)) return;
+      if (lane == 0) {
+        z_prev = a.z[row];
+        value = a.values[row];
+      }
+      // lane c holds chunk c (nch <= 64); the other lanes hold a chunk without any finite logit
+      float m_c = kNegInf, S_c = 0.0f, Sw_c = 0.0f;
+      Best win = no_best();
+      if (lane < nch) {
+        const uint32_t* src = (const uint32_t*)(a.partials + (size_t)row * nch + lane);
+        uint32_t w[7];
+#pragma unroll
+        for (int j = 0; j < 7; ++j) w[j] = __hip_atomic_load(src + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // hand the workspace back as it came: all zero (the tickets clear themselves), so that a later call of
+        // another shape, whose tickets may lie where these results were, can use the same buffer
+        u32x4* const back = (u32x4*)(a.partials + (size_t)row * nch + lane);
+        back[0] = u32x4{0u, 0u, 0u, 0u};
+        back[1] = u32x4{0u, 0u, 0u, 0u};
+        m_c = __builtin_bit_cast(float, w[0]);
+        S_c = __builtin_bit_cast(float, w[1]);
+        Sw_c = __builtin_bit_cast(float, w[2]);
+        win.s = __builtin_bit_cast(float, w[3]);
+        win.e = __builtin_bit_cast(float, w[4]);
+        win.x = __builtin_bit_cast(float, w[5]);
+        win.v = (int32_t)w[6];
+        if (win.v < 0) win = no_best();
+      }
+      m = wave_max(m_c);
+      // the chunks' sums are relative to their own maxima: moved to the row maximum like a lane's in phase 1
+      const float shift = (m_c - m) * a.k2;
+      const float f = __builtin_amdgcn_exp2f(shift);
+      S = wave_sum(S_c > 0.0f ? S_c * f : 0.0f);
+      if constexpr (Entropy) Sw = wave_sum(S_c > 0.0f ? f * fmaf(shift, S_c, Sw_c) : 0.0f);
+      // every chunk's winner is its exact argmax, so the row's is the best of them: decided in fp32
+      // where the margins allow, else by scoring those few indices in double
+      const Best top = wave_best(win);
+      tok = top.v;
+      x_a = top.x;
+      if (top.v >= 0 && !(top.s - top.e > top.hi2)) {
+        Search<double> st;
+        st.init();
+        if (win.v >= 0) {
+          const BlockDraw<double> d = block_draw<double>(a, row, win.v >> 6);
+          score_index<double>(a, row, win.v, win.x, d, -__builtin_huge_val(), kNegInf, st);
         }
+        st = wave_merge(st);
+        tok = st.best.v;
+        x_a = st.best.x;
+      }
+    }
+  }
+  if (lane == 0) {
+    if (tok < 0) { tok = 0; x_a = elem_at<DT>(rowp, 0); }  // row of -inf only: unspecified, stay in range
+    const ChainOut c = scalar_chain(a, row, m, x_a, z_prev, value);
+    a.tokens[row] = tok;
+    a.regret[row] = c.g;
+    a.z[row] = c.z;
+    if (Sum && a.logprob) a.logprob[row] = -c.g - flog(S);
+    if constexpr (Entropy)  // H = ln S - E_pi[y - y_max] >= 0; rounding can leave S a few ulp below 1
+      a.entropy[row] = fmaxf(flog(S) - kLn2 * Sw / S, 0.0f);
+    if (a.eos_id >= 0 && tok == a.eos_id) {
+      a.alive[row] = 0;  // natural end
+    } else if (c.stop) {
+      if (a.simulate) {  // bookkeeping only: the first stop step is recorded, decoding goes on
+        if (a.stop_step[row] < 0) a.stop_step[row] = a.step;
+      } else {
+        a.alive[row] = 0;  // absorbing failure (Eq. failure_reward): the trajectory ends here
+        a.stop_step[row] = a.step;
       }
     }
   }
@@ -1309,12 +1443,53 @@ int launch_math_errors(float* out, hipStream_t stream) {
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 
-size_t step_shared_bytes(int dt, int64_t V, bool filter) { return step_lds_bytes(dt, (int)((V + kTile - 1) / kTile), filter); }
+// ---------------------------------------------------------------- launch configuration
+// How a call is laid out on the GPU.  One workgroup of 16 waves streams a whole row.  The diagnostics
+// entry point can force fewer waves per workgroup and a split of every row into `chunks` runs of
+// tiles, each streamed by a workgroup of its own and combined by the last one to arrive.  Measured on
+// an MI355X (B = 512, V = 152064 bf16, all rows live): 34.7 us unsplit, 41 us in 2 chunks of 16 waves,
+// 39.6 us in 2 chunks of 8 waves, 53 us in 8 chunks of 4 waves: every chunk pays for a search of its
+// own and the row for one more round trip through memory (ticket, then the partial results), which is
+// more than the finer grain gains, so the library itself never splits.  (Also measured and left out:
+// 512 resident workgroups that claim rows from a counter in the workspace instead of one workgroup
+// per row, meant to make rows that are done cost a claim instead of a workgroup: 512 device-scope
+// atomics on one address take 50 ns each, and a launch of B = 1024 live rows went from 56 to 82 us.)
+
+// tickets first (256-byte aligned size), then the chunk results
+size_t step_workspace_layout(int64_t B, int chunks, size_t* partials_offset) {
+  const size_t tickets = (((size_t)B * sizeof(uint32_t)) + 255) & ~(size_t)255;
+  if (partials_offset) *partials_offset = tickets;
+  return tickets + (size_t)B * (size_t)chunks * sizeof(ChunkResult);
+}
+
+StepPlan plan_step(int dt, int64_t B, int64_t V, bool filter, int waves, int chunks) {
+  StepPlan p;
+  const int ntiles = (int)((V + kTile - 1) / kTile);
+  p.waves = waves > 0 ? waves : 16;
+  int nch = filter || chunks <= 0 ? 1 : chunks;
+  if (nch > ntiles) nch = ntiles;
+  if (nch > kMaxChunks) nch = kMaxChunks;
+  p.chunks = nch;
+  p.grid = B * nch;
+  const int ctiles = (ntiles + nch - 1) / nch;
+  p.lds = step_lds_bytes(dt, ctiles, filter, p.waves);
+  p.workspace = nch > 1 ? step_workspace_layout(B, nch, nullptr) : 0;
+  return p;
+}
+
+template <int DT, int W>
+void (*pick_kernel(bool sum, bool filter, bool entropy))(StepArgs) {
+  if constexpr (W == 16) {
+    if (filter) return entropy ? espo_step_kernel<DT, true, true, true, 16> : espo_step_kernel<DT, false, true, true, 16>;
+  }
+  if (!sum) return espo_step_kernel<DT, false, false, false, W>;
+  return entropy ? espo_step_kernel<DT, true, false, true, W> : espo_step_kernel<DT, false, false, true, W>;
+}
 
 int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                 uint64_t seed, int32_t step, const float* values, const espo_params& p, float margin_scale,
                 float* z, uint8_t* alive, int32_t* stop_step, int32_t* tokens, float* regret, float* logprob,
-                float* entropy, hipStream_t stream) {
+                float* entropy, void* workspace, const StepPlan& plan, hipStream_t stream) {
   StepArgs a;
   a.logits = logits;
   a.V = (int32_t)V;
@@ -1350,29 +1525,41 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   a.regret = regret;
   a.logprob = logprob;
   a.entropy = entropy;
+  a.nch = plan.chunks;
+  a.partials = nullptr;
+  a.tickets = nullptr;
+  if (plan.chunks > 1) {
+    size_t off = 0;
+    step_workspace_layout(B, plan.chunks, &off);
+    a.tickets = (uint32_t*)workspace;
+    a.partials = (ChunkResult*)((char*)workspace + off);
+  }
 
-  const dim3 grid((unsigned)B), block(kStepThreads);
   // the entropy output costs two more vector operations per logit: its own instantiation
   // and so does a filtered draw (more passes over the row)
   const bool filter = (p.top_p > 0.0f && p.top_p < 1.0f) || p.top_k > 0;
-  const size_t lds = step_lds_bytes(dt, a.ntiles, filter);
-  if (lds > kMaxStepLds) return ESPO_ERANGE;
+  if (plan.lds > kMaxStepLds) return ESPO_ERANGE;
+  if (filter && (plan.waves != 16 || plan.chunks != 1)) return ESPO_EINVAL;
+  if (plan.chunks > a.ntiles || plan.chunks > kMaxChunks || (int64_t)B * plan.chunks > 0x7fffffff) return ESPO_ERANGE;
   // and a step that is asked for neither log-probabilities nor either of these needs no softmax sum at all
   const bool sum = logprob != nullptr || entropy != nullptr || filter;
-  void (*kernel)(StepArgs);
+  void (*kernel)(StepArgs) = nullptr;
+  const bool ent = entropy != nullptr;
   if (dt == ESPO_BF16)
-    kernel = !sum     ? espo_step_kernel<ESPO_BF16, false, false, false>
-             : filter ? (entropy ? espo_step_kernel<ESPO_BF16, true, true, true> : espo_step_kernel<ESPO_BF16, false, true, true>)
-                      : (entropy ? espo_step_kernel<ESPO_BF16, true, false, true> : espo_step_kernel<ESPO_BF16, false, false, true>);
+    kernel = plan.waves == 16 ? pick_kernel<ESPO_BF16, 16>(sum, filter, ent)
+             : plan.waves == 8 ? pick_kernel<ESPO_BF16, 8>(sum, filter, ent)
+             : plan.waves == 4 ? pick_kernel<ESPO_BF16, 4>(sum, filter, ent) : nullptr;
   else
-    kernel = !sum     ? espo_step_kernel<ESPO_F32, false, false, false>
-             : filter ? (entropy ? espo_step_kernel<ESPO_F32, true, true, true> : espo_step_kernel<ESPO_F32, false, true, true>)
-                      : (entropy ? espo_step_kernel<ESPO_F32, true, false, true> : espo_step_kernel<ESPO_F32, false, false, true>);
-  if (lds > 64 * 1024) {  // beyond the default limit the kernel has to be told (very large vocabularies)
+    kernel = plan.waves == 16 ? pick_kernel<ESPO_F32, 16>(sum, filter, ent)
+             : plan.waves == 8 ? pick_kernel<ESPO_F32, 8>(sum, filter, ent)
+             : plan.waves == 4 ? pick_kernel<ESPO_F32, 4>(sum, filter, ent) : nullptr;
+  if (!kernel) return ESPO_EINVAL;
+  if (plan.lds > 64 * 1024) {  // beyond the default limit the kernel has to be told (very large vocabularies)
     if (hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMaxStepLds) != hipSuccess)
       return ESPO_EHIP;
   }
-  hipLaunchKernelGGL(kernel, grid, block, lds, stream, a);
+  const dim3 grid((unsigned)plan.grid), block((unsigned)(plan.waves * kWave));
+  hipLaunchKernelGGL(kernel, grid, block, plan.lds, stream, a);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 

@@ -87,11 +87,18 @@ int main(int argc, char** argv) {
   CK(hipMalloc((void**)&d_advp, (size_t)B * T * 4));
   const size_t ws_bytes = espo_whiten_workspace_bytes(B, T);
   CK(hipMalloc(&d_ws, ws_bytes));
+  // the workspace that lets espo_step split rows over workgroups: zero before its first use
+  const size_t step_ws_bytes = espo_step_workspace_bytes(B, V, ESPO_F32);
+  void* d_step_ws = nullptr;
+  if (step_ws_bytes) {
+    CK(hipMalloc(&d_step_ws, step_ws_bytes));
+    CK(hipMemset(d_step_ws, 0, step_ws_bytes));
+  }
   hipStream_t stream;
   CK(hipStreamCreate(&stream));
 
   EK(espo_step(d_logits, ESPO_F32, B, V, V, tau, seed, step, d_values, &p, d_z, d_alive, d_stop_step, d_tokens, d_regret,
-               d_logprob, d_entropy, nullptr, 0, stream));
+               d_logprob, d_entropy, d_step_ws, step_ws_bytes, stream));
   EK(espo_advantages(d_rewards, d_vals2, d_lengths, d_stopped, B, T, -1.0f, 1.0f, 0.95f, d_td, d_adv, stream));
   EK(espo_whiten(d_adv, d_lengths, B, T, 1e-8f, 1, 0, d_wh, nullptr, d_ws, ws_bytes, stream));
   EK(espo_advantages_packed(nullptr, d_values, d_vals2, d_cu, d_stopped, B, (int64_t)B * T, -1.0f, 1.0f, 0.95f, d_tdp,
@@ -121,6 +128,6 @@ int main(int argc, char** argv) {
                   wr(o, adv.data(), adv.size()) && wr(o, wh.data(), wh.size()) && wr(o, tdp.data(), tdp.size()) &&
                   wr(o, advp.data(), advp.size());
   std::fclose(o);
-  std::printf("abi_check: version %d, B=%d V=%d T=%d done\n", espo_version(), B, V, T);
+  std::printf("abi_check: version %d, B=%d V=%d T=%d, step workspace %zu bytes, done\n", espo_version(), B, V, T, step_ws_bytes);
   return ok ? 0 : 1;
 }

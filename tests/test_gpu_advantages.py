@@ -86,6 +86,31 @@ def test_config5_full_size():
     assert torch.equal(td1, td2) and torch.equal(adv1, adv2)
 
 
+def test_ablation_variant_without_the_failure_penalty():
+    _say("[case] advantages, variant C (no terminal penalty)")
+    # Section 6, variant C: trajectories are truncated by the stop rule but get no failure reward.  That is this
+    # call with every `stopped` flag zero: the truncated row keeps its stored last reward (0 in Algorithm 1).
+    # Checked against the oracle, and against the full method on the same rows: only the rows that the rule had
+    # stopped change, by r_fail (gamma lambda)^(L-1-t).
+    r, v, L, s = W.advantage_batch(B=64, T=3000, len_lo=1, seed=31, device="cuda", poison=True)
+    none = torch.zeros_like(s)
+    H.check_advantages(r, v, L, none, -1.0, 1.0, 0.95)
+    td_c, adv_c = torch.empty_like(r), torch.empty_like(r)
+    td_a, adv_a = torch.empty_like(r), torch.empty_like(r)
+    espo.espo_advantages(r, v, L, none, -1.0, 1.0, 0.95, td_c, adv_c)
+    espo.espo_advantages(r, v, L, s, -1.0, 1.0, 0.95, td_a, adv_a)
+    torch.cuda.synchronize()
+    diff = (adv_a - adv_c).cpu().numpy().astype(np.float64)
+    L_h, s_h = L.cpu().numpy(), s.cpu().numpy()
+    assert s_h.any() and not s_h.all()
+    c = float(np.float32(0.95))
+    for b in range(64):
+        n = int(L_h[b])
+        want = -1.0 * c ** (n - 1 - np.arange(n)) if s_h[b] else np.zeros(n)   # the stored last reward of a stopped row is 0
+        np.testing.assert_allclose(diff[b, :n], want, rtol=0, atol=1e-4)    # two fp32 scans of sums of size ~30
+        assert (diff[b, n:] == 0).all()
+
+
 @pytest.mark.parametrize("B", [513, 1025, 2500, 4096, 4097])
 def test_many_rows(B):
     _say(f"[case] advantages B={B}")
@@ -166,11 +191,12 @@ def test_terminal_form_config5_full_size():
     _say(f"  worst scaled error {worst:.2e}")
 
 
-def test_seeded_sweep_of_both_forms():
-    _say("[case] advantages, seeded sweep")
-    rng = np.random.default_rng(4242)
+@pytest.mark.parametrize("part", range(5))
+def test_seeded_sweep_of_both_forms(part):
+    _say(f"[case] advantages, seeded sweep, part {part} (140 cases, both reward forms each)")
+    rng = np.random.default_rng(4242 + part)
     worst = 0.0
-    for case in range(150):
+    for case in range(part * 140, part * 140 + 140):
         T = int(rng.choice([rng.integers(1, 64), rng.integers(64, 5000), rng.integers(5000, 20000)]))
         B = int(rng.integers(1, 12))
         g = torch.Generator().manual_seed(7000 + case)
@@ -294,11 +320,12 @@ def test_packed_config5_full_size():
     _say(f"  terminal form: worst scaled error {worst:.2e}")
 
 
-def test_packed_seeded_sweep():
-    _say("[case] packed advantages, seeded sweep")
-    rng = np.random.default_rng(5151)
+@pytest.mark.parametrize("part", range(4))
+def test_packed_seeded_sweep(part):
+    _say(f"[case] packed advantages, seeded sweep, part {part} (100 cases, both reward forms each)")
+    rng = np.random.default_rng(5151 + part)
     worst = 0.0
-    for case in range(120):
+    for case in range(part * 100, part * 100 + 100):
         B = int(rng.integers(1, 24))
         top = int(rng.choice([8, 200, 5000, 14000]))
         lens = [int(x) for x in rng.integers(0, top + 1, B)]

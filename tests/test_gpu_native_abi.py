@@ -18,13 +18,13 @@ def test_native_program_matches_the_oracle(tmp_path):
     if not os.path.exists(build.ABI_CHECK):
         build.build_abi_check()
     rng = np.random.default_rng(7)
-    B, V, T, step, seed, tau = 6, 5003, 300, 4, 123456789012345, 0.8
+    B, V, T, step, seed, tau = 516, 5003, 300, 4, 123456789012345, 0.8   # more rows than resident workgroups
     V_pad = 5004                              # a pitch of 5003 floats is not a multiple of 16 bytes: pad the rows
     logits = (rng.standard_normal((B, V_pad)) * 3).astype(np.float32)
     logits[:, V:] = 1e4
     values = rng.random(B).astype(np.float32)
     z = (rng.random(B) * 2 - 1).astype(np.float32)
-    alive = np.array([1, 1, 0, 1, 1, 1], np.uint8)
+    alive = (np.arange(B) % 6 != 2).astype(np.uint8)
     stop_step = np.full(B, -1, np.int32)
     rewards = rng.standard_normal((B, T)).astype(np.float32)
     vals2 = (rng.random((B, T)) * 2 - 1).astype(np.float32)
@@ -73,8 +73,8 @@ def test_native_program_matches_the_oracle(tmp_path):
     assert np.abs(logprob[live] - ref["logprob"][live]).max() <= 1e-5 * np.maximum(np.abs(ref["logprob"][live]), 1).max()
     assert (np.abs(entropy - ref["entropy"]) <= 1e-5 * np.maximum(ref["entropy"], 1)).all() and (entropy[~live] == 0).all()
     td_o, adv_o, scale = oracle.advantages(rewards, vals2, lengths, stopped, -1.0, 1.0, 0.95)
-    assert np.abs(td - td_o).max() <= 4e-7 * (np.abs(rewards).max() + 2 * np.abs(vals2).max() + 1)
-    assert (np.abs(adv - adv_o) <= 1e-5 * np.maximum(np.abs(adv_o), scale)).all()
+    assert np.abs(td - td_o).max() <= 2e-7 * (max(np.abs(rewards).max(), 1.0) + 2 * np.abs(vals2).max())
+    assert (np.abs(adv - adv_o) <= 2e-6 * np.maximum(np.abs(adv_o), scale)).all()
     # whitening of the advantages the program itself produced (its fp32 output is the oracle's input)
     wh_o, _ = oracle.whiten(adv, lengths)
     mask = np.arange(T)[None, :] < np.clip(lengths, 0, T)[:, None]
@@ -82,5 +82,5 @@ def test_native_program_matches_the_oracle(tmp_path):
     # the [B, T] values as B full trajectories stored back to back, terminal reward values[b]
     cu = (np.arange(B + 1) * T).astype(np.int64)
     tdp_o, advp_o, _, scale_p = oracle.advantages_packed(None, values, vals2.reshape(-1), cu, stopped, -1.0, 1.0, 0.95)
-    assert np.abs(td_p - tdp_o).max() <= 4e-7 * (np.abs(values).max() + 2 * np.abs(vals2).max() + 2)
-    assert (np.abs(adv_p - advp_o) <= 1e-5 * np.maximum(np.abs(advp_o), scale_p)).all()
+    assert np.abs(td_p - tdp_o).max() <= 2e-7 * (max(np.abs(values).max(), 1.0) + 2 * np.abs(vals2).max())
+    assert (np.abs(adv_p - advp_o) <= 2e-6 * np.maximum(np.abs(advp_o), scale_p)).all()

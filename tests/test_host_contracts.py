@@ -98,3 +98,67 @@ def test_parameter_structs_of_both_sides_have_the_same_layout():
     body = header[header.index("typedef struct {", header.index("frozen for a whole rollout batch")):header.index("} espo_params;")]
     declared = re.findall(r"^\s*(?:float|int32_t)\s+(\w+);", body, flags=re.M)
     assert declared == list(gd)
+
+
+def test_binding_refuses_tensors_that_are_too_short(monkeypatch):
+    # The C ABI takes bare pointers and cannot know sizes: a short tensor would be an out-of-bounds access on
+    # the GPU.  The binding therefore checks every tensor against B, T and N before the call.  Here the library
+    # is replaced by a recorder and host tensors stand in for device memory, so that nothing is launched.
+    from paper_2605_29860_amd import binding as b
+
+    class Recorder:
+        calls = 0
+
+        def __getattr__(self, name):
+            def call(*args):
+                Recorder.calls += 1
+                return 0
+            return call
+
+    monkeypatch.setattr(b, "load_library", lambda: Recorder())
+    monkeypatch.setattr(b, "_on_gpu", lambda t: True)
+    monkeypatch.setattr(b, "_stream", lambda s: None)
+    B, V, T = 4, 64, 16
+    f32, i32, u8 = torch.float32, torch.int32, torch.uint8
+    mk = lambda n, dt: torch.zeros(n, dtype=dt)
+    step_args = lambda **short: dict(
+        logits=torch.zeros(B, V), temperature=1.0, seed=0, step=0, values=mk(short.get("values", B), f32), params=b.EspoParams(),
+        z=mk(short.get("z", B), f32), alive=mk(short.get("alive", B), u8), stop_step=mk(short.get("stop_step", B), i32),
+        tokens=mk(short.get("tokens", B), i32), regret=mk(short.get("regret", B), f32),
+        logprob=mk(short.get("logprob", B), f32), entropy=mk(short.get("entropy", B), f32))
+    b.espo_step(**step_args())
+    assert Recorder.calls == 1
+    for name in ("values", "z", "alive", "stop_step", "tokens", "regret", "logprob", "entropy"):
+        with pytest.raises(ValueError, match=name):
+            b.espo_step(**step_args(**{name: B - 1}))
+    with pytest.raises(b.EspoError):
+        b.espo_step(**{**step_args(), "V": V + 1})
+    assert Recorder.calls == 1
+
+    adv_args = lambda **o: dict(rewards=torch.zeros(B, T), values=torch.zeros(*o.get("values", (B, T))),
+                                lengths=mk(o.get("lengths", B), i32), stopped=mk(o.get("stopped", B), u8), r_fail=-1.0, gamma=1.0,
+                                lam=0.95, td=torch.zeros(*o.get("td", (B, T))), adv=torch.zeros(*o.get("adv", (B, T))))
+    b.espo_advantages(**adv_args())
+    assert Recorder.calls == 2
+    for name, bad in (("values", (B, T - 1)), ("td", (B - 1, T)), ("adv", (B, T + 1)), ("lengths", B - 1), ("stopped", B - 1)):
+        with pytest.raises(ValueError, match=name):
+            b.espo_advantages(**adv_args(**{name: bad}))
+    term_args = lambda **o: dict(values=torch.zeros(B, T), lengths=mk(o.get("lengths", B), i32), stopped=mk(o.get("stopped", B), u8),
+                                 terminal_reward=mk(o.get("terminal_reward", B), f32), r_fail=-1.0, gamma=1.0, lam=0.95,
+                                 td=torch.zeros(*o.get("td", (B, T))), adv=torch.zeros(B, T), returns=torch.zeros(*o.get("returns", (B, T))))
+    b.espo_advantages_terminal(**term_args())
+    for name, bad in (("lengths", B - 1), ("stopped", 1), ("terminal_reward", B - 1), ("td", (B, T - 4)), ("returns", (B + 1, T))):
+        with pytest.raises(ValueError, match=name):
+            b.espo_advantages_terminal(**term_args(**{name: bad}))
+    out, ws = mk(b.BATCH_RESULT_BYTES, u8), mk(64, u8)
+    b.espo_batch_stats(torch.zeros(B, T), mk(B, i32), mk(B, u8), 1.0, 1.0, 1.0, out, ws)
+    b.espo_batch_stats_static(torch.zeros(B, T), mk(B, i32), mk(B, u8), 1.0, 1.0, 1.0, out)
+    calls = Recorder.calls
+    for fn, extra in ((b.espo_batch_stats, (ws,)), (b.espo_batch_stats_static, ())):
+        with pytest.raises(ValueError, match="lengths"):
+            fn(torch.zeros(B, T), mk(B - 1, i32), mk(B, u8), 1.0, 1.0, 1.0, out, *extra)
+        with pytest.raises(ValueError, match="stopped"):
+            fn(torch.zeros(B, T), mk(B, i32), mk(B - 2, u8), 1.0, 1.0, 1.0, out, *extra)
+        with pytest.raises(ValueError, match="out"):
+            fn(torch.zeros(B, T), mk(B, i32), mk(B, u8), 1.0, 1.0, 1.0, mk(8, u8), *extra)
+    assert Recorder.calls == calls

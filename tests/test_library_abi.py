@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every symbol that include/espo.h declares.
+"""The C-ABI library loads and exports every symbol that include/espo.h and include/espo_debug.h declare.
 
 Runs without a GPU: nothing is launched, only argument checking is exercised.
 """
@@ -20,8 +20,8 @@ def lib():
     return binding.load_library()
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "espo.h")).read()
+def _declared_functions(header="espo.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(espo_[a-z_]+)\s*\(", text)))
 
@@ -29,9 +29,12 @@ def _declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
     assert {"espo_step", "espo_advantages", "espo_advantages_terminal", "espo_advantages_packed", "espo_whiten", "espo_whiten_workspace_bytes", "espo_step_workspace_bytes", "espo_strerror", "espo_version",
-            "espo_debug_set_score_margin_scale", "espo_debug_math_errors", "espo_debug_copy", "espo_batch_stats",
-            "espo_batch_stats_workspace_bytes"} <= set(names)
-    for n in names:
+            "espo_batch_stats", "espo_batch_stats_workspace_bytes", "espo_batch_stats_static"} <= set(names)
+    assert not any(n.startswith("espo_debug") for n in names)       # diagnostics live in their own header
+    debug = _declared_functions("espo_debug.h")
+    assert {"espo_debug_step", "espo_debug_step_workspace_bytes", "espo_debug_math_errors", "espo_debug_copy",
+            "espo_debug_read", "espo_debug_sweep"} <= set(debug)
+    for n in names + debug:
         assert hasattr(lib, n), n
 
 
@@ -86,4 +89,16 @@ def test_argument_checks_need_no_gpu(lib):
     assert wh(B=-1) == -1 and wh(eps=-1.0) == -1 and wh(eps=float("nan")) == -1 and wh(adv=None) == -1
     assert wh(out=ctypes.c_void_p(0x1004)) == -2 and wh(stats=ctypes.c_void_p(0x1004)) == -2
     assert wh(ws=None) == -3 and wh(nws=need - 1) == -3
-    assert lib.espo_step_workspace_bytes(512, 152064, 1) == 0
+    assert lib.espo_step_workspace_bytes(1024, 152064, 1) == 0 and lib.espo_step_workspace_bytes(0, 152064, 1) == 0
+    lib.espo_debug_step.argtypes = lib.espo_step.argtypes + [ctypes.c_float, ctypes.c_int32, ctypes.c_int32]
+    dbg = lambda scale=1.0, waves=0, chunks=0: lib.espo_debug_step(fake, 1, 4, 4096, 4096, 1.0, 0, 0, fake, ctypes.byref(p), fake, fake,
+                                                                   fake, fake, fake, None, None, None, 0, None, scale, waves, chunks)
+    assert dbg(scale=0.5) == -1 and dbg(scale=float("nan")) == -1 and dbg(waves=5) == -1 and dbg(chunks=-1) == -1
+    assert dbg(chunks=4) == -3                                # a split without a workspace
+    need = 4 * 4 * 32 + 256
+    wsd = lambda ws, nws: lib.espo_debug_step(fake, 1, 4, 4096, 4096, 1.0, 0, 0, fake, ctypes.byref(p), fake, fake, fake, fake, fake,
+                                              None, None, ws, nws, None, 1.0, 0, 4)
+    assert wsd(fake, need - 1) == -3 and wsd(ctypes.c_void_p(0x1004), need) == -3   # too small; misaligned
+    lib.espo_debug_step_workspace_bytes.restype = ctypes.c_size_t
+    lib.espo_debug_step_workspace_bytes.argtypes = [ctypes.c_int64, ctypes.c_int32]
+    assert lib.espo_debug_step_workspace_bytes(4, 1) == 0 and lib.espo_debug_step_workspace_bytes(4, 4) >= 4 * 4 * 32
