@@ -7,7 +7,11 @@ quarter of the rows driven over the stop threshold at seeded steps, dead rows sk
 Every step reads its own logit buffer, all of them generated on the device before the
 timed region (288 GB of HBM hold hundreds of 156 MB steps), so no step can be served
 from a cache.  The companion `espo_advantages` pass is timed on the B=1024, T=16384 batch
-and reported in the same JSON line, as is the CPU oracle on a bounded sample.
+and reported in the same JSON line, as are two bare kernels of the same memory traffic
+(the ceilings this GPU's memory system sets for kernels of these shapes), the launch
+duration against the number of live rows on the heavy-termination rollout, and the CPU
+oracle on a bounded sample, whose tokens and state are compared with the GPU's for the
+same steps.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W]
 """
@@ -26,18 +30,23 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 STEP_SCALAR_BYTES = 34         # per live row: value, z in/out, alive in/out, stop step, token, regret, logprob
 B_STEP, V_STEP = 512, 152064
 B_ADV, T_ADV = 1024, 16384
+NEAR_TIE = 1e-6                # relative gap of the oracle's two best scores below which its runner-up is accepted
 
 
 def _traffic_from_profiles(kernel: str):
-    """HBM bytes per launch measured with rocprofv3 counters, if a summary was committed."""
+    """HBM bytes per launch measured with rocprofv3 counters, and the run they were measured on, if a
+    summary was committed (counters cannot be read from inside this process)."""
     path = os.path.join(ROOT, "profiles", f"traffic_{kernel}.txt")
+    val, where = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+                val = float(line.split(":")[1])
+            if line.startswith("measured_on:"):
+                where = line.split(":", 1)[1].strip()
     except OSError:
         pass
-    return None
+    return val, where
 
 
 def main() -> int:
@@ -50,9 +59,10 @@ def main() -> int:
     ap.add_argument("--calibration-copies", type=int, default=0,
                     help="also launch this many plain 1 GiB copies (known traffic, for counter calibration; untimed)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="oracle time to spend on the CPU baseline")
-    ap.add_argument("--live-curve", action="store_true",
-                    help="also run the heavy-termination rollout (B=1024, 256 steps, 60%% of rows planted to stop) "
-                         "and report the launch duration against the number of live rows")
+    ap.add_argument("--no-live-curve", action="store_true",
+                    help="skip the heavy-termination rollout (B=1024, 256 steps, 60%% of rows planted to stop) that "
+                         "reports the launch duration against the number of live rows")
+    ap.add_argument("--only-step", action="store_true", help="time the headline step loop only (for profiler runs)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU; rows shard over GPUs without any exchange, "
@@ -74,6 +84,22 @@ def main() -> int:
     total = K + Wm
     seed, tau = 3, 0.6
 
+    def timer():
+        return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(n, call, warm=0):
+        """Microseconds per call of n back-to-back calls between two events on the launch stream."""
+        for i in range(warm):
+            call(i)
+        torch.cuda.synchronize()
+        ev = timer()
+        ev[0].record()
+        for i in range(n):
+            call(i)
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / n * 1e3
+
     # ------------------------------------------------------------------ inputs, resident in HBM (untimed)
     gen = W.ZipfLogits(V=V_STEP, seed=seed, device=dev)
     plant = W.RegretPlant.make(B_STEP, V_STEP, 0.25, Wm, max(Wm, total - 24), seed)
@@ -87,19 +113,21 @@ def main() -> int:
     tokens = torch.empty(B_STEP, dtype=torch.int32, device=dev)
     regret = torch.empty(B_STEP, dtype=torch.float32, device=dev)
     logprob = torch.empty(B_STEP, dtype=torch.float32, device=dev)
+    # the workspace that lets the library split rows over workgroups: zero once, every call leaves it zero
+    step_ws = torch.zeros(max(espo.espo_step_workspace_bytes(B_STEP, V_STEP, torch.bfloat16), 16), dtype=torch.uint8, device=dev)
 
-    def run(first, last, z, alive, ss, events=None, entropy=None, params=params):
+    def run(first, last, z, alive, ss, events=None, entropy=None, params=params, lp=logprob, temperature=tau, ws=step_ws):
         for s in range(first, last):
             if events is not None:
                 events[s - first][0].record()
-            espo.espo_step(logits[s], tau, seed, s, values[s], params, z, alive, ss, tokens, regret, logprob,
-                           entropy=entropy)
+            espo.espo_step(logits[s], temperature, seed, s, values[s], params, z, alive, ss, tokens, regret, lp,
+                           entropy=entropy, workspace=ws)
             if events is not None:
                 events[s - first][1].record()
 
-    def fresh_state():
+    def fresh_state(**kw):
         z, alive, ss = W.initial_state(B_STEP, device=dev)
-        run(0, Wm, z, alive, ss)                 # warmup steps are the first steps of the trajectory
+        run(0, Wm, z, alive, ss, **kw)            # warmup steps are the first steps of the trajectory
         torch.cuda.synchronize()
         return z, alive, ss
 
@@ -111,9 +139,25 @@ def main() -> int:
         torch.cuda.synchronize()
         del src, dst
 
+    # ------------------------------------------------------------------ the first steps once more, kept for the parity check
+    # tokens, regret and state after each of the first steps of the same trajectory (untimed): what the CPU oracle
+    # is compared with further down
+    keep = 0 if args.no_cpu_baseline or args.only_step else min(total, 160)
+    hist = {"tokens": torch.empty(keep, B_STEP, dtype=torch.int32, device=dev),
+            "regret": torch.empty(keep, B_STEP, dtype=torch.float32, device=dev),
+            "z": torch.empty(keep, B_STEP, dtype=torch.float32, device=dev),
+            "alive": torch.empty(keep, B_STEP, dtype=torch.uint8, device=dev),
+            "stop_step": torch.empty(keep, B_STEP, dtype=torch.int32, device=dev)}
+    zp, ap_, sp = W.initial_state(B_STEP, device=dev)
+    for s in range(keep):
+        run(s, s + 1, zp, ap_, sp)
+        for k, t in (("tokens", tokens), ("regret", regret), ("z", zp), ("alive", ap_), ("stop_step", sp)):
+            hist[k][s].copy_(t)
+    torch.cuda.synchronize()
+
     # ------------------------------------------------------------------ timed region: exactly K steps
     z, alive, ss = fresh_state()
-    region = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    region = timer()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     region[0].record()                           # on the stream the kernels are launched on (torch's current one)
@@ -122,55 +166,92 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     region_ms = region[0].elapsed_time(region[1])
+    assert not bool(step_ws.any()), "espo_step left its workspace non-zero"
     ss_h = ss.cpu().numpy()
     steps_idx = np.arange(Wm, total)
     live = ((ss_h[None, :] < 0) | (ss_h[None, :] >= steps_idx[:, None])).sum(1)   # rows decoded at each timed step
     live_rows = int(live.sum())
+    step_bytes = live * (V_STEP * 2 + STEP_SCALAR_BYTES) + (B_STEP - live) * 1
+    step_gbs = float(step_bytes.sum() / (region_ms * 1e-3) / 1e9)   # events around the K back-to-back launches
+    step_us = region_ms / K * 1e3
+    step_traffic, step_traffic_on = _traffic_from_profiles("espo_step")
+
+    out = {
+        "metric": "logit rows/sec & HBM GB/s (fused step, V=152064 bf16); advantages tokens/sec",
+        "value": live_rows / wall, "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "sustained rollout step loop: B=512, V=152064 bf16, state carried, "
+                               "~25% of rows planted to stop, one resident logit buffer per step",
+                   "B": B_STEP, "V": V_STEP, "logits_dtype": "bf16", "temperature": tau, "live_rows_mean": float(live.mean()),
+                   "live_rows_last": int(live[-1])},
+        "step_hbm_gbs_wall": float(step_bytes.sum() / wall / 1e9),
+        "roofline": {"kernel": "espo_step_kernel<bf16>", "bound": "hbm", "achieved": step_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS,
+                     "avg_launch_us": step_us,
+                     "algorithmic_bytes_per_launch": float(step_bytes.mean()),
+                     "traffic": step_traffic, "traffic_measured_on": step_traffic_on},
+    }
+    if args.only_step:
+        print(json.dumps(out))
+        return 0
 
     # same K steps again with an event pair around every launch (each pair adds a few microseconds of its own)
     z2, alive2, ss2 = fresh_state()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    ev = [timer() for _ in range(K)]
     run(Wm, total, z2, alive2, ss2, events=ev)
     torch.cuda.synchronize()
     assert torch.equal(ss2, ss) and torch.equal(z2, z), "replay of the timed steps is not deterministic"
     kern_ms = np.array([a.elapsed_time(b) for a, b in ev])
+    out["roofline"]["avg_launch_us_event_pair_each"] = float(kern_ms.mean() * 1e3)
 
-    # and once more with the optional entropy output (the kernel's other instantiation)
-    z3, alive3, ss3 = fresh_state()
+    def variant(name, **kw):
+        """The same K steps through another form of the call; the trajectory must not change unless said so."""
+        zz, aa, sz = fresh_state(**kw)
+        r = timer()
+        r[0].record()
+        run(Wm, total, zz, aa, sz, **kw)
+        r[1].record()
+        torch.cuda.synchronize()
+        return r[0].elapsed_time(r[1]) / K * 1e3, zz, aa, sz
+
+    # without a workspace: one workgroup of 16 waves per row (the layout a caller without scratch memory gets)
+    whole_us, z6, _, ss6 = variant("whole", ws=None)
+    assert torch.equal(ss6, ss) and torch.equal(z6, z), "the layout changed the trajectory"
+    # with the optional entropy output (the kernel's other instantiation)
     entropy = torch.empty(B_STEP, dtype=torch.float32, device=dev)
-    eregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-    eregion[0].record()
-    run(Wm, total, z3, alive3, ss3, entropy=entropy)
-    eregion[1].record()
-    torch.cuda.synchronize()
+    ent_us, z3, alive3, ss3 = variant("entropy", entropy=entropy)
     assert torch.equal(ss3, ss) and torch.equal(z3, z), "the entropy output changed the trajectory"
-    ent_us = eregion[0].elapsed_time(eregion[1]) / K * 1e3
-
-    # and without the log-probability output (no softmax sum is formed then)
-    z5, alive5, ss5 = fresh_state()
-    nregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-    nregion[0].record()
-    for s in range(Wm, total):
-        espo.espo_step(logits[s], tau, seed, s, values[s], params, z5, alive5, ss5, tokens, regret, None)
-    nregion[1].record()
-    torch.cuda.synchronize()
+    # without the log-probability output (no softmax sum is formed then)
+    nolp_us, z5, _, ss5 = variant("nolp", lp=None)
     assert torch.equal(ss5, ss) and torch.equal(z5, z), "dropping the log-probability output changed the trajectory"
-    nolp_us = nregion[0].elapsed_time(nregion[1]) / K * 1e3
-
-    # and with the nucleus filter of the paper's evaluation set-up (top-p 0.7) on the same logits
+    # with the nucleus filter of the paper's evaluation set-up (top-p 0.7), at the rollout temperature and at 1.0
     params_p = espo.EspoParams(**{**W.RolloutParams().as_dict(), "top_p": 0.7})
-    z4, alive4, ss4 = W.initial_state(B_STEP, device=dev)
-    run(0, Wm, z4, alive4, ss4, params=params_p)
-    torch.cuda.synchronize()
-    pregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-    pregion[0].record()
-    run(Wm, total, z4, alive4, ss4, params=params_p)
-    pregion[1].record()
-    torch.cuda.synchronize()
-    topp_us = pregion[0].elapsed_time(pregion[1]) / K * 1e3
-    topp_live = float((alive4 > 0).sum())
-    step_bytes = live * (V_STEP * 2 + STEP_SCALAR_BYTES) + (B_STEP - live) * 1
-    step_gbs = float(step_bytes.sum() / (region_ms * 1e-3) / 1e9)   # events around the K back-to-back launches
+    topp_us, _, alive4, _ = variant("top_p", params=params_p)
+    topp1_us, _, alive7, _ = variant("top_p_tau1", params=params_p, temperature=1.0)
+    plain1_us, _, _, _ = variant("tau1", temperature=1.0)
+    frac_of = lambda us: step_gbs / HBM_PEAK_GBS * step_us / us
+    out["step_one_workgroup_per_row"] = {"avg_launch_us": whole_us, "frac": frac_of(whole_us),
+                                         "note": "workspace = NULL: a row is streamed by one workgroup of 16 waves"}
+    out["step_with_entropy"] = {"avg_launch_us": ent_us, "frac": frac_of(ent_us),
+                                "mean_entropy_last_step": float(entropy[alive3 > 0].mean()) if bool((alive3 > 0).any()) else None}
+    out["step_without_logprob"] = {"avg_launch_us": nolp_us, "frac": frac_of(nolp_us),
+                                   "note": "logprob = NULL: token, regret, state and masks only, no softmax sum"}
+    out["step_top_p_0.7"] = {"avg_launch_us": topp_us, "live_rows_last": float((alive4 > 0).sum()),
+                             "note": "filtered draw: own kernel instantiation, reads parts of the row again"}
+    out["step_top_p_0.7_tau1"] = {"avg_launch_us": topp1_us, "plain_step_at_tau1_us": plain1_us,
+                                  "ratio_to_plain": topp1_us / plain1_us, "live_rows_last": float((alive7 > 0).sum()),
+                                  "note": "the paper's evaluation sampling (temperature 1.0, nucleus 0.7) on the same rows"}
+
+    # ------------------------------------------------------------------ ceiling: a bare streaming read of the same buffers
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    read_us = timed(K, lambda i: espo.espo_debug_read(logits[Wm + i], sink), warm=4)
+    read_gbs = B_STEP * V_STEP * 2 / read_us / 1e3
+    out["roofline"]["ceiling_gbs"] = read_gbs
+    out["roofline"]["frac_of_ceiling"] = step_gbs / read_gbs
+    out["roofline"]["ceiling"] = {"kernel": "espo_debug_read: nontemporal 16-byte loads of a [512,152064] bf16 buffer, nothing else",
+                                  "bytes_per_launch": B_STEP * V_STEP * 2, "avg_launch_us": read_us,
+                                  "frac_of_peak": read_gbs / HBM_PEAK_GBS}
 
     # ------------------------------------------------------------------ advantages (B=1024, T=16384), rotated buffers
     nbuf = 8   # 2.1 GB of inputs and outputs in rotation: a re-read can never come from the 256 MB Infinity Cache
@@ -183,8 +264,8 @@ def main() -> int:
     for i in range(nbuf):
         adv_call(i)
     torch.cuda.synchronize()
-    aev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.adv_reps)]
-    aregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+    aev = [timer() for _ in range(args.adv_reps)]
+    aregion = timer()
     ta = time.perf_counter()
     aregion[0].record()
     for i in range(args.adv_reps):
@@ -202,6 +283,16 @@ def main() -> int:
     valid = np.array([int(adv_in[i % nbuf][2].sum()) for i in range(args.adv_reps)])
     adv_bytes = valid * 16 + (B_ADV * T_ADV - valid) * 8 + B_ADV * 5
     adv_gbs = float(adv_bytes.sum() / (adv_region_ms * 1e-3) / 1e9)
+    adv_traffic, adv_traffic_on = _traffic_from_profiles("espo_advantages")
+
+    # ceiling: a flat sweep with the same read / write mix (8 bytes read per valid token, 8 written per position)
+    rd_bytes = int(valid.mean()) * 8 // 16 * 16
+    wr_bytes = B_ADV * T_ADV * 8
+    sw_src = [torch.empty(rd_bytes // 4, device=dev).normal_() for _ in range(nbuf)]
+    sw_dst = [torch.empty(wr_bytes // 4, device=dev) for _ in range(nbuf)]
+    sweep_us = timed(args.adv_reps, lambda i: espo.espo_debug_sweep(sw_src[i % nbuf], rd_bytes, sw_dst[i % nbuf], wr_bytes), warm=nbuf)
+    sweep_gbs = (rd_bytes + wr_bytes) / sweep_us / 1e3
+    del sw_src, sw_dst
 
     # the same batches in the terminal-reward form (no reward array, padding left to the caller's mask)
     rows_all = torch.arange(B_ADV, device=dev)
@@ -210,16 +301,7 @@ def main() -> int:
         r, v, L, s = adv_in[i % nbuf]
         td, ad = adv_out[i % nbuf]
         espo.espo_advantages_terminal(v, L, s, adv_term[i % nbuf], -1.0, 1.0, 0.95, td, ad, zero_padding=False)
-    for i in range(nbuf):
-        advt_call(i)
-    torch.cuda.synchronize()
-    tregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-    tregion[0].record()
-    for i in range(args.adv_reps):
-        advt_call(i)
-    tregion[1].record()
-    torch.cuda.synchronize()
-    advt_us = tregion[0].elapsed_time(tregion[1]) / args.adv_reps * 1e3
+    advt_us = timed(args.adv_reps, advt_call, warm=nbuf)
     advt_bytes = float(np.mean(valid * 12 + B_ADV * 9))
 
     # the same trajectories stored back to back: nothing but the valid tokens is read or written
@@ -238,18 +320,7 @@ def main() -> int:
             espo.espo_advantages_packed(vp, cu, s, -1.0, 1.0, 0.95, td, ad, rewards=rp)
         else:
             espo.espo_advantages_packed(vp, cu, s, -1.0, 1.0, 0.95, td, ad, terminal_reward=adv_term[i % nbuf])
-    pk_us = {}
-    for dense in (True, False):
-        for i in range(nbuf):
-            pk_call(i, dense)
-        torch.cuda.synchronize()
-        kregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-        kregion[0].record()
-        for i in range(args.adv_reps):
-            pk_call(i, dense)
-        kregion[1].record()
-        torch.cuda.synchronize()
-        pk_us[dense] = kregion[0].elapsed_time(kregion[1]) / args.adv_reps * 1e3
+    pk_us = {dense: timed(args.adv_reps, lambda i, d=dense: pk_call(i, d), warm=nbuf) for dense in (True, False)}
     pk_bytes = {True: float(np.mean(valid * 16 + B_ADV * 9)), False: float(np.mean(valid * 12 + B_ADV * 13))}
     del pk
 
@@ -260,16 +331,7 @@ def main() -> int:
         espo.espo_whiten(ad, adv_in[i % nbuf][2], td, wh_ws)      # td serves as the output buffer here
     for i in range(nbuf):
         adv_call(i)                                               # the advantages these whiten
-    for i in range(nbuf):
-        wh_call(i)
-    torch.cuda.synchronize()
-    wregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-    wregion[0].record()
-    for i in range(args.adv_reps):
-        wh_call(i)
-    wregion[1].record()
-    torch.cuda.synchronize()
-    wh_us = wregion[0].elapsed_time(wregion[1]) / args.adv_reps * 1e3
+    wh_us = timed(args.adv_reps, wh_call, warm=nbuf)
     wh_bytes = float(np.mean(valid * 12 + B_ADV * 8))
 
     # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
@@ -279,24 +341,16 @@ def main() -> int:
     def bs_call(i):
         g, L, s = bs_sets[i % nbuf]
         espo.espo_batch_stats(g, L, s, 1.0, 2.0, 7.0, bs_out, bs_ws)
-    for i in range(nbuf):
-        bs_call(i)
-    torch.cuda.synchronize()
-    bregion = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-    bregion[0].record()
-    for i in range(args.adv_reps):
-        bs_call(i)
-    bregion[1].record()
-    torch.cuda.synchronize()
-    bs_us = bregion[0].elapsed_time(bregion[1]) / args.adv_reps * 1e3
+    bs_us = timed(args.adv_reps, bs_call, warm=nbuf)
     bs_bytes = float(np.mean([int(bs_sets[i % nbuf][1].sum()) * 4 + 512 * 5 for i in range(args.adv_reps)]))
     bs_res = espo.read_batch_result(bs_out)
+    del bs_sets
 
-    # ------------------------------------------------------------------ optional: launch duration vs live rows (B=1024)
+    # ------------------------------------------------------------------ launch duration vs live rows (B=1024)
     curve = None
-    if args.live_curve:
-        Bc, Sc, seed_c = 1024, 256, 4
-        plant_c = W.RegretPlant.make(Bc, V_STEP, 0.6, 12, 190, seed_c)
+    if not args.no_live_curve:
+        Bc, Sc, seed_c, blk = 1024, 256, 4, 8
+        plant_c = W.RegretPlant.make(Bc, V_STEP, 0.6, 14, 150, seed_c)
         gen_c = W.ZipfLogits(V=V_STEP, seed=seed_c, device=dev)
         logits_c = torch.empty(Sc, Bc, V_STEP, dtype=torch.bfloat16, device=dev)   # 80 GB, all steps resident
         values_c = torch.empty(Sc, Bc, dtype=torch.float32, device=dev)
@@ -309,47 +363,96 @@ def main() -> int:
         tok_c = torch.empty(Bc, dtype=torch.int32, device=dev)
         reg_c = torch.empty(Bc, dtype=torch.float32, device=dev)
         lp_c = torch.empty(Bc, dtype=torch.float32, device=dev)   # with the log-probability, as in the headline figure
-        cev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(Sc)]
+        ws_c = torch.zeros(max(espo.espo_step_workspace_bytes(Bc, V_STEP, torch.bfloat16), 16), dtype=torch.uint8, device=dev)
+        cev = [timer() for _ in range(Sc // blk)]                 # one event pair per block of 8 consecutive launches
         for t in range(Sc):
-            cev[t][0].record()
-            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, lp_c)
-            cev[t][1].record()
+            if t % blk == 0:
+                cev[t // blk][0].record()
+            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, lp_c, workspace=ws_c)
+            if t % blk == blk - 1:
+                cev[t // blk][1].record()
         torch.cuda.synchronize()
         ss_c = sc_.cpu().numpy()
         live_c = ((ss_c[None, :] < 0) | (ss_c[None, :] >= np.arange(Sc)[:, None])).sum(1)   # rows decoded at each step
-        cus = np.array([a.elapsed_time(b) * 1e3 for a, b in cev])
+        live_b = live_c.reshape(-1, blk).mean(1)
+        cus = np.array([a.elapsed_time(b) * 1e3 / blk for a, b in cev])
         curve = []
         for lo in range(400, 1025, 104):                                   # six bins of live rows
-            sel = (live_c > lo - 104) & (live_c <= lo)
+            sel = (live_b > lo - 104) & (live_b <= lo)
             if sel.any():
-                rows_m, us_m = float(live_c[sel].mean()), float(cus[sel].mean())
-                curve.append({"live_rows": rows_m, "steps": int(sel.sum()), "us_per_launch_event_pair": us_m,
+                rows_m, us_m = float(live_b[sel].mean()), float(cus[sel].mean())
+                curve.append({"live_rows": rows_m, "launches": int(sel.sum()) * blk, "us_per_launch": us_m,
                               "rows_per_s": rows_m / us_m * 1e6,
                               "gbs": (rows_m * (V_STEP * 2 + STEP_SCALAR_BYTES) + (Bc - rows_m)) / us_m / 1e3})
+        if curve:
+            top = curve[-1]
+            for c in curve:       # 1.0 = time falls in proportion to the live rows, measured from the fullest bin
+                c["us_over_proportional"] = c["us_per_launch"] / (top["us_per_launch"] * c["live_rows"] / top["live_rows"])
         del logits_c
 
-    # ------------------------------------------------------------------ CPU oracle on a bounded sample (context only)
-    cpu = None
+    # ------------------------------------------------------------------ CPU oracle on a bounded sample, compared with the GPU
+    cpu, parity = None, None
     if not args.no_cpu_baseline:
         import oracle
         oracle.build_oracle()
         op = oracle.OracleParams(**W.RolloutParams().as_dict())
         zc, ac, sc = (np.zeros(B_STEP, np.float32), np.ones(B_STEP, np.uint8), np.full(B_STEP, -1, np.int32))
         cpu_s, cpu_rows, cpu_steps = 0.0, 0, 0
-        while cpu_s < args.cpu_seconds and cpu_steps < total:      # the first steps of the same trajectory
+        hist_h = {k: v.cpu().numpy() for k, v in hist.items()}
+        parity = {"parity_checked_steps": 0, "parity_checked_rows": 0, "parity_near_ties": 0, "parity_ok": True}
+        while cpu_s < args.cpu_seconds and cpu_steps < keep:       # the first steps of the same trajectory
             bits = W.to_host_bits(logits[cpu_steps])               # copy to the host: untimed
             vals_h = values[cpu_steps].cpu().numpy()
             if cpu_steps == 0:
                 cpu_first_bits, cpu_first_vals = bits, vals_h
-            cpu_rows += int(ac.sum())
+            live_before = int(ac.sum())
+            cpu_rows += live_before
+            z0, a0, s0 = zc.copy(), ac.copy(), sc.copy()
             tc = time.perf_counter()
-            oracle.step(bits, tau, seed, cpu_steps, vals_h, op, zc, ac, sc)
+            ref = oracle.step(bits, tau, seed, cpu_steps, vals_h, op, zc, ac, sc)
             cpu_s += time.perf_counter() - tc
+            # the GPU's tokens, regret and state after the same step (untimed)
+            g_tok = hist_h["tokens"][cpu_steps]
+            mism = np.nonzero(g_tok != ref["tokens"])[0]
+            if len(mism):                                          # the oracle's runner-up is accepted in a near tie
+                forced = np.full(B_STEP, -1, np.int32)
+                for b in mism:
+                    s1, s2 = ref["best_score"][b], ref["second_score"][b]
+                    if g_tok[b] == ref["second_token"][b] and (s1 - s2) <= NEAR_TIE * abs(s1):
+                        forced[b] = g_tok[b]
+                    else:
+                        parity["parity_ok"] = False
+                        parity["first_mismatch"] = {"step": cpu_steps, "row": int(b), "gpu": int(g_tok[b]), "oracle": int(ref["tokens"][b])}
+                if not parity["parity_ok"]:
+                    break
+                parity["parity_near_ties"] += len(mism)
+                zc, ac, sc = z0, a0, s0
+                ref = oracle.step(bits, tau, seed, cpu_steps, vals_h, op, zc, ac, sc, forced_tokens=forced)
+            same = (np.array_equal(g_tok, ref["tokens"])
+                    and np.array_equal(hist_h["regret"][cpu_steps].view(np.uint32), ref["regret"].view(np.uint32))
+                    and np.array_equal(hist_h["z"][cpu_steps].view(np.uint32), zc.view(np.uint32))
+                    and np.array_equal(hist_h["alive"][cpu_steps], ac)
+                    and np.array_equal(hist_h["stop_step"][cpu_steps], sc))
+            if not same:
+                parity["parity_ok"] = False
+                parity["first_mismatch"] = {"step": cpu_steps, "what": "regret, state or masks"}
+                break
+            parity["parity_checked_steps"] += 1
+            parity["parity_checked_rows"] += live_before
             cpu_steps += 1
         r, v, L, s = [x.cpu().numpy() for x in adv_in[0]]
         tc = time.perf_counter()
         oracle.advantages(r, v, L, s, -1.0, 1.0, 0.95, want_scale=False)
         cpu_adv_s = time.perf_counter() - tc
+        # the advantage pass on that batch against the oracle (untimed): errors against the scale of the terms summed
+        td_o, adv_o, scale = oracle.advantages(r, v, L, s, -1.0, 1.0, 0.95)
+        adv_call(0)
+        torch.cuda.synchronize()
+        e_adv = np.abs(adv_out[0][1].cpu().numpy().astype(np.float64) - adv_o)
+        e_td = np.abs(adv_out[0][0].cpu().numpy().astype(np.float64) - td_o)
+        parity["advantages_worst_scaled_error"] = float((e_adv / np.maximum(scale, 1e-30)).max())
+        parity["advantages_worst_td_error"] = float(e_td.max())
+        parity["advantages_parity_ok"] = bool((e_adv <= 2e-6 * np.maximum(scale, 1e-30)).all() and e_td.max() <= 1e-6)
         # the same oracle on one thread, on a slice of the first step (it is deliberately plain code)
         nthreads = oracle.num_threads()
         oracle.set_threads(1)
@@ -362,35 +465,14 @@ def main() -> int:
         oracle.advantages(r[:64], v[:64], L[:64], s[:64], -1.0, 1.0, 0.95, want_scale=False)
         cpu_1t_adv = float(L[:64].clip(0, T_ADV).sum() / (time.perf_counter() - tc))
         oracle.set_threads(nthreads)
-        cpu = {"value": cpu_rows / cpu_s, "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
+        cpu = {"value": cpu_rows / max(cpu_s, 1e-9), "unit": "rows/s", "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"the first {cpu_steps} steps of the same workload ({cpu_rows} live rows x 152064 bf16 "
                          f"logits), {cpu_s:.1f} s of oracle time",
                "advantages_tokens_per_s": float(L.clip(0, T_ADV).sum() / cpu_adv_s),
                "one_thread": {"rows_per_s": cpu_1t_rows, "advantages_tokens_per_s": cpu_1t_adv,
                               "sample": f"{n1} rows of the first step; 64 rows of the advantage batch"}}
 
-    out = {
-        "metric": "logit rows/sec & HBM GB/s (fused step, V=152064 bf16); advantages tokens/sec",
-        "value": live_rows / wall, "unit": "rows/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": wall / K * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "sustained rollout step loop: B=512, V=152064 bf16, state carried, "
-                               "~25% of rows planted to stop, one resident logit buffer per step",
-                   "B": B_STEP, "V": V_STEP, "logits_dtype": "bf16", "temperature": tau, "live_rows_mean": float(live.mean()),
-                   "live_rows_last": int(live[-1])},
-        "step_hbm_gbs_wall": float(step_bytes.sum() / wall / 1e9),
-        "roofline": {"kernel": "espo_step_kernel<bf16>", "bound": "hbm", "achieved": step_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": step_gbs / HBM_PEAK_GBS,
-                     "avg_launch_us": region_ms / K * 1e3,
-                     "avg_launch_us_event_pair_each": float(kern_ms.mean() * 1e3),
-                     "algorithmic_bytes_per_launch": float(step_bytes.mean()),
-                     "traffic": _traffic_from_profiles("espo_step")},
-        "step_with_entropy": {"avg_launch_us": ent_us, "frac": step_gbs / HBM_PEAK_GBS * (region_ms / K * 1e3) / ent_us,
-                              "mean_entropy_last_step": float(entropy[alive3 > 0].mean()) if bool((alive3 > 0).any()) else None},
-        "step_without_logprob": {"avg_launch_us": nolp_us, "frac": step_gbs / HBM_PEAK_GBS * (region_ms / K * 1e3) / nolp_us,
-                                 "note": "logprob = NULL: token, regret, state and masks only, no softmax sum"},
-        "step_top_p_0.7": {"avg_launch_us": topp_us, "live_rows_last": topp_live,
-                           "note": "filtered draw: own kernel instantiation, reads parts of the row again"},
+    out.update({
         "advantages": {"workload": "B=1024, T=16384 fp32, lengths U[512,16384], 30% stopped, 8 rotated buffer sets",
                        "tokens_per_s": float(valid.sum() / adv_wall), "ms_per_call": adv_wall / args.adv_reps * 1e3,
                        "roofline": {"kernel": "espo_advantages_kernel", "bound": "hbm", "achieved": adv_gbs,
@@ -398,7 +480,12 @@ def main() -> int:
                                     "avg_launch_us": adv_region_ms / args.adv_reps * 1e3,
                                     "avg_launch_us_event_pair_each": float(adv_ms.mean() * 1e3),
                                     "algorithmic_bytes_per_launch": float(adv_bytes.mean()),
-                                    "traffic": _traffic_from_profiles("espo_advantages")}},
+                                    "traffic": adv_traffic, "traffic_measured_on": adv_traffic_on,
+                                    "ceiling_gbs": sweep_gbs, "frac_of_ceiling": adv_gbs / sweep_gbs,
+                                    "ceiling": {"kernel": "espo_debug_sweep: flat sweep, no dependency between elements, the same bytes "
+                                                          "read (8 per valid token) and written (8 per position)",
+                                                "read_bytes": rd_bytes, "write_bytes": wr_bytes, "avg_launch_us": sweep_us,
+                                                "frac_of_peak": sweep_gbs / HBM_PEAK_GBS}}},
         "advantages_terminal": {"workload": "the same batches, terminal-reward form: reads V, writes td and A at t < L only",
                                 "us_per_call": advt_us, "tokens_per_s": float(valid.mean() / advt_us * 1e6),
                                 "algorithmic_bytes_per_call": advt_bytes, "gbs": advt_bytes / advt_us / 1e3,
@@ -418,12 +505,17 @@ def main() -> int:
                         "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,
                         "mu_g": bs_res["mu_g"], "var_g": bs_res["var_g"], "beta": bs_res["beta"]},
         "cpu_baseline": cpu,
-    }
+    })
+    if parity is not None:
+        out.update(parity)
     if curve is not None:
         out["live_curve"] = {"workload": "heavy termination: B=1024, V=152064 bf16, 256 steps, 60% of rows planted to stop in "
-                                         "[16,200]; every step's logits resident, one event pair per launch",
+                                         "[16,200]; every step's logits resident, one event pair per 8 consecutive launches",
                              "bins": curve}
     print(json.dumps(out))
+    if parity is not None and not (parity["parity_ok"] and parity["advantages_parity_ok"]):
+        print("bench.py: the GPU's results differ from the oracle's", file=sys.stderr)
+        return 1
     return 0
 
 
