@@ -113,15 +113,15 @@ def main() -> int:
     tokens = torch.empty(B_STEP, dtype=torch.int32, device=dev)
     regret = torch.empty(B_STEP, dtype=torch.float32, device=dev)
     logprob = torch.empty(B_STEP, dtype=torch.float32, device=dev)
-    # the workspace that lets the library split rows over workgroups: zero once, every call leaves it zero
-    step_ws = torch.zeros(max(espo.espo_step_workspace_bytes(B_STEP, V_STEP, torch.bfloat16), 16), dtype=torch.uint8, device=dev)
+    nws = espo.espo_step_workspace_bytes(B_STEP, V_STEP, torch.bfloat16)      # 0 in this version: one workgroup per row
+    step_ws = torch.zeros(nws, dtype=torch.uint8, device=dev) if nws else None
 
-    def run(first, last, z, alive, ss, events=None, entropy=None, params=params, lp=logprob, temperature=tau, ws=step_ws):
+    def run(first, last, z, alive, ss, events=None, entropy=None, params=params, lp=logprob, temperature=tau, ws=step_ws, **layout):
         for s in range(first, last):
             if events is not None:
                 events[s - first][0].record()
             espo.espo_step(logits[s], temperature, seed, s, values[s], params, z, alive, ss, tokens, regret, lp,
-                           entropy=entropy, workspace=ws)
+                           entropy=entropy, workspace=ws, **layout)
             if events is not None:
                 events[s - first][1].record()
 
@@ -166,7 +166,6 @@ def main() -> int:
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     region_ms = region[0].elapsed_time(region[1])
-    assert not bool(step_ws.any()), "espo_step left its workspace non-zero"
     ss_h = ss.cpu().numpy()
     steps_idx = np.arange(Wm, total)
     live = ((ss_h[None, :] < 0) | (ss_h[None, :] >= steps_idx[:, None])).sum(1)   # rows decoded at each timed step
@@ -215,9 +214,15 @@ def main() -> int:
         torch.cuda.synchronize()
         return r[0].elapsed_time(r[1]) / K * 1e3, zz, aa, sz
 
-    # without a workspace: one workgroup of 16 waves per row (the layout a caller without scratch memory gets)
-    whole_us, z6, _, ss6 = variant("whole", ws=None)
-    assert torch.equal(ss6, ss) and torch.equal(z6, z), "the layout changed the trajectory"
+    # every row split over several workgroups that combine through a workspace (diagnostics entry point): the finer
+    # grain that was meant to fill the GPU better at this batch size, measured here beside the layout espo_step uses
+    split = {}
+    for waves, chunks in ((16, 2), (8, 2), (4, 8)):
+        ws_split = torch.zeros(espo.espo_debug_step_workspace_bytes(B_STEP, chunks), dtype=torch.uint8, device=dev)
+        us6, z6, _, ss6 = variant("split", ws=ws_split, waves=waves, chunks=chunks)
+        assert torch.equal(ss6, ss) and torch.equal(z6, z), "the layout changed the trajectory"
+        assert not bool(ws_split.any()), "a split step left its workspace non-zero"
+        split[f"{chunks}_chunks_of_{waves}_waves"] = us6
     # with the optional entropy output (the kernel's other instantiation)
     entropy = torch.empty(B_STEP, dtype=torch.float32, device=dev)
     ent_us, z3, alive3, ss3 = variant("entropy", entropy=entropy)
@@ -228,11 +233,14 @@ def main() -> int:
     # with the nucleus filter of the paper's evaluation set-up (top-p 0.7), at the rollout temperature and at 1.0
     params_p = espo.EspoParams(**{**W.RolloutParams().as_dict(), "top_p": 0.7})
     topp_us, _, alive4, _ = variant("top_p", params=params_p)
-    topp1_us, _, alive7, _ = variant("top_p_tau1", params=params_p, temperature=1.0)
-    plain1_us, _, _, _ = variant("tau1", temperature=1.0)
+    # at temperature 1 the regrets of these rows are large and most rows would stop within a few steps: the
+    # comparison with the plain step is made with the stop rule switched off, all 512 rows live in both runs
+    off = {**W.RolloutParams().as_dict(), "stop_enabled": 0}
+    topp1_us, _, alive7, _ = variant("top_p_tau1", params=espo.EspoParams(**{**off, "top_p": 0.7}), temperature=1.0)
+    plain1_us, _, _, _ = variant("tau1", params=espo.EspoParams(**off), temperature=1.0)
     frac_of = lambda us: step_gbs / HBM_PEAK_GBS * step_us / us
-    out["step_one_workgroup_per_row"] = {"avg_launch_us": whole_us, "frac": frac_of(whole_us),
-                                         "note": "workspace = NULL: a row is streamed by one workgroup of 16 waves"}
+    out["step_rows_split_over_workgroups"] = {"avg_launch_us": split, "one_workgroup_per_row_us": step_us,
+                                              "note": "espo_debug_step with forced chunks; same tokens, regret, state and masks"}
     out["step_with_entropy"] = {"avg_launch_us": ent_us, "frac": frac_of(ent_us),
                                 "mean_entropy_last_step": float(entropy[alive3 > 0].mean()) if bool((alive3 > 0).any()) else None}
     out["step_without_logprob"] = {"avg_launch_us": nolp_us, "frac": frac_of(nolp_us),
@@ -241,7 +249,8 @@ def main() -> int:
                              "note": "filtered draw: own kernel instantiation, reads parts of the row again"}
     out["step_top_p_0.7_tau1"] = {"avg_launch_us": topp1_us, "plain_step_at_tau1_us": plain1_us,
                                   "ratio_to_plain": topp1_us / plain1_us, "live_rows_last": float((alive7 > 0).sum()),
-                                  "note": "the paper's evaluation sampling (temperature 1.0, nucleus 0.7) on the same rows"}
+                                  "note": "the paper's evaluation sampling (temperature 1.0, nucleus 0.7) on the same rows, stop rule "
+                                          "off in both runs (all rows live)"}
 
     # ------------------------------------------------------------------ ceiling: a bare streaming read of the same buffers
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
@@ -293,6 +302,13 @@ def main() -> int:
     sweep_us = timed(args.adv_reps, lambda i: espo.espo_debug_sweep(sw_src[i % nbuf], rd_bytes, sw_dst[i % nbuf], wr_bytes), warm=nbuf)
     sweep_gbs = (rd_bytes + wr_bytes) / sweep_us / 1e3
     del sw_src, sw_dst
+    # and the same traffic in the pass's own layout (four [B, T] arrays, inputs read below the lengths), no dependency
+    def padded_call(i):
+        r, v, L, s = adv_in[i % nbuf]
+        td, ad = adv_out[i % nbuf]
+        espo.espo_debug_sweep_padded(r, v, L, td, ad)
+    padded_us = timed(args.adv_reps, padded_call, warm=nbuf)
+    padded_gbs = float(adv_bytes.mean()) / padded_us / 1e3
 
     # the same batches in the terminal-reward form (no reward array, padding left to the caller's mask)
     rows_all = torch.arange(B_ADV, device=dev)
@@ -363,12 +379,11 @@ def main() -> int:
         tok_c = torch.empty(Bc, dtype=torch.int32, device=dev)
         reg_c = torch.empty(Bc, dtype=torch.float32, device=dev)
         lp_c = torch.empty(Bc, dtype=torch.float32, device=dev)   # with the log-probability, as in the headline figure
-        ws_c = torch.zeros(max(espo.espo_step_workspace_bytes(Bc, V_STEP, torch.bfloat16), 16), dtype=torch.uint8, device=dev)
         cev = [timer() for _ in range(Sc // blk)]                 # one event pair per block of 8 consecutive launches
         for t in range(Sc):
             if t % blk == 0:
                 cev[t // blk][0].record()
-            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, lp_c, workspace=ws_c)
+            espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], params, zc_, ac_, sc_, tok_c, reg_c, lp_c)
             if t % blk == blk - 1:
                 cev[t // blk][1].record()
         torch.cuda.synchronize()
@@ -481,11 +496,14 @@ def main() -> int:
                                     "avg_launch_us_event_pair_each": float(adv_ms.mean() * 1e3),
                                     "algorithmic_bytes_per_launch": float(adv_bytes.mean()),
                                     "traffic": adv_traffic, "traffic_measured_on": adv_traffic_on,
-                                    "ceiling_gbs": sweep_gbs, "frac_of_ceiling": adv_gbs / sweep_gbs,
-                                    "ceiling": {"kernel": "espo_debug_sweep: flat sweep, no dependency between elements, the same bytes "
-                                                          "read (8 per valid token) and written (8 per position)",
-                                                "read_bytes": rd_bytes, "write_bytes": wr_bytes, "avg_launch_us": sweep_us,
-                                                "frac_of_peak": sweep_gbs / HBM_PEAK_GBS}}},
+                                    "ceiling_gbs": padded_gbs, "frac_of_ceiling": adv_gbs / padded_gbs,
+                                    "ceiling": {"kernel": "espo_debug_sweep_padded: the same four [B, T] arrays, inputs read below the "
+                                                          "lengths, outputs written everywhere, no dependency between elements",
+                                                "avg_launch_us": padded_us, "frac_of_peak": padded_gbs / HBM_PEAK_GBS},
+                                    "ceiling_contiguous": {"kernel": "espo_debug_sweep: the same bytes read (8 per valid token) and written "
+                                                                     "(8 per position) on two contiguous buffers",
+                                                           "read_bytes": rd_bytes, "write_bytes": wr_bytes, "avg_launch_us": sweep_us,
+                                                           "gbs": sweep_gbs, "frac_of_peak": sweep_gbs / HBM_PEAK_GBS}}},
         "advantages_terminal": {"workload": "the same batches, terminal-reward form: reads V, writes td and A at t < L only",
                                 "us_per_call": advt_us, "tokens_per_s": float(valid.mean() / advt_us * 1e6),
                                 "algorithmic_bytes_per_call": advt_bytes, "gbs": advt_bytes / advt_us / 1e3,

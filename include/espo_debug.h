@@ -58,7 +58,7 @@ size_t espo_debug_step_workspace_bytes(int64_t B, int32_t chunks);
 int espo_debug_math_errors(float* out, void* stream);
 
 /*
- * Three kernels of known memory traffic, to calibrate hardware counters and to measure what this
+ * Four kernels of known memory traffic, to calibrate hardware counters and to measure what this
  * GPU's memory system delivers to the simplest possible kernels of the same shape as the two hot
  * kernels.  Device pointers, 16-byte aligned; byte counts multiples of 16 (ESPO_EINVAL otherwise).
  *   espo_debug_copy   reads `bytes` once and writes them once.
@@ -67,11 +67,18 @@ int espo_debug_math_errors(float* out, void* stream);
  *                     particular word): the ceiling for espo_step's one read of the logits.
  *   espo_debug_sweep  lane i reads the i-th 16 bytes of src (read_bytes of them) and writes the i-th
  *                     16 bytes of dst (write_bytes of them), no dependency between elements: the
- *                     ceiling for a pass with the read / write mix of espo_advantages.
+ *                     ceiling for a pass with the read / write mix of espo_advantages on contiguous
+ *                     buffers.
+ *   espo_debug_sweep_padded  the traffic of espo_advantages in its own layout, no dependency between
+ *                     elements: rewards and values [B, T] are read below lengths[b], td and adv [B, T]
+ *                     are written everywhere (not the method's numbers).  T a multiple of 1024.  The
+ *                     ceiling for espo_advantages itself: what the four-array padded layout allows.
  */
 int espo_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
 int espo_debug_read(const void* src, size_t bytes, void* sink, void* stream);
 int espo_debug_sweep(const void* src, size_t read_bytes, void* dst, size_t write_bytes, void* stream);
+int espo_debug_sweep_padded(const float* rewards, const float* values, const int32_t* lengths, int64_t B, int64_t T,
+                            float* td, float* adv, void* stream);
 
 #ifdef __cplusplus
 }

@@ -111,6 +111,8 @@ def load_library():
         lib.espo_debug_read.argtypes = [vp, sz, vp, vp]
         lib.espo_debug_sweep.restype = C.c_int
         lib.espo_debug_sweep.argtypes = [vp, sz, vp, sz, vp]
+        lib.espo_debug_sweep_padded.restype = C.c_int
+        lib.espo_debug_sweep_padded.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp]
         lib.espo_debug_math_errors.restype = C.c_int
         lib.espo_debug_math_errors.argtypes = [C.c_void_p, C.c_void_p]
         lib.espo_batch_stats.restype = C.c_int
@@ -174,6 +176,16 @@ def espo_debug_sweep(src: torch.Tensor, read_bytes: int, dst: torch.Tensor, writ
             raise ValueError(f"{name}: need a contiguous GPU tensor of at least {n} bytes")
     _check(load_library().espo_debug_sweep(C.c_void_p(src.data_ptr()), int(read_bytes), C.c_void_p(dst.data_ptr()),
                                            int(write_bytes), _stream(stream)))
+
+
+def espo_debug_sweep_padded(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.Tensor, td: torch.Tensor,
+                            adv: torch.Tensor, stream=None) -> None:
+    """Diagnostics: the memory traffic of espo_advantages in its own layout, no dependency (see include/espo_debug.h)."""
+    B, T = rewards.shape
+    _check(load_library().espo_debug_sweep_padded(
+        _dev(rewards, torch.float32, "rewards"), _dev(values, torch.float32, "values", shape=(B, T)),
+        _dev(lengths, torch.int32, "lengths", numel=B), B, T, _dev(td, torch.float32, "td", shape=(B, T)),
+        _dev(adv, torch.float32, "adv", shape=(B, T)), _stream(stream)))
 
 
 def espo_batch_stats_workspace_bytes(B: int, T: int) -> int:

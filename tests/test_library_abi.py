@@ -33,7 +33,7 @@ def test_every_declared_symbol_is_exported(lib):
     assert not any(n.startswith("espo_debug") for n in names)       # diagnostics live in their own header
     debug = _declared_functions("espo_debug.h")
     assert {"espo_debug_step", "espo_debug_step_workspace_bytes", "espo_debug_math_errors", "espo_debug_copy",
-            "espo_debug_read", "espo_debug_sweep"} <= set(debug)
+            "espo_debug_read", "espo_debug_sweep", "espo_debug_sweep_padded"} <= set(debug)
     for n in names + debug:
         assert hasattr(lib, n), n
 
