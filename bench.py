@@ -350,6 +350,38 @@ def main() -> int:
     wh_us = timed(args.adv_reps, wh_call, warm=nbuf)
     wh_bytes = float(np.mean(valid * 12 + B_ADV * 8))
 
+    # the pair with a workspace between them: the advantage pass leaves every row's sums, the whitening starts
+    # from those; and the same pass taking its rows longest first, the order written beforehand or in the region
+    aw_ws = [torch.empty(espo.espo_advantages_ws_bytes(B_ADV), dtype=torch.uint8, device=dev) for _ in range(nbuf)]
+    aw_order = [torch.empty(B_ADV, dtype=torch.int32, device=dev) for _ in range(nbuf)]
+    def aw_call(i, ordered=False, order_now=False):
+        r, v, L, s = adv_in[i % nbuf]
+        td, ad = adv_out[i % nbuf]
+        if order_now:
+            espo.espo_length_order(L, T_ADV, aw_order[i % nbuf])
+        espo.espo_advantages_ws(r, v, L, s, -1.0, 1.0, 0.95, td, ad, aw_ws[i % nbuf], aw_order[i % nbuf] if ordered else None)
+    for i in range(nbuf):
+        espo.espo_length_order(adv_in[i][2], T_ADV, aw_order[i])
+    aw_us = timed(args.adv_reps, aw_call, warm=nbuf)
+    aw_ord_us = timed(args.adv_reps, lambda i: aw_call(i, ordered=True), warm=nbuf)
+    aw_ord_now_us = timed(args.adv_reps, lambda i: aw_call(i, ordered=True, order_now=True), warm=nbuf)
+    order_us = timed(args.adv_reps, lambda i: espo.espo_length_order(adv_in[i % nbuf][2], T_ADV, aw_order[i % nbuf]), warm=nbuf)
+    wh_tmp = torch.empty(B_ADV, T_ADV, device=dev)
+    def whw_call(i):
+        td, ad = adv_out[i % nbuf]
+        espo.espo_whiten_from_ws(ad, adv_in[i % nbuf][2], wh_tmp, aw_ws[i % nbuf])
+    whw_us = timed(args.adv_reps, whw_call, warm=nbuf)
+    def pair_call(i, fused):
+        td, ad = adv_out[i % nbuf]
+        if fused:
+            aw_call(i)
+            espo.espo_whiten_from_ws(ad, adv_in[i % nbuf][2], wh_tmp, aw_ws[i % nbuf])
+        else:
+            adv_call(i)
+            espo.espo_whiten(ad, adv_in[i % nbuf][2], wh_tmp, wh_ws)
+    pair_us = {f: timed(args.adv_reps, lambda i, f=f: pair_call(i, f), warm=nbuf) for f in (False, True)}
+    del wh_tmp
+
     # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
     bs_sets = [W.regret_batch(512, 8192, seed=70 + i, device=dev) for i in range(nbuf)]   # 134 MB in rotation
     bs_out = torch.zeros(espo.BATCH_RESULT_BYTES, dtype=torch.uint8, device=dev)
@@ -518,6 +550,19 @@ def main() -> int:
         "whiten": {"workload": "whitening of the advantages of the same batches over their valid tokens",
                    "us_per_call": wh_us, "launches_per_call": 2, "algorithmic_bytes_per_call": wh_bytes,
                    "gbs": wh_bytes / wh_us / 1e3, "frac": wh_bytes / wh_us / 1e3 / HBM_PEAK_GBS},
+        "advantages_ws": {"workload": "the same batches through espo_advantages_ws (every row's sums left in a workspace)",
+                          "us_per_call": aw_us, "frac": float(adv_bytes.mean()) / aw_us / 1e3 / HBM_PEAK_GBS,
+                          "rows_longest_first": {"us_per_call": aw_ord_us,
+                                                 "frac": float(adv_bytes.mean()) / aw_ord_us / 1e3 / HBM_PEAK_GBS,
+                                                 "order": "written by espo_length_order before the timed region",
+                                                 "us_per_call_with_the_order_written_in_the_region": aw_ord_now_us,
+                                                 "espo_length_order_us_per_call": order_us}},
+        "whiten_from_ws": {"workload": "the whitening of the same advantages from the rows' sums: the rewrite only",
+                           "us_per_call": whw_us, "launches_per_call": 1, "algorithmic_bytes_per_call": float(np.mean(valid * 8 + B_ADV * 36)),
+                           "frac": float(np.mean(valid * 8 + B_ADV * 36)) / whw_us / 1e3 / HBM_PEAK_GBS},
+        "advantages_then_whiten": {"workload": "both calls back to back on the same batches",
+                                   "espo_advantages_and_espo_whiten_us": pair_us[False],
+                                   "espo_advantages_ws_and_espo_whiten_from_ws_us": pair_us[True]},
         "batch_stats": {"workload": "B=512, T=8192 fp32 regrets, lengths U[64,8192], 25% stopped, 8 rotated sets",
                         "us_per_call": bs_us, "algorithmic_bytes_per_call": bs_bytes,
                         "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,

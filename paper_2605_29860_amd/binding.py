@@ -100,6 +100,14 @@ def load_library():
         lib.espo_advantages_terminal.restype = C.c_int
         lib.espo_advantages_terminal.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, i32, vp, vp, vp, vp]
         lib.espo_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
+        lib.espo_advantages_ws.restype = C.c_int
+        lib.espo_advantages_ws.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp, vp, sz, vp]
+        lib.espo_length_order.restype = C.c_int
+        lib.espo_length_order.argtypes = [vp, i64, i64, vp, vp]
+        lib.espo_advantages_ws_bytes.restype = sz
+        lib.espo_advantages_ws_bytes.argtypes = [i64]
+        lib.espo_whiten_from_ws.restype = C.c_int
+        lib.espo_whiten_from_ws.argtypes = [vp, vp, i64, i64, f32, i32, i32, vp, vp, vp, sz, vp]
         lib.espo_strerror.restype = C.c_char_p
         lib.espo_strerror.argtypes = [C.c_int]
         lib.espo_version.restype = C.c_int
@@ -302,6 +310,58 @@ def espo_advantages(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.
                              B, T, float(r_fail), float(gamma), float(lam),
                              _dev(td, torch.float32, "td", shape=(B, T)), _dev(adv, torch.float32, "adv", shape=(B, T)),
                              _stream(stream))
+    _check(rc)
+
+
+def espo_advantages_ws_bytes(B: int) -> int:
+    return int(load_library().espo_advantages_ws_bytes(B))
+
+
+def espo_length_order(lengths: torch.Tensor, T: int, order: torch.Tensor, stream=None) -> None:
+    """The rows by length, longest first; see `espo_length_order` in include/espo.h."""
+    lib = load_library()
+    B = lengths.numel()
+    _check(lib.espo_length_order(_dev(lengths, torch.int32, "lengths"), B, int(T), _dev(order, torch.int32, "order", numel=B),
+                                 _stream(stream)))
+
+
+def espo_advantages_ws(rewards: torch.Tensor, values: torch.Tensor, lengths: torch.Tensor,
+                       stopped: torch.Tensor, r_fail: float, gamma: float, lam: float,
+                       td: torch.Tensor, adv: torch.Tensor, workspace: torch.Tensor, order: torch.Tensor | None = None,
+                       stream=None) -> None:
+    """espo_advantages with the rows' sums left in `workspace` and, optionally, the rows taken in a
+    given order; see `espo_advantages_ws` in include/espo.h."""
+    lib = load_library()
+    if rewards.dim() != 2:
+        raise TypeError("rewards: need [B, T]")
+    B, T = rewards.shape
+    rc = lib.espo_advantages_ws(_dev(rewards, torch.float32, "rewards"), _dev(values, torch.float32, "values", shape=(B, T)),
+                                _dev(lengths, torch.int32, "lengths", numel=B), _dev(stopped, torch.uint8, "stopped", numel=B),
+                                B, T, float(r_fail), float(gamma), float(lam),
+                                _dev(td, torch.float32, "td", shape=(B, T)), _dev(adv, torch.float32, "adv", shape=(B, T)),
+                                _dev(order, torch.int32, "order", numel=B),
+                                _dev(workspace, torch.uint8, "workspace"), workspace.numel() if workspace is not None else 0,
+                                _stream(stream))
+    _check(rc)
+
+
+def espo_whiten_from_ws(adv: torch.Tensor, lengths: torch.Tensor, out: torch.Tensor, workspace: torch.Tensor,
+                        eps: float = 1e-8, shift_mean: bool = True, unbiased: bool = False,
+                        stats: torch.Tensor | None = None, stream=None) -> None:
+    """espo_whiten from the sums that espo_advantages_ws left in `workspace`; see
+    `espo_whiten_from_ws` in include/espo.h."""
+    lib = load_library()
+    if adv.dim() != 2:
+        raise TypeError("adv: need [B, T]")
+    B, T = adv.shape
+    if out.shape != adv.shape or lengths.numel() != B:
+        raise TypeError("out: need the shape of adv; lengths: need [B]")
+    if stats is not None and stats.numel() < 3:
+        raise TypeError("stats: need 3 doubles")
+    rc = lib.espo_whiten_from_ws(_dev(adv, torch.float32, "adv"), _dev(lengths, torch.int32, "lengths", numel=B), B, T,
+                                 float(eps), int(bool(shift_mean)), int(bool(unbiased)), _dev(out, torch.float32, "out"),
+                                 _dev(stats, torch.float64, "stats", numel=3), _dev(workspace, torch.uint8, "workspace"),
+                                 workspace.numel() if workspace is not None else 0, _stream(stream))
     _check(rc)
 
 

@@ -58,6 +58,8 @@ struct AdvArgs {
   float cwave[5];          // c^(256*2^k), k = 0..4: a distance of 2^k waves; cwave[4] spans a tile
   float* td;
   float* adv;
+  const int32_t* order;    // optional [B]: the rows, longest first (padded forms)
+  AdvRowStats* row_stats;  // optional [B]: sums of every row's advantages (padded forms)
 };
 
 struct TileIn {
@@ -116,7 +118,6 @@ __device__ __forceinline__ void store4(float* __restrict__ row, int64_t t0, int6
     if (t0 + j < T) row[t0 + j] = x[j];
 }
 
-// One step of a weighted inclusive prefix sum over lanes: s += w * (s of the lane the DPP control names).
 // Stores x[j] at t0 + j for lo <= t0 + j < hi (t0 a multiple of 4, the row 16-byte aligned).
 __device__ __forceinline__ void store_span(float* __restrict__ row, int64_t t0, int64_t lo, int64_t hi, const float x[kPerLane]) {
   if (t0 >= lo && t0 + kPerLane <= hi) {
@@ -128,6 +129,7 @@ __device__ __forceinline__ void store_span(float* __restrict__ row, int64_t t0, 
     if (t0 + j >= lo && t0 + j < hi) row[t0 + j] = x[j];
 }
 
+// One step of a weighted inclusive prefix sum over lanes: s += w * (s of the lane the DPP control names).
 template <int Ctrl, int RowMask>
 __device__ __forceinline__ float scan_step(float s, float w) {
   return fmaf(w, dpp_f32<Ctrl, RowMask>(0.0f, s), s);
@@ -143,7 +145,14 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
   // when they come in random order.  (Ranking the rows by length inside every workgroup, 8 or 64
   // classes, costs 3 to 5 us per launch, as much as the order gains.)
   const bool fill_only = !Packed && (int)blockIdx.x >= a.B;
-  const int row = fill_only ? (int)blockIdx.x - a.B : (int)blockIdx.x;
+  int row = fill_only ? (int)blockIdx.x - a.B : (int)blockIdx.x;
+  // Rows in order of length: the long scans start first and the short ones fill the launch's end (the
+  // workgroups that only fill take the rows the other way round: the shortest row has the most padding).
+  // An entry that names no row makes its workgroup do nothing.
+  if (!Packed && a.order) {
+    row = a.order[fill_only ? a.B - 1 - row : row];
+    if ((unsigned)row >= (unsigned)a.B) return;
+  }
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -189,7 +198,15 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
     }
     return;
   }
-  if (nvalid == 0) return;
+  if (nvalid == 0) {
+    if (!Packed && a.row_stats && tid == 0) a.row_stats[row] = AdvRowStats{0.0, 0.0, 0.0, 0};
+    return;
+  }
+  // Sums of the row's advantages for the batch statistics, in double about the advantage of the row's
+  // last token (r - V there: nothing is bootstrapped beyond the end), which every thread can form.
+  const bool want_stats = !Packed && a.row_stats != nullptr;
+  double st_shift = 0.0, st_s1 = 0.0, st_s2 = 0.0;
+  if (want_stats) st_shift = (double)((last_given ? r_last : rrow[L - 1]) - vrow[L - 1]);
 
   // per-lane weights of the cross-row scan steps and of the carry into this lane and this wave
   const float w_b15 = pow_from_table<5>(a.clane, (lane & 15) + 1);  // from lane 15 of the row before
@@ -279,16 +296,84 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
       store4<VEC>(arow, t0, T, outA);
       if (trow) store4<VEC>(trow, t0, T, outR);
     }
+    if (want_stats) {
+#pragma unroll
+      for (int j = 0; j < kPerLane; ++j)
+        if (j < rem) {
+          const double dd = (double)outA[j] - st_shift;
+          st_s1 += dd;
+          st_s2 += dd * dd;
+        }
+    }
     if (k > 0) cur = nxt;
   }
+  if (want_stats) {  // lanes, then waves, in a fixed order
+    __shared__ double s_stats[2][kAdvWaves];
+    st_s1 = wave_sum_f64(st_s1);
+    st_s2 = wave_sum_f64(st_s2);
+    if (lane == 0) {
+      s_stats[0][wave] = st_s1;
+      s_stats[1][wave] = st_s2;
+    }
+    __syncthreads();
+    if (tid == 0) {
+      double t1 = 0.0, t2 = 0.0;
+      for (int w = 0; w < kAdvWaves; ++w) {
+        t1 += s_stats[0][w];
+        t2 += s_stats[1][w];
+      }
+      a.row_stats[row] = AdvRowStats{t1, t2, st_shift, (long long)L};
+    }
+  }
+}
+
+// The rows of a batch, longest first: a counting sort of the clipped lengths into 256 classes by one
+// workgroup (rows of one class in no particular order; the results of the pass do not depend on it).
+constexpr int kOrderClasses = 256;
+__global__ __launch_bounds__(kAdvThreads) void length_order_kernel(const int32_t* __restrict__ lengths, int32_t B, int64_t T,
+                                                                  int32_t* __restrict__ order) {
+  __shared__ int count[kOrderClasses];
+  __shared__ int wave_total[kOrderClasses / kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  auto class_of = [&](int32_t i) {
+    int64_t L = lengths[i];
+    L = L < 0 ? 0 : (L > T ? T : L);
+    return kOrderClasses - 1 - (int)((L * kOrderClasses) / (T + 1));
+  };
+  if (tid < kOrderClasses) count[tid] = 0;
+  __syncthreads();
+  for (int32_t i = tid; i < B; i += kAdvThreads) atomicAdd(&count[class_of(i)], 1);
+  __syncthreads();
+  int mine = 0, incl = 0;
+  if (tid < kOrderClasses) {  // inclusive prefix over the classes: inside each wave, then over the four waves
+    mine = count[tid];
+    incl = mine;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int up = __shfl_up(incl, d);
+      if (lane >= d) incl += up;
+    }
+    if (lane == kWave - 1) wave_total[tid >> 6] = incl;
+  }
+  __syncthreads();
+  if (tid < kOrderClasses) {
+    int before = 0;
+    for (int w = 0; w < (tid >> 6); ++w) before += wave_total[w];
+    count[tid] = before + incl - mine;  // where the class starts
+  }
+  __syncthreads();
+  for (int32_t i = tid; i < B; i += kAdvThreads) order[atomicAdd(&count[class_of(i)], 1)] = i;
 }
 
 }  // namespace
 
 int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
                       const int64_t* cu, int64_t N, const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
-                      float lambda, int zero_padding, float* td, float* adv, float* returns, hipStream_t stream) {
+                      float lambda, int zero_padding, float* td, float* adv, float* returns, const int32_t* order,
+                      AdvRowStats* row_stats, hipStream_t stream) {
   AdvArgs a;
+  a.order = order;
+  a.row_stats = row_stats;
   a.rewards = rewards;
   a.terminal_reward = terminal_reward;
   a.returns = returns;
@@ -318,6 +403,11 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
     kernel = rewards ? (vec ? espo_advantages_kernel<true, true, false> : espo_advantages_kernel<false, true, false>)
                      : (vec ? espo_advantages_kernel<true, false, false> : espo_advantages_kernel<false, false, false>);
   hipLaunchKernelGGL(kernel, grid, block, 0, stream, a);
+  return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
+}
+
+int launch_length_order(const int32_t* lengths, int64_t B, int64_t T, int32_t* order, hipStream_t stream) {
+  hipLaunchKernelGGL(length_order_kernel, dim3(1), dim3(kAdvThreads), 0, stream, lengths, (int32_t)B, T, order);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 

@@ -43,7 +43,18 @@ int launch_batch_stats(const float* regret, const int32_t* lengths, const uint8_
 size_t batch_stats_static_capacity();
 void* batch_stats_static_scratch();
 
+// Sums of one row's advantages over its valid tokens, about a shift of the row's own (its last
+// token's advantage): n, sum (A - shift), sum (A - shift)^2.  The advantage pass can leave one per
+// row; the batch's mean and variance are combined from them without another pass over the batch.
+struct AdvRowStats {
+  double s1, s2, shift;
+  long long n;
+};
+
 size_t whiten_workspace(int64_t B, int64_t T);
+// The second half of the whitening alone: mean and variance from the rows' sums, then the rewrite.
+int launch_whiten_rows(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps, int shift_mean,
+                       int unbiased, float* out, double* stats, const AdvRowStats* rows, hipStream_t stream);
 int launch_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps, int shift_mean,
                   int unbiased, float* out, double* stats, void* workspace, hipStream_t stream);
 
@@ -51,8 +62,14 @@ int launch_math_errors(float* out, hipStream_t stream);
 
 // rewards != nullptr: dense form; else the terminal form with terminal_reward[B].
 // cu != nullptr: trajectories stored back to back in arrays of N tokens (lengths, T, zero_padding unused).
+// order != nullptr (padded forms only): the scanning workgroups take their rows in that order.
+// row_stats != nullptr (padded forms only): every row's sums of its advantages are left there.
 int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
                       const int64_t* cu, int64_t N, const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
-                      float lambda, int zero_padding, float* td, float* adv, float* returns, hipStream_t stream);
+                      float lambda, int zero_padding, float* td, float* adv, float* returns, const int32_t* order,
+                      AdvRowStats* row_stats, hipStream_t stream);
+
+// The rows 0 .. B-1 ordered by clipped length, longest first (256 classes of length; one workgroup).
+int launch_length_order(const int32_t* lengths, int64_t B, int64_t T, int32_t* order, hipStream_t stream);
 
 }  // namespace espo

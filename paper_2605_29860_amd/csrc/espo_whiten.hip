@@ -44,13 +44,6 @@ struct WhArgs {
   WhPartial* part;
 };
 
-__device__ __forceinline__ double shfl_down_f64(double v, int d) {
-  int lo = __double2loint(v), hi = __double2hiint(v);
-  lo = __shfl_down(lo, d);
-  hi = __shfl_down(hi, d);
-  return __hiloint2double(hi, lo);
-}
-
 // Sum over the workgroup in a fixed tree, returned to every thread.
 __device__ __forceinline__ double block_sum_all(double v, double* lds) {
 #pragma unroll
@@ -114,6 +107,36 @@ __device__ __forceinline__ void for_items(const WhArgs& a, Whole&& whole, Single
   }
 }
 
+// From the batch's count, mean and sum of squared deviations to the rewrite of this workgroup's items.
+template <bool VEC>
+__device__ __forceinline__ void normalise_items(const WhArgs& a, double n, double mean, double ss) {
+  const int tid = threadIdx.x;
+  if (n == 0.0) {  // no valid token in the batch: nothing to write
+    if (a.stats && blockIdx.x == 0 && tid < 3) a.stats[tid] = 0.0;
+    return;
+  }
+  if (ss < 0.0) ss = 0.0;
+  const double denom = n - (double)a.ddof;
+  const double var = denom > 0.0 ? ss / denom : 0.0;
+  const double sd = sqrt(var + (double)a.eps);
+  const double rstd = sd > 0.0 ? 1.0 / sd : 0.0;  // a constant batch with eps = 0: every output is 0
+  const double sub = a.shift_mean ? mean : 0.0;
+  if (a.stats && blockIdx.x == 0 && tid == 0) {
+    a.stats[0] = mean;
+    a.stats[1] = var;
+    a.stats[2] = n;
+  }
+  for_items<VEC>(
+      a,
+      [&](const f32x4& g, int64_t at) {
+        f32x4 o;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) o[j] = rstd > 0.0 ? (float)(((double)g[j] - sub) * rstd) : 0.0f;
+        __builtin_nontemporal_store(o, (f32x4*)(a.out + at));
+      },
+      [&](float x, int64_t at) { a.out[at] = rstd > 0.0 ? (float)(((double)x - sub) * rstd) : 0.0f; }, [](int64_t) {});
+}
+
 template <bool VEC>
 __global__ __launch_bounds__(kWhThreads) void whiten_partial_kernel(WhArgs a) {
   __shared__ double lds[kWhWaves];
@@ -175,34 +198,65 @@ __global__ __launch_bounds__(kWhThreads) void whiten_apply_kernel(WhArgs a) {
     s1 += lds[kWhWaves + w];
     s2 += lds[2 * kWhWaves + w];
   }
-  if (n == 0.0) {  // no valid token in the batch: nothing to write
-    if (a.stats && blockIdx.x == 0 && tid < 3) a.stats[tid] = 0.0;
-    return;
-  }
   const double shift = a.part[0].shift;
-  const double md = s1 / n;
-  const double mean = shift + md;
-  double ss = s2 - n * md * md;  // sum of squared deviations from the mean
-  if (ss < 0.0) ss = 0.0;
-  const double denom = n - (double)a.ddof;
-  const double var = denom > 0.0 ? ss / denom : 0.0;
-  const double sd = sqrt(var + (double)a.eps);
-  const double rstd = sd > 0.0 ? 1.0 / sd : 0.0;  // a constant batch with eps = 0: every output is 0
-  const double sub = a.shift_mean ? mean : 0.0;
-  if (a.stats && blockIdx.x == 0 && tid == 0) {
-    a.stats[0] = mean;
-    a.stats[1] = var;
-    a.stats[2] = n;
+  const double md = n > 0.0 ? s1 / n : 0.0;
+  normalise_items<VEC>(a, n, shift + md, s2 - n * md * md);  // s2 - n md^2: the sum of squared deviations from the mean
+}
+
+// The same rewrite with the mean and variance combined from sums that the advantage pass left per row,
+// each about a shift of that row's own: every row gives (n, mean, sum of squared deviations), and two
+// such triples merge exactly (the pairwise update of Chan, Golub and LeVeque).  Thread i merges rows
+// i, i + 1024, ...; lanes and waves follow in a fixed tree, so every workgroup gets the same bits.
+struct Moments {
+  double n, mean, m2;
+};
+
+__device__ __forceinline__ double shfl_lane0_f64(double v) {
+  return __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(v)), __builtin_amdgcn_readfirstlane(__double2loint(v)));
+}
+
+__device__ __forceinline__ Moments merge(const Moments& x, const Moments& y) {
+  const double n = x.n + y.n;
+  if (n == 0.0) return Moments{0.0, 0.0, 0.0};
+  const double delta = y.mean - x.mean;
+  return Moments{n, x.mean + delta * (y.n / n), x.m2 + y.m2 + delta * delta * (x.n * (y.n / n))};
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(kWhThreads) void whiten_apply_rows_kernel(WhArgs a, const AdvRowStats* __restrict__ rows) {
+  __shared__ double lds[3 * kWhWaves];
+  const int tid = threadIdx.x;
+  const int lane = tid & (kWave - 1), wave = tid >> 6;
+  Moments mine{0.0, 0.0, 0.0};
+  for (int64_t b = tid; b < a.B; b += kWhThreads) {
+    const AdvRowStats r = rows[b];
+    if (r.n > 0) {
+      const double n = (double)r.n, md = r.s1 / n;
+      const double m2 = r.s2 - n * md * md;
+      mine = merge(mine, Moments{n, r.shift + md, m2 > 0.0 ? m2 : 0.0});
+    }
   }
-  for_items<VEC>(
-      a,
-      [&](const f32x4& g, int64_t at) {
-        f32x4 o;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) o[j] = rstd > 0.0 ? (float)(((double)g[j] - sub) * rstd) : 0.0f;
-        __builtin_nontemporal_store(o, (f32x4*)(a.out + at));
-      },
-      [&](float x, int64_t at) { a.out[at] = rstd > 0.0 ? (float)(((double)x - sub) * rstd) : 0.0f; }, [](int64_t) {});
+  for (int d = 32; d >= 1; d >>= 1) {
+    const Moments other{shfl_down_f64(mine.n, d), shfl_down_f64(mine.mean, d), shfl_down_f64(mine.m2, d)};
+    if (lane + d < kWave) mine = merge(mine, other);
+  }
+  if (lane == 0) {
+    lds[wave] = mine.n;
+    lds[kWhWaves + wave] = mine.mean;
+    lds[2 * kWhWaves + wave] = mine.m2;
+  }
+  __syncthreads();
+  // the sixteen wave results, merged by the same tree in every wave
+  Moments all{0.0, 0.0, 0.0};
+  if (lane < kWhWaves) all = Moments{lds[lane], lds[kWhWaves + lane], lds[2 * kWhWaves + lane]};
+#pragma unroll
+  for (int d = kWhWaves / 2; d >= 1; d >>= 1) {
+    const Moments other{shfl_down_f64(all.n, d), shfl_down_f64(all.mean, d), shfl_down_f64(all.m2, d)};
+    if (lane + d < kWhWaves) all = merge(all, other);
+  }
+  all = Moments{shfl_lane0_f64(all.n), shfl_lane0_f64(all.mean), shfl_lane0_f64(all.m2)};
+  normalise_items<VEC>(a, all.n, all.mean, all.m2);
 }
 
 int whiten_groups(int64_t B, int64_t T) {
@@ -237,6 +291,28 @@ int launch_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T
   if (hipGetLastError() != hipSuccess) return ESPO_EHIP;
   hipLaunchKernelGGL(vec ? whiten_apply_kernel<true> : whiten_apply_kernel<false>, dim3(a.groups), dim3(kWhThreads), 0,
                      stream, a);
+  return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
+}
+
+int launch_whiten_rows(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps, int shift_mean,
+                       int unbiased, float* out, double* stats, const AdvRowStats* rows, hipStream_t stream) {
+  WhArgs a;
+  a.adv = adv;
+  a.lengths = lengths;
+  a.B = B;
+  a.T = T;
+  a.nch = (T + kWhItem - 1) / kWhItem;
+  a.items = B * a.nch;
+  a.groups = whiten_groups(B, T);
+  a.eps = eps;
+  a.shift_mean = shift_mean;
+  a.ddof = unbiased ? 1 : 0;
+  a.out = out;
+  a.stats = stats;
+  a.part = nullptr;
+  const bool vec = (T % 4 == 0);
+  hipLaunchKernelGGL(vec ? whiten_apply_rows_kernel<true> : whiten_apply_rows_kernel<false>, dim3(a.groups),
+                     dim3(kWhThreads), 0, stream, a, rows);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
 }
 

@@ -162,3 +162,21 @@ def test_binding_refuses_tensors_that_are_too_short(monkeypatch):
         with pytest.raises(ValueError, match="out"):
             fn(torch.zeros(B, T), mk(B, i32), mk(B, u8), 1.0, 1.0, 1.0, mk(8, u8), *extra)
     assert Recorder.calls == calls
+    # the pair with a workspace between them, and the order by length
+    wsp = mk(32 * B, u8)
+    b.espo_advantages_ws(**adv_args(), workspace=wsp, order=mk(B, i32))
+    b.espo_whiten_from_ws(torch.zeros(B, T), mk(B, i32), torch.zeros(B, T), wsp)
+    b.espo_length_order(mk(B, i32), T, mk(B, i32))
+    calls = Recorder.calls
+    for name, bad in (("values", (B, T - 1)), ("td", (B - 1, T)), ("adv", (B, T + 1)), ("lengths", B - 1), ("stopped", B - 1)):
+        with pytest.raises(ValueError, match=name):
+            b.espo_advantages_ws(**adv_args(**{name: bad}), workspace=wsp)
+    with pytest.raises(ValueError, match="order"):
+        b.espo_advantages_ws(**adv_args(), workspace=wsp, order=mk(B - 1, i32))
+    with pytest.raises(ValueError, match="order"):
+        b.espo_length_order(mk(B, i32), T, mk(B - 1, i32))
+    with pytest.raises(TypeError):
+        b.espo_whiten_from_ws(torch.zeros(B, T), mk(B - 1, i32), torch.zeros(B, T), wsp)
+    with pytest.raises(TypeError):
+        b.espo_whiten_from_ws(torch.zeros(B, T), mk(B, i32), torch.zeros(B, T + 1), wsp)
+    assert Recorder.calls == calls
