@@ -579,37 +579,50 @@ __device__ __forceinline__ void fast_visit(const StepArgs& a, const StepShared& 
 
 // For a row with a long survivor list: instead of scoring every index of every surviving
 // block, the blocks' logits are only compared with the bound (index v can win only if
-// y_v + M_q reaches it), four blocks per wave at a time so that their loads overlap; the few
-// indices that pass are collected and then scored by all threads at once.
+// y_v + M_q reaches it); the few indices that pass are collected and then scored by all threads
+// at once.  The blocks are read again from the row, laid out as in phase 1: a lane group of 8
+// lanes per block, 16 bytes per lane, so one load of a wave covers 8 blocks; with four loads in
+// flight the workgroup covers 512 blocks per trip to memory (a flat row at temperature 1 has a
+// hundred survivors and more; one block per load took a trip per 64 of them).
 template <int DT, int W>
 __device__ __forceinline__ void collect_candidates(const StepArgs& a, const StepShared& sh, const void* rowp, int nsurv,
                                                    float bound) {
-  constexpr int kStepWaves = W;
+  constexpr int kStepWaves = W, kLoads = 4;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int grp = lane >> 3;
+  const uint32_t sub = (uint32_t)(lane & 7) * 8u;  // the lane's 8 elements within its block
+  const uint32_t last_group = (uint32_t)(a.V - 1) & ~7u;
 #pragma unroll 1
-  for (int base = wave; base < nsurv; base += 4 * kStepWaves) {
-    int qs[4];
-    float xs[4];
+  for (int base = wave * kGroups; base < nsurv; base += kLoads * kStepWaves * kGroups) {
+    int qs[kLoads];
+    Raw<DT> raw[kLoads];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int k = base + j * kStepWaves;
-      qs[j] = k < nsurv ? __builtin_amdgcn_readfirstlane(sh.surv(k)) : -1;
-      xs[j] = kNegInf;
-      if (qs[j] >= 0) xs[j] = block_elem<DT, W>(a, sh, rowp, qs[j]);
+    for (int j = 0; j < kLoads; ++j) {
+      const int k = base + j * kStepWaves * kGroups + grp;
+      qs[j] = k < nsurv ? sh.surv(k) : -1;
+      // a group without a block reads block 0 and drops it; a ragged last block is masked below
+      const uint32_t e0 = (uint32_t)(qs[j] < 0 ? 0 : qs[j]) * kDrawBlock + sub;
+      raw[j] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
     }
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
+    for (int j = 0; j < kLoads; ++j) {
       if (qs[j] < 0) continue;
+      float x[8];
+      unpack<DT>(raw[j], x);
       const int32_t first = qs[j] * kDrawBlock;
       const int32_t n = a.V - first < kDrawBlock ? a.V - first : kDrawBlock;
       const float M = flog((float)n) - flog(neg_log_uniform<float>(sh.word(qs[j])));
-      const float y = xs[j] * a.inv_tau;
-      if (lane < n && xs[j] > sh.floor && (y + M) + 2.0f * score_margin(a, y) >= bound) {
-        const int i = atomicAdd(sh.ncand, 1);
-        if (i < kCandCap) {
-          sh.cand_v[i] = first + lane;
-          sh.cand_x[i] = xs[j];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int32_t v = first + (int32_t)sub + u;
+        const float y = x[u] * a.inv_tau;
+        if (v < a.V && x[u] > sh.floor && (y + M) + 2.0f * score_margin(a, y) >= bound) {
+          const int i = atomicAdd(sh.ncand, 1);
+          if (i < kCandCap) {
+            sh.cand_v[i] = v;
+            sh.cand_x[i] = x[u];
+          }
         }
       }
     }
