@@ -1,7 +1,8 @@
 // Calls the C ABI of libespo.so from a plain HIP host program (no Python, no PyTorch): reads a
 // binary file of inputs, runs one espo_step, one espo_advantages, one espo_whiten on its result
 // and one espo_advantages_packed (the [B, T] arrays taken as B full trajectories of T tokens
-// stored back to back, terminal reward values[b]), writes the outputs to another binary file.  The GPU test that drives it generates the inputs and compares the
+// stored back to back, terminal reward values[b]), then the pair with a workspace between them
+// (espo_length_order, espo_advantages_ws, espo_whiten_from_ws), writes the outputs to another binary file.  The GPU test that drives it generates the inputs and compares the
 // outputs with the CPU oracle.
 //
 // input file (little endian): int32 B, V, T; float tau; uint64 seed; int32 step; espo_params;
@@ -9,7 +10,8 @@
 //   float rewards[B*T]; float vals2[B*T]; int32 lengths[B]; uint8 stopped[B]
 // output file: int32 tokens[B]; float regret[B]; float z[B]; uint8 alive[B]; int32 stop_step[B];
 //   float logprob[B]; float entropy[B]; float td[B*T]; float adv[B*T];
-//   float whitened[B*T] (0 beyond the lengths); float td_packed[B*T]; float adv_packed[B*T]
+//   float whitened[B*T] (0 beyond the lengths); float td_packed[B*T]; float adv_packed[B*T];
+//   int32 order[B]; float adv_ws[B*T]; float whitened_from_ws[B*T] (0 beyond the lengths)
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
@@ -94,6 +96,15 @@ int main(int argc, char** argv) {
     CK(hipMalloc(&d_step_ws, step_ws_bytes));
     CK(hipMemset(d_step_ws, 0, step_ws_bytes));
   }
+  int32_t* d_order;
+  float *d_adv2, *d_wh2;
+  void* d_aws;
+  const size_t aws_bytes = espo_advantages_ws_bytes(B);
+  CK(hipMalloc((void**)&d_order, B * 4));
+  CK(hipMalloc((void**)&d_adv2, (size_t)B * T * 4));
+  CK(hipMalloc((void**)&d_wh2, (size_t)B * T * 4));
+  CK(hipMemset(d_wh2, 0, (size_t)B * T * 4));
+  CK(hipMalloc(&d_aws, aws_bytes));
   hipStream_t stream;
   CK(hipStreamCreate(&stream));
 
@@ -103,9 +114,18 @@ int main(int argc, char** argv) {
   EK(espo_whiten(d_adv, d_lengths, B, T, 1e-8f, 1, 0, d_wh, nullptr, d_ws, ws_bytes, stream));
   EK(espo_advantages_packed(nullptr, d_values, d_vals2, d_cu, d_stopped, B, (int64_t)B * T, -1.0f, 1.0f, 0.95f, d_tdp,
                             d_advp, nullptr, stream));
+  // the same advantages again, rows longest first, the rows' sums handed to the whitening (td is rewritten with the same bits)
+  EK(espo_length_order(d_lengths, B, T, d_order, stream));
+  EK(espo_advantages_ws(d_rewards, d_vals2, d_lengths, d_stopped, B, T, -1.0f, 1.0f, 0.95f, d_td, d_adv2, d_order, d_aws,
+                        aws_bytes, stream));
+  EK(espo_whiten_from_ws(d_adv2, d_lengths, B, T, 1e-8f, 1, 0, d_wh2, nullptr, d_aws, aws_bytes, stream));
   CK(hipStreamSynchronize(stream));
 
-  std::vector<int32_t> tokens(B);
+  std::vector<int32_t> tokens(B), order(B);
+  std::vector<float> adv2((size_t)B * T), wh2((size_t)B * T);
+  CK(hipMemcpy(order.data(), d_order, B * 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(adv2.data(), d_adv2, adv2.size() * 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(wh2.data(), d_wh2, wh2.size() * 4, hipMemcpyDeviceToHost));
   std::vector<float> regret(B), logprob(B), entropy(B), td((size_t)B * T), adv((size_t)B * T);
   std::vector<float> wh((size_t)B * T), tdp((size_t)B * T), advp((size_t)B * T);
   CK(hipMemcpy(tokens.data(), d_tokens, B * 4, hipMemcpyDeviceToHost));
@@ -126,7 +146,8 @@ int main(int argc, char** argv) {
                   wr(o, stop_step.data(), B) && wr(o, logprob.data(), B) && wr(o, entropy.data(), B) &&
                   wr(o, td.data(), td.size()) &&
                   wr(o, adv.data(), adv.size()) && wr(o, wh.data(), wh.size()) && wr(o, tdp.data(), tdp.size()) &&
-                  wr(o, advp.data(), advp.size());
+                  wr(o, advp.data(), advp.size()) && wr(o, order.data(), B) && wr(o, adv2.data(), adv2.size()) &&
+                  wr(o, wh2.data(), wh2.size());
   std::fclose(o);
   std::printf("abi_check: version %d, B=%d V=%d T=%d, step workspace %zu bytes, done\n", espo_version(), B, V, T, step_ws_bytes);
   return ok ? 0 : 1;

@@ -61,6 +61,7 @@ def test_native_program_matches_the_oracle(tmp_path):
     entropy = take(np.float32, B)
     td, adv = take(np.float32, B * T).reshape(B, T), take(np.float32, B * T).reshape(B, T)
     wh, td_p, adv_p = take(np.float32, B * T).reshape(B, T), take(np.float32, B * T), take(np.float32, B * T)
+    order, adv_ws, wh_ws = take(np.int32, B), take(np.float32, B * T).reshape(B, T), take(np.float32, B * T).reshape(B, T)
 
     z_o, alive_o, ss_o = z.copy(), alive.copy(), stop_step.copy()
     ref = oracle.step(logits_in, tau, seed, step, values, op, z_o, alive_o, ss_o, want_entropy=True)
@@ -84,3 +85,10 @@ def test_native_program_matches_the_oracle(tmp_path):
     tdp_o, advp_o, _, scale_p = oracle.advantages_packed(None, values, vals2.reshape(-1), cu, stopped, -1.0, 1.0, 0.95)
     assert np.abs(td_p - tdp_o).max() <= 2e-7 * (max(np.abs(values).max(), 1.0) + 2 * np.abs(vals2).max())
     assert (np.abs(adv_p - advp_o) <= 2e-6 * np.maximum(np.abs(advp_o), scale_p)).all()
+    # the pair with a workspace between them: a permutation with the longest rows first, the same advantages,
+    # and the whitening from the rows' sums against the oracle
+    assert sorted(order.tolist()) == list(range(B))
+    cls = (np.clip(lengths, 0, T)[order].astype(np.int64) * 256) // (T + 1)
+    assert (np.diff(cls) <= 0).all()
+    np.testing.assert_array_equal(adv_ws[mask].view(np.uint32), adv[mask].view(np.uint32))
+    assert (np.abs(wh_ws[mask] - wh_o[mask]) <= 2e-7 * np.maximum(np.abs(wh_o[mask]), 1)).all() and (wh_ws[~mask] == 0).all()
