@@ -350,9 +350,10 @@ def main() -> int:
     wh_us = timed(args.adv_reps, wh_call, warm=nbuf)
     wh_bytes = float(np.mean(valid * 12 + B_ADV * 8))
 
-    # the pair with a workspace between them: the advantage pass leaves every row's sums, the whitening starts
-    # from those; and the same pass taking its rows longest first, the order written beforehand or in the region
-    aw_ws = [torch.empty(espo.espo_advantages_ws_bytes(B_ADV), dtype=torch.uint8, device=dev) for _ in range(nbuf)]
+    # the pair with a workspace between them: the advantage pass sorts its later rows by length inside the launch and
+    # leaves every row's sums, the whitening starts from those; and the same pass with an order from the caller,
+    # written beforehand or in the region
+    aw_ws = [torch.zeros(espo.espo_advantages_ws_bytes(B_ADV), dtype=torch.uint8, device=dev) for _ in range(nbuf)]
     aw_order = [torch.empty(B_ADV, dtype=torch.int32, device=dev) for _ in range(nbuf)]
     def aw_call(i, ordered=False, order_now=False):
         r, v, L, s = adv_in[i % nbuf]
@@ -550,9 +551,12 @@ def main() -> int:
         "whiten": {"workload": "whitening of the advantages of the same batches over their valid tokens",
                    "us_per_call": wh_us, "launches_per_call": 2, "algorithmic_bytes_per_call": wh_bytes,
                    "gbs": wh_bytes / wh_us / 1e3, "frac": wh_bytes / wh_us / 1e3 / HBM_PEAK_GBS},
-        "advantages_ws": {"workload": "the same batches through espo_advantages_ws (every row's sums left in a workspace)",
-                          "us_per_call": aw_us, "frac": float(adv_bytes.mean()) / aw_us / 1e3 / HBM_PEAK_GBS,
-                          "rows_longest_first": {"us_per_call": aw_ord_us,
+        "advantages_ws": {"workload": "the same batches through espo_advantages_ws: rows 513.. sorted by length by the launch's "
+                                      "first workgroup, every row's sums left in the workspace; same td and adv",
+                          "us_per_call": aw_us, "gbs": float(adv_bytes.mean()) / aw_us / 1e3,
+                          "frac": float(adv_bytes.mean()) / aw_us / 1e3 / HBM_PEAK_GBS,
+                          "frac_of_ceiling": float(adv_bytes.mean()) / aw_us / 1e3 / padded_gbs,
+                          "order_from_the_caller": {"us_per_call": aw_ord_us,
                                                  "frac": float(adv_bytes.mean()) / aw_ord_us / 1e3 / HBM_PEAK_GBS,
                                                  "order": "written by espo_length_order before the timed region",
                                                  "us_per_call_with_the_order_written_in_the_region": aw_ord_now_us,

@@ -411,10 +411,13 @@ size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
  *
  * espo_advantages_ws computes exactly what espo_advantages computes (same td and adv, bit for
  * bit) and does two more things.  Every row leaves the count, sum and sum of squares of its
- * advantages in the workspace, in double about a shift of the row's own.  And if `order` is
- * given, the workgroups take their rows in that order instead of 0, 1, 2, ...: with the rows
- * longest first, a batch of more than 512 rows of mixed lengths takes about an eighth less
- * time, and no row has to be moved for it.
+ * advantages in the workspace, in double about a shift of the row's own.  And the rows are
+ * scanned in an order that suits their lengths instead of 0, 1, 2, ...: with the long rows
+ * first, a batch of more than 512 rows of mixed lengths takes about an eighth less time, and
+ * no row has to be moved for it.  If `order` is given, that is the order.  If it is NULL and
+ * the batch has more than 512 rows (what the chip works on at once), the launch's first
+ * workgroup sorts the rows from the 513th on by length while the first 512 are scanned in index
+ * order, which gains as much as a full order does.
  *
  * espo_length_order writes such an order: the rows 0 .. B-1 by length (clamped to [0, T]) in
  * 256 classes, longest first, rows of one class in no particular order.  It is one small
@@ -431,10 +434,13 @@ size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
  *   order      device, [B] int32, every row once, or NULL (rows in index order).  An entry
  *              outside [0, B) is skipped; a row that is missing from the order is not computed,
  *              one that is named twice is computed twice.
- *   workspace  device, at least espo_advantages_ws_bytes(B) bytes (32 per row), 16-byte
- *              aligned; written by espo_advantages_ws, read by espo_whiten_from_ws; contents
- *              before the first call are irrelevant.  Missing, misaligned or too small:
- *              ESPO_EWORKSPACE.
+ *   workspace  device, at least espo_advantages_ws_bytes(B) bytes (256, plus 32 per row, plus 4
+ *              per row beyond the 512th), 16-byte aligned.  Its first 256 bytes must be zero
+ *              before the first call that uses it (two words in there are how the sorting
+ *              workgroup tells the others that it is done and how the last of them knows that
+ *              it is the last; every call leaves them zero again); the rest may hold anything.
+ *              Written by espo_advantages_ws, read by espo_whiten_from_ws.  Missing, misaligned
+ *              or too small: ESPO_EWORKSPACE.  Two calls that overlap in time need a workspace each.
  * Calls on one stream are ordered; a caller that puts them on different streams orders them
  * itself.
  */

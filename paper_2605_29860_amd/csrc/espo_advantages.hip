@@ -60,7 +60,61 @@ struct AdvArgs {
   float* adv;
   const int32_t* order;    // optional [B]: the rows, longest first (padded forms)
   AdvRowStats* row_stats;  // optional [B]: sums of every row's advantages (padded forms)
+  int32_t* sorted;         // optional [B - kAdvFirstRows]: the rows from kAdvFirstRows on, longest first, written by
+                           //   workgroup 0 of this launch (padded forms, no `order` given)
+  uint32_t* sync;          // with `sorted`: [0] set once `sorted` is complete, [32] readers so far; both 0 between launches
 };
+
+// Workgroups that the chip holds at once (256 CUs x 2 of 1024 threads): the rows that are scanned first whatever
+// their lengths.  Only the order of the rows that follow decides how ragged the launch's end is (measured: rows
+// 512.. of 1024 longest first gives what a full order gives, 39.9 us against 45.3 in index order; rows 768.. 43.3).
+constexpr int kAdvFirstRows = 512;
+// The word that says "sorted" and the count of its readers lie in different 128-byte lines: loads of the one and
+// read-modify-writes of the other on the same line cost the readers 15 us per launch between them.
+constexpr int kAdvSyncStride = 32;       // words
+constexpr size_t kAdvSyncBytes = 256;
+constexpr int kOrderClasses = 256;
+
+// Writes the rows first .. B-1 to order[0 .. B-first), longest first: a counting sort of the clipped lengths into
+// 256 classes by one workgroup (rows of one class in no particular order; no result depends on it).  The entries
+// are written past the caches that other parts of the chip do not see, and are complete when the call returns.
+__device__ __forceinline__ void sort_rows_by_length(const int32_t* __restrict__ lengths, int32_t first, int32_t B, int64_t T,
+                                                    int32_t* __restrict__ order) {
+  __shared__ int count[kOrderClasses];
+  __shared__ int wave_total[kOrderClasses / kWave];
+  const int tid = threadIdx.x, lane = tid & (kWave - 1);
+  auto class_of = [&](int32_t i) {
+    int64_t L = lengths[i];
+    L = L < 0 ? 0 : (L > T ? T : L);
+    return kOrderClasses - 1 - (int)((L * kOrderClasses) / (T + 1));
+  };
+  if (tid < kOrderClasses) count[tid] = 0;
+  __syncthreads();
+  for (int32_t i = first + tid; i < B; i += kAdvThreads) atomicAdd(&count[class_of(i)], 1);
+  __syncthreads();
+  int mine = 0, incl = 0;
+  if (tid < kOrderClasses) {  // inclusive prefix over the classes: inside each wave, then over the four waves
+    mine = count[tid];
+    incl = mine;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+      const int up = __shfl_up(incl, d);
+      if (lane >= d) incl += up;
+    }
+    if (lane == kWave - 1) wave_total[tid >> 6] = incl;
+  }
+  __syncthreads();
+  if (tid < kOrderClasses) {
+    int before = 0;
+    for (int w = 0; w < (tid >> 6); ++w) before += wave_total[w];
+    count[tid] = before + incl - mine;  // where the class starts
+  }
+  __syncthreads();
+  for (int32_t i = first + tid; i < B; i += kAdvThreads)
+    __hip_atomic_store(order + atomicAdd(&count[class_of(i)], 1), i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
 
 struct TileIn {
   float r[kPerLane], v[kPerLane];
@@ -144,13 +198,39 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
   // 2 to 3 us on the B = 1024, T = 16384 batches when their rows come in order of length, nothing
   // when they come in random order.  (Ranking the rows by length inside every workgroup, 8 or 64
   // classes, costs 3 to 5 us per launch, as much as the order gains.)
-  const bool fill_only = !Packed && (int)blockIdx.x >= a.B;
-  int row = fill_only ? (int)blockIdx.x - a.B : (int)blockIdx.x;
+  int unit = (int)blockIdx.x;
+  if (!Packed && a.sorted) {
+    // No order was given and the batch has more rows than the chip holds workgroups: workgroup 0 of this launch
+    // sorts the later rows while the first kAdvFirstRows are being scanned, and tells the others when it is done.
+    // It waits for nobody and is dispatched before every workgroup that waits for it.
+    if (unit == 0) {
+      sort_rows_by_length(a.lengths, kAdvFirstRows, a.B, a.T, a.sorted);
+      if (threadIdx.x == 0) __hip_atomic_store(a.sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return;
+    }
+    unit -= 1;
+  }
+  const bool fill_only = !Packed && unit >= a.B;
+  int row = fill_only ? unit - a.B : unit;
   // Rows in order of length: the long scans start first and the short ones fill the launch's end (the
   // workgroups that only fill take the rows the other way round: the shortest row has the most padding).
   // An entry that names no row makes its workgroup do nothing.
   if (!Packed && a.order) {
     row = a.order[fill_only ? a.B - 1 - row : row];
+    if ((unsigned)row >= (unsigned)a.B) return;
+  } else if (!Packed && a.sorted && !fill_only && row >= kAdvFirstRows) {
+    // one of the later scans: its row comes from the sorted list.  The last reader clears the two words, so the
+    // next launch finds them as this one did.
+    __shared__ int s_row;
+    if (threadIdx.x == 0) {
+      while (__hip_atomic_load(a.sync, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) __builtin_amdgcn_s_sleep(8);
+      s_row = __hip_atomic_load(a.sorted + (row - kAdvFirstRows), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const uint32_t readers = (uint32_t)(a.B - kAdvFirstRows);
+      if (atomicInc(a.sync + kAdvSyncStride, readers - 1u) == readers - 1u)
+        __hip_atomic_store(a.sync, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    row = s_row;
     if ((unsigned)row >= (unsigned)a.B) return;
   }
   const int tid = threadIdx.x;
@@ -327,42 +407,9 @@ __global__ __launch_bounds__(kAdvThreads, 8) void espo_advantages_kernel(AdvArgs
   }
 }
 
-// The rows of a batch, longest first: a counting sort of the clipped lengths into 256 classes by one
-// workgroup (rows of one class in no particular order; the results of the pass do not depend on it).
-constexpr int kOrderClasses = 256;
 __global__ __launch_bounds__(kAdvThreads) void length_order_kernel(const int32_t* __restrict__ lengths, int32_t B, int64_t T,
                                                                   int32_t* __restrict__ order) {
-  __shared__ int count[kOrderClasses];
-  __shared__ int wave_total[kOrderClasses / kWave];
-  const int tid = threadIdx.x, lane = tid & (kWave - 1);
-  auto class_of = [&](int32_t i) {
-    int64_t L = lengths[i];
-    L = L < 0 ? 0 : (L > T ? T : L);
-    return kOrderClasses - 1 - (int)((L * kOrderClasses) / (T + 1));
-  };
-  if (tid < kOrderClasses) count[tid] = 0;
-  __syncthreads();
-  for (int32_t i = tid; i < B; i += kAdvThreads) atomicAdd(&count[class_of(i)], 1);
-  __syncthreads();
-  int mine = 0, incl = 0;
-  if (tid < kOrderClasses) {  // inclusive prefix over the classes: inside each wave, then over the four waves
-    mine = count[tid];
-    incl = mine;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-      const int up = __shfl_up(incl, d);
-      if (lane >= d) incl += up;
-    }
-    if (lane == kWave - 1) wave_total[tid >> 6] = incl;
-  }
-  __syncthreads();
-  if (tid < kOrderClasses) {
-    int before = 0;
-    for (int w = 0; w < (tid >> 6); ++w) before += wave_total[w];
-    count[tid] = before + incl - mine;  // where the class starts
-  }
-  __syncthreads();
-  for (int32_t i = tid; i < B; i += kAdvThreads) order[atomicAdd(&count[class_of(i)], 1)] = i;
+  sort_rows_by_length(lengths, 0, B, T, order);
 }
 
 }  // namespace
@@ -370,10 +417,13 @@ __global__ __launch_bounds__(kAdvThreads) void length_order_kernel(const int32_t
 int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
                       const int64_t* cu, int64_t N, const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
                       float lambda, int zero_padding, float* td, float* adv, float* returns, const int32_t* order,
-                      AdvRowStats* row_stats, hipStream_t stream) {
+                      AdvRowStats* row_stats, int32_t* sorted, uint32_t* sync, hipStream_t stream) {
   AdvArgs a;
   a.order = order;
   a.row_stats = row_stats;
+  const bool sort_here = cu == nullptr && order == nullptr && sorted != nullptr && sync != nullptr && B > kAdvFirstRows;
+  a.sorted = sort_here ? sorted : nullptr;
+  a.sync = sort_here ? sync : nullptr;
   a.rewards = rewards;
   a.terminal_reward = terminal_reward;
   a.returns = returns;
@@ -395,7 +445,7 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
   a.td = td;
   a.adv = adv;
   const bool vec = (T % 4 == 0);
-  const dim3 grid((unsigned)(cu == nullptr && zero_padding ? 2 * B : B)), block(kAdvThreads);
+  const dim3 grid((unsigned)((cu == nullptr && zero_padding ? 2 * B : B) + (sort_here ? 1 : 0))), block(kAdvThreads);
   void (*kernel)(AdvArgs);
   if (cu)
     kernel = rewards ? espo_advantages_kernel<true, true, true> : espo_advantages_kernel<true, false, true>;
@@ -404,6 +454,15 @@ int launch_advantages(const float* rewards, const float* terminal_reward, const 
                      : (vec ? espo_advantages_kernel<true, false, false> : espo_advantages_kernel<false, false, false>);
   hipLaunchKernelGGL(kernel, grid, block, 0, stream, a);
   return hipGetLastError() == hipSuccess ? ESPO_OK : ESPO_EHIP;
+}
+
+size_t advantages_workspace_layout(int64_t B, size_t* stats_offset, size_t* sorted_offset) {
+  // the two words of `sync` come first, so that they are where they were whatever B a call has
+  const size_t stats = (size_t)B * sizeof(AdvRowStats);
+  const size_t later = B > kAdvFirstRows ? (size_t)(B - kAdvFirstRows) : 0;
+  if (stats_offset) *stats_offset = kAdvSyncBytes;
+  if (sorted_offset) *sorted_offset = kAdvSyncBytes + stats;
+  return kAdvSyncBytes + stats + ((later * sizeof(int32_t) + 15) & ~(size_t)15);
 }
 
 int launch_length_order(const int32_t* lengths, int64_t B, int64_t T, int32_t* order, hipStream_t stream) {

@@ -273,12 +273,12 @@ int espo_advantages(const float* rewards, const float* values, const int32_t* le
   if (T > 0x7fffffff || B > 0x3fffffff) return ESPO_ERANGE;  // the grid has 2 B workgroups
   if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv)) return ESPO_EALIGN;
   return espo::launch_advantages(rewards, nullptr, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda, 1, td, adv,
-                                 nullptr, nullptr, nullptr, (hipStream_t)stream);
+                                 nullptr, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 size_t espo_advantages_ws_bytes(int64_t B) {
   if (B <= 0) return 0;
-  return (size_t)B * sizeof(espo::AdvRowStats);
+  return espo::advantages_workspace_layout(B, nullptr, nullptr);
 }
 
 int espo_length_order(const int32_t* lengths, int64_t B, int64_t T, int32_t* order, void* stream) {
@@ -298,10 +298,12 @@ int espo_advantages_ws(const float* rewards, const float* values, const int32_t*
   if (!rewards || !values || !lengths || !stopped || !td || !adv) return ESPO_EINVAL;
   if (T > 0x7fffffff || B > 0x3fffffff) return ESPO_ERANGE;  // the grid has 2 B workgroups
   if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv)) return ESPO_EALIGN;
-  if (!workspace || workspace_bytes < (size_t)B * sizeof(espo::AdvRowStats) || ((uintptr_t)workspace & 15u) != 0)
-    return ESPO_EWORKSPACE;
+  size_t stats_off = 0, sorted_off = 0;
+  const size_t need = espo::advantages_workspace_layout(B, &stats_off, &sorted_off);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u) != 0) return ESPO_EWORKSPACE;
   return espo::launch_advantages(rewards, nullptr, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda, 1, td, adv,
-                                 nullptr, order, (espo::AdvRowStats*)workspace, (hipStream_t)stream);
+                                 nullptr, order, (espo::AdvRowStats*)((char*)workspace + stats_off),
+                                 (int32_t*)((char*)workspace + sorted_off), (uint32_t*)workspace, (hipStream_t)stream);
 }
 
 int espo_whiten_from_ws(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps, int32_t shift_mean,
@@ -312,10 +314,11 @@ int espo_whiten_from_ws(const float* adv, const int32_t* lengths, int64_t B, int
   if (!adv || !lengths || !out) return ESPO_EINVAL;
   if (T > 0x7fffffff || B > 0x7fffffff || B * ((T + 4095) / 4096) > 0x7fffffff) return ESPO_ERANGE;  // 2^31 items of 4096 tokens
   if (!aligned16(adv) || !aligned16(out) || ((uintptr_t)stats & 7u) != 0) return ESPO_EALIGN;
-  if (!workspace || workspace_bytes < (size_t)B * sizeof(espo::AdvRowStats) || ((uintptr_t)workspace & 15u) != 0)
+  size_t stats_off = 0;
+  if (!workspace || workspace_bytes < espo::advantages_workspace_layout(B, &stats_off, nullptr) || ((uintptr_t)workspace & 15u) != 0)
     return ESPO_EWORKSPACE;
   return espo::launch_whiten_rows(adv, lengths, B, T, eps, shift_mean != 0, unbiased != 0, out, stats,
-                                  (const espo::AdvRowStats*)workspace, (hipStream_t)stream);
+                                  (const espo::AdvRowStats*)((const char*)workspace + stats_off), (hipStream_t)stream);
 }
 
 int espo_advantages_terminal(const float* values, const int32_t* lengths, const uint8_t* stopped,
@@ -329,7 +332,7 @@ int espo_advantages_terminal(const float* values, const int32_t* lengths, const 
   if (T > 0x7fffffff || B > 0x3fffffff) return ESPO_ERANGE;  // with zero padding the grid has 2 B workgroups
   if (!aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns)) return ESPO_EALIGN;
   return espo::launch_advantages(nullptr, terminal_reward, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda,
-                                 zero_padding != 0, td, adv, returns, nullptr, nullptr, (hipStream_t)stream);
+                                 zero_padding != 0, td, adv, returns, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int espo_advantages_packed(const float* rewards, const float* terminal_reward, const float* values,
@@ -344,7 +347,7 @@ int espo_advantages_packed(const float* rewards, const float* terminal_reward, c
   if (!aligned16(rewards) || !aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns))
     return ESPO_EALIGN;
   return espo::launch_advantages(rewards, terminal_reward, values, nullptr, cu_seqlens, N, stopped, B, 0, r_fail, gamma,
-                                 lambda, 0, td, adv, returns, nullptr, nullptr, (hipStream_t)stream);
+                                 lambda, 0, td, adv, returns, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 }  // extern "C"

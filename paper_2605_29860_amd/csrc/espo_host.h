@@ -64,10 +64,16 @@ int launch_math_errors(float* out, hipStream_t stream);
 // cu != nullptr: trajectories stored back to back in arrays of N tokens (lengths, T, zero_padding unused).
 // order != nullptr (padded forms only): the scanning workgroups take their rows in that order.
 // row_stats != nullptr (padded forms only): every row's sums of its advantages are left there.
+// sorted, sync != nullptr, no order and more rows than the chip holds workgroups (padded forms only): the
+// launch's first workgroup sorts the later rows by length into `sorted`, and `sync` (words 0 and 32, zero between
+// launches) tells the others when it is done.
 int launch_advantages(const float* rewards, const float* terminal_reward, const float* values, const int32_t* lengths,
                       const int64_t* cu, int64_t N, const uint8_t* stopped, int64_t B, int64_t T, float r_fail, float gamma,
                       float lambda, int zero_padding, float* td, float* adv, float* returns, const int32_t* order,
-                      AdvRowStats* row_stats, hipStream_t stream);
+                      AdvRowStats* row_stats, int32_t* sorted, uint32_t* sync, hipStream_t stream);
+
+// Workspace of espo_advantages_ws: the two words of `sync` (in 256 bytes of their own), B AdvRowStats, the sorted later rows.
+size_t advantages_workspace_layout(int64_t B, size_t* stats_offset, size_t* sorted_offset);
 
 // The rows 0 .. B-1 ordered by clipped length, longest first (256 classes of length; one workgroup).
 int launch_length_order(const int32_t* lengths, int64_t B, int64_t T, int32_t* order, hipStream_t stream);

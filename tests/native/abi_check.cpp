@@ -105,6 +105,7 @@ int main(int argc, char** argv) {
   CK(hipMalloc((void**)&d_wh2, (size_t)B * T * 4));
   CK(hipMemset(d_wh2, 0, (size_t)B * T * 4));
   CK(hipMalloc(&d_aws, aws_bytes));
+  CK(hipMemset(d_aws, 0, aws_bytes));  // its first 256 bytes have to be zero before the first call
   hipStream_t stream;
   CK(hipStreamCreate(&stream));
 

@@ -33,10 +33,16 @@ def _batch(B, T, seed, lengths=None, stop_p=0.4, offset=0.0):
     return rewards.cuda(), values.cuda(), L.to(torch.int32).cuda(), stopped.cuda()
 
 
+FIRST = 512  # rows that are scanned in index order when the launch sorts the rest itself
+HEAD = 256   # bytes at the start of the workspace that must be zero before its first use
+
+
 def _workspace(B):
     n = espo.espo_advantages_ws_bytes(B)
-    assert n == 32 * B
-    return torch.full((n,), 0xA5, dtype=torch.uint8, device="cuda")   # contents before the call are irrelevant
+    assert n == HEAD + 32 * B + (4 * max(B - FIRST, 0) + 15) // 16 * 16
+    ws = torch.full((n,), 0xA5, dtype=torch.uint8, device="cuda")      # contents are irrelevant ...
+    ws[:HEAD] = 0                                                     # ... but for the first 256 bytes
+    return ws
 
 
 def _run(r, v, L, s, r_fail=-1.0, gamma=1.0, lam=0.95, eps=1e-8, shift_mean=True, unbiased=False, oracle_pass=True,
@@ -62,9 +68,15 @@ def _run(r, v, L, s, r_fail=-1.0, gamma=1.0, lam=0.95, eps=1e-8, shift_mean=True
     assert torch.equal(td0.view(torch.int32), td1.view(torch.int32)), "td differs from espo_advantages"
     assert torch.equal(adv0.view(torch.int32), adv1.view(torch.int32)), "adv differs from espo_advantages"
 
+    assert not bool(ws[:HEAD].any()), "the first 256 bytes of the workspace must be zero again after the call"
+    if not ordered and B > FIRST:  # the launch sorted rows FIRST.. itself: a permutation of them, longest first
+        srt = ws[HEAD + 32 * B:HEAD + 32 * B + 4 * (B - FIRST)].view(torch.int32).cpu().numpy()
+        assert sorted(srt.tolist()) == list(range(FIRST, B)), "the launch's own order is not a permutation of the later rows"
+        assert (np.diff((Lc[srt] * CLASSES) // (T + 1)) <= 0).all()
+
     # the rows' sums: n, and mean and squared deviations as numpy forms them in double from adv
-    rows = ws.view(torch.float64).cpu().numpy().reshape(B, 4)
-    n = ws.view(torch.int64).cpu().numpy().reshape(B, 4)[:, 3]
+    rows = ws[HEAD:HEAD + 32 * B].view(torch.float64).cpu().numpy().reshape(B, 4)
+    n = ws[HEAD:HEAD + 32 * B].view(torch.int64).cpu().numpy().reshape(B, 4)[:, 3]
     assert (n == Lc).all()
     a_h = adv1.cpu().numpy().astype(np.float64)
     for b in range(B):
@@ -124,12 +136,13 @@ def test_shapes_and_ragged_lengths(T):
     H.check_advantages(r, v, Lt, s, -1.0, 1.0, 0.95)
 
 
-@pytest.mark.parametrize("B", [1, 9, 255, 256, 257, 300, 1025, 2600])
+@pytest.mark.parametrize("B", [1, 9, 255, 256, 257, 300, 512, 513, 514, 1025, 2600])
 def test_row_counts_around_the_class_count(B):
     _say(f"[case] advantages_ws B={B}")
     T = 700
     r, v, L, s = _batch(B, T, seed=B)
     _run(r, v, L, s, oracle_pass=B <= 300)
+    _run(r, v, L, s, oracle_pass=False, ordered=False)
     # all rows equally long (one class), and no valid token at all
     r, v, L, s = _batch(B, T, seed=B + 1, lengths=[T // 3] * B)
     _run(r, v, L, s, oracle_pass=B <= 300)
@@ -168,7 +181,7 @@ def test_workspace_contract_and_same_bits_on_every_run():
     assert e.value.code == -3
     big = torch.empty(ws.numel() + 256, dtype=torch.uint8, device="cuda")
     with pytest.raises(espo.EspoError) as e:
-        espo.espo_advantages_ws(r, v, L, s, -1.0, 1.0, 0.95, td, adv, big[8:8 + ws.numel()])   # not 16-byte aligned
+        espo.espo_advantages_ws(r, v, L, s, -1.0, 1.0, 0.95, td, adv, big[8:8 + ws.numel()].zero_())   # not 16-byte aligned
     assert e.value.code == -3
     with pytest.raises(ValueError):
         espo.espo_advantages_ws(r, v, L, s, -1.0, 1.0, 0.95, td, adv, ws, torch.zeros(B - 1, dtype=torch.int32, device="cuda"))
@@ -193,7 +206,7 @@ def test_workspace_contract_and_same_bits_on_every_run():
     espo.espo_length_order(torch.zeros(0, dtype=torch.int32, device="cuda"), 5, torch.zeros(0, dtype=torch.int32, device="cuda"))
     outs = []
     for _ in range(3):
-        ws.fill_(0x5A)
+        ws[HEAD:].fill_(0x5A)
         espo.espo_advantages_ws(r, v, L, s, -1.0, 1.0, 0.95, td, adv, ws)
         o = torch.zeros_like(adv)
         espo.espo_whiten_from_ws(adv, L, o, ws)
@@ -213,6 +226,17 @@ def test_config5_full_size():
     r, v, L, s = W.advantage_batch(device="cuda", poison=True, seed=5)
     worst = _run(r, v, L, s)
     _say(f"  worst whitening error {worst:.2e}")
+    _run(r, v, L, s, ordered=False, oracle_pass=False)      # the launch sorts rows 512.. itself
+    # a workspace that served another batch size, and the same call twice: the first 256 bytes are all that has to be zero
+    ws = _workspace(2600)
+    td, adv = torch.empty_like(r), torch.empty_like(r)
+    td_ref, adv_ref = torch.empty_like(r), torch.empty_like(r)
+    espo.espo_advantages(r, v, L, s, -1.0, 1.0, 0.95, td_ref, adv_ref)
+    for _ in range(3):
+        td.fill_(FILL); adv.fill_(FILL)
+        espo.espo_advantages_ws(r, v, L, s, -1.0, 1.0, 0.95, td, adv, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(td, td_ref) and torch.equal(adv, adv_ref) and not bool(ws[:HEAD].any())
 
 
 def test_seeded_sweep():
@@ -221,12 +245,13 @@ def test_seeded_sweep():
     worst = 0.0
     for case in range(120):
         T = int(rng.choice([rng.integers(1, 64), rng.integers(64, 5000), rng.integers(5000, 20000)]))
-        B = int(rng.choice([rng.integers(1, 40), rng.integers(40, 600)])) if T < 5000 else int(rng.integers(1, 40))
+        B = int(rng.choice([rng.integers(1, 40), rng.integers(40, 600), rng.integers(500, 1400)])) if T < 5000 else int(rng.integers(1, 40))
         r, v, L, s = _batch(B, T, seed=21000 + case, stop_p=float(rng.random()))
         try:
             worst = max(worst, _run(r, v, L, s, r_fail=float(rng.choice([-1.0, -5.0, 0.0])), gamma=float(rng.choice([1.0, 0.99])),
                                     lam=float(rng.choice([0.95, 1.0, 0.0])), eps=float(rng.choice([1e-8, 0.0, 0.1])),
-                                    shift_mean=bool(rng.random() < 0.7), unbiased=bool(rng.random() < 0.5), oracle_pass=B * T < 4e6))
+                                    shift_mean=bool(rng.random() < 0.7), unbiased=bool(rng.random() < 0.5), oracle_pass=B * T < 4e6,
+                                    ordered=bool(rng.random() < 0.5)))
         except AssertionError as err:
             raise AssertionError(f"case {case}: B={B} T={T}: {err}")
     _say(f"  worst whitening error {worst:.2e}")

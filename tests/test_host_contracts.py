@@ -163,7 +163,7 @@ def test_binding_refuses_tensors_that_are_too_short(monkeypatch):
             fn(torch.zeros(B, T), mk(B, i32), mk(B, u8), 1.0, 1.0, 1.0, mk(8, u8), *extra)
     assert Recorder.calls == calls
     # the pair with a workspace between them, and the order by length
-    wsp = mk(32 * B, u8)
+    wsp = mk(256 + 32 * B, u8)
     b.espo_advantages_ws(**adv_args(), workspace=wsp, order=mk(B, i32))
     b.espo_whiten_from_ws(torch.zeros(B, T), mk(B, i32), torch.zeros(B, T), wsp)
     b.espo_length_order(mk(B, i32), T, mk(B, i32))
