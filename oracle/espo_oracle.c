@@ -41,9 +41,10 @@
  * set of top-p / top-k against its O(V^2) definition and a sorted cumulative sum, frequencies of
  * filtered draws against the renormalised distribution, GAE against the
  * explicit double sum and against telescoping identities.
- * Parity unpinned by the paper: the identity of the sampled token on a large
- * vocabulary (the paper fixes no random stream); it is pinned by the distribution
- * tests and the structural Philox tests only.
+ * The paper fixes no random stream, so the identity of the sampled token on a large
+ * vocabulary rests on this file's own definition of the stream: the generator is pinned
+ * to the published Philox4x32-10 by its authors' three known-answer inputs (zeros, ones,
+ * digits of pi), the construction of the variates by the distribution tests.
  *
  * Precision: scores, the softmax sum and the advantages are in double.  The scalar
  * chain g -> g~ -> z -> test is in fp32, one rounding per operation in the order

@@ -240,6 +240,18 @@ def test_philox_weyl_constants_are_the_published_irrationals():
     assert int((math.sqrt(3) - 1) * 2 ** 32) == 0xBB67AE85
 
 
+def test_philox_known_answers(oracle):
+    # the identity of the oracle's generator with the published Philox4x32-10: its authors' known-answer inputs
+    # (zeros, ones, digits of pi); a wrong multiplier, Weyl constant, round count or word order fails all three
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "philox4x32_10_known_answers.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) == 3
+    for r in rows:
+        w = [int(x, 16) for x in r]
+        got = oracle.philox4x32_10(np.array(w[:4], np.uint32), np.array(w[4:6], np.uint32)).tolist()
+        assert got == w[6:], ([hex(x) for x in got], r)
+        assert _philox_py(w[:4], w[4:6]) == w[6:]
+
+
 def test_philox_c_matches_integer_restatement(oracle):
     rng = np.random.default_rng(0)
     for _ in range(200):
