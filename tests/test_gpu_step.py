@@ -827,6 +827,9 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
     ws = torch.empty(espo.espo_whiten_workspace_bytes(B, T), dtype=torch.uint8, device="cuda")
     # the last step runs with every row split in three: the tickets in its workspace must be back at zero after every replay
     step_ws = torch.zeros(espo.espo_debug_step_workspace_bytes(B, 3), dtype=torch.uint8, device="cuda")
+    # the advantage pass that sorts its later rows itself (B > 512) and the whitening from its rows' sums: the
+    # two words at the head of their workspace must be back at zero after every replay, too
+    adv_ws = torch.zeros(espo.espo_advantages_ws_bytes(B), dtype=torch.uint8, device="cuda")
 
     def fresh():
         st = H.GpuState(B, z=z0)
@@ -834,6 +837,8 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
         st.td, st.adv = torch.empty(B, T, device="cuda"), torch.empty(B, T, device="cuda")
         st.wh = torch.full((B, T), 7.0, device="cuda")
         st.tdp, st.advp = torch.empty_like(vp), torch.empty_like(vp)
+        st.td2, st.adv2 = torch.empty(B, T, device="cuda"), torch.empty(B, T, device="cuda")
+        st.wh2 = torch.full((B, T), 7.0, device="cuda")
         return st
 
     def work(st):
@@ -843,11 +848,14 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
         espo.espo_advantages(r, v, L, stp, -1.0, 1.0, 0.95, st.td, st.adv)
         espo.espo_whiten(st.adv, L, st.wh, ws)
         espo.espo_advantages_packed(vp, cu, stp, -1.0, 1.0, 0.95, st.tdp, st.advp, terminal_reward=term)
+        espo.espo_advantages_ws(r, v, L, stp, -1.0, 1.0, 0.95, st.td2, st.adv2, adv_ws)
+        espo.espo_whiten_from_ws(st.adv2, L, st.wh2, adv_ws)
 
     eager = fresh()
     work(eager)
     torch.cuda.synchronize()
-    want = {k: getattr(eager, k).clone() for k in ("z", "alive", "stop_step", "regret", "logprob", "entropy", "td", "adv", "wh", "tdp", "advp")}
+    want = {k: getattr(eager, k).clone() for k in ("z", "alive", "stop_step", "regret", "logprob", "entropy", "td", "adv", "wh", "tdp", "advp", "td2", "adv2", "wh2")}
+    assert torch.equal(want["adv2"], want["adv"]) and torch.equal(want["td2"], want["td"])
     want_tok = [t.clone() for t in eager.out]
     assert int(want["alive"].sum()) < B                      # some rows stop inside the graph
 
@@ -865,12 +873,13 @@ def test_steps_captured_in_a_graph_replay_like_eager_launches():
         st.z.copy_(z0); st.alive.fill_(1); st.stop_step.fill_(-1)       # restore the state the graph starts from
         st.td.fill_(7.0); st.adv.fill_(7.0); st.regret.fill_(-7.0)
         st.wh.fill_(7.0); st.tdp.fill_(7.0); st.advp.fill_(7.0); ws.fill_(0x5a)
+        st.td2.fill_(7.0); st.adv2.fill_(7.0); st.wh2.fill_(7.0); adv_ws[256:].fill_(0x5a)
         for t in st.out:
             t.fill_(-7)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        assert not bool(step_ws.any()), replay
+        assert not bool(step_ws.any()) and not bool(adv_ws[:256].any()), replay
         for k, w in want.items():
             assert torch.equal(getattr(st, k), w), (replay, k)
         for a, b in zip(st.out, want_tok):
