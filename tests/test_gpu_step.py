@@ -216,19 +216,20 @@ def _rollout(B, steps, plant_fraction, onset_lo, onset_hi, seed, oracle_rows, va
     return plant, st.host(), live_curve, stats
 
 
-def _oracle_subset(plant, B, n_each=16):
+def _oracle_subset(plant, B, n_each=32):
     """`n_each` planted rows (spread over the onset steps) and as many that are not planted."""
     order = np.argsort(plant.onset, kind="stable")
     planted = plant.rows[order[np.linspace(0, len(order) - 1, n_each).astype(int)]].tolist()
-    others = [r for r in range(0, B, max(B // (2 * n_each), 1)) if r not in set(plant.rows.tolist())][:n_each]
+    free = np.setdiff1d(np.arange(B), plant.rows)
+    others = free[np.linspace(0, len(free) - 1, n_each).astype(int)].tolist()
     return sorted(set(planted) | set(others))
 
 
 def test_config3_sustained_rollout():
-    _say("[case] config 3 (B=512, 1024 steps, oracle on 32 rows at every step)")
+    _say("[case] config 3 (B=512, 1024 steps, oracle on 64 rows at every step)")
     B, steps, seed = 512, 1024, 3
     rows = _oracle_subset(W.RegretPlant.make(B, W.QWEN_VOCAB, 0.25, 8, 1000, seed), B)
-    assert len(rows) >= 32
+    assert len(rows) >= 64
     plant, end, curve, stats = _rollout(B, steps, 0.25, 8, 1000, seed, rows, 0.2, 1.0)
     stopped_planted = (end["stop_step"][plant.rows] >= 0).mean()
     _say(f"  config 3: live at end {curve[-1]}, planted rows stopped {stopped_planted:.2f}, stats {stats}")
@@ -240,12 +241,12 @@ def test_config3_sustained_rollout():
 
 
 def test_config4_heavy_termination():
-    _say("[case] config 4 (B=1024, 256 steps, oracle on 32 rows at every step)")
+    _say("[case] config 4 (B=1024, 256 steps, oracle on 64 rows at every step)")
     B, steps, seed = 1024, 256, 4
     # onsets in [14, 150]: the smoothed regret needs at least three steps to cross the lowest threshold and
     # crosses a typical one within a dozen, so the stops land in the stated window [16, 200]
     rows = _oracle_subset(W.RegretPlant.make(B, W.QWEN_VOCAB, 0.6, 14, 150, seed), B)
-    assert len(rows) >= 32
+    assert len(rows) >= 64
     plant, end, curve, stats = _rollout(B, steps, 0.6, 14, 150, seed, rows, 0.2, 1.0)
     ss = end["stop_step"][plant.rows]
     _say(f"  config 4: live at end {curve[-1]}, planted stop steps in [{ss[ss >= 0].min()}, {ss.max()}], stats {stats}")
