@@ -381,6 +381,21 @@ def main() -> int:
             adv_call(i)
             espo.espo_whiten(ad, adv_in[i % nbuf][2], wh_tmp, wh_ws)
     pair_us = {f: timed(args.adv_reps, lambda i, f=f: pair_call(i, f), warm=nbuf) for f in (False, True)}
+    # the terminal-reward form of the same pair (no reward array, no zero fill)
+    def awt_call(i):
+        r, v, L, s = adv_in[i % nbuf]
+        td, ad = adv_out[i % nbuf]
+        espo.espo_advantages_terminal_ws(v, L, s, adv_term[i % nbuf], -1.0, 1.0, 0.95, td, ad, aw_ws[i % nbuf], zero_padding=False)
+    awt_us = timed(args.adv_reps, awt_call, warm=nbuf)
+    def pair_t_call(i, fused):
+        td, ad = adv_out[i % nbuf]
+        if fused:
+            awt_call(i)
+            espo.espo_whiten_from_ws(ad, adv_in[i % nbuf][2], wh_tmp, aw_ws[i % nbuf])
+        else:
+            advt_call(i)
+            espo.espo_whiten(ad, adv_in[i % nbuf][2], wh_tmp, wh_ws)
+    pair_t_us = {f: timed(args.adv_reps, lambda i, f=f: pair_t_call(i, f), warm=nbuf) for f in (False, True)}
     del wh_tmp
 
     # ------------------------------------------------------------------ batch-boundary statistics (B=512, T=8192)
@@ -566,7 +581,11 @@ def main() -> int:
                            "frac": float(np.mean(valid * 8 + B_ADV * 36)) / whw_us / 1e3 / HBM_PEAK_GBS},
         "advantages_then_whiten": {"workload": "both calls back to back on the same batches",
                                    "espo_advantages_and_espo_whiten_us": pair_us[False],
-                                   "espo_advantages_ws_and_espo_whiten_from_ws_us": pair_us[True]},
+                                   "espo_advantages_ws_and_espo_whiten_from_ws_us": pair_us[True],
+                                   "espo_advantages_terminal_and_espo_whiten_us": pair_t_us[False],
+                                   "espo_advantages_terminal_ws_and_espo_whiten_from_ws_us": pair_t_us[True]},
+        "advantages_terminal_ws": {"workload": "the terminal-reward form without zero fill through espo_advantages_terminal_ws",
+                                   "us_per_call": awt_us, "frac": advt_bytes / awt_us / 1e3 / HBM_PEAK_GBS},
         "batch_stats": {"workload": "B=512, T=8192 fp32 regrets, lengths U[64,8192], 25% stopped, 8 rotated sets",
                         "us_per_call": bs_us, "algorithmic_bytes_per_call": bs_bytes,
                         "gbs": bs_bytes / bs_us / 1e3, "launches_per_call": 2,

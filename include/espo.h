@@ -405,8 +405,8 @@ int espo_whiten(const float* adv, const int32_t* lengths, int64_t B, int64_t T, 
 size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
 
 /*
- * espo_advantages_ws, espo_whiten_from_ws, espo_length_order -- espo_advantages followed by
- * espo_whiten with less work between them (Section 3, Eq. gae; Section 4.4, Eq. failure_reward;
+ * espo_advantages_ws, espo_advantages_terminal_ws, espo_whiten_from_ws, espo_length_order --
+ * espo_advantages (or espo_advantages_terminal) followed by espo_whiten with less work between them (Section 3, Eq. gae; Section 4.4, Eq. failure_reward;
  * the whitening as described at espo_whiten).
  *
  * espo_advantages_ws computes exactly what espo_advantages computes (same td and adv, bit for
@@ -424,7 +424,7 @@ size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
  * launch, about as long as what the order then saves if it runs right before the pass; a caller
  * that knows the lengths earlier (they are final when the rollout ends) runs it then.
  *
- * espo_whiten_from_ws is espo_whiten for an `adv` that espo_advantages_ws has just written,
+ * espo_whiten_from_ws is espo_whiten for an `adv` that one of the two has just written,
  * with the same B, T, lengths and workspace: mean and variance are merged from the rows' sums
  * (pairwise, in a fixed order, in double) instead of by a first pass over adv, so only the
  * rewrite remains.  The two ways of summing differ by rounding: mean and variance agree with
@@ -449,6 +449,13 @@ int espo_advantages_ws(const float* rewards, const float* values,
                        int64_t B, int64_t T, float r_fail, float gamma, float lambda,
                        float* td, float* adv, const int32_t* order,
                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* espo_advantages_terminal with the same two additions (same td, adv and returns, bit for bit); arguments as there and as above. */
+int espo_advantages_terminal_ws(const float* values, const int32_t* lengths, const uint8_t* stopped,
+                                const float* terminal_reward, int64_t B, int64_t T,
+                                float r_fail, float gamma, float lambda, int32_t zero_padding,
+                                float* td, float* adv, float* returns, const int32_t* order,
+                                void* workspace, size_t workspace_bytes, void* stream);
 
 int espo_whiten_from_ws(const float* adv, const int32_t* lengths, int64_t B, int64_t T, float eps,
                         int32_t shift_mean, int32_t unbiased, float* out, double* stats,

@@ -102,6 +102,8 @@ def load_library():
         lib.espo_advantages.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp]
         lib.espo_advantages_ws.restype = C.c_int
         lib.espo_advantages_ws.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, vp, vp, vp, vp, sz, vp]
+        lib.espo_advantages_terminal_ws.restype = C.c_int
+        lib.espo_advantages_terminal_ws.argtypes = [vp, vp, vp, vp, i64, i64, f32, f32, f32, i32, vp, vp, vp, vp, vp, sz, vp]
         lib.espo_length_order.restype = C.c_int
         lib.espo_length_order.argtypes = [vp, i64, i64, vp, vp]
         lib.espo_advantages_ws_bytes.restype = sz
@@ -431,4 +433,27 @@ def espo_advantages_terminal(values: torch.Tensor, lengths: torch.Tensor, stoppe
                                       float(r_fail), float(gamma), float(lam), int(bool(zero_padding)),
                                       _dev(td, torch.float32, "td", shape=(B, T)), _dev(adv, torch.float32, "adv", shape=(B, T)),
                                       _dev(returns, torch.float32, "returns", shape=(B, T)), _stream(stream))
+    _check(rc)
+
+
+def espo_advantages_terminal_ws(values: torch.Tensor, lengths: torch.Tensor, stopped: torch.Tensor,
+                                terminal_reward: torch.Tensor, r_fail: float, gamma: float, lam: float,
+                                td: torch.Tensor, adv: torch.Tensor, workspace: torch.Tensor,
+                                returns: torch.Tensor | None = None, zero_padding: bool = True,
+                                order: torch.Tensor | None = None, stream=None) -> None:
+    """espo_advantages_terminal with the later rows taken longest first and the rows' sums left in
+    `workspace`; see `espo_advantages_terminal_ws` in include/espo.h."""
+    lib = load_library()
+    if values.dim() != 2:
+        raise TypeError("values: need [B, T]")
+    B, T = values.shape
+    rc = lib.espo_advantages_terminal_ws(_dev(values, torch.float32, "values"), _dev(lengths, torch.int32, "lengths", numel=B),
+                                         _dev(stopped, torch.uint8, "stopped", numel=B),
+                                         _dev(terminal_reward, torch.float32, "terminal_reward", numel=B), B, T,
+                                         float(r_fail), float(gamma), float(lam), int(bool(zero_padding)),
+                                         _dev(td, torch.float32, "td", shape=(B, T)), _dev(adv, torch.float32, "adv", shape=(B, T)),
+                                         _dev(returns, torch.float32, "returns", shape=(B, T)),
+                                         _dev(order, torch.int32, "order", numel=B),
+                                         _dev(workspace, torch.uint8, "workspace"), workspace.numel() if workspace is not None else 0,
+                                         _stream(stream))
     _check(rc)

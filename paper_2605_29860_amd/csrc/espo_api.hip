@@ -335,6 +335,24 @@ int espo_advantages_terminal(const float* values, const int32_t* lengths, const 
                                  zero_padding != 0, td, adv, returns, nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
+int espo_advantages_terminal_ws(const float* values, const int32_t* lengths, const uint8_t* stopped,
+                                const float* terminal_reward, int64_t B, int64_t T, float r_fail, float gamma,
+                                float lambda, int32_t zero_padding, float* td, float* adv, float* returns,
+                                const int32_t* order, void* workspace, size_t workspace_bytes, void* stream) {
+  if (B < 0 || T < 0) return ESPO_EINVAL;
+  if (!isfinite(gamma) || !isfinite(lambda) || isnan(r_fail)) return ESPO_EINVAL;
+  if (B == 0 || T == 0) return ESPO_OK;
+  if (!values || !lengths || !stopped || !terminal_reward || !td || !adv) return ESPO_EINVAL;
+  if (T > 0x7fffffff || B > 0x3fffffff) return ESPO_ERANGE;  // with zero padding the grid has 2 B + 1 workgroups
+  if (!aligned16(values) || !aligned16(td) || !aligned16(adv) || !aligned16(returns)) return ESPO_EALIGN;
+  size_t stats_off = 0, sorted_off = 0;
+  const size_t need = espo::advantages_workspace_layout(B, &stats_off, &sorted_off);
+  if (!workspace || workspace_bytes < need || ((uintptr_t)workspace & 15u) != 0) return ESPO_EWORKSPACE;
+  return espo::launch_advantages(nullptr, terminal_reward, values, lengths, nullptr, 0, stopped, B, T, r_fail, gamma, lambda,
+                                 zero_padding != 0, td, adv, returns, order, (espo::AdvRowStats*)((char*)workspace + stats_off),
+                                 (int32_t*)((char*)workspace + sorted_off), (uint32_t*)workspace, (hipStream_t)stream);
+}
+
 int espo_advantages_packed(const float* rewards, const float* terminal_reward, const float* values,
                            const int64_t* cu_seqlens, const uint8_t* stopped, int64_t B, int64_t N, float r_fail,
                            float gamma, float lambda, float* td, float* adv, float* returns, void* stream) {

@@ -255,3 +255,73 @@ def test_seeded_sweep():
         except AssertionError as err:
             raise AssertionError(f"case {case}: B={B} T={T}: {err}")
     _say(f"  worst whitening error {worst:.2e}")
+
+
+# --------------------------------------------------------------------------- the terminal-reward form
+def _run_terminal(v, L, s, term, zero_padding, want_returns, ordered, gamma=1.0, lam=0.95):
+    """espo_advantages_terminal_ws against espo_advantages_terminal (bits, wherever that call defines the result),
+    then the whitening from the rows' sums against espo_whiten on the same advantages."""
+    B, T = v.shape
+    Lc = np.clip(L.cpu().numpy().astype(np.int64), 0, T)
+    mask = torch.arange(T, device="cuda")[None, :] < L.clamp(0, T)[:, None]
+    outs = []
+    ws = _workspace(B)
+    for k in range(2):
+        td, adv = torch.full_like(v, FILL), torch.full_like(v, FILL)
+        ret = torch.full_like(v, FILL) if want_returns else None
+        if k == 0:
+            espo.espo_advantages_terminal(v, L, s, term, -1.0, gamma, lam, td, adv, returns=ret, zero_padding=zero_padding)
+        else:
+            order = None
+            if ordered:
+                order = torch.empty(B, dtype=torch.int32, device="cuda")
+                espo.espo_length_order(L, T, order)
+            espo.espo_advantages_terminal_ws(v, L, s, term, -1.0, gamma, lam, td, adv, ws, returns=ret,
+                                             zero_padding=zero_padding, order=order)
+        torch.cuda.synchronize()
+        outs.append((td, adv, ret))
+    for a, b in zip(outs[0], outs[1]):
+        if a is None:
+            continue
+        assert torch.equal(a[mask].view(torch.int32), b[mask].view(torch.int32))
+        if zero_padding:
+            assert torch.equal(a, b)
+        else:   # beyond the lengths every position is either untouched or zero
+            pad = b[~mask]
+            assert bool(((pad == FILL) | (pad == 0)).all())
+    assert not bool(ws[:HEAD].any())
+    n = ws[HEAD:HEAD + 32 * B].view(torch.int64).cpu().numpy().reshape(B, 4)[:, 3]
+    assert (n == Lc).all()
+    adv = outs[1][1]
+    out1, out0 = torch.full_like(v, FILL), torch.full_like(v, FILL)
+    espo.espo_whiten_from_ws(adv, L, out1, ws)
+    espo.espo_whiten(adv, L, out0, torch.empty(espo.espo_whiten_workspace_bytes(B, T), dtype=torch.uint8, device="cuda"))
+    torch.cuda.synchronize()
+    g1, g0 = out1[mask].cpu().numpy(), out0[mask].cpu().numpy()
+    ulp = np.spacing(np.abs(g0)).astype(np.float64)
+    assert (np.abs(g1.astype(np.float64) - g0.astype(np.float64)) <= ulp + 1e-11).all()
+    assert bool((out1[~mask] == FILL).all())
+
+
+@pytest.mark.parametrize("B,T", [(9, 700), (300, 1023), (513, 64), (1100, 2049)])
+def test_terminal_form(B, T):
+    _say(f"[case] advantages_terminal_ws B={B} T={T}")
+    g = torch.Generator().manual_seed(B + T)
+    values = torch.rand(B, T, generator=g) * 2 - 1
+    L = torch.randint(0, T + 1, (B,), generator=g)
+    values[torch.arange(T)[None, :] >= L[:, None]] = float("nan")
+    stopped = (torch.rand(B, generator=g) < 0.4).to(torch.uint8)
+    term = torch.rand(B, generator=g)
+    v, Lt, s, tr = values.cuda(), L.to(torch.int32).cuda(), stopped.cuda(), term.cuda()
+    for zero_padding, want_returns, ordered in ((True, True, False), (False, False, False), (False, True, True), (True, False, True)):
+        _run_terminal(v, Lt, s, tr, zero_padding, want_returns, ordered)
+    # and against the oracle once per shape (the plain call is what the other tests hold against it)
+    H.check_advantages_terminal(v, Lt, s, tr, -1.0, 1.0, 0.95)
+
+
+def test_terminal_form_config5_full_size():
+    _say("[case] advantages_terminal_ws on config 5 (B=1024, T=16384)")
+    r, v, L, s = W.advantage_batch(device="cuda", poison=True, seed=5)
+    term = torch.rand(r.shape[0], device="cuda")
+    _run_terminal(v, L, s, term, False, True, False)
+    _run_terminal(v, L, s, term, True, False, False)
