@@ -180,3 +180,11 @@ def test_binding_refuses_tensors_that_are_too_short(monkeypatch):
     with pytest.raises(TypeError):
         b.espo_whiten_from_ws(torch.zeros(B, T), mk(B, i32), torch.zeros(B, T + 1), wsp)
     assert Recorder.calls == calls
+    b.espo_advantages_terminal_ws(**term_args(), workspace=wsp, order=mk(B, i32))
+    calls = Recorder.calls
+    for name, bad in (("lengths", B - 1), ("stopped", 1), ("terminal_reward", B - 1), ("td", (B, T - 4)), ("returns", (B + 1, T))):
+        with pytest.raises(ValueError, match=name):
+            b.espo_advantages_terminal_ws(**term_args(**{name: bad}), workspace=wsp)
+    with pytest.raises(ValueError, match="order"):
+        b.espo_advantages_terminal_ws(**term_args(), workspace=wsp, order=mk(B - 2, i32))
+    assert Recorder.calls == calls
