@@ -431,7 +431,8 @@ size_t espo_whiten_workspace_bytes(int64_t B, int64_t T);
  * espo_whiten's to about 1e-14 relative, `out` to the last bit or one unit of it.
  *
  * Arguments as for espo_advantages and espo_whiten, and
- *   order      device, [B] int32, every row once, or NULL (rows in index order).  An entry
+ *   order      device, [B] int32, every row once, or NULL (the launch then sorts its later rows
+ *              itself, as described above).  An entry
  *              outside [0, B) is skipped; a row that is missing from the order is not computed,
  *              one that is named twice is computed twice.
  *   workspace  device, at least espo_advantages_ws_bytes(B) bytes (256, plus 32 per row, plus 4

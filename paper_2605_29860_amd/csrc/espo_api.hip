@@ -117,7 +117,7 @@ int step_checked(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_
 #pragma GCC visibility push(default)
 extern "C" {
 
-int espo_version(void) { return 300; }
+int espo_version(void) { return 310; }
 
 int espo_debug_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride, float temperature,
                     uint64_t seed, int32_t step, const float* values, const espo_params* params, float* z, uint8_t* alive,
