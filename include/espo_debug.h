@@ -19,7 +19,8 @@ extern "C" {
  *                       margin.  A scale >= 1 multiplies that margin (1 = what espo_step uses; a
  *                       huge value sends every row through the double-precision search).  The
  *                       sampled token does not depend on it.  ESPO_EINVAL below 1 or for NaN.
- *   waves               wavefronts per workgroup: 4, 8 or 16, or 0 for the library's choice (16).
+ *   waves               wavefronts per workgroup: 4, 8 or 16, or 0 for the library's choice (16; 8 for a
+ *                       filtered draw).
  *   chunks              workgroups a row is split over, or 0 for the library's choice (1).  With
  *                       more than one, every workgroup streams a run of 512-index tiles of its row,
  *                       finds the exact winner of that run and leaves it in the workspace with the
@@ -31,7 +32,7 @@ extern "C" {
  *                       otherwise), which comes back zero; the value is lowered to the number of
  *                       tiles of a row and to 64 if it exceeds them.  espo_step itself never splits
  *                       rows: on an MI355X every split measured slower than one workgroup per row.
- * A filtered draw (top_p / top_k) has one layout: waves 0 or 16, chunks 0 or 1.
+ * A filtered draw (top_p / top_k) has one layout: waves 0 or 8, chunks 0 or 1.
  * Everything else is espo_step.
  */
 int espo_debug_step(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_t row_stride,

@@ -104,7 +104,7 @@ int step_checked(const void* logits, espo_dtype dt, int64_t B, int64_t V, int64_
   const size_t esize = dt == ESPO_BF16 ? 2 : 4;
   if (!aligned16(logits) || ((size_t)row_stride * esize) % 16 != 0) return ESPO_EALIGN;
   const bool filter = filtered(params);
-  if (filter && ((waves != 0 && waves != 16) || chunks > 1)) return ESPO_EINVAL;  // a filtered draw has one layout
+  if (filter && ((waves != 0 && waves != 8) || chunks > 1)) return ESPO_EINVAL;  // a filtered draw has one layout
   const espo::StepPlan plan = espo::plan_step(dt, B, V, filter, waves, chunks);
   if (plan.lds > espo::kMaxStepLds) return ESPO_ERANGE;
   if (plan.workspace > 0 && (!workspace || workspace_bytes < plan.workspace || !aligned16(workspace))) return ESPO_EWORKSPACE;

@@ -782,9 +782,9 @@ __device__ __forceinline__ bool row_is_done(const uint8_t* alive, int row) {
 }
 
 template <int DT, bool Entropy, bool Filter, bool Sum, int W>
-__global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
+__global__ __launch_bounds__(W * kWave, Filter ? 4 : 8) void espo_step_kernel(StepArgs a) {
   static_assert(Sum || (!Entropy && !Filter), "entropy and filtered draws need the softmax sum");
-  static_assert(!Filter || W == 16, "a filtered draw looks at the whole row: one workgroup of 16 waves per row");
+  static_assert(!Filter || W == 8, "a filtered draw looks at the whole row: one workgroup of 8 waves per row");
   constexpr int kStepWaves = W, kStepThreads = W * kWave, kSlots = W * kGroups;
   extern __shared__ __align__(16) unsigned char smem_raw[];
   const int tid = threadIdx.x;
@@ -867,6 +867,7 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
   float sum = 0.0f;
   float sumw = 0.0f;         // entropy output: sum_v 2^t_v t_v with t_v = x_v k2 + nrk (see below)
   float mx = kNegInf;        // largest logit this lane group has seen
+  float mx_odd = kNegInf;    // filtered draws keep it apart for the odd tiles: twice as many values to choose a floor from
   float top_ub = kNegInf;    // largest block bound this lane group has seen, and its block
   int top_q = -1;
   char* const my_raw = (char*)sh.top_raw + ((size_t)(wave * kGroups + grp) * kDrawBlock + (lane & 7) * 8) * elem_bytes<DT>();
@@ -937,7 +938,8 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
     const float ub = fmaf(bm, a.inv_tau, mu[0]);
     mu[1] = ub;  // the 8 lanes of the group store the same value
     if constexpr (Filter) bmx_lane[(size_t)i * (kStepWaves * kGroups)] = bm;
-    mx = fmaxf(mx, bm);
+    if (Filter && (i & 1)) mx_odd = fmaxf(mx_odd, bm);
+    else mx = fmaxf(mx, bm);
     if (ub > top_ub) {  // keep the data of the block with the group's largest bound
       top_ub = ub;
       top_q = t * kGroups + grp;
@@ -964,6 +966,8 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
       if (i0 + d < my_tiles) iteration(std::false_type{}, d, i0 + d);  // wave-uniform
   }
   // The wave's largest logit, and the block with its largest bound (lowest block among equals).
+  const float mx_even = mx;
+  if constexpr (Filter) mx = fmaxf(mx, mx_odd);
   const float mw = wave_max(mx);
   const float ubw = wave_max(top_ub);
   const int q_own = (int)wave_min_u32(top_q >= 0 && top_ub == ubw ? (uint32_t)top_q : 0xffffffffu);  // -1 if none
@@ -1032,30 +1036,38 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
   if constexpr (Filter) {
     // Filtered draw (top-p as in the evaluation set-up of Section 5, or top-k).  The kept set is
     // {v : the mass (the number) of strictly larger logits is below p (k)}, an upper set in the
-    // logit, so the filtered draw is the argmax of y + G over it: the unfiltered winner if it is
-    // kept, else the winner of one more search above the kept set's edge.  What is needed is the
-    // mass (number) of the logits above a given floor, and those logits themselves when they are
-    // few.  A table of the blocks' largest logits, filled while streaming, names the blocks that
-    // hold any; a handful of blocks is read again directly, more of them by one more pass over
-    // the row.  First a floor that leaves about 64 blocks above it is tried: on rows like a
-    // language model's the kept set lies above it, its smallest logit is then read off the
-    // collected logits (the smallest whose strictly larger ones hold less than p, number fewer
-    // than k) and one search above that edge gives the token; the unfiltered winner is not
-    // needed then and is not searched for.  Otherwise (flat rows) the unfiltered winner is found
-    // and tested, and while it is not kept the search is repeated above it; that floor rises
-    // strictly, so the loop ends.  Sums within 1e-5 of p times the softmax sum are not trusted in fp32: the
-    // candidate path is then left for the loop, whose test repeats them in double over the
-    // whole row, in the oracle's arithmetic.
+    // logit, so the filtered draw is the argmax of y + G over it.  What is needed is the mass
+    // (number) of the logits above a given floor, and those logits themselves when they are few.
+    // A table of the blocks' largest logits, filled while streaming, names the blocks that hold
+    // any; up to two thirds of the row's blocks are read again block by block, more of them by one
+    // more pass over the row.  First a floor that leaves about 64 blocks above it is tried: on rows
+    // like a language model's the kept set lies above it.  If it does not (a flat row, some hundred
+    // kept logits), a floor that leaves several hundred blocks is tried.  The smallest kept logit is
+    // then read off the collected logits (the smallest whose strictly larger ones hold less than p,
+    // number fewer than k) and one search above that edge gives the token; the unfiltered winner is
+    // not needed then and is not searched for.  Sums within 1e-5 of p times the softmax sum are not
+    // trusted in fp32: the search then runs above the smallest logit that may be kept, and its winner
+    // stands if it is kept for sure.  Otherwise (still flatter rows, or a winner in doubt) the winner
+    // is tested by measuring the mass above it, in double over the whole row and in the oracle's
+    // arithmetic where fp32 cannot tell, and while it is not kept the search is repeated above it;
+    // that floor rises strictly, so the loop ends.
+    // A workgroup of 8 waves with 128 registers per lane runs this instantiation, two of them on a
+    // compute unit: with 64 registers the stages below spill, and every reload is a trip to a memory
+    // system whose queues are full of the other rows' streaming (measured: 53 us per launch with 16
+    // waves and 64 registers, 46 us this way, B = 512, V = 152064, top-p 0.7 at temperature 0.6).
     const auto nothing = [] {};
     const bool by_count = a.top_k > 0;
     const float nrk_row = -m * a.k2;
     const float total = wave_sum(lane < kStepWaves ? sh.sum[lane] : 0.0f);  // S, as the last step forms it
     const float want = a.top_p * total;
-    float* const cand_e = (float*)sh.cand_v;  // the candidates' 2^t, beside their logits in cand_x
+    // The collected logits use both candidate areas as one array; their 2^t are formed again where needed.
+    constexpr int kKeptCap = 2 * kCandCap;
+    float* const kept_x = (float*)sh.cand_v;
+    static_assert(kCandCap % 4 == 0, "cand_x follows cand_v without a gap");
     float mass = 0.0f, count = 0.0f;
     int ncand = 0;
 
-    // mass and number of the logits above floor_x; the logits themselves in cand_x / cand_e if they fit
+    // mass and number of the logits above floor_x; the logits themselves in kept_x if they fit
     auto measure = [&](float floor_x) {
       __syncthreads();  // whatever used the scratch before is over in every wave
       if (tid == 0) {
@@ -1068,8 +1080,11 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
       __syncthreads();
       const int nabove = *sh.nsurv;
       float acc_m = 0.0f, acc_n = 0.0f;
-      constexpr int kVisit = 8;
-      if (nabove <= 16 * kStepWaves) {  // the usual case: one block per wave visit, one index per lane, eight loads in flight
+      constexpr int kVisit = 8, kLoads = 4, kGroupRead = 1536;  // beyond that many blocks (two thirds of this row's) the whole row is streamed
+      if (nabove <= 16 * kStepWaves) {
+        // The usual case: one block per wave visit, one index per lane, eight loads in flight.  Most of
+        // these blocks are their lane group's best, which phase 1 kept in LDS: no trip to memory, whose
+        // queues are full of the other rows' streaming.
 #pragma unroll 1
         for (int base = wave; base < nabove; base += kVisit * kStepWaves) {
           float xs[kVisit];
@@ -1088,13 +1103,57 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
 #pragma unroll
           for (int u = 0; u < kVisit; ++u) {
             if (lane < ns[u] && xs[u] > floor_x) {
-              const float e = __builtin_amdgcn_exp2f(fmaf(xs[u], a.k2, nrk_row));
-              acc_m += e;
+              acc_m += __builtin_amdgcn_exp2f(fmaf(xs[u], a.k2, nrk_row));
               acc_n += 1.0f;  // counts stay exact in fp32: V < 2^24
               const int c = atomicAdd(sh.ncand, 1);
-              if (c < kCandCap) {
-                sh.cand_x[c] = xs[u];
-                cand_e[c] = e;
+              if (c < kKeptCap) kept_x[c] = xs[u];
+            }
+          }
+        }
+      } else if (nabove <= kGroupRead) {
+        // The listed blocks only, laid out as in phase 1: a lane group of 8 lanes per block, 16 bytes
+        // per lane, so one load of a wave covers 8 blocks and the workgroup 256 per trip to memory (eight
+        // loads in flight instead of four: 8 us slower on every row, with spills).
+        const uint32_t sub = (uint32_t)(lane & 7) * 8u;
+#pragma unroll 1
+        for (int base = wave * kGroups; base < nabove; base += kLoads * kStepWaves * kGroups) {
+          int qs[kLoads];
+          Raw<DT> raw[kLoads];
+#pragma unroll
+          for (int j = 0; j < kLoads; ++j) {
+            const int k = base + j * kStepWaves * kGroups + grp;
+            qs[j] = k < nabove ? sh.surv(k) : -1;
+            // a group without a block reads block 0 and drops it; a ragged last block is masked below
+            const uint32_t e0 = (uint32_t)(qs[j] < 0 ? 0 : qs[j]) * kDrawBlock + sub;
+            raw[j] = load_raw<DT>(rowp, e0 < last_group ? e0 : last_group, (uint32_t)a.V);
+          }
+          uint64_t mine = 0;  // which of this lane's elements are above the floor
+#pragma unroll
+          for (int j = 0; j < kLoads; ++j) {
+            float x[8];
+            unpack<DT>(raw[j], x);
+            const int32_t v0 = qs[j] * kDrawBlock + (int32_t)sub;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              const bool above = qs[j] >= 0 && v0 + u < a.V && x[u] > floor_x;
+              const float e = __builtin_amdgcn_exp2f(fmaf(x[u], a.k2, nrk_row));
+              acc_m += above ? e : 0.0f;
+              acc_n += above ? 1.0f : 0.0f;  // counts stay exact in fp32: V < 2^24
+              mine |= above ? 1ull << (j * 8 + u) : 0ull;
+            }
+          }
+          // one counter update per lane that has any; its logits take consecutive entries
+          int c = mine != 0 ? atomicAdd(sh.ncand, (int)__builtin_popcountll(mine)) : 0;
+#pragma unroll
+          for (int j = 0; j < kLoads; ++j) {
+            if (((mine >> (j * 8)) & 0xffull) == 0) continue;
+            float x[8];
+            unpack<DT>(raw[j], x);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+              if ((mine >> (j * 8 + u)) & 1ull) {
+                if (c < kKeptCap) kept_x[c] = x[u];
+                ++c;
               }
             }
           }
@@ -1113,7 +1172,7 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
               float x[8];
               unpack<DT>(raw[d], x);
               const int32_t e0 = ((i0 + d) * kStepWaves + wave) * kTile + (int32_t)lane_off;
-              const bool room = *sh.ncand <= kCandCap;  // once the buffer has overflowed nothing more is kept
+              const bool room = *sh.ncand <= kKeptCap;  // once the buffer has overflowed nothing more is kept
 #pragma unroll
               for (int u = 0; u < 8; ++u) {
                 const bool above = e0 + u < a.V && x[u] > floor_x;
@@ -1126,10 +1185,7 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
                   if (lane == (int)__builtin_ctzll(who)) base = atomicAdd(sh.ncand, (int)__builtin_popcountll(who));
                   base = __builtin_amdgcn_readlane(base, (int)__builtin_ctzll(who));
                   const int c = base + (int)__builtin_popcountll(who & ((1ull << lane) - 1ull));
-                  if (above && c < kCandCap) {
-                    sh.cand_x[c] = x[u];
-                    cand_e[c] = e;
-                  }
+                  if (above && c < kKeptCap) kept_x[c] = x[u];
                 }
               }
             }
@@ -1152,107 +1208,216 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
       ncand = *sh.ncand;
     };
 
-    // The smallest kept logit among the collected ones (all logits above some floor below the kept
-    // set): the smallest candidate whose strictly larger candidates hold less than p (number fewer
-    // than k).  False if a sum is too close to p to tell in fp32.
-    auto kept_edge = [&](float& edge_all) {
-      float mine_x = __builtin_huge_valf();  // this thread's candidate if it is kept, else +inf
-      bool unsure = false;
-      for (int c = tid; c < ncand; c += kStepThreads) {  // at most one per thread
-        const float xc = sh.cand_x[c];
-        float m_above = 0.0f, n_above = 0.0f;
-        // every thread reads the same entries (LDS broadcasts), four at a time and several
-        // reads in flight: one entry per dependent read would cost a microsecond per ten candidates
-        const int whole = ncand & ~3;
+    // The smallest kept logit among the collected ones (all logits above floor_x, which lies below the
+    // kept set): the smallest candidate whose strictly larger candidates hold less than p (number
+    // fewer than k).  False if a sum is too close to p to tell in fp32, or if the method at hand
+    // does not fit.  A few hundred candidates are compared all with all.  More of them are first
+    // binned by their distance from the row's largest logit (256 bins of equal width down to the
+    // floor): the bins' weights, summed from the top, name the one bin in which
+    // the edge lies, and only that bin's candidates are compared with each other.  Weights are
+    // integers there (2^t in units of 2^-31 of the measured mass, or 1 for top-k), so the sums do
+    // not depend on the order in which the candidates arrive.
+    constexpr int kPairwise = 256, kBins = 256, kMembers = 256;
+    auto kept_edge = [&](float floor_x, float& edge_sure, float& edge_maybe) {
+      // this thread's candidate if it is kept for sure / if it may be kept, else +inf
+      float mine_sure = __builtin_huge_valf(), mine_maybe = __builtin_huge_valf();
+      const float slack = by_count ? 0.0f : 1e-5f * total;  // what an fp32 sum may be off by
+      const bool binned = ncand > kPairwise && nslots >= kBins + 2 * kMembers && (by_count || mass > 0.0f) && floor_x > kNegInf;
+      if (!binned) {
+        if (ncand > kCandCap) return false;
+        float* const cand_e = kept_x + kCandCap;  // the candidates' 2^t, in the half that their logits leave free
+        for (int c = tid; c < ncand; c += kStepThreads) cand_e[c] = __builtin_amdgcn_exp2f(fmaf(kept_x[c], a.k2, nrk_row));
+        __syncthreads();
+        for (int c = tid; c < ncand; c += kStepThreads) {  // at most one per thread
+          const float xc = kept_x[c];
+          float m_above = 0.0f, n_above = 0.0f;
+          // every thread reads the same entries (LDS broadcasts), four at a time and several
+          // reads in flight: one entry per dependent read would cost a microsecond per ten candidates
+          const int whole = ncand & ~3;
 #pragma unroll 4
-        for (int o = 0; o < whole; o += 4) {
-          const f32x4 xo = *(const f32x4*)(sh.cand_x + o), eo = *(const f32x4*)(cand_e + o);
+          for (int o = 0; o < whole; o += 4) {
+            const f32x4 xo = *(const f32x4*)(kept_x + o), eo = *(const f32x4*)(cand_e + o);
 #pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const bool larger = xo[u] > xc;
-            m_above += larger ? eo[u] : 0.0f;
+            for (int u = 0; u < 4; ++u) {
+              const bool larger = xo[u] > xc;
+              m_above += larger ? eo[u] : 0.0f;
+              n_above += larger ? 1.0f : 0.0f;
+            }
+          }
+          for (int o = whole; o < ncand; ++o) {
+            const bool larger = kept_x[o] > xc;
+            m_above += larger ? cand_e[o] : 0.0f;
             n_above += larger ? 1.0f : 0.0f;
           }
+          if (by_count ? n_above < (float)a.top_k : m_above < want - slack) mine_sure = xc;
+          if (by_count ? n_above < (float)a.top_k : m_above < want + slack) mine_maybe = xc;
         }
-        for (int o = whole; o < ncand; ++o) {
-          const bool larger = sh.cand_x[o] > xc;
-          m_above += larger ? cand_e[o] : 0.0f;
-          n_above += larger ? 1.0f : 0.0f;
+      } else {
+        // the survivor list of the measurement is over: its words hold the bins and the edge bin's members
+        uint32_t* const words = (uint32_t*)sh.mu;
+        auto bin_w = [&](int b) -> uint32_t& { return words[2 * b]; };
+        auto mem_x = [&](int i) -> float& { return ((float*)words)[2 * (kBins + i)]; };
+        auto mem_w = [&](int i) -> uint32_t& { return words[2 * (kBins + kMembers + i)]; };
+        const float per_logit = (float)kBins / (m - floor_x);  // bins of equal width between the floor and the row's largest logit
+        const float scale = by_count ? 1.0f : 2147483648.0f / (mass * 1.001f);
+        const float limit_f = by_count ? (float)a.top_k : (want + slack) * scale;  // what may be kept has less than this above it
+        const uint32_t limit = limit_f < 1.0f ? 1u : limit_f < 4.0e9f ? (uint32_t)limit_f : 4000000000u;
+        if (tid < kBins) bin_w(tid) = 0;
+        if (tid == 0) *sh.nsurv = 0;
+        __syncthreads();
+        float cx[kKeptCap / kStepThreads];
+        uint32_t cw[kKeptCap / kStepThreads];
+        int cb[kKeptCap / kStepThreads];
+#pragma unroll
+        for (int i = 0; i < kKeptCap / kStepThreads; ++i) {
+          const int c = tid + i * kStepThreads;
+          cb[i] = -1;
+          if (c < ncand) {
+            cx[i] = kept_x[c];
+            cw[i] = by_count ? 1u : (uint32_t)(__builtin_amdgcn_exp2f(fmaf(cx[i], a.k2, nrk_row)) * scale + 0.5f);
+            const int b = (int)((m - cx[i]) * per_logit);  // rounding is monotone: a larger logit never lands in a later bin
+            cb[i] = b < kBins ? b : kBins - 1;
+            atomicAdd(&bin_w(cb[i]), cw[i]);
+          }
         }
-        const bool keep = by_count ? n_above < (float)a.top_k : m_above < want;
-        unsure = !by_count && fabsf(m_above - want) <= 1e-5f * total;
-        if (keep) mine_x = xc;
+        __syncthreads();
+        // every wave for itself: the weight above each bin, and the last bin that has candidates and less than the limit above it
+        static_assert(kBins == 4 * kWave, "four bins per lane");
+        uint32_t h[4], above[4];
+        uint32_t lane_total = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          h[u] = bin_w(4 * lane + u);
+          lane_total += h[u];
+        }
+        uint32_t incl = lane_total;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+          const uint32_t up = __shfl_up(incl, d);
+          if (lane >= d) incl += up;
+        }
+        above[0] = incl - lane_total;
+#pragma unroll
+        for (int u = 1; u < 4; ++u) above[u] = above[u - 1] + h[u - 1];
+        float best = -1.0f;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (h[u] != 0 && above[u] < limit) best = (float)(4 * lane + u);
+        const int edge_bin = (int)wave_max(best);  // the bin of the largest candidate at least: nothing is above it
+        const int u_sel = edge_bin & 3;
+        const uint32_t above_sel = u_sel == 0 ? above[0] : u_sel == 1 ? above[1] : u_sel == 2 ? above[2] : above[3];
+        const uint32_t above_edge_bin = __shfl(above_sel, edge_bin >> 2);
+#pragma unroll
+        for (int i = 0; i < kKeptCap / kStepThreads; ++i) {
+          if (cb[i] == edge_bin) {
+            const int k = atomicAdd(sh.nsurv, 1);
+            if (k < kMembers) {
+              mem_x(k) = cx[i];
+              mem_w(k) = cw[i];
+            }
+          }
+        }
+        __syncthreads();
+        const int members = *sh.nsurv;
+        if (members > kMembers) return false;  // (uniform) a bin of ties, or of many close logits
+        // (the largest candidate of the next bin that has any has everything through the edge bin above
+        // it, the limit at least: it is not kept, nor is anything after it)
+        if (tid < members) {
+          const float xc = mem_x(tid);
+          uint32_t w_above = above_edge_bin;
+#pragma unroll 4
+          for (int o = 0; o < members; ++o) w_above += mem_x(o) > xc ? mem_w(o) : 0u;
+          const float m_above = (float)w_above / scale;
+          if (by_count ? w_above < (uint32_t)a.top_k : m_above < want - slack) mine_sure = xc;
+          if (by_count ? w_above < (uint32_t)a.top_k : m_above < want + slack) mine_maybe = xc;
+        }
       }
-      const float edge = -wave_max(-mine_x);  // smallest kept candidate of the wave
-      const bool any_unsure = __builtin_amdgcn_ballot_w64(unsure) != 0;
+      const float wave_sure = -wave_max(-mine_sure), wave_maybe = -wave_max(-mine_maybe);  // the wave's smallest ones
       __syncthreads();  // the sums of the measurement have been read by everyone
       if (lane == 0) {
-        sh.fres[wave] = edge;
-        sh.fres[kStepWaves + wave] = any_unsure ? 1.0f : 0.0f;
+        sh.fres[wave] = wave_sure;
+        sh.fres[kStepWaves + wave] = wave_maybe;
       }
       __syncthreads();
-      edge_all = __builtin_huge_valf();
-      float unsure_all = 0.0f;
+      edge_sure = __builtin_huge_valf();
+      edge_maybe = __builtin_huge_valf();
       for (int w = 0; w < kStepWaves; ++w) {
-        edge_all = fminf(edge_all, sh.fres[w]);
-        unsure_all += sh.fres[kStepWaves + w];
+        edge_sure = fminf(edge_sure, sh.fres[w]);
+        edge_maybe = fminf(edge_maybe, sh.fres[kStepWaves + w]);
       }
-      return unsure_all == 0.0f && edge_all < __builtin_huge_valf();
+      return edge_maybe < __builtin_huge_valf();
     };
 
-    // the token once the smallest kept logit is known: the winner so far if it is kept, else the winner above the edge
-    auto settle = [&](float edge) {
-      if (x_a >= edge) return;
-      StepShared kept_only = sh;  // everything at or above the edge: the floor is the next float below it
-      kept_only.floor = next_below(edge);
+    // The winner among everything that may be kept (the floor is the next float below that edge).  If
+    // its logit is kept for sure it is the token: leaving out the logits in doubt would not change the
+    // winner.  Else (seldom: the winner is one of the few logits whose sums are too close to p to
+    // tell in fp32) false, and the loop below tests that winner in double.
+    auto winner_above = [&](float edge_sure, float edge_maybe) {
+      StepShared kept_only = sh;
+      kept_only.floor = next_below(edge_maybe);
       search(kept_only, nothing);
+      return tok < 0 || x_a >= edge_sure;
     };
 
     bool done = !(m > kNegInf);
-    float edge_known = kNegInf;
+    float edge_known = kNegInf, edge_open = kNegInf;  // the edge of the kept set for sure, and the smallest logit that may be kept
     bool have_edge = false;
     if (!done && a.top_k == 1) {  // greedy decoding up to ties: the kept set is the row's largest logit
-      edge_known = m;
+      edge_known = edge_open = m;
       have_edge = true;
     } else if (!done) {
       // a floor with about 64 blocks above it, the 64th largest of the 128 lane groups' largest logits
       // (for top-k the (32 + k)-th: k logits have to lie above it).  Measured, 32 is 2 us faster on rows
-      // whose nucleus is a few dozen tokens and 10 to 30 us slower where it is a few hundred.
+      // whose nucleus is a few dozen tokens and 10 to 30 us slower where it is a few hundred.  If the
+      // kept set turns out to reach below that floor (a flat row), the smallest of the 128 is tried:
+      // several hundred blocks lie above it, and a nucleus of some hundred tokens still does.
       __syncthreads();
-      if ((lane & 7) == 0) sh.cand_x[wave * kGroups + grp] = mx;
-      if (tid < kSlots) sh.cand_v[tid] = 0;  // the ranks, summed from eight partial counts each
+      constexpr int kVals = 2 * kSlots;  // two values per lane group: its even and its odd tiles
+      if ((lane & 7) == 0) {
+        sh.cand_x[2 * (wave * kGroups + grp)] = mx_even;
+        sh.cand_x[2 * (wave * kGroups + grp) + 1] = mx_odd;
+      }
+      if (tid < kVals) sh.cand_v[tid] = 0;  // the ranks, summed from partial counts
       __syncthreads();
-      float trial = kNegInf;
-      const int trial_rank = by_count ? (a.top_k < kSlots - 32 ? 31 + a.top_k : kSlots - 1) : 63;
+      const int trial_rank = by_count ? (a.top_k < kVals - 32 ? 31 + a.top_k : kVals - 1) : kVals / 2 - 1;
       {
-        static_assert(kStepThreads / kSlots == 8 && kSlots % 16 == 0, "eight threads per value, sixteen others each");
-        const int j = tid & (kSlots - 1), part = tid / kSlots;
+        constexpr int kParts = kStepThreads / kVals, kOthers = kVals / kParts;  // threads per value, values each of them compares with
+        static_assert(kStepThreads % kVals == 0 && kVals % kParts == 0 && kOthers % 4 == 0, "the values are shared out evenly, four at a time");
+        const int j = tid & (kVals - 1), part = tid / kVals;
         const float mine = sh.cand_x[j];
         int r = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const f32x4 o4 = ((const f32x4*)sh.cand_x)[part * 4 + q];
+        for (int q = 0; q < kOthers / 4; ++q) {
+          const f32x4 o4 = ((const f32x4*)sh.cand_x)[part * (kOthers / 4) + q];
 #pragma unroll
           for (int u = 0; u < 4; ++u) {
-            const int o = part * 16 + q * 4 + u;
+            const int o = part * kOthers + q * 4 + u;
             r += (o4[u] > mine || (o4[u] == mine && o < j)) ? 1 : 0;
           }
         }
         atomicAdd(&sh.cand_v[j], r);
       }
       __syncthreads();
-      if (tid < kSlots && sh.cand_v[tid] == trial_rank) sh.fres[2 * kStepWaves] = sh.cand_x[tid];
+      if (tid < kVals) {  // -inf if fewer lane groups than that saw a finite logit
+        if (sh.cand_v[tid] == trial_rank) sh.fres[2 * kStepWaves] = sh.cand_x[tid];
+        if (sh.cand_v[tid] == kVals - 1) sh.fres[2 * kStepWaves + 1] = sh.cand_x[tid];
+      }
       __syncthreads();
-      trial = sh.fres[2 * kStepWaves];  // -inf if fewer lane groups than that saw a finite logit
-      measure(trial);
-      const bool below_edge = by_count ? count >= (float)a.top_k : mass - want > 1e-5f * total;
-      if (below_edge && ncand <= kCandCap) have_edge = kept_edge(edge_known);
+      const float trials[2] = {sh.fres[2 * kStepWaves], sh.fres[2 * kStepWaves + 1]};
+#pragma unroll 1
+      for (int attempt = 0; attempt < 2; ++attempt) {
+        if (attempt == 1 && !(trials[1] < trials[0])) break;
+        const float trial = attempt == 0 ? trials[0] : trials[1];
+        measure(trial);
+        const bool below_edge = by_count ? count >= (float)a.top_k : mass - want > 1e-5f * total;
+        if (below_edge) {  // every kept logit has been seen; a lower floor could only add to them
+          if (ncand <= kKeptCap) have_edge = kept_edge(trial, edge_known, edge_open);
+          break;
+        }
+      }
     }
     if (have_edge) {  // the kept set is everything at or above the edge
-      StepShared kept_only = sh;
-      kept_only.floor = next_below(edge_known);
-      search(kept_only, nothing);
-      done = true;
+      done = winner_above(edge_known, edge_open);
     } else if (!done) {
       search(sh, nothing);  // the unfiltered winner, for the loop below
     }
@@ -1302,11 +1467,11 @@ __global__ __launch_bounds__(W * kWave, 8) void espo_step_kernel(StepArgs a) {
         kept = dmass < (double)a.top_p * dtotal;
       }
       if (kept) break;
-      if (ncand <= kCandCap) {  // every logit above the winner's is at hand
-        float edge;
-        if (kept_edge(edge)) {
-          settle(edge);
-          break;  // that winner is kept by construction
+      if (ncand <= kKeptCap) {  // every logit above the winner's is at hand
+        float edge, open_edge;
+        if (kept_edge(floor_x, edge, open_edge)) {
+          if (winner_above(edge, open_edge)) break;  // that winner is kept by construction
+          continue;                                  // or it is in doubt: tested next
         }
       }
       StepShared above = sh;  // the bulk case, or a sum too close to tell: the next winner above the floor
@@ -1457,7 +1622,8 @@ int launch_math_errors(float* out, hipStream_t stream) {
 }
 
 // ---------------------------------------------------------------- launch configuration
-// How a call is laid out on the GPU.  One workgroup of 16 waves streams a whole row.  The diagnostics
+// How a call is laid out on the GPU.  One workgroup of 16 waves streams a whole row (8 waves with twice
+// the registers each for a filtered draw).  The diagnostics
 // entry point can force fewer waves per workgroup and a split of every row into `chunks` runs of
 // tiles, each streamed by a workgroup of its own and combined by the last one to arrive.  Measured on
 // an MI355X (B = 512, V = 152064 bf16, all rows live): 34.7 us unsplit, 41 us in 2 chunks of 16 waves,
@@ -1478,7 +1644,7 @@ size_t step_workspace_layout(int64_t B, int chunks, size_t* partials_offset) {
 StepPlan plan_step(int dt, int64_t B, int64_t V, bool filter, int waves, int chunks) {
   StepPlan p;
   const int ntiles = (int)((V + kTile - 1) / kTile);
-  p.waves = waves > 0 ? waves : 16;
+  p.waves = waves > 0 ? waves : filter ? 8 : 16;
   int nch = filter || chunks <= 0 ? 1 : chunks;
   if (nch > ntiles) nch = ntiles;
   if (nch > kMaxChunks) nch = kMaxChunks;
@@ -1492,8 +1658,8 @@ StepPlan plan_step(int dt, int64_t B, int64_t V, bool filter, int waves, int chu
 
 template <int DT, int W>
 void (*pick_kernel(bool sum, bool filter, bool entropy))(StepArgs) {
-  if constexpr (W == 16) {
-    if (filter) return entropy ? espo_step_kernel<DT, true, true, true, 16> : espo_step_kernel<DT, false, true, true, 16>;
+  if constexpr (W == 8) {
+    if (filter) return entropy ? espo_step_kernel<DT, true, true, true, 8> : espo_step_kernel<DT, false, true, true, 8>;
   }
   if (!sum) return espo_step_kernel<DT, false, false, false, W>;
   return entropy ? espo_step_kernel<DT, true, false, true, W> : espo_step_kernel<DT, false, false, true, W>;
@@ -1552,7 +1718,7 @@ int launch_step(const void* logits, int dt, int64_t B, int64_t V, int64_t row_st
   // and so does a filtered draw (more passes over the row)
   const bool filter = (p.top_p > 0.0f && p.top_p < 1.0f) || p.top_k > 0;
   if (plan.lds > kMaxStepLds) return ESPO_ERANGE;
-  if (filter && (plan.waves != 16 || plan.chunks != 1)) return ESPO_EINVAL;
+  if (filter && (plan.waves != 8 || plan.chunks != 1)) return ESPO_EINVAL;
   if (plan.chunks > a.ntiles || plan.chunks > kMaxChunks || (int64_t)B * plan.chunks > 0x7fffffff) return ESPO_ERANGE;
   // and a step that is asked for neither log-probabilities nor either of these needs no softmax sum at all
   const bool sum = logprob != nullptr || entropy != nullptr || filter;

@@ -777,11 +777,45 @@ def test_top_p_and_top_k_draws_match_the_oracle(dtype):
         H.gpu_step(logits, 0.9, 8, 0, vals, gp, st)
         outs.append(st.host())
     for o in outs[1:3]:
-        for k in ("tokens", "regret", "z", "logprob"):
+        for k in ("tokens", "regret", "z"):
             np.testing.assert_array_equal(o[k].view(np.uint8), outs[0][k].view(np.uint8))
+        # the filtered draw streams the row with 8 waves instead of 16: the softmax sum is associated differently
+        np.testing.assert_allclose(o["logprob"], outs[0]["logprob"], rtol=2e-6, atol=2e-6)
     with pytest.raises(espo.EspoError):
         gp, _ = H.params_pair(top_p=0.5, top_k=3)
         H.gpu_step(logits, 0.9, 8, 0, vals, gp, H.GpuState(B))
+    _say(f"  {stats}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_filtered_draws_on_flat_rows_match_the_oracle(dtype):
+    _say(f"[case] filtered draws, nuclei of hundreds of tokens {dtype}")
+    # At temperature 1 and above the synthetic rows are flat: the kept set has from a few dozen to a few
+    # thousand tokens, below the first trial floor on many rows.  These rows take the second trial floor,
+    # the selection of the edge through bins (several hundred collected logits) and, for the widest
+    # filters, the loop over successive winners.  V = 30000 has too few blocks for the bins and compares
+    # all collected logits with each other instead.
+    stats = {}
+    for case, (V, B, tau, filters) in enumerate([
+            (152064, 40, 1.0, [dict(top_p=0.7), dict(top_p=0.5), dict(top_p=0.85), dict(top_k=96), dict(top_k=400)]),
+            (152064, 12, 1.3, [dict(top_p=0.7), dict(top_p=0.3), dict(top_k=1000)]),
+            (30000, 12, 1.0, [dict(top_p=0.7), dict(top_p=0.9), dict(top_k=200)]),
+            (100003, 12, 1.0, [dict(top_p=0.7), dict(top_k=150)])]):
+        stride = ((V + 7) // 8) * 8 + 8
+        g = torch.Generator().manual_seed(900 + case)
+        x = torch.randn(B, stride, generator=g) * 3.0
+        x[:, :V] += W.ZipfLogits(V=V, seed=40 + case, device="cpu").boost
+        x[:, V:] = 1e4
+        logits = x.to(dtype).cuda()
+        vals = torch.rand(B, generator=g).cuda()
+        for f in filters:
+            gp, op = H.params_pair(mu_g=1.0, var_g=2.0, beta=3.0, stop_enabled=0, **f)
+            st = H.GpuState(B)
+            for step in range(2):
+                try:
+                    H.compare_step(logits, tau, 67, step, vals, gp, op, st, V=V, stats=stats)
+                except AssertionError as err:
+                    raise AssertionError(f"case {case} V={V} tau={tau} {f} step {step}: {err}")
     _say(f"  {stats}")
 
 
