@@ -345,7 +345,7 @@ struct StepShared {
   int* res_v;
   float* res_x;
   float* lo;        // [W] score each wave knows to be attained
-  int* visq;        // [W] block each wave scored before the first barrier, or -1
+  int* visq;        // [2][W] blocks each wave scored before the first barrier, or -1
   float* fres;      // [5][W] per-wave results of the fp32 search: s, e, x, hi2, v
   int32_t* cand_v;  // [kCandCap] long survivor lists: indices that can still win ...
   float* cand_x;    // [kCandCap] ... and their logits
@@ -375,7 +375,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots, int
   s.res_v = (int*)take(kStepWaves * 4);
   s.res_x = (float*)take(kStepWaves * 4);
   s.lo = (float*)take(kStepWaves * 4);
-  s.visq = (int*)take(kStepWaves * 4);
+  s.visq = (int*)take(2 * kStepWaves * 4);
   s.fres = (float*)take(5 * kStepWaves * 4);
   s.cand_v = (int32_t*)take(kCandCap * 4);
   s.cand_x = (float*)take(kCandCap * 4);
@@ -392,7 +392,7 @@ __device__ __forceinline__ StepShared carve(unsigned char* base, int nslots, int
 size_t step_lds_bytes(int dt, int ntiles, bool filter, int waves) {
   const size_t esz = dt == ESPO_BF16 ? 2 : 4;
   const size_t nslots = (size_t)ntiles * kGroups, slots = (size_t)waves * kGroups;
-  return 2 * (size_t)waves * 8 + slots * kDrawBlock * esz + slots * 4 + 13 * (size_t)waves * 4 + 16 + 2 * kCandCap * 4 +
+  return 2 * (size_t)waves * 8 + slots * kDrawBlock * esz + slots * 4 + 14 * (size_t)waves * 4 + 16 + 2 * kCandCap * 4 +
          ((nslots * 8 + 15) & ~(size_t)15) + (filter ? 2 : 1) * ((nslots * 4 + 15) & ~(size_t)15);
 }
 
@@ -684,29 +684,38 @@ __device__ __forceinline__ Best wave_best(const Best& st) {
 __device__ __forceinline__ float key_float(int k) { return __builtin_bit_cast(float, k >= 0 ? k : k ^ 0x7fffffff); }
 
 // The fp32 search over the row.  Every wave first scores `q_own`, the block with the largest
-// bound it has streamed; the best lower end s - e found that way is a score known to be
+// bound it has streamed, and `q_own2`, its second (or -1: a workgroup of 16 waves scores one each,
+// one of 8 waves two each: with fewer first blocks the bound is poorer and flat rows keep many more
+// survivors; measured at temperature 1.0, B = 512: 58 us per launch with 8 first blocks, 38 with 16);
+// the best lower end s - e found that way is a score known to be
 // attained, and every other block whose bound reaches it is then scored, one block per wave
 // visit.  `between` runs right after the first barrier.  Returns the wave-uniform result,
 // the same in every wave; all threads of the workgroup must call it.
 template <int DT, int W, typename Between>
 __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared& sh, const void* rowp, int row, int nslots,
-                                            int q_own, Between between) {
+                                            int q_own, int q_own2, Between between) {
   constexpr int kStepWaves = W, kStepThreads = W * kWave;
   const int tid = threadIdx.x;
   const int lane = tid & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   Best st = no_best();
   int q = q_own, k = wave, nsurv = 0;
-  bool first = true;
+  bool first = true, second = q_own2 >= 0;
 #pragma unroll 1
-  while (true) {  // one visit site for the wave's own block and for the survivors
+  while (true) {  // one visit site for the wave's own blocks and for the survivors
     if (q >= 0) fast_visit<DT, W>(a, sh, rowp, row, q, st);
+    if (first && second) {  // (wave-uniform)
+      second = false;
+      q = q_own2;
+      continue;
+    }
     if (first) {
       first = false;
       const float lo = wave_max(st.s - st.e);
       if (lane == 0) {
         sh.lo[wave] = lo;
         sh.visq[wave] = q_own;
+        sh.visq[kStepWaves + wave] = q_own2;
       }
       if (tid == 0) {
         *sh.nsurv = 0;
@@ -717,7 +726,8 @@ __device__ __forceinline__ Best fast_argmax(const StepArgs& a, const StepShared&
       const float bound = wave_max(lane < kStepWaves ? sh.lo[lane] : kNegInf);
       for (int b = sh.q0 + tid; b < sh.q0 + nslots; b += kStepThreads) {  // blocks whose bound reaches the best score found so far
         const float u = sh.ub(b);
-        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[wave_of<W>(sh, b)] != b && holds_eligible(sh, b))
+        const int w_b = wave_of<W>(sh, b);
+        if (u > -1e30f && ub_rounded_up(u) >= bound && sh.visq[w_b] != b && sh.visq[kStepWaves + w_b] != b && holds_eligible(sh, b))
           sh.surv(atomicAdd(sh.nsurv, 1)) = b;
       }
       if (tid == 0) *sh.bkey = float_key(bound);
@@ -782,7 +792,9 @@ __device__ __forceinline__ bool row_is_done(const uint8_t* alive, int row) {
 }
 
 template <int DT, bool Entropy, bool Filter, bool Sum, int W>
-__global__ __launch_bounds__(W * kWave, Filter ? 4 : 8) void espo_step_kernel(StepArgs a) {
+// Registers: 64 per lane for 16 waves (two workgroups on a compute unit); workgroups of 8 waves get up
+// to 80 (three of them fit, in registers and in LDS) and use 75 without spilling; a filtered draw gets 128.
+__global__ __launch_bounds__(W * kWave, Filter ? 4 : W == 8 ? 6 : 8) void espo_step_kernel(StepArgs a) {
   static_assert(Sum || (!Entropy && !Filter), "entropy and filtered draws need the softmax sum");
   static_assert(!Filter || W == 8, "a filtered draw looks at the whole row: one workgroup of 8 waves per row");
   constexpr int kStepWaves = W, kStepThreads = W * kWave, kSlots = W * kGroups;
@@ -971,6 +983,12 @@ __global__ __launch_bounds__(W * kWave, Filter ? 4 : 8) void espo_step_kernel(St
   const float mw = wave_max(mx);
   const float ubw = wave_max(top_ub);
   const int q_own = (int)wave_min_u32(top_q >= 0 && top_ub == ubw ? (uint32_t)top_q : 0xffffffffu);  // -1 if none
+  int q_own2 = -1;  // with fewer than 16 waves, also the best block of the wave's other lane groups
+  if constexpr (W < 16) {
+    const bool other = top_q >= 0 && top_q != q_own;
+    const float ubw2 = wave_max(other ? top_ub : kNegInf);
+    q_own2 = (int)wave_min_u32(other && top_ub == ubw2 ? (uint32_t)top_q : 0xffffffffu);
+  }
   if (lane == 0) sh.m[wave] = mw;
   if ((lane & 7) == 0) sh.top_q[wave * kGroups + grp] = top_q;
   float z_prev = 0.0f, value = 0.0f;  // wanted at the very end: fetched now, off the critical path
@@ -999,7 +1017,7 @@ __global__ __launch_bounds__(W * kWave, Filter ? 4 : 8) void espo_step_kernel(St
   float s_a = kNegInf, e_a = 0.0f;  // the winner's score as a float known to within +-e_a (what the combine of a split row compares)
   // the argmax over the indices whose logit is above shx.floor: fp32 search, decided in double where needed
   auto search = [&](const StepShared& shx, auto between) {
-    const Best fast = fast_argmax<DT, W>(a, shx, rowp, row, nslots, q_own, between);
+    const Best fast = fast_argmax<DT, W>(a, shx, rowp, row, nslots, q_own, q_own2, between);
     tok = fast.v;
     x_a = fast.x;
     s_a = fast.s;
@@ -1622,8 +1640,14 @@ int launch_math_errors(float* out, hipStream_t stream) {
 }
 
 // ---------------------------------------------------------------- launch configuration
-// How a call is laid out on the GPU.  One workgroup of 16 waves streams a whole row (8 waves with twice
-// the registers each for a filtered draw).  The diagnostics
+// How a call is laid out on the GPU.  One workgroup streams a whole row: 8 waves, three workgroups to a
+// compute unit, from 256 rows on; 16 waves, two to a compute unit, for smaller batches, where a
+// compute unit has one row at most and more waves stream it faster (B = 128: 17.0 against 18.5 us).
+// With every row live the two are within 1 us of each other from B = 256 to 4096; with rows that are
+// done in the batch the smaller workgroups are 2 to 5 us faster (B = 1024 with 431 live rows: 36.8
+// against 41.7 us; B = 512 with 446: 30.6 against 32.9): a compute unit takes a third workgroup as soon
+// as a done row's has left, so the live rows spread evenly.  A filtered draw always runs 8 waves, with
+// twice the registers each.  The diagnostics
 // entry point can force fewer waves per workgroup and a split of every row into `chunks` runs of
 // tiles, each streamed by a workgroup of its own and combined by the last one to arrive.  Measured on
 // an MI355X (B = 512, V = 152064 bf16, all rows live): 34.7 us unsplit, 41 us in 2 chunks of 16 waves,
@@ -1641,10 +1665,12 @@ size_t step_workspace_layout(int64_t B, int chunks, size_t* partials_offset) {
   return tickets + (size_t)B * (size_t)chunks * sizeof(ChunkResult);
 }
 
+constexpr int64_t kEightWavesFrom = 256;
+
 StepPlan plan_step(int dt, int64_t B, int64_t V, bool filter, int waves, int chunks) {
   StepPlan p;
   const int ntiles = (int)((V + kTile - 1) / kTile);
-  p.waves = waves > 0 ? waves : filter ? 8 : 16;
+  p.waves = waves > 0 ? waves : filter || B >= kEightWavesFrom ? 8 : 16;
   int nch = filter || chunks <= 0 ? 1 : chunks;
   if (nch > ntiles) nch = ntiles;
   if (nch > kMaxChunks) nch = kMaxChunks;
