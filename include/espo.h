@@ -188,6 +188,12 @@ typedef enum {
  *               no filter on the draw the softmax sum is not needed by anything that is
  *               left (token, regret and state take the row maximum only) and is not formed:
  *               a leaner instantiation of the kernel runs (about 8 % faster at B = 512).
+ *               logprob and entropy are fp32 sums whose order of summation follows the
+ *               launch layout (how many wavefronts stream a row), which the library picks
+ *               from B and from whether the draw is filtered: the same row can differ in
+ *               the last bits between a batch below 256 rows and a larger one, and
+ *               between a filtered and a plain draw.  Tokens, regret, z, alive and
+ *               stop_step do not depend on the layout.
  *   entropy     device, [B] fp32 out, may be NULL (then nothing is spent on it: the
  *               pass with the entropy does two more vector operations per logit).
  *   workspace   device scratch of at least espo_step_workspace_bytes(B, V, dt) bytes, 16-byte

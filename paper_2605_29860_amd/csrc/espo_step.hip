@@ -1278,8 +1278,11 @@ __global__ __launch_bounds__(W * kWave, Filter ? 4 : W == 8 ? 6 : 8) void espo_s
         auto mem_w = [&](int i) -> uint32_t& { return words[2 * (kBins + kMembers + i)]; };
         const float per_logit = (float)kBins / (m - floor_x);  // bins of equal width between the floor and the row's largest logit
         const float scale = by_count ? 1.0f : 2147483648.0f / (mass * 1.001f);
-        const float limit_f = by_count ? (float)a.top_k : (want + slack) * scale;  // what may be kept has less than this above it
+        // what may be kept has less than `limit` above it, what is kept for sure less than `limit_sure`
+        const float limit_f = by_count ? (float)a.top_k : (want + slack) * scale;
+        const float limit_sure_f = by_count ? (float)a.top_k : (want - slack) * scale;
         const uint32_t limit = limit_f < 1.0f ? 1u : limit_f < 4.0e9f ? (uint32_t)limit_f : 4000000000u;
+        const uint32_t limit_sure = limit_sure_f < 1.0f ? 1u : limit_sure_f < 4.0e9f ? (uint32_t)limit_sure_f : 4000000000u;
         if (tid < kBins) bin_w(tid) = 0;
         if (tid == 0) *sh.nsurv = 0;
         __syncthreads();
@@ -1299,7 +1302,8 @@ __global__ __launch_bounds__(W * kWave, Filter ? 4 : W == 8 ? 6 : 8) void espo_s
           }
         }
         __syncthreads();
-        // every wave for itself: the weight above each bin, and the last bin that has candidates and less than the limit above it
+        // every wave for itself: the weight above each bin, and the last bins that have candidates and less
+        // than the two limits above them: the two edges lie in these bins or between them (nearly always one bin)
         static_assert(kBins == 4 * kWave, "four bins per lane");
         uint32_t h[4], above[4];
         uint32_t lane_total = 0;
@@ -1317,17 +1321,20 @@ __global__ __launch_bounds__(W * kWave, Filter ? 4 : W == 8 ? 6 : 8) void espo_s
         above[0] = incl - lane_total;
 #pragma unroll
         for (int u = 1; u < 4; ++u) above[u] = above[u - 1] + h[u - 1];
-        float best = -1.0f;
+        float best = -1.0f, best_sure = -1.0f;
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < 4; ++u) {
           if (h[u] != 0 && above[u] < limit) best = (float)(4 * lane + u);
-        const int edge_bin = (int)wave_max(best);  // the bin of the largest candidate at least: nothing is above it
+          if (h[u] != 0 && above[u] < limit_sure) best_sure = (float)(4 * lane + u);
+        }
+        const int last_bin = (int)wave_max(best);        // the bin of the largest candidate at least: nothing is above it
+        const int edge_bin = (int)wave_max(best_sure);   // not after last_bin: its limit is the smaller one
         const int u_sel = edge_bin & 3;
         const uint32_t above_sel = u_sel == 0 ? above[0] : u_sel == 1 ? above[1] : u_sel == 2 ? above[2] : above[3];
         const uint32_t above_edge_bin = __shfl(above_sel, edge_bin >> 2);
 #pragma unroll
         for (int i = 0; i < kKeptCap / kStepThreads; ++i) {
-          if (cb[i] == edge_bin) {
+          if (cb[i] >= edge_bin && cb[i] <= last_bin) {
             const int k = atomicAdd(sh.nsurv, 1);
             if (k < kMembers) {
               mem_x(k) = cx[i];
@@ -1338,8 +1345,8 @@ __global__ __launch_bounds__(W * kWave, Filter ? 4 : W == 8 ? 6 : 8) void espo_s
         __syncthreads();
         const int members = *sh.nsurv;
         if (members > kMembers) return false;  // (uniform) a bin of ties, or of many close logits
-        // (the largest candidate of the next bin that has any has everything through the edge bin above
-        // it, the limit at least: it is not kept, nor is anything after it)
+        // (the largest candidate of the next bin after last_bin that has any has the limit at least above
+        // it: it is not kept, nor is anything after it; everything before edge_bin is kept for sure)
         if (tid < members) {
           const float xc = mem_x(tid);
           uint32_t w_above = above_edge_bin;
