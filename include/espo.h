@@ -231,8 +231,9 @@ size_t espo_step_workspace_bytes(int64_t B, int64_t V, espo_dtype dt);
  * and td[b,t] = adv[b,t] = 0 for L <= t < T.  rewards and values are never read at
  * t >= L.  (The ablation without the terminal failure penalty, Section 6 variant C, is this
  * call with all `stopped` flags zero: the truncated trajectory then keeps its stored last
- * reward.)  Rows are independent and may come in any order; a batch of more than 512 rows
- * whose rows come in order of length, longest first, takes about a tenth less time.
+ * reward.)  Rows are independent and may come in any order: in a batch of more than 512 rows
+ * the library itself scans the rows from the 513th on longest first (the workgroups look their
+ * rows up by length; no result depends on it).
  *
  * Arguments
  *   rewards, values  device, [B, T] fp32 row-major, 16-byte aligned base; T*4 need
