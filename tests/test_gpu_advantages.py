@@ -130,6 +130,10 @@ def test_many_rows(B):
     r = torch.nan_to_num(r, nan=0.0)
     v = torch.nan_to_num(v, nan=0.0)
     H.check_advantages(r, v, Lt, s, -0.5, 0.97, 0.9)
+    # all rows of one length: the scans after the first 512 look their rows up by class of length and,
+    # inside a class, by index; here that is one class, over several chunks of 1024 rows for the larger B
+    r, v, Lt, s = _batch(B, T, seed=B + 1, lengths=[T - 1] * B)
+    H.check_advantages(r, v, Lt, s, -1.0, 1.0, 0.95)
 
 
 # --------------------------------------------------------------------------- terminal-reward form
