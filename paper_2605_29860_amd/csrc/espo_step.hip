@@ -1652,8 +1652,9 @@ int launch_math_errors(float* out, hipStream_t stream) {
 // compute unit has one row at most and more waves stream it faster (B = 128: 17.0 against 18.5 us).
 // With every row live the two are within 1 us of each other from B = 256 to 4096; with rows that are
 // done in the batch the smaller workgroups are 2 to 5 us faster (B = 1024 with 431 live rows: 36.8
-// against 41.7 us; B = 512 with 446: 30.6 against 32.9): a compute unit takes a third workgroup as soon
-// as a done row's has left, so the live rows spread evenly.  A filtered draw always runs 8 waves, with
+// against 41.7 us; B = 512 with 446: 30.6 against 32.9): workgroups are dispatched in order, and with
+// only 512 slots live rows further back in the batch wait for one (timestamps: a tenth of them start
+// more than 8 us late); with 768 slots all have started within 4 us.  A filtered draw always runs 8 waves, with
 // twice the registers each.  The diagnostics
 // entry point can force fewer waves per workgroup and a split of every row into `chunks` runs of
 // tiles, each streamed by a workgroup of its own and combined by the last one to arrive.  Measured on
