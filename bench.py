@@ -451,6 +451,26 @@ def main() -> int:
             top = curve[-1]
             for c in curve:       # 1.0 = time falls in proportion to the live rows, measured from the fullest bin
                 c["us_over_proportional"] = c["us_per_launch"] / (top["us_per_launch"] * c["live_rows"] / top["live_rows"])
+        # What the position of the done rows in the batch costs: the mask the rollout ended with, as it is
+        # and with the same number of live rows moved to the front (what a caller gets who keeps the batch
+        # compacted), stop rule and end-of-sequence off so that the mask stays as it is.
+        fixed = espo.EspoParams(**{**W.RolloutParams().as_dict(), "stop_enabled": 0, "eos_id": -1})
+        n_live_end = int((ac_ > 0).sum())
+        masks = {"as_the_rollout_left_them": ac_.clone(),
+                 "live_rows_first": (torch.arange(Bc, device=dev) < n_live_end).to(torch.uint8)}
+        position = {"live_rows": n_live_end}
+        for name, mask in masks.items():
+            zz_ = torch.zeros(Bc, dtype=torch.float32, device=dev)
+            for t in range(Sc - 72, Sc - 64):                                  # warm-up
+                espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], fixed, zz_, mask, sc_, tok_c, reg_c, lp_c)
+            r = timer()
+            r[0].record()
+            for t in range(Sc - 64, Sc):
+                espo.espo_step(logits_c[t], tau, seed_c, t, values_c[t], fixed, zz_, mask, sc_, tok_c, reg_c, lp_c)
+            r[1].record()
+            torch.cuda.synchronize()
+            assert int((mask > 0).sum()) == n_live_end
+            position[name + "_us"] = r[0].elapsed_time(r[1]) / 64 * 1e3
         del logits_c
 
     # ------------------------------------------------------------------ CPU oracle on a bounded sample, compared with the GPU
@@ -597,7 +617,9 @@ def main() -> int:
     if curve is not None:
         out["live_curve"] = {"workload": "heavy termination: B=1024, V=152064 bf16, 256 steps, 60% of rows planted to stop in "
                                          "[16,200]; every step's logits resident, one event pair per 8 consecutive launches",
-                             "bins": curve}
+                             "bins": curve,
+                             "done_rows_by_position": {**position, "note": "64 launches each on the last 64 steps' logits, mask held "
+                                                       "fixed; the second figure is what a compacted batch costs"}}
     print(json.dumps(out))
     if parity is not None and not (parity["parity_ok"] and parity["advantages_parity_ok"]):
         print("bench.py: the GPU's results differ from the oracle's", file=sys.stderr)
